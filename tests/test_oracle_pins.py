@@ -1,0 +1,178 @@
+"""Invariants the paper fixes for the speculative step, checked on the oracle.
+
+Greedy verification (top-K_a with K_a = 1, Sec. 5.4) must reproduce plain
+greedy next-token decoding token for token; every step accepts between 1 and
+K+1 tokens (Alg. 1 inner loop bounds); the cache after a step is exactly the
+cache of the accepted tokens; logits at a block row do not depend on later
+candidates (Sec. 3.1, Eq. 1)."""
+import copy
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import synth_inputs as si
+from oracle import Oracle, VerifyParams, accept, rank_of, sample, softmax
+
+GREEDY = VerifyParams(mode=0, sample=0)
+
+
+def _setup(cfg, perturb=True, cap=None):
+    w = si.make_weights(cfg, perturb=perturb)
+    orc = Oracle(cfg, w)
+    st = orc.new_state(cap=cap or cfg["max_ctx"])
+    cond = si.make_cond(cfg, 1)
+    orc.prefill(st, si.make_prefix(cfg, 1)[0], None if cond is None else cond[0])
+    return orc, st
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("seed", [7, 8])
+def test_greedy_spec_equals_plain_greedy_tiny(K, seed):
+    cfg = si.tiny_config(n_draft=K, seed=seed)
+    orc, st = _setup(cfg)
+    st2 = copy.deepcopy(st)
+    blk = si.first_block(cfg, 1)[0]
+    spec, steps, hist = orc.generate_spec(st, blk, 40, GREEDY)
+    plain = orc.generate_plain(st2, blk[0], 40, GREEDY)
+    assert spec == plain
+    assert all(1 <= a <= K + 1 for a in hist)
+    assert 1.0 <= sum(hist) / steps <= K + 1
+
+
+def test_greedy_spec_equals_plain_greedy_config0():
+    cfg = si.get_config("c0")
+    orc, st = _setup(cfg, perturb=False)
+    st2 = copy.deepcopy(st)
+    blk = si.first_block(cfg, 1)[0]
+    spec, steps, hist = orc.generate_spec(st, blk, 512, GREEDY)
+    plain = orc.generate_plain(st2, blk[0], 512, GREEDY)
+    assert spec == plain
+    assert all(1 <= a <= cfg["n_draft"] + 1 for a in hist)
+    # the identity-plus-noise heads repeat the backbone's token, so some drafts do get accepted
+    assert len(set(hist)) > 1
+
+
+def test_rollback_restores_exact_cache_and_ignores_stale_slots():
+    cfg = si.tiny_config(n_draft=4)
+    orc, st = _setup(cfg)
+    st_plain = copy.deepcopy(st)
+    st_poison = copy.deepcopy(st)
+    blk = list(si.first_block(cfg, 1)[0])
+    blk_p = list(blk)
+    toks = [blk[0]]
+    for _ in range(12):
+        r = orc.spec_step(st, blk, GREEDY)
+        # same step on a state whose slots >= n were overwritten with NaN beforehand
+        for l in range(orc.L):
+            st_poison.k[l][st_poison.n:] = np.nan
+            st_poison.v[l][st_poison.n:] = np.nan
+        rp = orc.spec_step(st_poison, blk_p, GREEDY)
+        assert rp["out_tokens"] == r["out_tokens"] and rp["next_block"] == r["next_block"]
+        np.testing.assert_array_equal(rp["Z0"], r["Z0"])
+        toks += r["out_tokens"]
+        blk, blk_p = r["next_block"], rp["next_block"]
+    # cache built by next-token stepping over the same accepted tokens
+    for t in toks[:-1]:
+        orc.forward_block(st_plain, orc.w["E"][[t]])
+        st_plain.n += 1
+    assert st_plain.n == st.n
+    for l in range(orc.L):
+        np.testing.assert_allclose(st.k[l][:st.n], st_plain.k[l][:st.n], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(st.v[l][:st.n], st_plain.v[l][:st.n], rtol=1e-12, atol=1e-14)
+
+
+def test_block_causality():
+    cfg = si.tiny_config(n_draft=5)
+    orc, st = _setup(cfg)
+    blk = np.array([3, 1, 4, 1, 5, 9])
+    _, Z = orc.forward_block(copy.deepcopy(st), orc.w["E"][blk])
+    for j in range(5):
+        alt = blk.copy()
+        alt[j + 1:] = (alt[j + 1:] + 7) % cfg["vocab"]
+        _, Z2 = orc.forward_block(copy.deepcopy(st), orc.w["E"][alt])
+        np.testing.assert_allclose(Z2[:j + 1], Z[:j + 1], rtol=1e-12, atol=1e-14)
+        assert np.abs(Z2[j + 1:] - Z[j + 1:]).max() > 1e-9
+
+
+def test_forced_drafts_hit_every_accept_length():
+    cfg = si.tiny_config(n_draft=4)
+    K = 4
+    orc, st = _setup(cfg)
+    first = int(si.first_block(cfg, 1)[0][0])
+    truth = orc.generate_plain(copy.deepcopy(st), first, K + 1, GREEDY)
+    full = [first] + truth[:K]
+    r = orc.spec_step(copy.deepcopy(st), full, GREEDY)
+    assert r["n_accepted"] == K + 1 and r["out_tokens"] == truth[:K + 1]
+    for j in range(1, K + 1):                       # corrupt candidate j only
+        blk = list(full)
+        blk[j] = (blk[j] + 1) % cfg["vocab"]
+        r = orc.spec_step(copy.deepcopy(st), blk, GREEDY)
+        assert r["a"] == j - 1
+        assert r["out_tokens"] == truth[:j]         # accepted prefix + resampled true token
+
+
+def test_top_ka_full_vocab_accepts_everything_and_heads_on_all_rows_agree():
+    cfg = si.tiny_config(n_draft=4)
+    orc, st = _setup(cfg)
+    vp = VerifyParams(mode=1, top_ka=cfg["vocab"], sample=0)
+    blk = list(si.first_block(cfg, 1)[0])
+    for _ in range(5):
+        ra = orc.spec_step(copy.deepcopy(st), blk, vp, heads_on_all_rows=True)
+        r = orc.spec_step(st, blk, vp)
+        assert r["n_accepted"] == cfg["n_draft"] + 1
+        assert r["next_block"] == ra["next_block"]
+        np.testing.assert_allclose(r["Zh"], ra["Zh"], rtol=1e-12)
+        blk = r["next_block"]
+
+
+def test_threshold_mode():
+    cfg = si.tiny_config(n_draft=3)
+    orc, st = _setup(cfg)
+    blk = si.first_block(cfg, 1)[0]
+    plain = orc.generate_plain(copy.deepcopy(st), blk[0], 30, GREEDY)
+    # p > 0.5 makes the token the unique argmax, so argmax resampling equals plain greedy
+    for delta in (0.5, 0.8):
+        spec, _, _ = orc.generate_spec(copy.deepcopy(st), blk, 30, VerifyParams(mode=2, delta=delta, sample=0))
+        assert spec == plain
+    # delta > 1 never accepts; positions key the RNG, so sampled output equals plain sampling
+    vp = VerifyParams(mode=2, delta=1.5, temperature=0.8, sample=1, seed=99)
+    spec, steps, hist = orc.generate_spec(copy.deepcopy(st), blk, 30, vp)
+    assert hist == [1] * steps
+    assert spec == orc.generate_plain(copy.deepcopy(st), blk[0], 30, vp)
+    # strictness: probability exactly delta is rejected
+    z = np.log(np.array([0.5, 0.25, 0.25]))
+    assert not accept(z, 0, VerifyParams(mode=2, delta=0.5))
+    assert accept(z, 0, VerifyParams(mode=2, delta=0.49))
+
+
+def test_rank_and_accept_on_hand_made_rows():
+    z = np.array([0.1, 2.0, 2.0, -1.0, 0.5])
+    assert [rank_of(z, i) for i in range(5)] == [3, 0, 1, 4, 2]       # equal logits: lower index first
+    assert accept(z, 1, VerifyParams(mode=0)) and not accept(z, 2, VerifyParams(mode=0))
+    assert accept(z, 2, VerifyParams(mode=1, top_ka=2)) and not accept(z, 4, VerifyParams(mode=1, top_ka=2))
+    assert accept(z, 4, VerifyParams(mode=1, top_ka=3))
+    tok, dg = sample(z, VerifyParams(sample=0), 0, 0, 0)
+    assert tok == 1 and dg["margin"] == 0.0
+    # temperature does not change ranks
+    assert rank_of(z / 0.8, 4) == rank_of(z, 4)
+
+
+def test_categorical_sampler_distribution():
+    rng = np.random.default_rng(11)
+    z = rng.standard_normal(12) * 2
+    vp = VerifyParams(sample=1, temperature=0.8, seed=2024)
+    draws = np.array([sample(z, vp, pos, 1, 0)[0] for pos in range(6000)])
+    p = softmax(z / 0.8)
+    counts = np.bincount(draws, minlength=12)
+    keep = p * 6000 >= 5
+    chi = stats.chisquare(np.append(counts[keep], counts[~keep].sum()),
+                          np.append(p[keep], p[~keep].sum()) * 6000)
+    assert chi.pvalue > 1e-3
+    # inverse CDF over ascending index: u just below / above a boundary
+    z2 = np.log(np.array([0.25, 0.25, 0.5]))
+    from oracle import philox
+    for pos in range(50):
+        u = philox.uniform24(7, pos, 0, 0)
+        tok, _ = sample(z2, VerifyParams(sample=1, seed=7), pos, 0, 0)
+        assert tok == (0 if u < 0.25 else 1 if u < 0.5 else 2)
