@@ -1,0 +1,382 @@
+// C ABI of libxsm: context, buffer layout, weight upload, prefill, speculative
+// and plain decoding steps.  All device work is enqueued on the caller's
+// stream; nothing here allocates device memory.
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "xsm_internal.h"
+
+using namespace xsm;
+
+namespace {
+
+thread_local std::string g_create_err;
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+int fail(xsm_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_err = msg;
+  return code;
+}
+
+#define XSM_HIP(call)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (call);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return fail(ctx, XSM_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));    \
+  } while (0)
+
+void build_weight_offsets(xsm_ctx* c) {
+  const xsm_config& g = c->cfg;
+  const size_t d = g.d_model, F = g.d_ffn, V = g.vocab;
+  WeightOff& o = c->woff;
+  size_t p = 0;
+  auto take = [&](size_t n) { size_t r = p; p += n; return r; };
+  o.E = take(V * d);
+  o.layer.resize(g.n_layers);
+  for (int l = 0; l < g.n_layers; ++l) {
+    LayerOff& L = o.layer[l];
+    L.g1 = take(d); L.Wqkv = take(3 * d * d); L.Wo = take(d * d);
+    if (g.n_cond > 0) { L.gc = take(d); L.Wcq = take(d * d); L.Wckv = take(2 * d * d); L.Wco = take(d * d); }
+    else { L.gc = L.Wcq = L.Wckv = L.Wco = 0; }
+    L.g2 = take(d); L.W1 = take(F * d); L.W2 = take(d * F);
+  }
+  o.gf = take(d); o.WU = take(V * d);
+  o.hW.resize(g.n_draft); o.hb.resize(g.n_draft);
+  for (int k = 0; k < g.n_draft; ++k) { o.hW[k] = take(d * d); o.hb[k] = take(d); }
+  o.total = p;
+}
+
+void build_work_offsets(xsm_ctx* c) {
+  const xsm_config& g = c->cfg;
+  const size_t d = g.d_model, F = g.d_ffn, V = g.vocab, K = g.n_draft;
+  const size_t Mmax = (size_t)g.max_batch * kMaxRows;     // rows of one backbone pass
+  const size_t Mb = (size_t)g.max_batch * (K + 1);        // rows of one step
+  WorkOff& w = c->ws;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { size_t r = p; p = align_up(p + bytes); return r; };
+  w.X = take(Mmax * d * 4); w.Xn = take(Mmax * d * 4); w.QKV = take(Mmax * 3 * d * 4);
+  w.Qr = take(Mmax * d * 4); w.AO = take(Mmax * d * 4); w.U = take(Mmax * F * 4);
+  w.Z0 = take(Mb * V * 4);
+  w.G = take((size_t)g.max_batch * d * 4);
+  w.Hh = take((size_t)g.max_batch * (K ? K : 1) * d * 4);
+  w.Rk = take((size_t)g.max_batch * (K ? K : 1) * d * 4);
+  w.Zh = take((size_t)g.max_batch * (K ? K : 1) * V * 4);
+  w.eff_len = take(g.max_batch * 4); w.slot = take(g.max_batch * 4); w.acc = take(g.max_batch * 4);
+  w.y0 = take(g.max_batch * 4); w.wflags = take(g.max_batch * 4);
+  w.toks = take((size_t)g.max_batch * kMaxRows * 4);
+  w.total = p;
+}
+
+struct LayerPtrs {
+  const char *g1, *Wqkv, *Wo, *gc, *Wcq, *Wckv, *Wco, *g2, *W1, *W2;
+};
+LayerPtrs layer_ptrs(const xsm_ctx* c, int l) {
+  const LayerOff& L = c->woff.layer[l];
+  const char* b = c->d_w;
+  const size_t e = c->esz;
+  return {b + L.g1 * e, b + L.Wqkv * e, b + L.Wo * e, b + L.gc * e, b + L.Wcq * e, b + L.Wckv * e,
+          b + L.Wco * e, b + L.g2 * e, b + L.W1 * e, b + L.W2 * e};
+}
+
+// cache addressing: self cache [L][2][max_batch][H][max_ctx][hd], then cross cache
+// [L][2][max_batch][H][n_cond][hd]
+char* self_cache(const xsm_ctx* c, int layer, int which) {
+  const xsm_config& g = c->cfg;
+  const size_t per = (size_t)g.max_batch * g.n_heads * g.max_ctx * g.head_dim;
+  return c->d_kv + ((size_t)layer * 2 + which) * per * c->esz;
+}
+char* cross_cache(const xsm_ctx* c, int layer, int which) {
+  const xsm_config& g = c->cfg;
+  const size_t per = (size_t)g.max_batch * g.n_heads * g.n_cond * g.head_dim;
+  return c->d_kv + (c->kv_self_elems + ((size_t)layer * 2 + which) * per) * c->esz;
+}
+
+// All decoder blocks over M = n_seq*R rows held in ws.X; row m = b*R + j sits at position
+// eff_len[b] + j.  Leaves the final residual stream in ws.X.
+void forward_blocks(xsm_ctx* c, int n_seq, int R, hipStream_t s) {
+  const xsm_config& g = c->cfg;
+  const int d = g.d_model, F = g.d_ffn, H = g.n_heads, hd = g.head_dim, dt = g.dtype;
+  const int M = n_seq * R;
+  char* ws = c->d_ws;
+  float* X = (float*)(ws + c->ws.X);
+  float* Xn = (float*)(ws + c->ws.Xn);
+  float* QKV = (float*)(ws + c->ws.QKV);
+  float* Qr = (float*)(ws + c->ws.Qr);
+  float* AO = (float*)(ws + c->ws.AO);
+  float* U = (float*)(ws + c->ws.U);
+  const int32_t* eff = (const int32_t*)(ws + c->ws.eff_len);
+  const int32_t* slot = (const int32_t*)(ws + c->ws.slot);
+  const float2* rope = (const float2*)(c->d_w + c->rope_off);
+  for (int l = 0; l < g.n_layers; ++l) {
+    const LayerPtrs P = layer_ptrs(c, l);
+    launch_rmsnorm(dt, X, P.g1, Xn, M, d, g.rms_eps, s);
+    launch_gemm(dt, EPI_STORE, Xn, d, P.Wqkv, QKV, 3 * d, M, 3 * d, d, s);
+    launch_rope_kv(dt, QKV, rope, eff, slot, Qr, self_cache(c, l, 0), self_cache(c, l, 1), n_seq, R,
+                   H, hd, g.max_ctx, s);
+    launch_attention(dt, Qr, self_cache(c, l, 0), self_cache(c, l, 1), eff, slot, AO, n_seq, R, H,
+                     hd, g.max_ctx, 0, s);
+    launch_gemm(dt, EPI_ADD, AO, d, P.Wo, X, d, M, d, d, s);
+    if (g.n_cond > 0) {
+      launch_rmsnorm(dt, X, P.gc, Xn, M, d, g.rms_eps, s);
+      launch_gemm(dt, EPI_STORE, Xn, d, P.Wcq, Qr, d, M, d, d, s);
+      launch_attention(dt, Qr, cross_cache(c, l, 0), cross_cache(c, l, 1), eff, slot, AO, n_seq, R,
+                       H, hd, g.n_cond, g.n_cond, s);
+      launch_gemm(dt, EPI_ADD, AO, d, P.Wco, X, d, M, d, d, s);
+    }
+    launch_rmsnorm(dt, X, P.g2, Xn, M, d, g.rms_eps, s);
+    launch_gemm(dt, EPI_GELU, Xn, d, P.W1, U, F, M, F, d, s);
+    launch_gemm(dt, EPI_ADD, U, F, P.W2, X, d, M, d, F, s);
+  }
+}
+
+int check_ready(xsm_ctx* ctx) {
+  if (!ctx) return XSM_EINVAL;
+  if (!ctx->d_w || !ctx->d_kv || !ctx->d_ws) return fail(ctx, XSM_ESTATE, "buffers not bound");
+  if (!ctx->loaded) return fail(ctx, XSM_ESTATE, "weights not loaded");
+  return XSM_OK;
+}
+
+int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, xsm_stream stream,
+                int R) {
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if (!bt || !vp) return fail(ctx, XSM_EINVAL, "null batch or verify params");
+  const xsm_config& g = ctx->cfg;
+  if (bt->n_seq < 1) return fail(ctx, XSM_EINVAL, "n_seq < 1");
+  if (bt->n_seq > g.max_batch) return fail(ctx, XSM_ECAPACITY, "n_seq > max_batch");
+  if (!bt->slot || !bt->kv_len || !bt->block || !bt->out_tokens || !bt->n_accepted || !bt->flags)
+    return fail(ctx, XSM_EINVAL, "null batch array");
+  if (bt->kv_len_bound < 0) return fail(ctx, XSM_EINVAL, "kv_len_bound < 0");
+  if ((long)bt->kv_len_bound + R > g.max_ctx)
+    return fail(ctx, XSM_ECAPACITY, "kv_len_bound + rows per step exceeds max_ctx");
+  if (vp->mode < 0 || vp->mode > 2) return fail(ctx, XSM_EINVAL, "bad verify mode");
+  if (vp->mode == XSM_VERIFY_TOPK && vp->top_ka < 1) return fail(ctx, XSM_EINVAL, "top_ka < 1");
+  if ((vp->sample == 1 || vp->mode == XSM_VERIFY_THRESHOLD) && !(vp->temperature > 0.f))
+    return fail(ctx, XSM_EINVAL, "temperature must be > 0");
+  if (vp->sample != 0 && vp->sample != 1) return fail(ctx, XSM_EINVAL, "bad sample rule");
+
+  hipStream_t s = (hipStream_t)stream;
+  const int n_seq = bt->n_seq, K = R - 1, d = g.d_model, V = g.vocab, dt = g.dtype;
+  const int M = n_seq * R;
+  char* ws = ctx->d_ws;
+  float* X = (float*)(ws + ctx->ws.X);
+  float* Xn = (float*)(ws + ctx->ws.Xn);
+  float* Z0 = (float*)(ws + ctx->ws.Z0);
+  float* G = (float*)(ws + ctx->ws.G);
+  float* Hh = (float*)(ws + ctx->ws.Hh);
+  float* Rk = (float*)(ws + ctx->ws.Rk);
+  float* Zh = (float*)(ws + ctx->ws.Zh);
+  int32_t* eff = (int32_t*)(ws + ctx->ws.eff_len);
+  int32_t* slot = (int32_t*)(ws + ctx->ws.slot);
+  int32_t* acc = (int32_t*)(ws + ctx->ws.acc);
+  int32_t* y0 = (int32_t*)(ws + ctx->ws.y0);
+  uint32_t* wfl = (uint32_t*)(ws + ctx->ws.wflags);
+  const char* wb = ctx->d_w;
+  const size_t e = ctx->esz;
+
+  launch_prepare(bt->kv_len, bt->slot, bt->block, n_seq, R, V, g.max_batch, g.max_ctx,
+                 bt->kv_len_bound, eff, slot, wfl, s);
+  launch_embed(dt, wb + ctx->woff.E * e, bt->block, eff, X, n_seq, R, d, s);
+  forward_blocks(ctx, n_seq, R, s);
+  launch_rmsnorm(dt, X, wb + ctx->woff.gf * e, Xn, M, d, g.rms_eps, s);            // Hf
+  launch_gemm(dt, EPI_STORE, Xn, d, wb + ctx->woff.WU * e, Z0, V, M, V, d, s);      // Eq. 3 logits
+  if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
+  launch_verify(Z0, Xn, bt->block, eff, slot, *vp, acc, y0, wfl, K > 0 ? G : nullptr, n_seq, R, V,
+                d, s);
+  if (K > 0) {
+    const void* bias[16];
+    for (int k = 0; k < K; ++k) {
+      launch_gemm(dt, EPI_STORE, G, d, wb + ctx->woff.hW[k] * e, Hh + (size_t)k * d, K * d, n_seq, d,
+                  d, s);
+      bias[k] = wb + ctx->woff.hb[k] * e;
+    }
+    launch_head_act(dt, G, Hh, bias, Rk, n_seq, K, d, s);
+    launch_gemm(dt, EPI_STORE, Rk, d, wb + ctx->woff.WU * e, Zh, V, n_seq * K, V, d, s);
+    if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
+  }
+  launch_emit(Zh, *vp, eff, slot, acc, y0, wfl, bt->block, bt->kv_len, bt->out_tokens,
+              bt->n_accepted, bt->flags, n_seq, R, K, V, s);
+  hipError_t e2 = hipGetLastError();
+  if (e2 != hipSuccess) return fail(ctx, XSM_EHIP, std::string("launch: ") + hipGetErrorString(e2));
+  return XSM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
+  if (!cfg || !out) return fail(nullptr, XSM_EINVAL, "null argument");
+  const xsm_config& g = *cfg;
+  auto bad = [&](const char* m) { return fail(nullptr, XSM_EINVAL, m); };
+  if (g.n_layers < 1 || g.d_model < 8 || g.n_heads < 1 || g.d_ffn < 8 || g.vocab < 2)
+    return bad("model dimensions out of range");
+  if (g.n_heads * g.head_dim != g.d_model) return bad("n_heads * head_dim != d_model");
+  if (g.head_dim != 16 && g.head_dim != 32 && g.head_dim != 64 && g.head_dim != 128)
+    return bad("head_dim must be 16, 32, 64 or 128");
+  if (g.d_model % 8 || g.d_ffn % 8) return bad("d_model and d_ffn must be multiples of 8");
+  if (g.n_draft < 0 || g.n_draft + 1 > kMaxRows) return bad("n_draft must be in [0, 15]");
+  if (g.max_batch < 1 || g.max_ctx < kMaxRows) return bad("max_batch < 1 or max_ctx < 16");
+  if (g.n_cond < 0) return bad("n_cond < 0");
+  if (g.dtype != XSM_F32 && g.dtype != XSM_BF16) return bad("dtype must be XSM_F32 or XSM_BF16");
+  if (!(g.rope_theta > 1.f) || !(g.rms_eps > 0.f)) return bad("rope_theta must be > 1, rms_eps > 0");
+  xsm_ctx* c = new (std::nothrow) xsm_ctx();
+  if (!c) return bad("out of host memory");
+  c->cfg = g;
+  c->esz = g.dtype == XSM_BF16 ? 2 : 4;
+  build_weight_offsets(c);
+  build_work_offsets(c);
+  c->w_canon_bytes = align_up(c->woff.total * c->esz);
+  c->rope_off = c->w_canon_bytes;
+  c->weights_bytes = c->rope_off + align_up((size_t)g.max_ctx * (g.head_dim / 2) * sizeof(float2));
+  c->kv_self_elems = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * g.max_ctx * g.head_dim;
+  const size_t cross = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * g.n_cond * g.head_dim;
+  c->kv_bytes = align_up((c->kv_self_elems + cross) * c->esz);
+  *out = c;
+  return XSM_OK;
+}
+
+void xsm_destroy(xsm_ctx* ctx) { delete ctx; }
+
+const char* xsm_last_error(const xsm_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_err.c_str(); }
+
+size_t xsm_weights_bytes(const xsm_ctx* ctx) { return ctx ? ctx->weights_bytes : 0; }
+size_t xsm_kv_bytes(const xsm_ctx* ctx) { return ctx ? ctx->kv_bytes : 0; }
+size_t xsm_workspace_bytes(const xsm_ctx* ctx) { return ctx ? ctx->ws.total : 0; }
+size_t xsm_canonical_weight_elems(const xsm_ctx* ctx) { return ctx ? ctx->woff.total : 0; }
+
+int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspace) {
+  if (!ctx) return XSM_EINVAL;
+  if (!d_weights || !d_kv || !d_workspace) return fail(ctx, XSM_EINVAL, "null buffer");
+  if (((uintptr_t)d_weights | (uintptr_t)d_kv | (uintptr_t)d_workspace) & 255)
+    return fail(ctx, XSM_EINVAL, "buffers must be 256-byte aligned");
+  ctx->d_w = (char*)d_weights; ctx->d_kv = (char*)d_kv; ctx->d_ws = (char*)d_workspace;
+  ctx->loaded = false;
+  return XSM_OK;
+}
+
+int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_stream stream) {
+  if (!ctx) return XSM_EINVAL;
+  if (!ctx->d_w) return fail(ctx, XSM_ESTATE, "buffers not bound");
+  if (!h_canonical) return fail(ctx, XSM_EINVAL, "null weights");
+  if (n_elems != ctx->woff.total) return fail(ctx, XSM_EINVAL, "weight element count does not match the configuration");
+  hipStream_t s = (hipStream_t)stream;
+  XSM_HIP(hipMemcpyAsync(ctx->d_w, h_canonical, n_elems * ctx->esz, hipMemcpyHostToDevice, s));
+  launch_rope_table((float2*)(ctx->d_w + ctx->rope_off), ctx->cfg.max_ctx, ctx->cfg.head_dim,
+                    ctx->cfg.rope_theta, s);
+  XSM_HIP(hipGetLastError());
+  ctx->loaded = true;
+  return XSM_OK;
+}
+
+int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* d_prefix_emb,
+                int32_t P, const void* d_cond, xsm_stream stream) {
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  const xsm_config& g = ctx->cfg;
+  if (n_seq < 1 || !h_slot) return fail(ctx, XSM_EINVAL, "n_seq < 1 or null slots");
+  if (n_seq > g.max_batch) return fail(ctx, XSM_ECAPACITY, "n_seq > max_batch");
+  if (P < 0 || (P > 0 && !d_prefix_emb)) return fail(ctx, XSM_EINVAL, "bad prefix");
+  if (P > g.max_ctx) return fail(ctx, XSM_ECAPACITY, "prefix longer than max_ctx");
+  if (g.n_cond > 0 && !d_cond) return fail(ctx, XSM_EINVAL, "condition tokens required");
+  for (int i = 0; i < n_seq; ++i) {
+    if (h_slot[i] < 0 || h_slot[i] >= g.max_batch) return fail(ctx, XSM_EINVAL, "slot out of range");
+    for (int j = 0; j < i; ++j)
+      if (h_slot[j] == h_slot[i]) return fail(ctx, XSM_EINVAL, "duplicate slot");
+  }
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = ctx->d_ws;
+  const int d = g.d_model, dt = g.dtype;
+  float* X = (float*)(ws + ctx->ws.X);
+  float* QKV = (float*)(ws + ctx->ws.QKV);
+  int32_t* eff = (int32_t*)(ws + ctx->ws.eff_len);
+  int32_t* slot = (int32_t*)(ws + ctx->ws.slot);
+  XSM_HIP(hipMemcpyAsync(slot, h_slot, (size_t)n_seq * 4, hipMemcpyHostToDevice, s));
+  if (g.n_cond > 0) {      // per-layer cross-attention keys/values of the condition tokens
+    for (int r0 = 0; r0 < g.n_cond; r0 += kPrefillChunk) {
+      const int C = g.n_cond - r0 < kPrefillChunk ? g.n_cond - r0 : kPrefillChunk;
+      launch_load_rows(dt, d_cond, X, n_seq, C, r0, g.n_cond, d, s);
+      for (int l = 0; l < g.n_layers; ++l) {
+        const LayerPtrs L = layer_ptrs(ctx, l);
+        launch_gemm(dt, EPI_STORE, X, d, L.Wckv, QKV, 2 * d, n_seq * C, 2 * d, d, s);
+        launch_store_cond(dt, QKV, slot, cross_cache(ctx, l, 0), cross_cache(ctx, l, 1), n_seq, C,
+                          r0, g.n_heads, g.head_dim, g.n_cond, s);
+      }
+    }
+  }
+  for (int r0 = 0; r0 < P; r0 += kPrefillChunk) {
+    const int C = P - r0 < kPrefillChunk ? P - r0 : kPrefillChunk;
+    launch_fill_i32(eff, n_seq, r0, s);
+    launch_load_rows(dt, d_prefix_emb, X, n_seq, C, r0, P, d, s);
+    forward_blocks(ctx, n_seq, C, s);
+  }
+  XSM_HIP(hipGetLastError());
+  return XSM_OK;
+}
+
+int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
+                  xsm_stream stream) {
+  if (!ctx) return XSM_EINVAL;
+  if (ctx->cfg.n_draft < 1) return fail(ctx, XSM_EINVAL, "speculative step needs n_draft >= 1");
+  return step_common(ctx, batch, vp, stream, ctx->cfg.n_draft + 1);
+}
+
+int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
+                   xsm_stream stream) {
+  if (!ctx) return XSM_EINVAL;
+  return step_common(ctx, batch, vp, stream, 1);
+}
+
+static int kv_debug(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, int32_t pos0,
+                    int32_t n_pos, float* h_buf, bool to_cache) {
+  if (!ctx) return XSM_EINVAL;
+  if (!ctx->d_kv || !ctx->d_ws) return fail(ctx, XSM_ESTATE, "buffers not bound");
+  const xsm_config& g = ctx->cfg;
+  const bool cross = which >= 2;
+  const int cap = cross ? g.n_cond : g.max_ctx;
+  if (layer < 0 || layer >= g.n_layers || which < 0 || which > 3 || slot < 0 || slot >= g.max_batch ||
+      pos0 < 0 || n_pos < 1 || pos0 + n_pos > cap || !h_buf)
+    return fail(ctx, XSM_EINVAL, "bad cache range");
+  char* base = cross ? cross_cache(ctx, layer, which - 2) : self_cache(ctx, layer, which);
+  char* rows = base + (size_t)slot * g.n_heads * cap * g.head_dim * ctx->esz;
+  // staged through the activation region of the workspace in pieces that fit
+  const size_t stage_elems = (size_t)g.max_batch * kMaxRows * g.d_model * 2;   // X + Xn regions
+  float* stage = (float*)(ctx->d_ws + ctx->ws.X);
+  const int per = (int)(stage_elems / ((size_t)g.n_heads * g.head_dim));
+  XSM_HIP(hipDeviceSynchronize());
+  for (int p = 0; p < n_pos; p += per) {
+    const int np = n_pos - p < per ? n_pos - p : per;
+    const size_t n = (size_t)g.n_heads * np * g.head_dim;
+    std::vector<float> tmp(n);
+    if (to_cache) {
+      for (int h = 0; h < g.n_heads; ++h)
+        memcpy(&tmp[(size_t)h * np * g.head_dim], h_buf + ((size_t)h * n_pos + p) * g.head_dim,
+               (size_t)np * g.head_dim * 4);
+      XSM_HIP(hipMemcpy(stage, tmp.data(), n * 4, hipMemcpyHostToDevice));
+      launch_kv_convert(g.dtype, rows, stage, g.n_heads, cap, pos0 + p, np, g.head_dim, 1, 0);
+      XSM_HIP(hipDeviceSynchronize());
+    } else {
+      XSM_HIP(hipDeviceSynchronize());
+      launch_kv_convert(g.dtype, rows, stage, g.n_heads, cap, pos0 + p, np, g.head_dim, 0, 0);
+      XSM_HIP(hipMemcpy(tmp.data(), stage, n * 4, hipMemcpyDeviceToHost));
+      for (int h = 0; h < g.n_heads; ++h)
+        memcpy(h_buf + ((size_t)h * n_pos + p) * g.head_dim, &tmp[(size_t)h * np * g.head_dim],
+               (size_t)np * g.head_dim * 4);
+    }
+  }
+  return XSM_OK;
+}
+
+int xsm_debug_kv_export(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, int32_t pos0,
+                        int32_t n_pos, float* h_out) {
+  return kv_debug(ctx, layer, which, slot, pos0, n_pos, h_out, false);
+}
+int xsm_debug_kv_import(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, int32_t pos0,
+                        int32_t n_pos, const float* h_in) {
+  return kv_debug(ctx, layer, which, slot, pos0, n_pos, const_cast<float*>(h_in), true);
+}
+
+}  // extern "C"

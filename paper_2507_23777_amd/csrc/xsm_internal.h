@@ -1,0 +1,104 @@
+// Host-side internals of libxsm: context, buffer layouts, kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/xsm.h"
+
+namespace xsm {
+
+constexpr int kPrefillChunk = 16;   // prefix rows per sequence per backbone pass
+constexpr int kMaxRows = 16;        // rows per sequence per pass (K+1 <= 16)
+
+// Element offsets of the canonical weight tensors (same order as the weight file).
+struct LayerOff {
+  size_t g1, Wqkv, Wo, gc, Wcq, Wckv, Wco, g2, W1, W2;
+};
+struct WeightOff {
+  size_t E, gf, WU, total;
+  std::vector<LayerOff> layer;
+  std::vector<size_t> hW, hb;
+};
+
+// Byte offsets inside the caller's workspace buffer.
+struct WorkOff {
+  size_t X, Xn, QKV, Qr, AO, U, Z0, G, Hh, Rk, Zh;
+  size_t eff_len, slot, acc, y0, wflags, toks;   // int32 arrays
+  size_t total;
+};
+
+}  // namespace xsm
+
+struct xsm_ctx {
+  xsm_config cfg;
+  xsm::WeightOff woff;
+  xsm::WorkOff ws;
+  size_t esz;              // bytes per storage element
+  size_t w_canon_bytes;    // canonical weights
+  size_t rope_off;         // byte offset of the rotary table in the weights buffer
+  size_t weights_bytes, kv_bytes;
+  size_t kv_self_elems;    // elements of the self-attention cache (cross cache follows)
+  char* d_w = nullptr;
+  char* d_kv = nullptr;
+  char* d_ws = nullptr;
+  bool loaded = false;
+  std::string err;
+};
+
+namespace xsm {
+
+// ---- launchers (xsm_kernels_basic.hip) -------------------------------------
+// dtype: XSM_F32 or XSM_BF16 selects the storage type of weights / cache / embeddings.
+void launch_rope_table(float2* tab, int max_ctx, int head_dim, float theta, hipStream_t s);
+
+// Validate one step's inputs: eff_len[b] = kv_len[b] or -1 (sequence skipped), slot copy,
+// flag bits.
+void launch_prepare(const int32_t* kv_len, const int32_t* slot, const int32_t* block, int n_seq,
+                    int R, int vocab, int max_batch, int max_ctx, int kv_len_bound,
+                    int32_t* eff_len, int32_t* slot_out, uint32_t* wflags, hipStream_t s);
+void launch_fill_i32(int32_t* p, int n, int32_t v, hipStream_t s);
+
+void launch_embed(int dtype, const void* E, const int32_t* block, const int32_t* eff_len, float* X,
+                  int n_seq, int R, int d, hipStream_t s);
+// X[b*C + j] = emb[b][row0 + j] for j < C
+void launch_load_rows(int dtype, const void* emb, float* X, int n_seq, int C, int row0,
+                      int rows_per_seq, int d, hipStream_t s);
+void launch_rmsnorm(int dtype, const float* X, const void* gain, float* Y, int M, int d, float eps,
+                    hipStream_t s);
+enum { EPI_STORE = 0, EPI_ADD = 1, EPI_GELU = 2 };
+// Y[m][n] (op)= sum_k A[m][k] * W[n][k]
+void launch_gemm(int dtype, int epi, const float* A, int lda, const void* W, float* Y, int ldy,
+                 int M, int N, int K, hipStream_t s);
+// rotate q,k of QKV[M][3d], write q to Qr[M][d], k/v into the cache at eff_len[b] + j
+void launch_rope_kv(int dtype, const float* QKV, const float2* rope, const int32_t* eff_len,
+                    const int32_t* slot, float* Qr, void* Kc, void* Vc, int n_seq, int R, int H,
+                    int hd, int max_ctx, hipStream_t s);
+// cond K/V rows of one chunk into the cross cache: KV[M][2d] -> caches at rows row0..row0+C-1
+void launch_store_cond(int dtype, const float* KV, const int32_t* slot, void* Kc, void* Vc,
+                       int n_seq, int C, int row0, int H, int hd, int n_cond, hipStream_t s);
+// attention of row m = b*R + j over cache positions < (fixed_limit > 0 ? fixed_limit
+// : eff_len[b] + j + 1)
+void launch_attention(int dtype, const float* Q, const void* Kc, const void* Vc,
+                      const int32_t* eff_len, const int32_t* slot, float* O, int n_seq, int R,
+                      int H, int hd, int cap, int fixed_limit, hipStream_t s);
+
+// ---- launchers (xsm_kernels_verify.hip) --------------------------------------
+void launch_verify(const float* Z0, const float* Hf, const int32_t* block, const int32_t* eff_len,
+                   const int32_t* slot, const xsm_verify_params& vp, int32_t* acc, int32_t* y0,
+                   uint32_t* wflags, float* G, int n_seq, int R, int V, int d, hipStream_t s);
+void launch_head_act(int dtype, const float* G, const float* Hh, const void* const* bias_ptrs,
+                     float* Rk, int n_seq, int K, int d, hipStream_t s);
+void launch_emit(const float* Zh, const xsm_verify_params& vp, const int32_t* eff_len,
+                 const int32_t* slot, const int32_t* acc, const int32_t* y0,
+                 const uint32_t* wflags, int32_t* block, int32_t* kv_len, int32_t* out_tokens,
+                 int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
+                 hipStream_t s);
+void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
+// cache rows <-> float staging [H][n_pos][hd]
+void launch_kv_convert(int dtype, void* cache_rows, float* staging, int H, int cap, int pos0,
+                       int n_pos, int hd, int to_cache, hipStream_t s);
+
+}  // namespace xsm

@@ -1,0 +1,257 @@
+// Verification, resampling and emission (Sec. 4.2; Alg. 1 inner while loop,
+// resample line and "s <- s*"): accept scan over the draft block, token draw from
+// the backbone row at the first rejected position, gather of that row's hidden
+// state for the decoding heads, draws from the head distributions, and the
+// length-only cache rollback.  One 256-thread workgroup per sequence; all
+// reductions run in a fixed order so results do not depend on timing.
+#include "xsm_device.h"
+#include "xsm_internal.h"
+
+namespace xsm {
+
+constexpr float kTieMargin = 1e-2f;
+
+struct RowScratch {
+  float redf[8];
+  int redi[8];
+  float part[256];
+  float bestv[4], secv[4];
+  int besti[4];
+};
+
+// argmax with lowest index among equal maxima; *margin = top1 - top2
+__device__ int row_argmax(const float* z, int V, RowScratch& sm, float* margin) {
+  float bv = -INFINITY, sv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int v = threadIdx.x; v < V; v += 256) {
+    const float x = z[v];
+    if (x > bv) { sv = bv; bv = x; bi = v; }          // ascending v: ties keep the lower index
+    else sv = fmaxf(sv, x);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float bv2 = __shfl_xor(bv, o, WAVE), sv2 = __shfl_xor(sv, o, WAVE);
+    const int bi2 = __shfl_xor(bi, o, WAVE);
+    const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);
+    sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));
+    if (take) { bv = bv2; bi = bi2; }
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) {
+    sm.bestv[threadIdx.x >> 6] = bv; sm.secv[threadIdx.x >> 6] = sv; sm.besti[threadIdx.x >> 6] = bi;
+  }
+  __syncthreads();
+  bv = sm.bestv[0]; sv = sm.secv[0]; bi = sm.besti[0];
+  for (int w = 1; w < 4; ++w) {
+    const float bv2 = sm.bestv[w], sv2 = sm.secv[w];
+    const int bi2 = sm.besti[w];
+    const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);
+    sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));
+    if (take) { bv = bv2; bi = bi2; }
+  }
+  *margin = bv - sv;
+  return bi;
+}
+
+// number of tokens ranked ahead of x (larger logit, or equal logit and lower index);
+// *gap = distance of z[x] to the nearest other logit on either side of the K_a boundary
+__device__ int row_rank(const float* z, int V, int x, RowScratch& sm) {
+  const float zx = z[x];
+  int c = 0;
+  for (int v = threadIdx.x; v < V; v += 256) {
+    const float y = z[v];
+    c += (y > zx || (y == zx && v < x)) ? 1 : 0;
+  }
+  return block_sum_i(c, sm.redi);
+}
+
+// near-tie test for the rank criterion: is some other logit within the margin of z[x]
+// while x sits at rank ka-1 or ka (a small change could flip the decision)
+__device__ bool rank_near_boundary(const float* z, int V, int x, int rank, int ka, RowScratch& sm) {
+  const float zx = z[x];
+  int above = 0, below = 0;                      // neighbours within the margin
+  for (int v = threadIdx.x; v < V; v += 256) {
+    if (v == x) continue;
+    const float dlt = z[v] - zx;
+    if (dlt >= 0.f && dlt <= kTieMargin) ++above;
+    if (dlt < 0.f && -dlt <= kTieMargin) ++below;
+  }
+  above = block_sum_i(above, sm.redi);
+  below = block_sum_i(below, sm.redi);
+  // accepted (rank < ka) could become rejected if enough close-below tokens overtake it,
+  // rejected could become accepted if enough close-above tokens drop behind it
+  if (rank < ka) return rank + below >= ka;
+  return rank - above < ka;
+}
+
+// softmax(z/T)[x]
+__device__ float row_prob(const float* z, int V, int x, float invT, RowScratch& sm) {
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+  mx = block_max(mx, sm.redf);
+  float s = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) s += expf((z[v] - mx) * invT);
+  s = block_sum(s, sm.redf);
+  return expf((z[x] - mx) * invT) / s;
+}
+
+// categorical draw by inverse CDF over ascending token index
+__device__ int row_categorical(const float* z, int V, float invT, float u, RowScratch& sm) {
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+  mx = block_max(mx, sm.redf);
+  const int chunk = (V + 255) / 256;
+  const int v0 = threadIdx.x * chunk, v1 = min(V, v0 + chunk);
+  float loc = 0.f;
+  for (int v = v0; v < v1; ++v) loc += expf((z[v] - mx) * invT);
+  __syncthreads();
+  sm.part[threadIdx.x] = loc;
+  __syncthreads();
+  if (threadIdx.x == 0) {                       // exclusive scan, fixed order
+    float run = 0.f;
+    for (int t = 0; t < 256; ++t) { const float p = sm.part[t]; sm.part[t] = run; run += p; }
+    sm.redf[4] = run;
+  }
+  __syncthreads();
+  const float target = u * sm.redf[4];
+  float run = sm.part[threadIdx.x];
+  int hit = 0x7FFFFFFF, lastpos = -1;
+  for (int v = v0; v < v1; ++v) {
+    const float w = expf((z[v] - mx) * invT);
+    run += w;
+    if (w > 0.f) lastpos = v;
+    if (hit == 0x7FFFFFFF && run > target) hit = v;
+  }
+  hit = block_min_i(hit, sm.redi);
+  if (hit != 0x7FFFFFFF) return hit;
+  return block_max_i(lastpos, sm.redi);
+}
+
+__device__ int row_sample(const float* z, int V, const xsm_verify_params& vp, uint32_t pos,
+                          uint32_t head, uint32_t seq, RowScratch& sm, uint32_t* flag) {
+  if (vp.sample == 0) {
+    float margin;
+    const int t = row_argmax(z, V, sm, &margin);
+    if (margin <= kTieMargin) *flag |= XSM_FLAG_NEAR_TIE;
+    return t;
+  }
+  const float u = philox_uniform(vp.seed, pos, head, seq);
+  return row_categorical(z, V, 1.0f / vp.temperature, u, sm);
+}
+
+// accept scan + backbone draw + hidden-state gather
+__global__ __launch_bounds__(256) void k_verify(const float* Z0, const float* Hf,
+                                                const int32_t* block, const int32_t* eff_len,
+                                                const int32_t* slot, xsm_verify_params vp,
+                                                int32_t* acc, int32_t* y0, uint32_t* wflags,
+                                                float* G, int R, int V, int d) {
+  __shared__ RowScratch sm;
+  const int b = blockIdx.x;
+  const int n = eff_len[b];
+  if (n < 0) {
+    if (threadIdx.x == 0) { acc[b] = -1; y0[b] = 0; }
+    if (G) for (int i = threadIdx.x; i < d; i += 256) G[(size_t)b * d + i] = 0.f;
+    return;
+  }
+  uint32_t flag = 0;
+  int a = 0;
+  for (int j = 1; j < R; ++j) {
+    const float* z = Z0 + (size_t)(b * R + j - 1) * V;
+    const int x = block[b * R + j];
+    bool ok;
+    if (vp.mode == XSM_VERIFY_THRESHOLD) {
+      ok = row_prob(z, V, x, 1.0f / vp.temperature, sm) > vp.delta;
+    } else {
+      const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
+      const int rank = row_rank(z, V, x, sm);
+      ok = rank < ka;
+      if (rank_near_boundary(z, V, x, rank, ka, sm)) flag |= XSM_FLAG_NEAR_TIE;
+    }
+    if (!ok) break;
+    ++a;
+  }
+  const int tok = row_sample(Z0 + (size_t)(b * R + a) * V, V, vp, (uint32_t)(n + a + 1), 0u,
+                             (uint32_t)slot[b], sm, &flag);
+  if (threadIdx.x == 0) { acc[b] = a; y0[b] = tok; wflags[b] |= flag; }
+  if (G) {
+    const float* h = Hf + (size_t)(b * R + a) * d;
+    for (int i = threadIdx.x; i < d; i += 256) G[(size_t)b * d + i] = h[i];
+  }
+}
+void launch_verify(const float* Z0, const float* Hf, const int32_t* block, const int32_t* eff_len,
+                   const int32_t* slot, const xsm_verify_params& vp, int32_t* acc, int32_t* y0,
+                   uint32_t* wflags, float* G, int n_seq, int R, int V, int d, hipStream_t s) {
+  hipLaunchKernelGGL(k_verify, dim3(n_seq), dim3(256), 0, s, Z0, Hf, block, eff_len, slot, vp, acc,
+                     y0, wflags, G, R, V, d);
+}
+
+// r_k = g + SiLU(W_k g + b_k): Hh holds W_k g for all heads, [n_seq][K][d]
+struct BiasPtrs { const void* p[16]; };
+template <typename T>
+__global__ void k_head_act(const float* G, const float* Hh, BiasPtrs bias, float* Rk, int K, int d,
+                           long total) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int i = (int)(idx % d), k = (int)((idx / d) % K), b = (int)(idx / ((long)d * K));
+  const float pre = Hh[idx] + ldf((const T*)bias.p[k] + i);
+  Rk[idx] = G[(size_t)b * d + i] + pre / (1.0f + expf(-pre));
+}
+void launch_head_act(int dtype, const float* G, const float* Hh, const void* const* bias_ptrs,
+                     float* Rk, int n_seq, int K, int d, hipStream_t s) {
+  BiasPtrs bp;
+  for (int k = 0; k < 16; ++k) bp.p[k] = k < K ? bias_ptrs[k] : nullptr;
+  const long total = (long)n_seq * K * d;
+  const dim3 grid((unsigned)((total + 255) / 256)), blk(256);
+  if (dtype == XSM_BF16)
+    hipLaunchKernelGGL(k_head_act<bf16_t>, grid, blk, 0, s, G, Hh, bp, Rk, K, d, total);
+  else
+    hipLaunchKernelGGL(k_head_act<float>, grid, blk, 0, s, G, Hh, bp, Rk, K, d, total);
+}
+
+// draws from the K head rows, then emit: accepted tokens, count, next block, new length
+__global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params vp,
+                                              const int32_t* eff_len, const int32_t* slot,
+                                              const int32_t* acc, const int32_t* y0,
+                                              const uint32_t* wflags, int32_t* block,
+                                              int32_t* kv_len, int32_t* out_tokens,
+                                              int32_t* n_accepted, uint32_t* flags, int R, int K,
+                                              int V) {
+  __shared__ RowScratch sm;
+  __shared__ int old_block[16];
+  __shared__ int cand[16];
+  const int b = blockIdx.x;
+  const int n = eff_len[b];
+  if (n < 0) {
+    if (threadIdx.x == 0) { n_accepted[b] = 0; flags[b] = wflags[b]; }
+    return;
+  }
+  const int a = acc[b];
+  if (threadIdx.x < R) old_block[threadIdx.x] = block[b * R + threadIdx.x];
+  uint32_t flag = 0;
+  for (int k = 1; k <= K; ++k) {
+    const int t = row_sample(Zh + (size_t)(b * K + k - 1) * V, V, vp, (uint32_t)(n + a + 1 + k),
+                             (uint32_t)k, (uint32_t)slot[b], sm, &flag);
+    if (threadIdx.x == 0) cand[k] = t;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int j = 0; j < a; ++j) out_tokens[b * R + j] = old_block[j + 1];
+    out_tokens[b * R + a] = y0[b];
+    for (int j = a + 1; j < R; ++j) out_tokens[b * R + j] = -1;
+    block[b * R] = y0[b];
+    for (int k = 1; k <= K; ++k) block[b * R + k] = cand[k];
+    n_accepted[b] = a + 1;
+    kv_len[b] = n + a + 1;
+    flags[b] = wflags[b] | flag;
+  }
+}
+void launch_emit(const float* Zh, const xsm_verify_params& vp, const int32_t* eff_len,
+                 const int32_t* slot, const int32_t* acc, const int32_t* y0,
+                 const uint32_t* wflags, int32_t* block, int32_t* kv_len, int32_t* out_tokens,
+                 int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
+                 hipStream_t s) {
+  hipLaunchKernelGGL(k_emit, dim3(n_seq), dim3(256), 0, s, Zh, vp, eff_len, slot, acc, y0, wflags,
+                     block, kv_len, out_tokens, n_accepted, flags, R, K, V);
+}
+
+}  // namespace xsm

@@ -1,0 +1,208 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Token decisions must agree wherever the oracle's margin
+exceeds 1e-2 (flagged otherwise); logits within 2e-2 (bf16) / 1e-5 (fp32) max
+relative error per row."""
+import copy
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import Oracle, VerifyParams
+
+pytestmark = pytest.mark.gpu
+
+GREEDY = VerifyParams(mode=0, sample=0)
+
+
+@pytest.fixture(scope="module")
+def X():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the xsm hot path has no CPU fallback")
+    import paper_2507_23777_amd as pkg
+    from paper_2507_23777_amd import xsm
+    import xsm_harness as H
+    xsm.lib()
+    return type("X", (), {"pkg": pkg, "xsm": xsm, "H": H, "torch": torch})
+
+
+def _mid_cfg(**kw):
+    cfg = si.tiny_config(n_layers=3, d_model=256, n_heads=4, head_dim=64, d_ffn=1024, vocab=1000,
+                         n_draft=4, dtype="bf16", prefix=37, max_ctx=512, seed=21)
+    cfg.update(kw)
+    return cfg
+
+
+def _report(tal, name):
+    print(f"[{name}] rows {tal.rows} max_rel {tal.max_rel:.3e} decisions {tal.decisions} "
+          f"flagged {tal.flagged} mismatches {len(tal.mismatches)} accept_hist {tal.accept_hist}", flush=True)
+    assert not tal.mismatches, tal.mismatches[:5]
+
+
+def test_config0_fp32_lockstep_and_free_running(X):
+    cfg = si.get_config("c0")
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1, perturb=False)
+    st0 = copy.deepcopy(states[0])
+    first = si.first_block(cfg, 1)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 40, first)
+    _report(tal, "c0 lockstep")
+    assert tal.max_rel < 1e-5
+    # free-running generation: 512 tokens, GPU alone, must equal the oracle's and plain decoding
+    ref, _, _ = orc.generate_spec(copy.deepcopy(st0), first[0], 512, GREEDY)
+    torch = X.torch
+    buf = eng.buffers(1, spec=True)
+    buf.kv_len.fill_(cfg["prefix"]); buf.block.copy_(torch.tensor(first))
+    vpg = X.H.to_vp_gpu(X.xsm, GREEDY)
+    toks, steps, flagged = [], 0, 0
+    while len(toks) < 512:
+        eng.xsm_spec_step(buf, vpg, cfg["prefix"] + len(toks))
+        torch.cuda.synchronize()
+        n = int(buf.n_accepted[0]); assert 1 <= n <= cfg["n_draft"] + 1
+        toks += buf.out_tokens[0, :n].tolist(); steps += 1
+        flagged += int(buf.flags[0]) & 1
+    assert int(buf.kv_len[0]) == cfg["prefix"] + len(toks)
+    pb = eng.buffers(1, spec=False)
+    # plain decoding restarts from the prefix: the cache beyond it is simply overwritten
+    pb.kv_len.fill_(cfg["prefix"]); pb.block.copy_(torch.tensor(first[:, :1]))
+    ptoks = []
+    for i in range(512):
+        eng.xsm_plain_step(pb, vpg, cfg["prefix"] + i)
+        ptoks.append(int(pb.out_tokens[0, 0]))
+    print(f"[c0 free-run] steps {steps} device near-tie flags {flagged}", flush=True)
+    assert toks[:512] == ref, "speculative GPU output differs from the oracle"
+    assert ptoks == ref, "plain GPU decoding differs from greedy speculative decoding"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_ragged_batch(X, dtype):
+    cfg = si.tiny_config(n_layers=2, d_model=64, n_heads=2, head_dim=32, d_ffn=128, vocab=64, n_draft=3,
+                         dtype=dtype, max_ctx=160, seed=11)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, prefix_lens=[5, 17, 33])
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 12, si.first_block(cfg, 3))
+    _report(tal, f"tiny ragged {dtype}")
+
+
+def test_mid_bf16_forced_drafts_hit_every_accept_length(X):
+    cfg = _mid_cfg()
+    K = cfg["n_draft"]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
+
+    def forced(step, b, st, blk):
+        full = X.H.true_continuation(orc, st, blk[0], K, GREEDY)
+        j = (step + b) % (K + 1)            # corrupt candidate j+1 (none when j == K)
+        if j < K:
+            full[j + 1] = (full[j + 1] + 1) % cfg["vocab"]
+        return full
+
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 2 * (K + 1), si.first_block(cfg, 2), forced=forced)
+    _report(tal, "mid forced")
+    assert set(tal.accept_hist) == set(range(1, K + 2))
+
+
+def test_mid_bf16_topk_categorical(X):
+    cfg = _mid_cfg(n_draft=6, seed=22)
+    vp = VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=0xABCDEF0123)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 4, prefix_lens=[37, 20, 37, 9])
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 10, si.first_block(cfg, 4))
+    _report(tal, "mid top-8 T=0.8")
+    # threshold criterion with argmax draws
+    vp2 = VerifyParams(mode=2, delta=0.02, temperature=1.0, sample=0)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp2, 6, si.first_block(cfg, 4))
+    _report(tal, "mid threshold")
+
+
+def test_plain_step_matches_oracle(X):
+    cfg = _mid_cfg(seed=23)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 8, si.first_block(cfg, 2), plain=True)
+    _report(tal, "mid plain")
+
+
+def test_cross_attention_backbone(X):
+    cfg = _mid_cfg(n_cond=50, prefix=0, seed=24, n_layers=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 8, si.first_block(cfg, 2))
+    _report(tal, "cross-attn")
+    cfg = _mid_cfg(n_cond=19, prefix=21, seed=25, n_layers=2, dtype="f32", d_model=128, head_dim=32, d_ffn=256)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 6, si.first_block(cfg, 1))
+    _report(tal, "cross-attn f32")
+    assert tal.max_rel < 1e-5
+
+
+def test_cache_contents_and_rollback(X):
+    cfg = _mid_cfg(seed=26, n_layers=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 5, si.first_block(cfg, 2))
+    _report(tal, "rollback warm-up")
+    for b, st in enumerate(states):
+        for l in range(cfg["n_layers"]):
+            for which, ref in ((0, st.k[l]), (1, st.v[l])):
+                got = eng.xsm_debug_kv_export(l, which, b, 0, st.n)            # [H][n][hd]
+                want = np.transpose(ref[:st.n], (1, 0, 2))
+                err = np.abs(got - want).max() / np.abs(want).max()
+                assert err < 1e-2, (b, l, which, err)
+    # stale slots beyond the accepted length are garbage by contract: poison them with NaN
+    for b, st in enumerate(states):
+        for l in range(cfg["n_layers"]):
+            nan = np.full((cfg["n_heads"], 8, cfg["head_dim"]), np.nan, np.float32)
+            # rows n .. n+K are rewritten by the next step; poison the ones after them too
+            eng.xsm_debug_kv_import(l, 0, b, st.n, nan)
+            eng.xsm_debug_kv_import(l, 1, b, st.n, nan)
+    blocks = [[1, 2, 3, 4, 5], [5, 4, 3, 2, 1]]
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, blocks)
+    _report(tal, "after NaN poisoning")
+
+
+def test_long_context_synthetic_cache(X):
+    cfg = _mid_cfg(seed=27, n_layers=2, max_ctx=8192 + 64, prefix=0)
+    n_pos = 8192
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, max_ctx=cfg["max_ctx"], kv_dtype=np.float32)
+    fill = si.make_kv_fill(cfg, 2, n_pos)
+    lens = [n_pos, n_pos - 1237]
+    for b, st in enumerate(states):
+        for l in range(cfg["n_layers"]):
+            st.k[l][:lens[b]] = np.transpose(fill[l, 0, b, :, :lens[b]], (1, 0, 2))
+            st.v[l][:lens[b]] = np.transpose(fill[l, 1, b, :, :lens[b]], (1, 0, 2))
+            eng.xsm_debug_kv_import(l, 0, b, 0, fill[l, 0, b, :, :lens[b]])
+            eng.xsm_debug_kv_import(l, 1, b, 0, fill[l, 1, b, :, :lens[b]])
+        st.n = lens[b]
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 2))
+    _report(tal, "ctx 8192")
+
+
+def test_config1_shape_bf16(X):
+    cfg = si.get_config("c1")
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1, perturb=False, max_ctx=512)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 6, si.first_block(cfg, 1))
+    _report(tal, "c1 lockstep")
+
+
+def test_argument_and_device_side_errors(X):
+    cfg = _mid_cfg(seed=28, n_layers=1)
+    torch = X.torch
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
+    vpg = X.H.to_vp_gpu(X.xsm, GREEDY)
+    buf = eng.buffers(2, spec=True)
+    buf.kv_len.fill_(cfg["prefix"]); buf.block.fill_(3)
+    with pytest.raises(X.xsm.XsmError, match="max_ctx"):
+        eng.xsm_spec_step(buf, vpg, cfg["max_ctx"] - 2)
+    big = eng.buffers(3, spec=True)
+    with pytest.raises(X.xsm.XsmError, match="max_batch"):
+        eng.xsm_spec_step(big, vpg, 10)
+    bad = X.xsm.xsm_verify_params(1, 0, 0.5, 1.0, 0, 0)
+    with pytest.raises(X.xsm.XsmError, match="top_ka"):
+        eng.xsm_spec_step(buf, bad, 100)
+    # device-side: sequence 0 has a token outside the vocabulary, sequence 1 is fine
+    buf.block[0, 2] = cfg["vocab"] + 5
+    eng.xsm_spec_step(buf, vpg, cfg["prefix"])
+    torch.cuda.synchronize()
+    assert int(buf.n_accepted[0]) == 0 and int(buf.flags[0]) & 4
+    assert 1 <= int(buf.n_accepted[1]) <= cfg["n_draft"] + 1 and (int(buf.flags[1]) & ~1) == 0
+    assert int(buf.kv_len[0]) == cfg["prefix"]
+    # a length beyond the caller's bound is skipped, not run
+    buf.block.fill_(3); buf.kv_len[0] = cfg["prefix"] + 50
+    eng.xsm_spec_step(buf, vpg, cfg["prefix"] + 10)
+    torch.cuda.synchronize()
+    assert int(buf.n_accepted[0]) == 0 and int(buf.flags[0]) & 2

@@ -1,0 +1,177 @@
+"""Lock-step comparison of the HIP library against the CPU oracle.
+
+The oracle drives: every step the GPU receives the oracle's draft block and
+cache lengths (both live in caller-visible device arrays), so a single flagged
+near-tie cannot desynchronise the two sides.  Cache rows written by a step
+depend only on the input block, so the GPU cache stays valid under this
+teacher forcing.  A decision is *flagged, not counted* when the oracle's own
+margin for it is within 1e-2 (logit gap) or 1e-3 (inverse-CDF gap)."""
+from __future__ import annotations
+
+import copy
+from dataclasses import dataclass, field
+
+import numpy as np
+
+import synth_inputs as si
+from oracle import Oracle, VerifyParams
+
+TIE = 1e-2
+CDF_TIE = 1e-3
+
+
+def logit_tol(cfg):
+    return 2e-2 if cfg["dtype"] == "bf16" else 1e-5
+
+
+def rel_err(z_gpu: np.ndarray, z_ref: np.ndarray) -> float:
+    """max_v |z_gpu - z_ref| / max_v |z_ref| for one row."""
+    return float(np.max(np.abs(z_gpu.astype(np.float64) - z_ref)) / np.max(np.abs(z_ref)))
+
+
+def accept_margin(z: np.ndarray, x: int, vp: VerifyParams) -> float:
+    """Oracle-side distance of the accept decision from flipping."""
+    if vp.mode == 2:
+        e = np.exp((z - z.max()) / vp.temperature)
+        return float(abs(e[x] / e.sum() - vp.delta)) * 10.0       # probability gap, scaled to the logit rule
+    ka = 1 if vp.mode == 0 else vp.top_ka
+    srt = np.sort(z)[::-1]
+    others = np.delete(z, x)
+    rank = int(np.sum(z > z[x]) + np.sum(z[:x] == z[x]))
+    so = np.sort(others)[::-1]
+    if rank < ka:                      # accepted: flips if the ka-th best other token overtakes it
+        return float(z[x] - so[ka - 1]) if ka - 1 < so.size else np.inf
+    return float(so[ka - 1] - z[x])    # rejected: flips if it passes the ka-th best other token
+
+
+def draw_margin_ok(dg: dict) -> bool:
+    return dg["margin"] > TIE if dg["kind"] == "argmax" else dg["gap"] > CDF_TIE
+
+
+@dataclass
+class Tally:
+    rows: int = 0
+    decisions: int = 0
+    flagged: int = 0
+    mismatches: list = field(default_factory=list)
+    max_rel: float = 0.0
+    accept_hist: dict = field(default_factory=dict)
+
+
+def to_vp_gpu(xsm, vp: VerifyParams):
+    return xsm.xsm_verify_params(vp.mode, vp.top_ka, vp.delta, vp.temperature, vp.sample, vp.seed)
+
+
+def setup_pair(cfg, engine_cls, n_seq, prefix_lens=None, perturb=True, max_ctx=None, kv_dtype=np.float64):
+    """Weights, oracle states and a GPU engine prefilled with the same condition prefixes.
+    prefix_lens: per-sequence prefix lengths (ragged batches); default cfg['prefix']."""
+    w = si.make_weights(cfg, perturb=perturb)
+    orc = Oracle(cfg, w, kv_dtype=kv_dtype)
+    eng = engine_cls(cfg, max_batch=n_seq, max_ctx=max_ctx or cfg["max_ctx"])
+    eng.xsm_load_weights(si.pack_canonical(cfg, w))
+    prefix_lens = prefix_lens or [cfg["prefix"]] * n_seq
+    pmax = max(prefix_lens)
+    prefix = si.make_prefix(cfg, n_seq, P=pmax) if pmax > 0 else None
+    cond = si.make_cond(cfg, n_seq)
+    states = []
+    for b in range(n_seq):
+        st = orc.new_state(cap=max_ctx or cfg["max_ctx"], seq_id=b)
+        orc.prefill(st, None if prefix is None else prefix[b, :prefix_lens[b]], None if cond is None else cond[b])
+        states.append(st)
+    # GPU: one prefill call per distinct length (a call takes one P for all its sequences)
+    d_cond = None if cond is None else eng.to_device(cond)
+    for P in sorted(set(prefix_lens)):
+        slots = [b for b in range(n_seq) if prefix_lens[b] == P]
+        dp = None if P == 0 else eng.to_device(prefix[slots, :P])
+        dc = None if d_cond is None else d_cond[slots].contiguous()
+        eng.xsm_prefill(slots, dp, dc)
+    eng.torch.cuda.synchronize()
+    return w, orc, states, eng
+
+
+def lockstep(cfg, orc, states, eng, xsm, vp: VerifyParams, n_steps: int, first_blocks, plain=False,
+             forced=None, tally: Tally | None = None) -> Tally:
+    """Run n_steps with the oracle driving.  forced(step, b, state, block) may replace the block
+    (e.g. with the true continuation) before both sides run it."""
+    torch = eng.torch
+    tal = tally or Tally()
+    n_seq = len(states)
+    K = 0 if plain else cfg["n_draft"]
+    R = K + 1
+    buf = eng.buffers(n_seq, spec=not plain, debug=True)
+    blocks = [list(map(int, bl[:R])) for bl in first_blocks]
+    vpg = to_vp_gpu(xsm, vp)
+    tol = logit_tol(cfg)
+    for step in range(n_steps):
+        if forced is not None:
+            blocks = [forced(step, b, states[b], blocks[b]) for b in range(n_seq)]
+        lens = [st.n for st in states]
+        buf.kv_len.copy_(torch.tensor(lens, dtype=torch.int32))
+        buf.block.copy_(torch.tensor(blocks, dtype=torch.int32))
+        if plain:
+            eng.xsm_plain_step(buf, vpg, max(lens))
+        else:
+            eng.xsm_spec_step(buf, vpg, max(lens))
+        torch.cuda.synchronize()
+        g_logits = buf.logits.cpu().numpy()
+        g_heads = None if plain else buf.head_logits.cpu().numpy()
+        g_acc = buf.n_accepted.cpu().numpy()
+        g_out = buf.out_tokens.cpu().numpy()
+        g_blk = buf.block.cpu().numpy()
+        g_len = buf.kv_len.cpu().numpy()
+        g_flags = buf.flags.cpu().numpy()
+        for b in range(n_seq):
+            st = states[b]
+            blk = blocks[b]
+            r = orc.plain_step(st, blk[0], vp) if plain else orc.spec_step(st, blk, vp)
+            where = f"step {step} seq {b}"
+            assert (g_flags[b] & ~1) == 0, f"{where}: device flagged input error {g_flags[b]}"
+            for j in range(R):
+                e = rel_err(g_logits[b, j], r["Z0"][j])
+                tal.max_rel = max(tal.max_rel, e)
+                tal.rows += 1
+                assert e <= tol, f"{where}: backbone logits row {j} rel err {e:.3e} > {tol}"
+            # accept scan: every decision up to and including the first rejection
+            a = r["n_accepted"] - 1
+            safe = True
+            for j in range(1, min(a + 1, K) + 1):
+                tal.decisions += 1
+                if accept_margin(r["Z0"][j - 1], blk[j], vp) <= TIE:
+                    safe = False
+            tal.accept_hist[a + 1] = tal.accept_hist.get(a + 1, 0) + 1
+            if not safe:
+                tal.flagged += 1
+                blocks[b] = r["next_block"]
+                continue
+            if int(g_acc[b]) != a + 1:
+                tal.mismatches.append(f"{where}: n_accepted gpu {g_acc[b]} oracle {a + 1}")
+                blocks[b] = r["next_block"]
+                continue
+            assert int(g_len[b]) == st.n, f"{where}: kv_len {g_len[b]} vs {st.n}"
+            assert list(g_out[b, :a]) == r["out_tokens"][:a], f"{where}: accepted prefix differs"
+            # draws: backbone row, then heads
+            tal.decisions += 1
+            if draw_margin_ok(r["diag"][0]):
+                if int(g_out[b, a]) != r["out_tokens"][a] or int(g_blk[b, 0]) != r["next_block"][0]:
+                    tal.mismatches.append(f"{where}: y0 gpu {g_out[b, a]} oracle {r['out_tokens'][a]}")
+            else:
+                tal.flagged += 1
+            for k in range(1, K + 1):
+                e = rel_err(g_heads[b, k - 1], r["Zh"][k - 1])
+                tal.max_rel = max(tal.max_rel, e)
+                tal.rows += 1
+                assert e <= tol, f"{where}: head {k} logits rel err {e:.3e} > {tol}"
+                tal.decisions += 1
+                if draw_margin_ok(r["diag"][k]):
+                    if int(g_blk[b, k]) != r["next_block"][k]:
+                        tal.mismatches.append(f"{where}: head {k} gpu {g_blk[b, k]} oracle {r['next_block'][k]}")
+                else:
+                    tal.flagged += 1
+            blocks[b] = r["next_block"]
+    return tal
+
+
+def true_continuation(orc, st, first_token: int, K: int, vp: VerifyParams):
+    """Block whose candidates are what plain decoding would produce (all accepted under greedy)."""
+    toks = orc.generate_plain(copy.deepcopy(st), first_token, K, vp)
+    return [int(first_token)] + toks
