@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative decoding step on one MI355X.
+
+A step is one call of xsm_spec_step: backbone forward over K+1 rows per sequence
+against the KV cache, K decoding heads, verification, resampling, length-only
+rollback.  Workload: the single-mesh latency configuration (24 layers, d=1024,
+16 heads, FFN 4096, vocab 4096, bf16, batch 1, K=4, greedy verification,
+257-token condition prefix), free-running generation so the context grows from
+the prefix as tokens are accepted.  Weights are random-init and inputs synthetic;
+everything is resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see the design doc for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(cfg: dict, n_seq: int, sum_ctx: float) -> float:
+    """Bytes one speculative step must move: every weight once, the cached keys/values of
+    all live positions once, the new keys/values once, and the logits rows."""
+    L, d, F, V, K = cfg["n_layers"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_draft"]
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    cross = 2 * d * d if cfg["n_cond"] else 0
+    w = e * (L * (4 * d * d + 2 * d * F + cross) + V * d + K * d * d)
+    kv_read = 2 * e * L * d * (sum_ctx + cfg["n_cond"] * n_seq * (1 if cfg["n_cond"] else 0))
+    kv_write = 2 * e * L * d * n_seq * (K + 1)
+    small = 4 * n_seq * (2 * K + 1) * V
+    return w + kv_read + kv_write + small
+
+
+def cpu_baseline(cfg: dict, w: dict, prefix, first, budget_s: float = 15.0) -> dict:
+    """The float64 numpy oracle on the host cores, same workload, bounded sample."""
+    from threadpoolctl import threadpool_info
+    from oracle import Oracle, VerifyParams
+    orc = Oracle(cfg, w)
+    st = orc.new_state(cap=cfg["prefix"] + 64 * (cfg["n_draft"] + 1) + 16)
+    orc.prefill(st, prefix[0])
+    block, steps, acc = list(first[0]), 0, 0
+    t0 = time.perf_counter()
+    while True:
+        r = orc.spec_step(st, block, VerifyParams())
+        block = r["next_block"]
+        steps += 1
+        acc += r["n_accepted"]
+        el = time.perf_counter() - t0
+        if el > budget_s or steps >= 60:
+            break
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": round((cfg["n_draft"] + 1) * steps / el, 2), "unit": "tok/s", "cores": int(threads),
+            "kind": "oracle", "accepted_tok_per_s": round(acc / el, 2),
+            "ms_per_step": round(1e3 * el / steps, 2),
+            "sample": f"{steps} speculative steps of the same model after the same 257-token prefix "
+                      f"(context {cfg['prefix']}..{st.n}), float64 numpy"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=800)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="c1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent; "
+              "it would shard by batch with no collectives). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2507_23777_amd as pkg
+    from paper_2507_23777_amd import xsm
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        return 2
+    cfg = si.get_config(args.config)
+    B, K, P = cfg["batch"], cfg["n_draft"], cfg["prefix"]
+    R = K + 1
+    total_steps = args.steps + args.warmup
+    max_ctx = P + total_steps * R + 16
+    w = si.make_weights(cfg)
+    eng = pkg.Engine(cfg, max_batch=B, max_ctx=max_ctx)
+    eng.xsm_load_weights(si.pack_canonical(cfg, w))
+    prefix = si.make_prefix(cfg, B)
+    first = si.first_block(cfg, B)
+    eng.xsm_prefill(list(range(B)), eng.to_device(prefix))
+    buf = eng.buffers(B, spec=True)
+    buf.kv_len.fill_(P)
+    buf.block.copy_(torch.tensor(first))
+    vp = pkg.xsm_verify_params(0, 1, 0.5, 1.0, 0, 0)
+    torch.cuda.synchronize()
+
+    def run(n, step0):
+        for i in range(n):
+            eng.xsm_spec_step(buf, vp, P + (step0 + i) * R)
+
+    run(args.warmup, 0)
+    torch.cuda.synchronize()
+    len0 = buf.kv_len.clone()
+    # ---- timed region: exactly `steps` steps, untraced ---------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    len1 = buf.kv_len.clone()
+    accepted = int((len1 - len0).sum())
+    ms_per_step = 1e3 * sec / args.steps
+    verified_tps = B * R * args.steps / sec
+    mean_ctx = float((len0.float().mean() + len1.float().mean()) / 2)
+
+    # ---- same steps again with per-kernel HIP events (on the launch stream) ---------------
+    buf.kv_len.copy_(len0)
+    torch.cuda.synchronize()
+    xsm.xsm_debug_trace_enable(True)
+    tr_steps = min(args.steps, 200)
+    run(tr_steps, args.warmup)
+    trace = xsm.xsm_debug_trace_report()
+    xsm.xsm_debug_trace_enable(False)
+    dom = max(trace.items(), key=lambda kv: kv[1][1])
+    dom_name, (dom_cnt, dom_ms) = dom
+    tot_ms = sum(v[1] for v in trace.values())
+    # dominant kernel class: algorithmic bytes it must move per step / its time per step
+    step_bytes = algorithmic_bytes(cfg, B, B * mean_ctx)
+    kernels = {k: {"launches_per_step": v[0] / tr_steps, "us_per_step": round(1e3 * v[1] / tr_steps, 2)}
+               for k, v in sorted(trace.items(), key=lambda kv: -kv[1][1])}
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    L, d, F, V = cfg["n_layers"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"]
+    gemm_bytes = e * (L * (4 * d * d + 2 * d * F) + V * d + K * d * d + V * d)
+    dom_bytes = gemm_bytes if dom_name == "gemm" else step_bytes
+    achieved = dom_bytes / (1e6 * dom_ms / tr_steps)           # GB/s
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 3),
+                "bytes_per_step": dom_bytes, "step_frac_whole": round(step_bytes / (1e6 * ms_per_step) / HBM_PEAK_GBS, 4)}
+
+    out = {"metric": "verified tok/s/GPU per spec step", "value": round(verified_tps, 1), "unit": "tok/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": cfg["dtype"], "data": "synthetic",
+           "config": {"workload": f"{args.config}: single-mesh latency, L{L} d{d} H{cfg['n_heads']} F{F} V{V} "
+                                  f"{cfg['dtype']}, batch {B}, K={K}, greedy verification, prefix {P}, "
+                                  f"free-running generation",
+                      "batch": B, "n_draft": K, "ctx_start": int(len0.max()), "ctx_end": int(len1.max())},
+           "accepted_tok_per_s": round(accepted / sec, 1), "scr": round(accepted / (B * args.steps), 4),
+           "roofline": roofline, "kernels_us_per_step": kernels,
+           "traced_ms_per_step": round(tot_ms / tr_steps, 4)}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w, prefix, first)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -160,6 +160,14 @@ XSM_API int xsm_debug_kv_export(xsm_ctx* ctx, int32_t layer, int32_t which, int3
 XSM_API int xsm_debug_kv_import(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, int32_t pos0,
                         int32_t n_pos, const float* h_in);
 
+/* Benchmark only: per-kernel timing with HIP events recorded on the launch stream around
+ * every kernel the library enqueues (process-wide switch, off by default; adds two event
+ * records per launch).  xsm_debug_trace_report synchronises the device, writes one text line
+ * "kernel_class count total_ms" per class into h_buf (NUL-terminated, at most cap bytes),
+ * clears the records and returns the number of classes (negative on a HIP error). */
+XSM_API void xsm_debug_trace_enable(int on);
+XSM_API int xsm_debug_trace_report(char* h_buf, size_t cap);
+
 #ifdef __cplusplus
 }
 #endif

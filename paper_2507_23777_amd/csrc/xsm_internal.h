@@ -50,6 +50,15 @@ struct xsm_ctx {
 
 namespace xsm {
 
+// Optional per-kernel timing with HIP events on the launch stream (off by default; used by
+// the benchmark to attribute step time to kernels).  A scope brackets one launch.
+struct TraceScope {
+  TraceScope(const char* name, hipStream_t s);
+  ~TraceScope();
+  hipStream_t s_;
+  int idx_;
+};
+
 // ---- launchers (xsm_kernels_basic.hip) -------------------------------------
 // dtype: XSM_F32 or XSM_BF16 selects the storage type of weights / cache / embeddings.
 void launch_rope_table(float2* tab, int max_ctx, int head_dim, float theta, hipStream_t s);

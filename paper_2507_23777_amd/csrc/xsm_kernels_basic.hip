@@ -19,6 +19,7 @@ __global__ void k_rope_table(float2* tab, int max_ctx, int half, int hd, double 
   tab[idx] = make_float2((float)cos(ang), (float)sin(ang));
 }
 void launch_rope_table(float2* tab, int max_ctx, int head_dim, float theta, hipStream_t s) {
+  TraceScope trace_("rope_table", s);
   const long n = (long)max_ctx * (head_dim / 2);
   hipLaunchKernelGGL(k_rope_table, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, tab, max_ctx,
                      head_dim / 2, head_dim, (double)theta);
@@ -47,6 +48,7 @@ __global__ void k_prepare(const int32_t* kv_len, const int32_t* slot, const int3
 void launch_prepare(const int32_t* kv_len, const int32_t* slot, const int32_t* block, int n_seq,
                     int R, int vocab, int max_batch, int max_ctx, int kv_len_bound,
                     int32_t* eff_len, int32_t* slot_out, uint32_t* wflags, hipStream_t s) {
+  TraceScope trace_("prepare", s);
   hipLaunchKernelGGL(k_prepare, dim3((n_seq + 63) / 64), dim3(64), 0, s, kv_len, slot, block, n_seq,
                      R, vocab, max_batch, max_ctx, kv_len_bound, eff_len, slot_out, wflags);
 }
@@ -56,6 +58,7 @@ __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
   if (i < n) p[i] = v;
 }
 void launch_fill_i32(int32_t* p, int n, int32_t v, hipStream_t s) {
+  TraceScope trace_("fill_i32", s);
   hipLaunchKernelGGL(k_fill_i32, dim3((n + 255) / 256), dim3(256), 0, s, p, n, v);
 }
 
@@ -64,6 +67,7 @@ __global__ void k_copy_f32(const float* src, float* dst, size_t n) {
   if (i < n) dst[i] = src[i];
 }
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s) {
+  TraceScope trace_("copy_f32", s);
   if (n == 0) return;
   hipLaunchKernelGGL(k_copy_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dst, n);
 }
@@ -81,6 +85,7 @@ __global__ void k_embed(const T* E, const int32_t* block, const int32_t* eff_len
 }
 void launch_embed(int dtype, const void* E, const int32_t* block, const int32_t* eff_len, float* X,
                   int n_seq, int R, int d, hipStream_t s) {
+  TraceScope trace_("embed", s);
   if (dtype == XSM_BF16)
     hipLaunchKernelGGL(k_embed<bf16_t>, dim3(n_seq * R), dim3(256), 0, s, (const bf16_t*)E, block,
                        eff_len, X, R, d);
@@ -97,6 +102,7 @@ __global__ void k_load_rows(const T* emb, float* X, int C, int row0, int rows_pe
 }
 void launch_load_rows(int dtype, const void* emb, float* X, int n_seq, int C, int row0,
                       int rows_per_seq, int d, hipStream_t s) {
+  TraceScope trace_("load_rows", s);
   if (dtype == XSM_BF16)
     hipLaunchKernelGGL(k_load_rows<bf16_t>, dim3(n_seq * C), dim3(256), 0, s, (const bf16_t*)emb, X,
                        C, row0, rows_per_seq, d);
@@ -121,6 +127,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const float* X, const T* g, flo
 }
 void launch_rmsnorm(int dtype, const float* X, const void* gain, float* Y, int M, int d, float eps,
                     hipStream_t s) {
+  TraceScope trace_("rmsnorm", s);
   if (dtype == XSM_BF16)
     hipLaunchKernelGGL(k_rmsnorm<bf16_t>, dim3(M), dim3(256), 0, s, X, (const bf16_t*)gain, Y, d, eps);
   else
@@ -194,6 +201,7 @@ static void gemm_dispatch(int epi, const float* A, int lda, const T* W, float* Y
 }
 void launch_gemm(int dtype, int epi, const float* A, int lda, const void* W, float* Y, int ldy,
                  int M, int N, int K, hipStream_t s) {
+  TraceScope trace_("gemm", s);
   if (M <= 0) return;
   if (dtype == XSM_BF16) gemm_dispatch<bf16_t>(epi, A, lda, (const bf16_t*)W, Y, ldy, M, N, K, s);
   else gemm_dispatch<float>(epi, A, lda, (const float*)W, Y, ldy, M, N, K, s);
@@ -230,6 +238,7 @@ __global__ void k_rope_kv(const float* QKV, const float2* rope, const int32_t* e
 void launch_rope_kv(int dtype, const float* QKV, const float2* rope, const int32_t* eff_len,
                     const int32_t* slot, float* Qr, void* Kc, void* Vc, int n_seq, int R, int H,
                     int hd, int max_ctx, hipStream_t s) {
+  TraceScope trace_("rope_kv", s);
   const long n = (long)n_seq * R * H * (hd / 2);
   const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
   if (dtype == XSM_BF16)
@@ -254,6 +263,7 @@ __global__ void k_store_cond(const float* KV, const int32_t* slot, T* Kc, T* Vc,
 }
 void launch_store_cond(int dtype, const float* KV, const int32_t* slot, void* Kc, void* Vc,
                        int n_seq, int C, int row0, int H, int hd, int n_cond, hipStream_t s) {
+  TraceScope trace_("store_cond", s);
   const long n = (long)n_seq * C * H * hd;
   const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
   if (dtype == XSM_BF16)
@@ -389,6 +399,7 @@ static void attn_dispatch(const float* Q, const T* Kc, const T* Vc, const int32_
 void launch_attention(int dtype, const float* Q, const void* Kc, const void* Vc,
                       const int32_t* eff_len, const int32_t* slot, float* O, int n_seq, int R,
                       int H, int hd, int cap, int fixed_limit, hipStream_t s) {
+  TraceScope trace_("attention", s);
   if (dtype == XSM_BF16)
     attn_dispatch<bf16_t>(Q, (const bf16_t*)Kc, (const bf16_t*)Vc, eff_len, slot, O, n_seq, R, H, hd,
                           cap, fixed_limit, s);
@@ -412,6 +423,7 @@ __global__ void k_kv_convert(T* rows, float* staging, int H, int cap, int pos0, 
 }
 void launch_kv_convert(int dtype, void* cache_rows, float* staging, int H, int cap, int pos0,
                        int n_pos, int hd, int to_cache, hipStream_t s) {
+  TraceScope trace_("kv_convert", s);
   const long n = (long)H * n_pos * hd;
   const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
   if (dtype == XSM_BF16)

@@ -181,6 +181,7 @@ __global__ __launch_bounds__(256) void k_verify(const float* Z0, const float* Hf
 void launch_verify(const float* Z0, const float* Hf, const int32_t* block, const int32_t* eff_len,
                    const int32_t* slot, const xsm_verify_params& vp, int32_t* acc, int32_t* y0,
                    uint32_t* wflags, float* G, int n_seq, int R, int V, int d, hipStream_t s) {
+  TraceScope trace_("verify", s);
   hipLaunchKernelGGL(k_verify, dim3(n_seq), dim3(256), 0, s, Z0, Hf, block, eff_len, slot, vp, acc,
                      y0, wflags, G, R, V, d);
 }
@@ -198,6 +199,7 @@ __global__ void k_head_act(const float* G, const float* Hh, BiasPtrs bias, float
 }
 void launch_head_act(int dtype, const float* G, const float* Hh, const void* const* bias_ptrs,
                      float* Rk, int n_seq, int K, int d, hipStream_t s) {
+  TraceScope trace_("head_act", s);
   BiasPtrs bp;
   for (int k = 0; k < 16; ++k) bp.p[k] = k < K ? bias_ptrs[k] : nullptr;
   const long total = (long)n_seq * K * d;
@@ -250,6 +252,7 @@ void launch_emit(const float* Zh, const xsm_verify_params& vp, const int32_t* ef
                  const uint32_t* wflags, int32_t* block, int32_t* kv_len, int32_t* out_tokens,
                  int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
                  hipStream_t s) {
+  TraceScope trace_("emit", s);
   hipLaunchKernelGGL(k_emit, dim3(n_seq), dim3(256), 0, s, Zh, vp, eff_len, slot, acc, y0, wflags,
                      block, kv_len, out_tokens, n_accepted, flags, R, K, V);
 }

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libxsm.so")
 API = ["xsm_create", "xsm_destroy", "xsm_last_error", "xsm_weights_bytes", "xsm_kv_bytes",
        "xsm_workspace_bytes", "xsm_canonical_weight_elems", "xsm_bind", "xsm_load_weights",
        "xsm_prefill", "xsm_spec_step", "xsm_plain_step", "xsm_debug_kv_export",
-       "xsm_debug_kv_import"]
+       "xsm_debug_kv_import", "xsm_debug_trace_enable", "xsm_debug_trace_report"]
 
 
 class XsmError(RuntimeError):
@@ -64,8 +64,27 @@ def lib() -> C.CDLL:
         getattr(L, f).restype = C.c_int
     for f in ("xsm_debug_kv_export", "xsm_debug_kv_import"):
         getattr(L, f).argtypes, getattr(L, f).restype = [vp, i32, i32, i32, i32, i32, vp], C.c_int
+    L.xsm_debug_trace_enable.argtypes, L.xsm_debug_trace_enable.restype = [C.c_int], None
+    L.xsm_debug_trace_report.argtypes, L.xsm_debug_trace_report.restype = [C.c_char_p, sz], C.c_int
     _lib = L
     return L
+
+
+def xsm_debug_trace_enable(on: bool) -> None:
+    lib().xsm_debug_trace_enable(1 if on else 0)
+
+
+def xsm_debug_trace_report() -> dict:
+    """{kernel_class: (count, total_ms)} since the last report."""
+    buf = C.create_string_buffer(1 << 16)
+    n = lib().xsm_debug_trace_report(buf, len(buf))
+    if n < 0:
+        raise XsmError("xsm_debug_trace_report failed")
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, cnt, ms = line.split()
+        out[name] = (int(cnt), float(ms))
+    return out
 
 
 def make_config(cfg: dict, max_batch: int | None = None, max_ctx: int | None = None) -> xsm_config:

@@ -160,6 +160,7 @@ def test_long_context_synthetic_cache(X):
     n_pos = 8192
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, max_ctx=cfg["max_ctx"], kv_dtype=np.float32)
     fill = si.make_kv_fill(cfg, 2, n_pos)
+    fill[:, 0] = si.bf16_round(fill[:, 0] * 6.0)        # sharper scores: a few hundred keys carry the weight
     lens = [n_pos, n_pos - 1237]
     for b, st in enumerate(states):
         for l in range(cfg["n_layers"]):
