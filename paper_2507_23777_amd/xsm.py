@@ -49,6 +49,9 @@ def lib() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise XsmError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_23777_amd.build`")
+    # torch first: its bundled HIP runtime must be the one already in the process, so that
+    # libxsm.so binds to the same runtime that owns the tensors' device memory and streams
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32
     L.xsm_create.argtypes, L.xsm_create.restype = [C.POINTER(xsm_config), C.POINTER(vp)], C.c_int
