@@ -1,6 +1,7 @@
 // C ABI of libxsm: context, buffer layout, weight upload, prefill, speculative
 // and plain decoding steps.  All device work is enqueued on the caller's
 // stream; nothing here allocates device memory.
+#include <math.h>
 #include <stdio.h>
 #include <string.h>
 
@@ -67,7 +68,34 @@ void build_work_offsets(xsm_ctx* c) {
   w.eff_len = take(g.max_batch * 4); w.slot = take(g.max_batch * 4); w.acc = take(g.max_batch * 4);
   w.y0 = take(g.max_batch * 4); w.wflags = take(g.max_batch * 4);
   w.toks = take((size_t)g.max_batch * kMaxRows * 4);
+  w.rowidx = take(g.max_batch * 4);
+  w.Qbf = take(Mmax * d * 2); w.AObf = take(Mmax * d * 2); w.Ubf = take(Mmax * F * 2);
+  w.Rkbf = take((size_t)g.max_batch * (K ? K : 1) * d * 2);
+  c->part_entries = (size_t)g.max_batch * g.n_heads;
+  if (c->part_entries < 1024) c->part_entries = 1024;
+  w.part = take(fattn_part_bytes(c->part_entries));
+  w.tickets = take((size_t)g.max_batch * g.n_heads * 4);
   w.total = p;
+}
+
+// Fragment-ordered copies of the bf16 matrices, placed after the rotary table.
+size_t build_tiled_offsets(xsm_ctx* c, size_t start) {
+  const xsm_config& g = c->cfg;
+  const size_t d = g.d_model, F = g.d_ffn, V = g.vocab, K = g.n_draft;
+  size_t p = start;
+  auto take = [&](size_t elems) { size_t r = p; p = align_up(p + elems * 2); return r; };
+  TiledOff& t = c->toff;
+  t.layer.resize(g.n_layers);
+  for (int l = 0; l < g.n_layers; ++l) {
+    TiledLayer& L = t.layer[l];
+    L.Wqkv = take(3 * d * d); L.Wo = take(d * d);
+    if (g.n_cond > 0) { L.Wcq = take(d * d); L.Wco = take(d * d); } else { L.Wcq = L.Wco = 0; }
+    L.W1 = take(F * d); L.W2 = take(d * F);
+  }
+  t.WU = take(V * d);
+  t.Wh = take((K ? K : 1) * d * d);
+  t.hb = take((K ? K : 1) * d);
+  return p;
 }
 
 struct LayerPtrs {
@@ -85,18 +113,96 @@ LayerPtrs layer_ptrs(const xsm_ctx* c, int l) {
 // [L][2][max_batch][H][n_cond][hd]
 char* self_cache(const xsm_ctx* c, int layer, int which) {
   const xsm_config& g = c->cfg;
-  const size_t per = (size_t)g.max_batch * g.n_heads * g.max_ctx * g.head_dim;
+  const size_t per = (size_t)g.max_batch * g.n_heads * c->cap_self * g.head_dim;
   return c->d_kv + ((size_t)layer * 2 + which) * per * c->esz;
 }
 char* cross_cache(const xsm_ctx* c, int layer, int which) {
   const xsm_config& g = c->cfg;
-  const size_t per = (size_t)g.max_batch * g.n_heads * g.n_cond * g.head_dim;
+  const size_t per = (size_t)g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
   return c->d_kv + (c->kv_self_elems + ((size_t)layer * 2 + which) * per) * c->esz;
+}
+
+// split count of the key range per (sequence, head): enough workgroups to fill the chip, at
+// least ~4 chunks of 64 keys each, bounded by the partial slots in the workspace
+int attn_splits(const xsm_ctx* c, int n_seq, int len_bound) {
+  const int BH = n_seq * c->cfg.n_heads;
+  const int chunks = (len_bound + 63) / 64;
+  int S = 512 / BH;
+  if (S > chunks / 4) S = chunks / 4;
+  if ((size_t)S * BH > c->part_entries) S = (int)(c->part_entries / BH);
+  return S < 1 ? 1 : S;
+}
+
+// MFMA path: all decoder blocks over M = n_seq*R rows held in ws.X (fp32 residual stream).
+void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_t s) {
+  const xsm_config& g = c->cfg;
+  const int d = g.d_model, F = g.d_ffn, H = g.n_heads, hd = g.head_dim;
+  const int M = n_seq * R;
+  char* ws = c->d_ws;
+  float* X = (float*)(ws + c->ws.X);
+  uint16_t* Qbf = (uint16_t*)(ws + c->ws.Qbf);
+  uint16_t* AObf = (uint16_t*)(ws + c->ws.AObf);
+  uint16_t* Ubf = (uint16_t*)(ws + c->ws.Ubf);
+  const int32_t* eff = (const int32_t*)(ws + c->ws.eff_len);
+  const int32_t* slot = (const int32_t*)(ws + c->ws.slot);
+  const float2* rope = (const float2*)(c->d_w + c->rope_off);
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
+  for (int l = 0; l < g.n_layers; ++l) {
+    const LayerPtrs P = layer_ptrs(c, l);
+    const TiledLayer& T = c->toff.layer[l];
+    FastGemm q{};
+    q.Wt = (const uint4*)(c->d_w + T.Wqkv); q.N = 3 * d; q.K = d; q.M = M;
+    q.X = X; q.ldx = d; q.gain = (const uint16_t*)P.g1; q.eps = g.rms_eps;
+    q.Ybf = Qbf; q.ldyb = d;
+    q.rope = rope; q.eff_len = eff; q.slot = slot; q.R = R; q.H = H; q.hd = hd; q.cap = c->cap_self;
+    q.v_transposed = 1; q.Kc = (uint16_t*)self_cache(c, l, 0); q.Vc = (uint16_t*)self_cache(c, l, 1);
+    launch_fgemm(PRO_NORM, FEPI_QKV, q, s);
+
+    FastAttn a{};
+    a.Q = Qbf; a.ldq = d; a.Kc = (const uint16_t*)self_cache(c, l, 0); a.Vt = (const uint16_t*)self_cache(c, l, 1);
+    a.eff_len = eff; a.slot = slot; a.O = AObf; a.ldo = d;
+    a.part = (float*)(ws + c->ws.part); a.tickets = (uint32_t*)(ws + c->ws.tickets);
+    a.R = R; a.H = H; a.cap = c->cap_self; a.S = attn_splits(c, n_seq, len_bound + R); a.fixed_limit = 0;
+    a.scale_log2 = scale_log2;
+    launch_fattn(a, n_seq, s);
+
+    FastGemm o{};
+    o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
+    o.Abf = AObf; o.lda = d; o.Y = X; o.ldy = d;
+    launch_fgemm(PRO_BF16, FEPI_ADD, o, s);
+
+    if (g.n_cond > 0) {
+      FastGemm cq{};
+      cq.Wt = (const uint4*)(c->d_w + T.Wcq); cq.N = d; cq.K = d; cq.M = M;
+      cq.X = X; cq.ldx = d; cq.gain = (const uint16_t*)P.gc; cq.eps = g.rms_eps;
+      cq.Ybf = Qbf; cq.ldyb = d;
+      launch_fgemm(PRO_NORM, FEPI_BF16, cq, s);
+      FastAttn ca = a;
+      ca.Kc = (const uint16_t*)cross_cache(c, l, 0); ca.Vt = (const uint16_t*)cross_cache(c, l, 1);
+      ca.cap = c->cap_cross; ca.fixed_limit = g.n_cond; ca.S = attn_splits(c, n_seq, g.n_cond);
+      launch_fattn(ca, n_seq, s);
+      FastGemm co = o;
+      co.Wt = (const uint4*)(c->d_w + T.Wco);
+      launch_fgemm(PRO_BF16, FEPI_ADD, co, s);
+    }
+
+    FastGemm u{};
+    u.Wt = (const uint4*)(c->d_w + T.W1); u.N = F; u.K = d; u.M = M;
+    u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
+    u.Ybf = Ubf; u.ldyb = F;
+    launch_fgemm(PRO_NORM, FEPI_GELU_BF16, u, s);
+
+    FastGemm dn{};
+    dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
+    dn.Abf = Ubf; dn.lda = F; dn.Y = X; dn.ldy = d;
+    launch_fgemm(PRO_BF16, FEPI_ADD, dn, s);
+  }
 }
 
 // All decoder blocks over M = n_seq*R rows held in ws.X; row m = b*R + j sits at position
 // eff_len[b] + j.  Leaves the final residual stream in ws.X.
-void forward_blocks(xsm_ctx* c, int n_seq, int R, hipStream_t s) {
+void forward_blocks(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_t s) {
+  if (c->fast) { forward_blocks_fast(c, n_seq, R, len_bound, s); return; }
   const xsm_config& g = c->cfg;
   const int d = g.d_model, F = g.d_ffn, H = g.n_heads, hd = g.head_dim, dt = g.dtype;
   const int M = n_seq * R;
@@ -115,15 +221,15 @@ void forward_blocks(xsm_ctx* c, int n_seq, int R, hipStream_t s) {
     launch_rmsnorm(dt, X, P.g1, Xn, M, d, g.rms_eps, s);
     launch_gemm(dt, EPI_STORE, Xn, d, P.Wqkv, QKV, 3 * d, M, 3 * d, d, s);
     launch_rope_kv(dt, QKV, rope, eff, slot, Qr, self_cache(c, l, 0), self_cache(c, l, 1), n_seq, R,
-                   H, hd, g.max_ctx, s);
+                   H, hd, c->cap_self, s);
     launch_attention(dt, Qr, self_cache(c, l, 0), self_cache(c, l, 1), eff, slot, AO, n_seq, R, H,
-                     hd, g.max_ctx, 0, s);
+                     hd, c->cap_self, 0, s);
     launch_gemm(dt, EPI_ADD, AO, d, P.Wo, X, d, M, d, d, s);
     if (g.n_cond > 0) {
       launch_rmsnorm(dt, X, P.gc, Xn, M, d, g.rms_eps, s);
       launch_gemm(dt, EPI_STORE, Xn, d, P.Wcq, Qr, d, M, d, d, s);
       launch_attention(dt, Qr, cross_cache(c, l, 0), cross_cache(c, l, 1), eff, slot, AO, n_seq, R,
-                       H, hd, g.n_cond, g.n_cond, s);
+                       H, hd, c->cap_cross, g.n_cond, s);
       launch_gemm(dt, EPI_ADD, AO, d, P.Wco, X, d, M, d, d, s);
     }
     launch_rmsnorm(dt, X, P.g2, Xn, M, d, g.rms_eps, s);
@@ -180,22 +286,48 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   launch_prepare(bt->kv_len, bt->slot, bt->block, n_seq, R, V, g.max_batch, g.max_ctx,
                  bt->kv_len_bound, eff, slot, wfl, s);
   launch_embed(dt, wb + ctx->woff.E * e, bt->block, eff, X, n_seq, R, d, s);
-  forward_blocks(ctx, n_seq, R, s);
-  launch_rmsnorm(dt, X, wb + ctx->woff.gf * e, Xn, M, d, g.rms_eps, s);            // Hf
-  launch_gemm(dt, EPI_STORE, Xn, d, wb + ctx->woff.WU * e, Z0, V, M, V, d, s);      // Eq. 3 logits
-  if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
-  launch_verify(Z0, Xn, bt->block, eff, slot, *vp, acc, y0, wfl, K > 0 ? G : nullptr, n_seq, R, V,
-                d, s);
-  if (K > 0) {
-    const void* bias[16];
-    for (int k = 0; k < K; ++k) {
-      launch_gemm(dt, EPI_STORE, G, d, wb + ctx->woff.hW[k] * e, Hh + (size_t)k * d, K * d, n_seq, d,
-                  d, s);
-      bias[k] = wb + ctx->woff.hb[k] * e;
+  forward_blocks(ctx, n_seq, R, bt->kv_len_bound, s);
+  if (ctx->fast) {
+    // Eq. 3 logits straight from the residual stream: final RMSNorm is the GEMM prologue
+    FastGemm z{};
+    z.Wt = (const uint4*)(wb + ctx->toff.WU); z.N = V; z.K = d; z.M = M;
+    z.X = X; z.ldx = d; z.gain = (const uint16_t*)(wb + ctx->woff.gf * e); z.eps = g.rms_eps;
+    z.Y = Z0; z.ldy = V;
+    launch_fgemm(PRO_NORM, FEPI_STORE, z, s);
+    if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
+    launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
+    if (K > 0) {
+      int32_t* rowidx = (int32_t*)(ws + ctx->ws.rowidx);
+      uint16_t* Rkbf = (uint16_t*)(ws + ctx->ws.Rkbf);
+      launch_head_rows(acc, rowidx, n_seq, R, s);
+      FastGemm hg{};                               // all K heads at once: [K*d][d] stacked
+      hg.Wt = (const uint4*)(wb + ctx->toff.Wh); hg.N = K * d; hg.K = d; hg.M = n_seq;
+      hg.X = X; hg.ldx = d; hg.gain = z.gain; hg.eps = g.rms_eps; hg.row_index = rowidx;
+      hg.Ybf = Rkbf; hg.ldyb = K * d; hg.bias = (const uint16_t*)(wb + ctx->toff.hb);
+      launch_fgemm(PRO_NORM, FEPI_HEAD, hg, s);
+      FastGemm zh{};
+      zh.Wt = z.Wt; zh.N = V; zh.K = d; zh.M = n_seq * K;
+      zh.Abf = Rkbf; zh.lda = d; zh.Y = Zh; zh.ldy = V;
+      launch_fgemm(PRO_BF16, FEPI_STORE, zh, s);
+      if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     }
-    launch_head_act(dt, G, Hh, bias, Rk, n_seq, K, d, s);
-    launch_gemm(dt, EPI_STORE, Rk, d, wb + ctx->woff.WU * e, Zh, V, n_seq * K, V, d, s);
-    if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
+  } else {
+    launch_rmsnorm(dt, X, wb + ctx->woff.gf * e, Xn, M, d, g.rms_eps, s);            // Hf
+    launch_gemm(dt, EPI_STORE, Xn, d, wb + ctx->woff.WU * e, Z0, V, M, V, d, s);      // Eq. 3 logits
+    if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
+    launch_verify(Z0, Xn, bt->block, eff, slot, *vp, acc, y0, wfl, K > 0 ? G : nullptr, n_seq, R, V,
+                  d, s);
+    if (K > 0) {
+      const void* bias[16];
+      for (int k = 0; k < K; ++k) {
+        launch_gemm(dt, EPI_STORE, G, d, wb + ctx->woff.hW[k] * e, Hh + (size_t)k * d, K * d, n_seq, d,
+                    d, s);
+        bias[k] = wb + ctx->woff.hb[k] * e;
+      }
+      launch_head_act(dt, G, Hh, bias, Rk, n_seq, K, d, s);
+      launch_gemm(dt, EPI_STORE, Rk, d, wb + ctx->woff.WU * e, Zh, V, n_seq * K, V, d, s);
+      if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
+    }
   }
   launch_emit(Zh, *vp, eff, slot, acc, y0, wfl, bt->block, bt->kv_len, bt->out_tokens,
               bt->n_accepted, bt->flags, n_seq, R, K, V, s);
@@ -229,11 +361,16 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
   c->esz = g.dtype == XSM_BF16 ? 2 : 4;
   build_weight_offsets(c);
   build_work_offsets(c);
+  c->cap_self = (g.max_ctx + 63) / 64 * 64;
+  c->cap_cross = (g.n_cond + 63) / 64 * 64;
+  c->fast = g.dtype == XSM_BF16 && g.head_dim == 64 && g.d_model % 32 == 0 && g.d_ffn % 32 == 0 &&
+            g.vocab % 16 == 0;
   c->w_canon_bytes = align_up(c->woff.total * c->esz);
   c->rope_off = c->w_canon_bytes;
   c->weights_bytes = c->rope_off + align_up((size_t)g.max_ctx * (g.head_dim / 2) * sizeof(float2));
-  c->kv_self_elems = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * g.max_ctx * g.head_dim;
-  const size_t cross = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * g.n_cond * g.head_dim;
+  if (c->fast) c->weights_bytes = build_tiled_offsets(c, c->weights_bytes);
+  c->kv_self_elems = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_self * g.head_dim;
+  const size_t cross = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
   c->kv_bytes = align_up((c->kv_self_elems + cross) * c->esz);
   *out = c;
   return XSM_OK;
@@ -267,6 +404,30 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
   XSM_HIP(hipMemcpyAsync(ctx->d_w, h_canonical, n_elems * ctx->esz, hipMemcpyHostToDevice, s));
   launch_rope_table((float2*)(ctx->d_w + ctx->rope_off), ctx->cfg.max_ctx, ctx->cfg.head_dim,
                     ctx->cfg.rope_theta, s);
+  if (ctx->fast) {             // fragment-ordered copies for the MFMA kernels
+    const xsm_config& g = ctx->cfg;
+    const int d = g.d_model, F = g.d_ffn, V = g.vocab;
+    char* wb = ctx->d_w;
+    for (int l = 0; l < g.n_layers; ++l) {
+      const LayerPtrs P = layer_ptrs(ctx, l);
+      const TiledLayer& T = ctx->toff.layer[l];
+      launch_tile_weights(P.Wqkv, wb + T.Wqkv, 3 * d, d, d, g.head_dim, s);
+      launch_tile_weights(P.Wo, wb + T.Wo, d, d, 0, 0, s);
+      if (g.n_cond > 0) {
+        launch_tile_weights(P.Wcq, wb + T.Wcq, d, d, 0, 0, s);
+        launch_tile_weights(P.Wco, wb + T.Wco, d, d, 0, 0, s);
+      }
+      launch_tile_weights(P.W1, wb + T.W1, F, d, 0, 0, s);
+      launch_tile_weights(P.W2, wb + T.W2, d, F, 0, 0, s);
+    }
+    launch_tile_weights(wb + ctx->woff.WU * 2, wb + ctx->toff.WU, V, d, 0, 0, s);
+    for (int k = 0; k < g.n_draft; ++k) {
+      launch_tile_weights(wb + ctx->woff.hW[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
+      launch_copy_u16(wb + ctx->woff.hb[k] * 2, wb + ctx->toff.hb + (size_t)k * d * 2, d, s);
+    }
+    if (ctx->d_ws)
+      launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), g.max_batch * g.n_heads, 0, s);
+  }
   XSM_HIP(hipGetLastError());
   ctx->loaded = true;
   return XSM_OK;
@@ -303,7 +464,7 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
         const LayerPtrs L = layer_ptrs(ctx, l);
         launch_gemm(dt, EPI_STORE, X, d, L.Wckv, QKV, 2 * d, n_seq * C, 2 * d, d, s);
         launch_store_cond(dt, QKV, slot, cross_cache(ctx, l, 0), cross_cache(ctx, l, 1), n_seq, C,
-                          r0, g.n_heads, g.head_dim, g.n_cond, s);
+                          r0, g.n_heads, g.head_dim, ctx->cap_cross, ctx->fast ? 1 : 0, s);
       }
     }
   }
@@ -311,7 +472,7 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
     const int C = P - r0 < kPrefillChunk ? P - r0 : kPrefillChunk;
     launch_fill_i32(eff, n_seq, r0, s);
     launch_load_rows(dt, d_prefix_emb, X, n_seq, C, r0, P, d, s);
-    forward_blocks(ctx, n_seq, C, s);
+    forward_blocks(ctx, n_seq, C, r0, s);
   }
   XSM_HIP(hipGetLastError());
   return XSM_OK;
@@ -341,7 +502,11 @@ static int kv_debug(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, in
       pos0 < 0 || n_pos < 1 || pos0 + n_pos > cap || !h_buf)
     return fail(ctx, XSM_EINVAL, "bad cache range");
   char* base = cross ? cross_cache(ctx, layer, which - 2) : self_cache(ctx, layer, which);
-  char* rows = base + (size_t)slot * g.n_heads * cap * g.head_dim * ctx->esz;
+  const int capp = cross ? ctx->cap_cross : ctx->cap_self;       // padded capacity
+  char* rows = base + (size_t)slot * g.n_heads * capp * g.head_dim * ctx->esz;
+  const bool tr = ctx->fast && (which & 1);                       // values are cached transposed
+  const size_t st_h = (size_t)capp * g.head_dim;
+  const size_t st_p = tr ? 1 : (size_t)g.head_dim, st_i = tr ? (size_t)capp : 1;
   // staged through the activation region of the workspace in pieces that fit
   const size_t stage_elems = (size_t)g.max_batch * kMaxRows * g.d_model * 2;   // X + Xn regions
   float* stage = (float*)(ctx->d_ws + ctx->ws.X);
@@ -356,11 +521,11 @@ static int kv_debug(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, in
         memcpy(&tmp[(size_t)h * np * g.head_dim], h_buf + ((size_t)h * n_pos + p) * g.head_dim,
                (size_t)np * g.head_dim * 4);
       XSM_HIP(hipMemcpy(stage, tmp.data(), n * 4, hipMemcpyHostToDevice));
-      launch_kv_convert(g.dtype, rows, stage, g.n_heads, cap, pos0 + p, np, g.head_dim, 1, 0);
+      launch_kv_convert(g.dtype, rows, stage, g.n_heads, pos0 + p, np, g.head_dim, st_h, st_p, st_i, 1, 0);
       XSM_HIP(hipDeviceSynchronize());
     } else {
       XSM_HIP(hipDeviceSynchronize());
-      launch_kv_convert(g.dtype, rows, stage, g.n_heads, cap, pos0 + p, np, g.head_dim, 0, 0);
+      launch_kv_convert(g.dtype, rows, stage, g.n_heads, pos0 + p, np, g.head_dim, st_h, st_p, st_i, 0, 0);
       XSM_HIP(hipMemcpy(tmp.data(), stage, n * 4, hipMemcpyDeviceToHost));
       for (int h = 0; h < g.n_heads; ++h)
         memcpy(h_buf + ((size_t)h * n_pos + p) * g.head_dim, &tmp[(size_t)h * np * g.head_dim],

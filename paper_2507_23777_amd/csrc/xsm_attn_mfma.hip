@@ -1,0 +1,222 @@
+// Block-causal KV-cache attention for R <= 16 query rows per sequence on bf16 MFMA
+// (gfx950), head_dim 64.  Query row j of sequence b sits at position n_b + j and sees cache
+// positions 0..n_b + j (Sec. 4.2: causal mask inside the draft block x_{s:s+D}).
+//
+// HBM-bound: every cached key and value is read once per step, so the layout is chosen for
+// the loads.  Keys are [position][64] (128 B rows); values are stored transposed,
+// [64][capacity], so that both MFMA "A" operands are read with 16-byte lane loads:
+//   S^T[key][query] = K[key][:] . Q[query][:]      A = 16 keys x 32 dims of K
+//   O^T[dim][query] = V^T[dim][key] . P^T[key][query]   A = 16 dims x 32 keys of V^T
+// A wavefront takes 64 keys at a time.  The 16-key score tiles are formed from keys
+// {g*16 + t*4 + i}, so that the probabilities a lane holds after the first product are
+// exactly the 16 consecutive keys it must supply as the "B" operand of the second one, and no
+// cross-lane movement is needed.  Online softmax in fp32 (base 2); the key range of one
+// (sequence, head) is split over S workgroups whose partial (max, sum, O) are merged in
+// fixed order by the last one to finish.
+#include "xsm_device.h"
+#include "xsm_internal.h"
+
+namespace xsm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPartFloats = (2 + 64) * 16;     // per split: m[16], l[16], O^T[64][16]
+
+__device__ __forceinline__ void st_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+}
+
+__global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
+  __shared__ float sm_ml[4][2][16];
+  __shared__ __align__(16) float sm_o[4][4][64][4];
+  __shared__ int sm_last;
+  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const int R = a.R, S = a.S;
+  const int n = a.eff_len[b];
+  if (n < 0) {                                     // skipped sequence: defined (zero) output
+    if (s == 0)
+      for (int i = tid; i < R * 64; i += 256)
+        a.O[(size_t)(b * R + i / 64) * a.ldo + h * 64 + (i & 63)] = 0;
+    return;
+  }
+  const int Ltot = a.fixed_limit > 0 ? a.fixed_limit : n + R;
+  const int NC = (Ltot + 63) >> 6, CPS = (NC + S - 1) / S;
+  const int c_lo = s * CPS, c_hi = min(NC, c_lo + CPS);
+  const size_t head = (size_t)a.slot[b] * a.H + h;
+  const uint16_t* kb = a.Kc + head * (size_t)a.cap * 64;
+  const uint16_t* vb = a.Vt + head * 64 * (size_t)a.cap;
+  // keys visible to this lane's query: positions < lim
+  const int lim = r < R ? (a.fixed_limit > 0 ? Ltot : n + r + 1) : 0;
+  const int first_masked = a.fixed_limit > 0 ? Ltot : n + 1;     // below this every live query sees the key
+
+  uint4 qf[2] = {uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
+  if (r < R) {
+    const uint16_t* q = a.Q + (size_t)(b * R + r) * a.ldq + h * 64 + g * 8;
+    qf[0] = *reinterpret_cast<const uint4*>(q);
+    qf[1] = *reinterpret_cast<const uint4*>(q + 32);
+  }
+  const bf16x8 q0 = __builtin_bit_cast(bf16x8, qf[0]), q1 = __builtin_bit_cast(bf16x8, qf[1]);
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 o[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int c = c_lo + wave; c < c_hi; c += 4) {
+    const int key0 = c << 6;
+    uint4 kf[4][2], vf[4][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint16_t* kr = kb + (size_t)(key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 64 + g * 8;
+      kf[t][0] = *reinterpret_cast<const uint4*>(kr);
+      kf[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
+      vf[dt][0] = *reinterpret_cast<const uint4*>(vr);
+      vf[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
+    }
+    f32x4 sc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][0]), q0,
+                                                      f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+      sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][1]), q1, sc[t], 0, 0, 0);
+    }
+    // this lane's 16 scores belong to keys key0 + g*16 + t*4 + i
+    const int kbase = key0 + g * 16;
+    const bool edge = key0 + 64 > first_masked || r >= R;
+    float cmax = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = sc[t][i] * a.scale_log2;
+        if (edge && kbase + t * 4 + i >= lim) v = -INFINITY;
+        sc[t][i] = v;
+        cmax = fmaxf(cmax, v);
+      }
+    cmax = fmaxf(cmax, __shfl_xor(cmax, 16, WAVE));
+    cmax = fmaxf(cmax, __shfl_xor(cmax, 32, WAVE));
+    const float m_new = fmaxf(m_run, cmax);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = exp2f(m_run - m_use);
+    float psum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = exp2f(sc[t][i] - m_use);
+        sc[t][i] = p;
+        psum += p;
+      }
+    psum += __shfl_xor(psum, 16, WAVE);
+    psum += __shfl_xor(psum, 32, WAVE);
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) o[dt] *= alpha;
+    if (key0 + 64 > Ltot) {                         // slots past the live range hold garbage
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          uint32_t* w = reinterpret_cast<uint32_t*>(&vf[dt][jj]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            if (kbase + jj * 8 + e >= Ltot) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+          }
+        }
+    }
+    uint4 pf[2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+      pf[jj] = uint4{pack2(sc[2 * jj][0], sc[2 * jj][1]), pack2(sc[2 * jj][2], sc[2 * jj][3]),
+                     pack2(sc[2 * jj + 1][0], sc[2 * jj + 1][1]), pack2(sc[2 * jj + 1][2], sc[2 * jj + 1][3])};
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt][jj]),
+                                                        __builtin_bit_cast(bf16x8, pf[jj]), o[dt], 0, 0, 0);
+  }
+
+  // merge the four wavefronts (fixed order); wavefront w finishes dim tile w
+  if (g == 0) { sm_ml[wave][0][r] = m_run; sm_ml[wave][1][r] = l_run; }
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) *reinterpret_cast<f32x4*>(&sm_o[wave][dt][lane][0]) = o[dt];
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) M = fmaxf(M, sm_ml[w][0][r]);
+  float L = 0.f;
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const float mw = sm_ml[w][0][r];
+    const float f = mw == -INFINITY ? 0.f : exp2f(mw - M);
+    L += sm_ml[w][1][r] * f;
+    acc += *reinterpret_cast<const f32x4*>(&sm_o[w][wave][lane][0]) * f;
+  }
+  const int dt = wave;                                // dims dt*16 + g*4 + i, query r
+  if (S == 1) {
+    if (r < R) {
+      const float inv = 1.0f / L;
+      uint16_t* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
+      *reinterpret_cast<uint2*>(dst) = uint2{pack2(acc[0] * inv, acc[1] * inv), pack2(acc[2] * inv, acc[3] * inv)};
+    }
+    return;
+  }
+  // split keys: publish this workgroup's partial, the last one to arrive merges all S
+  float* part = a.part + ((size_t)(b * a.H + h) * S + s) * kPartFloats;
+  if (wave == 0 && g == 0) { st_coherent(part + r, M); st_coherent(part + 16 + r, L); }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) st_coherent(part + 32 + (dt * 16 + g * 4 + i) * 16 + r, acc[i]);
+  __builtin_amdgcn_s_waitcnt(0);                      // partial is complete in memory
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t* tk = a.tickets + b * a.H + h;
+    const uint32_t old = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sm_last = old == (uint32_t)(S - 1);
+    if (sm_last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!sm_last) return;
+  const float* p0 = a.part + (size_t)(b * a.H + h) * S * kPartFloats;
+  float Mg = -INFINITY;
+  for (int k = 0; k < S; ++k) Mg = fmaxf(Mg, ld_coherent(p0 + (size_t)k * kPartFloats + r));
+  float Lg = 0.f;
+  f32x4 og = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < S; ++k) {
+    const float* pk = p0 + (size_t)k * kPartFloats;
+    const float mk = ld_coherent(pk + r);
+    const float f = mk == -INFINITY ? 0.f : exp2f(mk - Mg);
+    Lg += ld_coherent(pk + 16 + r) * f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) og[i] += ld_coherent(pk + 32 + (dt * 16 + g * 4 + i) * 16 + r) * f;
+  }
+  if (r < R) {
+    const float inv = 1.0f / Lg;
+    uint16_t* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
+    *reinterpret_cast<uint2*>(dst) = uint2{pack2(og[0] * inv, og[1] * inv), pack2(og[2] * inv, og[3] * inv)};
+  }
+}
+
+void launch_fattn(const FastAttn& a, int n_seq, hipStream_t s) {
+  TraceScope trace_("fattn", s);
+  hipLaunchKernelGGL(k_fattn, dim3(a.S, a.H, n_seq), dim3(256), 0, s, a);
+}
+
+size_t fattn_part_bytes(size_t entries) { return entries * kPartFloats * sizeof(float); }
+
+}  // namespace xsm

@@ -1,0 +1,284 @@
+// Weight-streaming GEMM for the small-M regime on bf16 MFMA (gfx950):
+//   Y[m][n] = sum_k A[m][k] * W[n][k],  M = sequences x block rows (a few to ~100).
+//
+// The weight matrix sits on the MFMA's 16-row "A" side (v_mfma_f32_16x16x32_bf16:
+// D[n][m] += W[n][k] A[m][k]), the activation rows on the 16-column side, so no lane
+// streams padding from HBM.  Weights are re-laid at load time into fragment order: tile
+// (nt, kt) = 16 rows x 32 k is 1 KB, lane l holds row l%16, k (l/16)*8..+8, so one wavefront
+// load instruction is one contiguous kilobyte.  One workgroup owns one 16-row tile; its four
+// wavefronts split the contraction index and are summed through LDS in a fixed order.  The
+// first weight fragments are requested before the activation prologue runs, because they
+// do not depend on it.
+//
+// Prologues: RMSNorm of fp32 rows (optionally gathered by a row index), fp32 rows, bf16 rows.
+// Epilogues: store, residual add, erf-GELU to bf16, rotary + q / cache write (fused QKV),
+// decoding-head activation r = g + SiLU(y + b).
+#include "xsm_device.h"
+#include "xsm_internal.h"
+
+namespace xsm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// canonical [N][K] -> fragment-ordered tiles.  rope_hd > 0: the first two thirds of the
+// rows are q and k of a fused QKV matrix; inside each head the rows of a tile are arranged
+// as 8 low dims + their 8 rotary partners (dim + hd/2) so that a tile holds whole pairs.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int qkv_src_row(int nt, int r, int d, int hd) {
+  const int tiles_per_sec = d / 16, tiles_per_head = hd / 16;
+  const int sec = nt / tiles_per_sec, ts = nt % tiles_per_sec;
+  const int h = ts / tiles_per_head, tt = ts % tiles_per_head;
+  int dim;
+  if (sec < 2) dim = r < 8 ? tt * 8 + r : hd / 2 + tt * 8 + (r - 8);
+  else dim = tt * 16 + r;
+  return sec * d + h * hd + dim;
+}
+
+__global__ void k_tile_weights(const uint16_t* __restrict__ W, uint4* __restrict__ out, int N, int K,
+                               int rope_d, int rope_hd) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;       // one 16-byte fragment piece
+  const int KT = K / 32;
+  if (idx >= (long)(N / 16) * KT * 64) return;
+  const int lane = (int)(idx & 63);
+  const int kt = (int)((idx >> 6) % KT), nt = (int)((idx >> 6) / KT);
+  const int r = lane & 15, g = lane >> 4;
+  const int row = rope_hd > 0 ? qkv_src_row(nt, r, rope_d, rope_hd) : nt * 16 + r;
+  out[idx] = *reinterpret_cast<const uint4*>(W + (size_t)row * K + kt * 32 + g * 8);
+}
+void launch_tile_weights(const void* W, void* out, int N, int K, int rope_d, int rope_hd,
+                         hipStream_t s) {
+  TraceScope trace_("tile_weights", s);
+  const long n = (long)(N / 16) * (K / 32) * 64;
+  hipLaunchKernelGGL(k_tile_weights, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                     (const uint16_t*)W, (uint4*)out, N, K, rope_d, rope_hd);
+}
+
+__global__ void k_copy_u16(const uint16_t* src, uint16_t* dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+void launch_copy_u16(const void* src, void* dst, int n, hipStream_t s) {
+  hipLaunchKernelGGL(k_copy_u16, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t*)src,
+                     (uint16_t*)dst, n);
+}
+
+// ---------------------------------------------------------------------------
+// the GEMM
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float gelu_erf_f(float x) {
+  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+}
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+}
+
+template <int PRO, int EPI, int MT>
+__global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int KC = g.KC, stride = KC + 8;                 // LDS row stride in bf16 elements
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+  float* red = reinterpret_cast<float*>(smem + (size_t)16 * MT * stride * 2);
+  float* srms = red + 4 * MT * 256;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nt = blockIdx.x, KT = g.K / 32;
+  const uint4* wbase = g.Wt + (size_t)nt * KT * 64 + lane;
+
+  for (int m0 = 0; m0 < g.M; m0 += 16 * MT) {
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int kc0 = 0; kc0 < g.K; kc0 += KC) {
+      const int kc = min(KC, g.K - kc0), ktc = kc / 32;
+      const int per = (ktc + 3) >> 2;
+      const int kt_lo = kc0 / 32 + wave * per;
+      const int kt_hi = min(kc0 / 32 + ktc, kt_lo + per);
+      uint4 wa[8], wb[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (kt_lo + i < kt_hi) wa[i] = wbase[(size_t)(kt_lo + i) * 64];
+
+      __syncthreads();                                   // earlier readers of As / srms are done
+      if (PRO == PRO_NORM && kc0 == 0) {                 // row scales over the full contraction length
+        for (int r = wave; r < 16 * MT; r += 4) {
+          const int m = m0 + r;
+          float ss = 0.f;
+          if (m < g.M) {
+            const float* x = g.X + (size_t)(g.row_index ? g.row_index[m] : m) * g.ldx;
+            for (int c = lane * 4; c < g.K; c += 256) {
+              const float4 v = *reinterpret_cast<const float4*>(x + c);
+              ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            }
+          }
+          ss = wave_sum(ss);
+          if (lane == 0) srms[r] = 1.0f / sqrtf(ss / (float)g.K + g.eps);
+        }
+        __syncthreads();
+      }
+      // stage the activation chunk as bf16
+      for (int r = wave; r < 16 * MT; r += 4) {
+        const int m = m0 + r;
+        uint16_t* dst = As + (size_t)r * stride;
+        if (m >= g.M) {
+          for (int c = lane * 8; c < kc; c += 512) *reinterpret_cast<uint4*>(dst + c) = uint4{0, 0, 0, 0};
+        } else if (PRO == PRO_BF16) {
+          const uint16_t* a = g.Abf + (size_t)m * g.lda + kc0;
+          for (int c = lane * 8; c < kc; c += 512)
+            *reinterpret_cast<uint4*>(dst + c) = *reinterpret_cast<const uint4*>(a + c);
+        } else {
+          const float* x = g.X + (size_t)(g.row_index ? g.row_index[m] : m) * g.ldx + kc0;
+          const float sc = PRO == PRO_NORM ? srms[r] : 1.0f;
+          for (int c = lane * 4; c < kc; c += 256) {
+            float4 v = *reinterpret_cast<const float4*>(x + c);
+            if (PRO == PRO_NORM) {
+              const uint2 gg = *reinterpret_cast<const uint2*>(g.gain + kc0 + c);
+              v.x *= sc * __uint_as_float(gg.x << 16); v.y *= sc * __uint_as_float(gg.x & 0xFFFF0000u);
+              v.z *= sc * __uint_as_float(gg.y << 16); v.w *= sc * __uint_as_float(gg.y & 0xFFFF0000u);
+            }
+            *reinterpret_cast<uint2*>(dst + c) = uint2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
+          }
+        }
+      }
+      __syncthreads();
+
+      const uint16_t* arow = As + (size_t)(lane & 15) * stride + (lane >> 4) * 8 - kc0;
+      for (int kt = kt_lo; kt < kt_hi; kt += 16) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (kt + 8 + i < kt_hi) wb[i] = wbase[(size_t)(kt + 8 + i) * 64];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (kt + i < kt_hi) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wa[i]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              const bf16x8 b = __builtin_bit_cast(
+                  bf16x8, *reinterpret_cast<const uint4*>(arow + (size_t)mt * 16 * stride + (kt + i) * 32));
+              acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[mt], 0, 0, 0);
+            }
+          }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (kt + 16 + i < kt_hi) wa[i] = wbase[(size_t)(kt + 16 + i) * 64];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (kt + 8 + i < kt_hi) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wb[i]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              const bf16x8 b = __builtin_bit_cast(
+                  bf16x8, *reinterpret_cast<const uint4*>(arow + (size_t)mt * 16 * stride + (kt + 8 + i) * 32));
+              acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[mt], 0, 0, 0);
+            }
+          }
+      }
+    }
+
+    // sum the four wavefronts' partial tiles in a fixed order
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      *reinterpret_cast<f32x4*>(red + ((size_t)(wave * MT + mt) * 64 + lane) * 4) = acc[mt];
+    __syncthreads();
+    const int li = lane, ii = wave;                       // this thread finishes D[nrow][mcol]
+    const int nrow = (li >> 4) * 4 + ii, mcol = li & 15;
+    const int n = nt * 16 + nrow;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) v += red[((size_t)(w * MT + mt) * 64 + li) * 4 + ii];
+      const int m = m0 + mt * 16 + mcol;
+      if (EPI == FEPI_QKV) {
+        const float partner = __shfl_xor(v, 32, WAVE);    // row nrow +- 8 of the same tile
+        if (m < g.M) {
+          const int b = m / g.R, j = m % g.R;
+          const int len = g.eff_len[b];
+          if (len >= 0) {
+            const int d = g.H * g.hd, tps = d / 16, tph = g.hd / 16, half = g.hd / 2;
+            const int sec = nt / tps, ts = nt % tps, h = ts / tph, tt = ts % tph;
+            const int pos = len + j;
+            int dim;
+            float o = v;
+            if (sec < 2) {
+              const int pi = tt * 8 + (nrow & 7);
+              const float2 cs = g.rope[(size_t)pos * half + pi];
+              if (nrow < 8) { dim = pi; o = v * cs.x - partner * cs.y; }
+              else { dim = half + pi; o = partner * cs.y + v * cs.x; }
+            } else {
+              dim = tt * 16 + nrow;
+            }
+            if (sec == 0) {
+              g.Ybf[(size_t)m * g.ldyb + h * g.hd + dim] = f2bf(o);
+            } else if (sec == 1) {
+              g.Kc[(((size_t)g.slot[b] * g.H + h) * g.cap + pos) * g.hd + dim] = f2bf(o);
+            } else if (g.v_transposed) {
+              g.Vc[(((size_t)g.slot[b] * g.H + h) * g.hd + dim) * g.cap + pos] = f2bf(o);
+            } else {
+              g.Vc[(((size_t)g.slot[b] * g.H + h) * g.cap + pos) * g.hd + dim] = f2bf(o);
+            }
+          }
+        }
+      } else if (m < g.M) {
+        if (EPI == FEPI_STORE) g.Y[(size_t)m * g.ldy + n] = v;
+        else if (EPI == FEPI_ADD) g.Y[(size_t)m * g.ldy + n] += v;
+        else if (EPI == FEPI_GELU_BF16) g.Ybf[(size_t)m * g.ldyb + n] = f2bf(gelu_erf_f(v));
+        else if (EPI == FEPI_BF16) g.Ybf[(size_t)m * g.ldyb + n] = f2bf(v);
+        else if (EPI == FEPI_HEAD) {
+          // n = k*d + c: head k, column c; r = g + SiLU(y + b_k[c]) with g the normalised row
+          const int c = n % g.K;
+          const float pre = v + bf2f(g.bias[n]);
+          const float x = g.X[(size_t)(g.row_index ? g.row_index[m] : m) * g.ldx + c];
+          const float gn = x * bf2f(g.gain[c]) * srms[mt * 16 + mcol];
+          g.Ybf[(size_t)m * g.ldyb + n] = f2bf(gn + pre / (1.0f + __expf(-pre)));
+        }
+      }
+    }
+  }
+}
+
+static size_t fgemm_lds(int MT, int KC) {
+  return (size_t)16 * MT * (KC + 8) * 2 + (size_t)4 * MT * 256 * 4 + (size_t)16 * MT * 4;
+}
+
+bool fgemm_supported(int N, int K) { return N % 16 == 0 && K % 32 == 0; }
+
+template <int PRO, int EPI>
+static void fgemm_launch(FastGemm g, hipStream_t s) {
+  const int MT = g.M <= 16 ? 1 : g.M <= 32 ? 2 : g.M <= 64 ? 4 : 8;
+  // largest chunk of the contraction index (multiple of 128) whose staging fits 160 KB of LDS
+  const size_t budget = 160 * 1024;
+  int KC = g.K;
+  while (fgemm_lds(MT, KC) > budget) KC = ((KC / 2) + 127) / 128 * 128;
+  g.KC = KC;
+  const size_t lds = fgemm_lds(MT, KC);
+  const dim3 grid(g.N / 16), blk(256);
+#define XSM_FG(MTV)                                                                             \
+  {                                                                                             \
+    auto kfn = k_fgemm<PRO, EPI, MTV>;                                                          \
+    static size_t configured = 0;                                                               \
+    if (lds > 64 * 1024 && lds > configured) {                                                  \
+      (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)budget); \
+      configured = budget;                                                                      \
+    }                                                                                           \
+    hipLaunchKernelGGL(kfn, grid, blk, lds, s, g);                                              \
+  }
+  if (MT == 1) XSM_FG(1) else if (MT == 2) XSM_FG(2) else if (MT == 4) XSM_FG(4) else XSM_FG(8)
+#undef XSM_FG
+}
+
+void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
+  TraceScope trace_("fgemm", s);
+  if (g.M <= 0) return;
+  if (pro == PRO_NORM && epi == FEPI_QKV) fgemm_launch<PRO_NORM, FEPI_QKV>(g, s);
+  else if (pro == PRO_NORM && epi == FEPI_STORE) fgemm_launch<PRO_NORM, FEPI_STORE>(g, s);
+  else if (pro == PRO_NORM && epi == FEPI_GELU_BF16) fgemm_launch<PRO_NORM, FEPI_GELU_BF16>(g, s);
+  else if (pro == PRO_NORM && epi == FEPI_HEAD) fgemm_launch<PRO_NORM, FEPI_HEAD>(g, s);
+  else if (pro == PRO_NORM && epi == FEPI_BF16) fgemm_launch<PRO_NORM, FEPI_BF16>(g, s);
+  else if (pro == PRO_F32 && epi == FEPI_ADD) fgemm_launch<PRO_F32, FEPI_ADD>(g, s);
+  else if (pro == PRO_BF16 && epi == FEPI_ADD) fgemm_launch<PRO_BF16, FEPI_ADD>(g, s);
+  else if (pro == PRO_BF16 && epi == FEPI_STORE) fgemm_launch<PRO_BF16, FEPI_STORE>(g, s);
+}
+
+}  // namespace xsm

@@ -26,8 +26,18 @@ struct WeightOff {
 // Byte offsets inside the caller's workspace buffer.
 struct WorkOff {
   size_t X, Xn, QKV, Qr, AO, U, Z0, G, Hh, Rk, Zh;
-  size_t eff_len, slot, acc, y0, wflags, toks;   // int32 arrays
+  size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
+  size_t Qbf, AObf, Ubf, Rkbf;                           // bf16 activations of the MFMA path
+  size_t part, tickets;                                  // split-key attention partials
   size_t total;
+};
+
+// Byte offsets of the fragment-ordered (tiled) bf16 matrices inside the weights buffer.
+struct TiledLayer { size_t Wqkv, Wo, Wcq, Wco, W1, W2; };
+struct TiledOff {
+  std::vector<TiledLayer> layer;
+  size_t WU, Wh, hb;       // unembedding, stacked head matrices [K*d][d], stacked head biases [K][d]
+  bool wu_ok;              // vocabulary is a multiple of 16
 };
 
 }  // namespace xsm
@@ -41,6 +51,10 @@ struct xsm_ctx {
   size_t rope_off;         // byte offset of the rotary table in the weights buffer
   size_t weights_bytes, kv_bytes;
   size_t kv_self_elems;    // elements of the self-attention cache (cross cache follows)
+  bool fast = false;       // bf16 MFMA path (head_dim 64, values cached transposed)
+  xsm::TiledOff toff;
+  int cap_self = 0, cap_cross = 0;   // cache capacities in positions, padded to 64
+  size_t part_entries = 0;           // (sequence, head, split) partial slots in the workspace
   char* d_w = nullptr;
   char* d_kv = nullptr;
   char* d_ws = nullptr;
@@ -87,12 +101,52 @@ void launch_rope_kv(int dtype, const float* QKV, const float2* rope, const int32
                     int hd, int max_ctx, hipStream_t s);
 // cond K/V rows of one chunk into the cross cache: KV[M][2d] -> caches at rows row0..row0+C-1
 void launch_store_cond(int dtype, const float* KV, const int32_t* slot, void* Kc, void* Vc,
-                       int n_seq, int C, int row0, int H, int hd, int n_cond, hipStream_t s);
+                       int n_seq, int C, int row0, int H, int hd, int cap, int v_transposed,
+                       hipStream_t s);
 // attention of row m = b*R + j over cache positions < (fixed_limit > 0 ? fixed_limit
 // : eff_len[b] + j + 1)
 void launch_attention(int dtype, const float* Q, const void* Kc, const void* Vc,
                       const int32_t* eff_len, const int32_t* slot, float* O, int n_seq, int R,
                       int H, int hd, int cap, int fixed_limit, hipStream_t s);
+
+// ---- MFMA path (xsm_gemm_mfma.hip, xsm_attn_mfma.hip) ----------------------------
+enum { PRO_NORM = 0, PRO_F32 = 1, PRO_BF16 = 2 };
+enum { FEPI_STORE = 0, FEPI_ADD = 1, FEPI_GELU_BF16 = 2, FEPI_QKV = 3, FEPI_HEAD = 4, FEPI_BF16 = 5 };
+struct FastGemm {
+  const uint4* Wt;             // fragment-ordered weights [N/16][K/32][64 lanes][8]
+  int N, K, M, KC;
+  const float* X; int ldx;     // fp32 input rows (PRO_NORM, PRO_F32; FEPI_HEAD residual)
+  const uint16_t* gain;        // bf16 RMSNorm gain [K]
+  float eps;
+  const int32_t* row_index;    // optional gather: input row of output row m
+  const uint16_t* Abf; int lda;   // bf16 input rows (PRO_BF16)
+  float* Y; int ldy;           // fp32 output (STORE, ADD)
+  uint16_t* Ybf; int ldyb;     // bf16 output (GELU, HEAD, q of QKV)
+  const uint16_t* bias;        // FEPI_HEAD: stacked biases [N]
+  // FEPI_QKV
+  const float2* rope; const int32_t* eff_len; const int32_t* slot;
+  int R, H, hd, cap, v_transposed;
+  uint16_t* Kc; uint16_t* Vc;
+};
+bool fgemm_supported(int N, int K);
+void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s);
+void launch_tile_weights(const void* W, void* out, int N, int K, int rope_d, int rope_hd, hipStream_t s);
+void launch_copy_u16(const void* src, void* dst, int n, hipStream_t s);
+
+struct FastAttn {
+  const uint16_t* Q; int ldq;         // bf16 rotated queries [M][d]
+  const uint16_t* Kc;                 // layer's keys [slot][H][cap][64]
+  const uint16_t* Vt;                 // layer's values, transposed [slot][H][64][cap]
+  const int32_t* eff_len; const int32_t* slot;
+  uint16_t* O; int ldo;               // bf16 output [M][d]
+  float* part; uint32_t* tickets;     // split-key partials and arrival counters
+  int R, H, cap, S, fixed_limit;
+  float scale_log2;                   // log2(e) / sqrt(head_dim)
+};
+void launch_fattn(const FastAttn& a, int n_seq, hipStream_t s);
+size_t fattn_part_bytes(size_t entries);
+// row_index[b] = b*R + acc[b] (the hidden state the decoding heads read)
+void launch_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R, hipStream_t s);
 
 // ---- launchers (xsm_kernels_verify.hip) --------------------------------------
 void launch_verify(const float* Z0, const float* Hf, const int32_t* block, const int32_t* eff_len,
@@ -106,8 +160,10 @@ void launch_emit(const float* Zh, const xsm_verify_params& vp, const int32_t* ef
                  int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
                  hipStream_t s);
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
-// cache rows <-> float staging [H][n_pos][hd]
-void launch_kv_convert(int dtype, void* cache_rows, float* staging, int H, int cap, int pos0,
-                       int n_pos, int hd, int to_cache, hipStream_t s);
+// cache <-> float staging [H][n_pos][hd]; element (h, p, i) of the slot lives at
+// base[h*stride_h + p*stride_p + i*stride_i]
+void launch_kv_convert(int dtype, void* slot_base, float* staging, int H, int pos0, int n_pos,
+                       int hd, size_t stride_h, size_t stride_p, size_t stride_i, int to_cache,
+                       hipStream_t s);
 
 }  // namespace xsm

@@ -251,27 +251,29 @@ void launch_rope_kv(int dtype, const float* QKV, const float2* rope, const int32
 
 template <typename T>
 __global__ void k_store_cond(const float* KV, const int32_t* slot, T* Kc, T* Vc, int n_rows, int C,
-                             int row0, int H, int hd, int n_cond) {
+                             int row0, int H, int hd, int cap, int v_transposed) {
   const int d = H * hd;
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long)n_rows * d) return;
   const int c = (int)(idx % d), m = (int)(idx / d);
   const int b = m / C, j = m % C, h = c / hd, i = c % hd;
-  const size_t base = (((size_t)slot[b] * H + h) * n_cond + row0 + j) * hd + i;
-  stf(Kc + base, KV[(size_t)m * 2 * d + c]);
-  stf(Vc + base, KV[(size_t)m * 2 * d + d + c]);
+  const size_t head = (size_t)slot[b] * H + h;
+  stf(Kc + (head * cap + row0 + j) * hd + i, KV[(size_t)m * 2 * d + c]);
+  const size_t vi = v_transposed ? (head * hd + i) * cap + row0 + j : (head * cap + row0 + j) * hd + i;
+  stf(Vc + vi, KV[(size_t)m * 2 * d + d + c]);
 }
 void launch_store_cond(int dtype, const float* KV, const int32_t* slot, void* Kc, void* Vc,
-                       int n_seq, int C, int row0, int H, int hd, int n_cond, hipStream_t s) {
+                       int n_seq, int C, int row0, int H, int hd, int cap, int v_transposed,
+                       hipStream_t s) {
   TraceScope trace_("store_cond", s);
   const long n = (long)n_seq * C * H * hd;
   const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
   if (dtype == XSM_BF16)
     hipLaunchKernelGGL(k_store_cond<bf16_t>, grid, blk, 0, s, KV, slot, (bf16_t*)Kc, (bf16_t*)Vc,
-                       n_seq * C, C, row0, H, hd, n_cond);
+                       n_seq * C, C, row0, H, hd, cap, v_transposed);
   else
     hipLaunchKernelGGL(k_store_cond<float>, grid, blk, 0, s, KV, slot, (float*)Kc, (float*)Vc,
-                       n_seq * C, C, row0, H, hd, n_cond);
+                       n_seq * C, C, row0, H, hd, cap, v_transposed);
 }
 
 // ---------------------------------------------------------------------------
@@ -409,29 +411,39 @@ void launch_attention(int dtype, const float* Q, const void* Kc, const void* Vc,
 }
 
 // ---------------------------------------------------------------------------
-// cache rows <-> float staging [H][n_pos][hd] (debug import / export)
+// cache <-> float staging [H][n_pos][hd] (debug import / export), any cache layout
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ void k_kv_convert(T* rows, float* staging, int H, int cap, int pos0, int n_pos, int hd,
-                             int to_cache) {
+__global__ void k_kv_convert(T* base, float* staging, int H, int pos0, int n_pos, int hd,
+                             size_t stride_h, size_t stride_p, size_t stride_i, int to_cache) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (long)H * n_pos * hd) return;
   const int i = (int)(idx % hd), p = (int)((idx / hd) % n_pos), h = (int)(idx / ((long)hd * n_pos));
-  T* c = rows + ((size_t)h * cap + pos0 + p) * hd + i;
+  T* c = base + h * stride_h + (size_t)(pos0 + p) * stride_p + i * stride_i;
   if (to_cache) stf(c, staging[idx]);
   else staging[idx] = ldf(c);
 }
-void launch_kv_convert(int dtype, void* cache_rows, float* staging, int H, int cap, int pos0,
-                       int n_pos, int hd, int to_cache, hipStream_t s) {
+void launch_kv_convert(int dtype, void* slot_base, float* staging, int H, int pos0, int n_pos,
+                       int hd, size_t stride_h, size_t stride_p, size_t stride_i, int to_cache,
+                       hipStream_t s) {
   TraceScope trace_("kv_convert", s);
   const long n = (long)H * n_pos * hd;
   const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
   if (dtype == XSM_BF16)
-    hipLaunchKernelGGL(k_kv_convert<bf16_t>, grid, blk, 0, s, (bf16_t*)cache_rows, staging, H, cap,
-                       pos0, n_pos, hd, to_cache);
+    hipLaunchKernelGGL(k_kv_convert<bf16_t>, grid, blk, 0, s, (bf16_t*)slot_base, staging, H, pos0,
+                       n_pos, hd, stride_h, stride_p, stride_i, to_cache);
   else
-    hipLaunchKernelGGL(k_kv_convert<float>, grid, blk, 0, s, (float*)cache_rows, staging, H, cap,
-                       pos0, n_pos, hd, to_cache);
+    hipLaunchKernelGGL(k_kv_convert<float>, grid, blk, 0, s, (float*)slot_base, staging, H, pos0,
+                       n_pos, hd, stride_h, stride_p, stride_i, to_cache);
+}
+
+__global__ void k_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < n_seq) row_index[b] = b * R + (acc[b] < 0 ? 0 : acc[b]);
+}
+void launch_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R, hipStream_t s) {
+  TraceScope trace_("head_rows", s);
+  hipLaunchKernelGGL(k_head_rows, dim3((n_seq + 63) / 64), dim3(64), 0, s, acc, row_index, n_seq, R);
 }
 
 }  // namespace xsm
