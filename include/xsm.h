@@ -49,7 +49,8 @@ typedef enum {
   XSM_EINVAL = -1,      /* bad argument or configuration */
   XSM_ECAPACITY = -2,   /* kv_len_bound + rows per step exceeds max_ctx, or too many sequences */
   XSM_ESTATE = -3,      /* buffers not bound / weights not loaded */
-  XSM_EHIP = -4         /* a HIP runtime call failed */
+  XSM_EHIP = -4,        /* a HIP runtime call failed */
+  XSM_EDEVICE = -5      /* a device-side wait timed out (see xsm_check_device) */
 } xsm_status;
 
 enum { XSM_F32 = 0, XSM_BF16 = 1 };
@@ -151,6 +152,17 @@ XSM_API int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify
  * [n_seq][1], one token is sampled from p^(0) and written to out_tokens / block. */
 XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
                    xsm_stream stream);
+
+/* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total,
+ * greedy verification with argmax draws, and the model shape is supported, run it as one
+ * persistent kernel instead of one kernel per stage; 0 forces the per-stage kernels. */
+enum { XSM_OPT_SINGLE_LAUNCH = 1 };
+XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
+
+/* Synchronises the device and reports whether a bounded device-side wait of the
+ * single-launch step ever gave up (XSM_EDEVICE; results of that step are invalid and later
+ * single-launch steps return immediately until weights are loaded again).  XSM_OK otherwise. */
+XSM_API int xsm_check_device(xsm_ctx* ctx);
 
 /* Test/bench only, synchronous (they synchronise the device): copy cache rows of
  * one layer/slot to or from a host float array [n_heads][n_pos][head_dim].

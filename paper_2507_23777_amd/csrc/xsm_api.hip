@@ -75,6 +75,12 @@ void build_work_offsets(xsm_ctx* c) {
   if (c->part_entries < 1024) c->part_entries = 1024;
   w.part = take(fattn_part_bytes(c->part_entries));
   w.tickets = take((size_t)g.max_batch * g.n_heads * 4);
+  w.ll = w.ctrl = w.head_all = 0;
+  if (c->small_ok) {
+    w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
+    w.ctrl = take(256);
+    w.head_all = take((size_t)80 * V * 4);
+  }
   w.total = p;
 }
 
@@ -283,6 +289,36 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   const char* wb = ctx->d_w;
   const size_t e = ctx->esz;
 
+  if (ctx->small_ok && ctx->use_small && M <= 16 && M + M * K <= 80 && n_seq * g.n_heads <= 256 &&
+      vp->mode == XSM_VERIFY_GREEDY && vp->sample == 0) {
+    // the whole step as one persistent kernel
+    SmallArgs a{};
+    a.layers = (const LayerTab*)(wb + ctx->layer_tab_off); a.L = g.n_layers;
+    a.E = (const uint16_t*)(wb + ctx->woff.E * e); a.gf = (const uint16_t*)(wb + ctx->woff.gf * e);
+    a.hb = (const uint16_t*)(wb + ctx->toff.hb);
+    a.WU = (const uint4*)(wb + ctx->toff.WU); a.Wh = (const uint4*)(wb + ctx->toff.Wh);
+    a.rope = (const float2*)(wb + ctx->rope_off);
+    a.ll = (uint64_t*)(ws + ctx->ws.ll); a.ll_layer_stride = small_ll_layer_stride(d, g.d_ffn);
+    a.ctrl = (uint32_t*)(ws + ctx->ws.ctrl);
+    a.slot = bt->slot; a.kv_len = bt->kv_len; a.block = bt->block; a.out_tokens = bt->out_tokens;
+    a.n_accepted = bt->n_accepted; a.flags = bt->flags;
+    a.logits_dbg = bt->logits_dbg; a.head_logits_dbg = bt->head_logits_dbg;
+    a.head_all_dbg = (float*)(ws + ctx->ws.head_all); a.acc_out = acc;
+    a.n_seq = n_seq; a.R = R; a.V = V; a.max_batch = g.max_batch; a.max_ctx = g.max_ctx;
+    a.bound = bt->kv_len_bound; a.cap = ctx->cap_self;
+    a.eps = g.rms_eps; a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
+    // key-range slices per (sequence, head): one 4-wavefront round of 64-key chunks each
+    const int chunks = (bt->kv_len_bound + 63) / 64;
+    int S = 1;
+    while (S < 16 && S * 4 < chunks && 2 * S * n_seq * g.n_heads <= 256) S *= 2;
+    a.S = S;
+    launch_step_small(a, d, g.d_ffn, s);
+    if (bt->head_logits_dbg && K > 0)
+      launch_gather_head_dbg(a.head_all_dbg, acc, bt->head_logits_dbg, n_seq, R, K, V, s);
+    hipError_t e3 = hipGetLastError();
+    if (e3 != hipSuccess) return fail(ctx, XSM_EHIP, std::string("launch: ") + hipGetErrorString(e3));
+    return XSM_OK;
+  }
   launch_prepare(bt->kv_len, bt->slot, bt->block, n_seq, R, V, g.max_batch, g.max_ctx,
                  bt->kv_len_bound, eff, slot, wfl, s);
   launch_embed(dt, wb + ctx->woff.E * e, bt->block, eff, X, n_seq, R, d, s);
@@ -359,16 +395,21 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
   if (!c) return bad("out of host memory");
   c->cfg = g;
   c->esz = g.dtype == XSM_BF16 ? 2 : 4;
+  c->fast = g.dtype == XSM_BF16 && g.head_dim == 64 && g.d_model % 32 == 0 && g.d_ffn % 32 == 0 &&
+            g.vocab % 16 == 0;
+  c->small_ok = c->fast && g.n_cond == 0 && small_supported(g.d_model, g.d_ffn) && g.vocab <= 65536;
   build_weight_offsets(c);
   build_work_offsets(c);
   c->cap_self = (g.max_ctx + 63) / 64 * 64;
   c->cap_cross = (g.n_cond + 63) / 64 * 64;
-  c->fast = g.dtype == XSM_BF16 && g.head_dim == 64 && g.d_model % 32 == 0 && g.d_ffn % 32 == 0 &&
-            g.vocab % 16 == 0;
   c->w_canon_bytes = align_up(c->woff.total * c->esz);
   c->rope_off = c->w_canon_bytes;
   c->weights_bytes = c->rope_off + align_up((size_t)g.max_ctx * (g.head_dim / 2) * sizeof(float2));
   if (c->fast) c->weights_bytes = build_tiled_offsets(c, c->weights_bytes);
+  if (c->small_ok) {
+    c->layer_tab_off = c->weights_bytes;
+    c->weights_bytes += align_up(sizeof(LayerTab) * g.n_layers);
+  }
   c->kv_self_elems = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_self * g.head_dim;
   const size_t cross = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
   c->kv_bytes = align_up((c->kv_self_elems + cross) * c->esz);
@@ -425,8 +466,24 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
       launch_tile_weights(wb + ctx->woff.hW[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
       launch_copy_u16(wb + ctx->woff.hb[k] * 2, wb + ctx->toff.hb + (size_t)k * d * 2, d, s);
     }
-    if (ctx->d_ws)
-      launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), g.max_batch * g.n_heads, 0, s);
+    launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), g.max_batch * g.n_heads, 0, s);
+    if (ctx->small_ok) {
+      ctx->layer_tab.resize(g.n_layers);
+      for (int l = 0; l < g.n_layers; ++l) {
+        const LayerPtrs P = layer_ptrs(ctx, l);
+        const TiledLayer& T = ctx->toff.layer[l];
+        ctx->layer_tab[l] = LayerTab{(const uint4*)(wb + T.Wqkv), (const uint4*)(wb + T.Wo),
+                                     (const uint4*)(wb + T.W1), (const uint4*)(wb + T.W2),
+                                     (const uint16_t*)P.g1, (const uint16_t*)P.g2,
+                                     (uint16_t*)self_cache(ctx, l, 0), (uint16_t*)self_cache(ctx, l, 1)};
+      }
+      XSM_HIP(hipMemcpyAsync(wb + ctx->layer_tab_off, ctx->layer_tab.data(),
+                             sizeof(LayerTab) * g.n_layers, hipMemcpyHostToDevice, s));
+      // exchange words start with tag 0; the step epoch starts at 1, error word clear
+      launch_fill_u64((uint64_t*)(ctx->d_ws + ctx->ws.ll),
+                      small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft), 0ull, s);
+      launch_fill_u64((uint64_t*)(ctx->d_ws + ctx->ws.ctrl), 1, 1ull, s);
+    }
   }
   XSM_HIP(hipGetLastError());
   ctx->loaded = true;
@@ -489,6 +546,24 @@ int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params
                    xsm_stream stream) {
   if (!ctx) return XSM_EINVAL;
   return step_common(ctx, batch, vp, stream, 1);
+}
+
+int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value) {
+  if (!ctx) return XSM_EINVAL;
+  if (option == XSM_OPT_SINGLE_LAUNCH) { ctx->use_small = value != 0; return XSM_OK; }
+  return fail(ctx, XSM_EINVAL, "unknown option");
+}
+
+int xsm_check_device(xsm_ctx* ctx) {
+  if (!ctx) return XSM_EINVAL;
+  XSM_HIP(hipDeviceSynchronize());
+  if (!ctx->small_ok || !ctx->d_ws || !ctx->loaded) return XSM_OK;
+  uint32_t c[2] = {0, 0};
+  XSM_HIP(hipMemcpy(c, ctx->d_ws + ctx->ws.ctrl, 8, hipMemcpyDeviceToHost));
+  if (c[1] != 0)
+    return fail(ctx, XSM_EDEVICE, "single-launch step: a wait for stage inputs timed out (stage code " +
+                                      std::to_string(c[1]) + ")");
+  return XSM_OK;
 }
 
 static int kv_debug(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, int32_t pos0,

@@ -29,6 +29,7 @@ struct WorkOff {
   size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
   size_t Qbf, AObf, Ubf, Rkbf;                           // bf16 activations of the MFMA path
   size_t part, tickets;                                  // split-key attention partials
+  size_t ll, ctrl, head_all;                             // single-launch step: exchange buffers
   size_t total;
 };
 
@@ -38,6 +39,13 @@ struct TiledOff {
   std::vector<TiledLayer> layer;
   size_t WU, Wh, hb;       // unembedding, stacked head matrices [K*d][d], stacked head biases [K][d]
   bool wu_ok;              // vocabulary is a multiple of 16
+};
+
+// Per-layer pointers of the single-launch step (uploaded to the device at load time).
+struct LayerTab {
+  const uint4 *Wqkv, *Wo, *W1, *W2;     // fragment-ordered weights
+  const uint16_t *g1, *g2;              // RMSNorm gains (bf16)
+  uint16_t *Kc, *Vt;                    // this layer's key cache and transposed value cache
 };
 
 }  // namespace xsm
@@ -52,6 +60,10 @@ struct xsm_ctx {
   size_t weights_bytes, kv_bytes;
   size_t kv_self_elems;    // elements of the self-attention cache (cross cache follows)
   bool fast = false;       // bf16 MFMA path (head_dim 64, values cached transposed)
+  bool small_ok = false;   // single-launch step available for this model shape
+  bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
+  size_t layer_tab_off = 0;              // byte offset of the LayerTab array in the weights buffer
+  std::vector<xsm::LayerTab> layer_tab;  // host copy (source of the upload)
   xsm::TiledOff toff;
   int cap_self = 0, cap_cross = 0;   // cache capacities in positions, padded to 64
   size_t part_entries = 0;           // (sequence, head, split) partial slots in the workspace
@@ -147,6 +159,29 @@ void launch_fattn(const FastAttn& a, int n_seq, hipStream_t s);
 size_t fattn_part_bytes(size_t entries);
 // row_index[b] = b*R + acc[b] (the hidden state the decoding heads read)
 void launch_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R, hipStream_t s);
+
+// ---- single-launch step for <= 16 block rows (xsm_step_small.hip) -------------------
+struct SmallArgs {
+  const LayerTab* layers; int L;
+  const uint16_t* E; const uint16_t* gf; const uint16_t* hb;
+  const uint4* WU; const uint4* Wh;
+  const float2* rope;
+  uint64_t* ll; size_t ll_layer_stride;  // tagged-word exchange buffers
+  uint32_t* ctrl;                        // [0] step epoch, [1] error word
+  const int32_t* slot; int32_t* kv_len; int32_t* block; int32_t* out_tokens; int32_t* n_accepted;
+  uint32_t* flags;
+  float* logits_dbg; float* head_logits_dbg; float* head_all_dbg; int32_t* acc_out;
+  int n_seq, R, S, V, max_batch, max_ctx, bound, cap;
+  float eps, scale_log2;
+};
+bool small_supported(int D, int F);
+size_t small_ll_words(int n_layers, int D, int F, int K);
+size_t small_ll_layer_stride(int D, int F);
+void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s);
+void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s);
+// head_logits_dbg[b][k][:] = head_all[(b*R + acc[b])*K + k][:]
+void launch_gather_head_dbg(const float* head_all, const int32_t* acc, float* out, int n_seq, int R,
+                            int K, int V, hipStream_t s);
 
 // ---- launchers (xsm_kernels_verify.hip) --------------------------------------
 void launch_verify(const float* Z0, const float* Hf, const int32_t* block, const int32_t* eff_len,

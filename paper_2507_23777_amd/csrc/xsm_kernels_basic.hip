@@ -437,6 +437,28 @@ void launch_kv_convert(int dtype, void* slot_base, float* staging, int H, int po
                        n_pos, hd, stride_h, stride_p, stride_i, to_cache);
 }
 
+__global__ void k_fill_u64(uint64_t* p, size_t n, uint64_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s) {
+  hipLaunchKernelGGL(k_fill_u64, dim3(2048), dim3(256), 0, s, p, n, v);
+}
+
+__global__ void k_gather_head_dbg(const float* head_all, const int32_t* acc, float* out, int R, int K,
+                                  int V) {
+  const int b = blockIdx.y, k = blockIdx.z;
+  const int a = acc[b] < 0 ? 0 : acc[b];
+  const float* src = head_all + ((size_t)(b * R + a) * K + k) * V;
+  float* dst = out + ((size_t)b * K + k) * V;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < V; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}
+void launch_gather_head_dbg(const float* head_all, const int32_t* acc, float* out, int n_seq, int R,
+                            int K, int V, hipStream_t s) {
+  hipLaunchKernelGGL(k_gather_head_dbg, dim3(4, n_seq, K), dim3(256), 0, s, head_all, acc, out, R, K, V);
+}
+
 __global__ void k_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b < n_seq) row_index[b] = b * R + (acc[b] < 0 ? 0 : acc[b]);

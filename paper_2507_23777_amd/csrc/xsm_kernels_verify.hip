@@ -23,10 +23,26 @@ struct RowScratch {
 __device__ int row_argmax(const float* z, int V, RowScratch& sm, float* margin) {
   float bv = -INFINITY, sv = -INFINITY;
   int bi = 0x7FFFFFFF;
-  for (int v = threadIdx.x; v < V; v += 256) {
-    const float x = z[v];
-    if (x > bv) { sv = bv; bv = x; bi = v; }          // ascending v: ties keep the lower index
+  auto feed = [&](float x, int v) {
+    if (x > bv || (x == bv && v < bi)) { sv = bv; bv = x; bi = v; }
     else sv = fmaxf(sv, x);
+  };
+  if ((V & 3) == 0) {                 // 16-byte loads, several in flight per thread
+    const float4* z4 = reinterpret_cast<const float4*>(z);
+    const int n4 = V >> 2;
+    for (int q0 = threadIdx.x; q0 < n4; q0 += 1024) {
+      float4 x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        x[u] = q0 + u * 256 < n4 ? z4[q0 + u * 256] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int v = (q0 + u * 256) * 4;
+        if (q0 + u * 256 < n4) { feed(x[u].x, v); feed(x[u].y, v + 1); feed(x[u].z, v + 2); feed(x[u].w, v + 3); }
+      }
+    }
+  } else {
+    for (int v = threadIdx.x; v < V; v += 256) feed(z[v], v);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -58,9 +74,21 @@ __device__ int row_argmax(const float* z, int V, RowScratch& sm, float* margin) 
 __device__ int row_rank(const float* z, int V, int x, RowScratch& sm) {
   const float zx = z[x];
   int c = 0;
-  for (int v = threadIdx.x; v < V; v += 256) {
-    const float y = z[v];
-    c += (y > zx || (y == zx && v < x)) ? 1 : 0;
+  if ((V & 3) == 0) {
+    const float4* z4 = reinterpret_cast<const float4*>(z);
+    const int n4 = V >> 2;
+#pragma unroll 4
+    for (int q = threadIdx.x; q < n4; q += 256) {
+      const float4 y = z4[q];
+      const int v = q * 4;
+      c += (y.x > zx || (y.x == zx && v < x)) + (y.y > zx || (y.y == zx && v + 1 < x)) +
+           (y.z > zx || (y.z == zx && v + 2 < x)) + (y.w > zx || (y.w == zx && v + 3 < x));
+    }
+  } else {
+    for (int v = threadIdx.x; v < V; v += 256) {
+      const float y = z[v];
+      c += (y > zx || (y == zx && v < x)) ? 1 : 0;
+    }
   }
   return block_sum_i(c, sm.redi);
 }
@@ -70,11 +98,11 @@ __device__ int row_rank(const float* z, int V, int x, RowScratch& sm) {
 __device__ bool rank_near_boundary(const float* z, int V, int x, int rank, int ka, RowScratch& sm) {
   const float zx = z[x];
   int above = 0, below = 0;                      // neighbours within the margin
+#pragma unroll 4
   for (int v = threadIdx.x; v < V; v += 256) {
-    if (v == x) continue;
     const float dlt = z[v] - zx;
-    if (dlt >= 0.f && dlt <= kTieMargin) ++above;
-    if (dlt < 0.f && -dlt <= kTieMargin) ++below;
+    if (v != x && dlt >= 0.f && dlt <= kTieMargin) ++above;
+    if (v != x && dlt < 0.f && -dlt <= kTieMargin) ++below;
   }
   above = block_sum_i(above, sm.redi);
   below = block_sum_i(below, sm.redi);

@@ -9,12 +9,14 @@ import os
 import numpy as np
 
 XSM_F32, XSM_BF16 = 0, 1
+XSM_OPT_SINGLE_LAUNCH = 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libxsm.so")
 API = ["xsm_create", "xsm_destroy", "xsm_last_error", "xsm_weights_bytes", "xsm_kv_bytes",
        "xsm_workspace_bytes", "xsm_canonical_weight_elems", "xsm_bind", "xsm_load_weights",
        "xsm_prefill", "xsm_spec_step", "xsm_plain_step", "xsm_debug_kv_export",
-       "xsm_debug_kv_import", "xsm_debug_trace_enable", "xsm_debug_trace_report"]
+       "xsm_debug_kv_import", "xsm_debug_trace_enable", "xsm_debug_trace_report", "xsm_set_option",
+       "xsm_check_device"]
 
 
 class XsmError(RuntimeError):
@@ -67,6 +69,8 @@ def lib() -> C.CDLL:
         getattr(L, f).restype = C.c_int
     for f in ("xsm_debug_kv_export", "xsm_debug_kv_import"):
         getattr(L, f).argtypes, getattr(L, f).restype = [vp, i32, i32, i32, i32, i32, vp], C.c_int
+    L.xsm_set_option.argtypes, L.xsm_set_option.restype = [vp, i32, i32], C.c_int
+    L.xsm_check_device.argtypes, L.xsm_check_device.restype = [vp], C.c_int
     L.xsm_debug_trace_enable.argtypes, L.xsm_debug_trace_enable.restype = [C.c_int], None
     L.xsm_debug_trace_report.argtypes, L.xsm_debug_trace_report.restype = [C.c_char_p, sz], C.c_int
     _lib = L
@@ -198,6 +202,12 @@ class Engine:
     def xsm_plain_step(self, buf: StepBuffers, vp: xsm_verify_params, kv_len_bound: int):
         bt = buf.struct(kv_len_bound)
         self._check(self.L.xsm_plain_step(self.h, C.byref(bt), C.byref(vp), self.stream()), "xsm_plain_step")
+
+    def xsm_set_option(self, option: int, value: int):
+        self._check(self.L.xsm_set_option(self.h, option, value), "xsm_set_option")
+
+    def xsm_check_device(self):
+        self._check(self.L.xsm_check_device(self.h), "xsm_check_device")
 
     def xsm_debug_kv_export(self, layer: int, which: int, slot: int, pos0: int, n_pos: int) -> np.ndarray:
         out = np.empty((self.c_cfg.n_heads, n_pos, self.c_cfg.head_dim), np.float32)

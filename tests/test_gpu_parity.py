@@ -180,6 +180,87 @@ def test_config1_shape_bf16(X):
     _report(tal, "c1 lockstep")
 
 
+def _c1_small(**kw):
+    """The latency model's shape (d=1024, FFN 4096, 16 heads, vocab 4096) with few layers: the
+    shape the single-launch step kernel is built for."""
+    cfg = si.get_config("c1", n_layers=3, max_ctx=1536, prefix=70)
+    cfg.update(kw)
+    return cfg
+
+
+@pytest.mark.parametrize("single_launch", [1, 0])
+def test_single_launch_step_matches_oracle_and_per_stage_kernels(X, single_launch):
+    cfg = _c1_small()
+    K = cfg["n_draft"]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, prefix_lens=[70, 33, 5], perturb=True)
+    eng.xsm_set_option(X.xsm.XSM_OPT_SINGLE_LAUNCH, single_launch)
+
+    def forced(step, b, st, blk):
+        if step < 2:
+            return blk
+        full = X.H.true_continuation(orc, st, blk[0], K, GREEDY)
+        j = (step + b) % (K + 1)
+        if j < K:
+            full[j + 1] = (full[j + 1] + 1) % cfg["vocab"]
+        return full
+
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 2 + K + 1, si.first_block(cfg, 3), forced=forced)
+    _report(tal, f"c1-shape B3 single_launch={single_launch}")
+    assert set(tal.accept_hist) == set(range(1, K + 2))
+    eng.xsm_check_device()
+    # plain next-token steps through the same kernel
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 3), plain=True)
+    _report(tal, f"c1-shape plain single_launch={single_launch}")
+    eng.xsm_check_device()
+
+
+def test_single_launch_long_context_split_keys(X):
+    cfg = _c1_small(n_layers=2, max_ctx=4608, prefix=0)
+    n_pos = 4352
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1, max_ctx=cfg["max_ctx"], kv_dtype=np.float32)
+    fill = si.make_kv_fill(cfg, 1, n_pos)
+    fill[:, 0] = si.bf16_round(fill[:, 0] * 6.0)
+    for l in range(cfg["n_layers"]):
+        states[0].k[l][:n_pos] = np.transpose(fill[l, 0, 0], (1, 0, 2))
+        states[0].v[l][:n_pos] = np.transpose(fill[l, 1, 0], (1, 0, 2))
+        eng.xsm_debug_kv_import(l, 0, 0, 0, fill[l, 0, 0])
+        eng.xsm_debug_kv_import(l, 1, 0, 0, fill[l, 1, 0])
+    states[0].n = n_pos - 30          # ragged tail inside a 64-key chunk, 16 key slices
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 1))
+    _report(tal, "single-launch ctx 4.3k")
+    eng.xsm_check_device()
+
+
+def test_single_launch_free_running_equals_per_stage(X):
+    """Same engine, same start: the persistent kernel and the per-stage kernels must emit the
+    same tokens (both are fixed-order reductions over identical bf16 operands, up to ties)."""
+    cfg = _c1_small()
+    torch = X.torch
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1, perturb=False)
+    vpg = X.H.to_vp_gpu(X.xsm, GREEDY)
+    outs = []
+    for mode in (1, 0):
+        eng.xsm_set_option(X.xsm.XSM_OPT_SINGLE_LAUNCH, mode)
+        buf = eng.buffers(1, spec=True)
+        buf.kv_len.fill_(cfg["prefix"]); buf.block.copy_(torch.tensor(si.first_block(cfg, 1)))
+        toks, tie = [], False
+        for i in range(40):
+            eng.xsm_spec_step(buf, vpg, cfg["prefix"] + 5 * i)
+            torch.cuda.synchronize()
+            n = int(buf.n_accepted[0]); assert 1 <= n <= cfg["n_draft"] + 1
+            toks += buf.out_tokens[0, :n].tolist()
+            if int(buf.flags[0]) & 1:
+                tie = True
+                break
+        outs.append((toks, tie))
+    eng.xsm_check_device()
+    n = min(len(outs[0][0]), len(outs[1][0]))
+    # compare up to the first step either side flagged as a near-tie
+    if not (outs[0][1] or outs[1][1]):
+        assert outs[0][0][:n] == outs[1][0][:n]
+    print(f"[single vs per-stage] {n} tokens compared, ties {outs[0][1]} {outs[1][1]}", flush=True)
+
+
 def test_argument_and_device_side_errors(X):
     cfg = _mid_cfg(seed=28, n_layers=1)
     torch = X.torch
