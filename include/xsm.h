@@ -156,8 +156,13 @@ XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verif
 /* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total,
  * greedy verification with argmax draws, and the model shape is supported, run it as one
  * persistent kernel instead of one kernel per stage; 0 forces the per-stage kernels. */
-enum { XSM_OPT_SINGLE_LAUNCH = 1 };
+enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2 };
 XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
+
+/* Tuning aid.  With XSM_OPT_TIMELINE = 1 every workgroup of the single-launch step stamps the
+ * device's 100 MHz clock at its stage boundaries; this copies the stamps of the last step to
+ * h_out as [256 workgroups][n_layers*8 + 8] words (synchronises the device). */
+XSM_API int xsm_debug_timeline(xsm_ctx* ctx, uint64_t* h_out, size_t n_words);
 
 /* Synchronises the device and reports whether a bounded device-side wait of the
  * single-launch step ever gave up (XSM_EDEVICE; results of that step are invalid and later

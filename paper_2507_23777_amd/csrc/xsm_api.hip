@@ -75,11 +75,12 @@ void build_work_offsets(xsm_ctx* c) {
   if (c->part_entries < 1024) c->part_entries = 1024;
   w.part = take(fattn_part_bytes(c->part_entries));
   w.tickets = take((size_t)g.max_batch * g.n_heads * 4);
-  w.ll = w.ctrl = w.head_all = 0;
+  w.ll = w.ctrl = w.head_all = w.tlog = 0;
   if (c->small_ok) {
     w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
     w.ctrl = take(256);
     w.head_all = take((size_t)80 * V * 4);
+    w.tlog = take((size_t)256 * (g.n_layers * 8 + 8) * 8);
   }
   w.total = p;
 }
@@ -304,13 +305,15 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     a.n_accepted = bt->n_accepted; a.flags = bt->flags;
     a.logits_dbg = bt->logits_dbg; a.head_logits_dbg = bt->head_logits_dbg;
     a.head_all_dbg = (float*)(ws + ctx->ws.head_all); a.acc_out = acc;
+    a.tlog = ctx->timeline ? (uint64_t*)(ws + ctx->ws.tlog) : nullptr;
     a.n_seq = n_seq; a.R = R; a.V = V; a.max_batch = g.max_batch; a.max_ctx = g.max_ctx;
     a.bound = bt->kv_len_bound; a.cap = ctx->cap_self;
     a.eps = g.rms_eps; a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
-    // key-range slices per (sequence, head): one 4-wavefront round of 64-key chunks each
+    // key-range slices per (sequence, head): up to two 64-key chunks per wavefront before the
+    // range is split (a split costs one more exchange stage for the merge)
     const int chunks = (bt->kv_len_bound + 63) / 64;
     int S = 1;
-    while (S < 16 && S * 4 < chunks && 2 * S * n_seq * g.n_heads <= 256) S *= 2;
+    while (S < 16 && S * 8 < chunks && 2 * S * n_seq * g.n_heads <= 256) S *= 2;
     a.S = S;
     launch_step_small(a, d, g.d_ffn, s);
     if (bt->head_logits_dbg && K > 0)
@@ -397,7 +400,8 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
   c->esz = g.dtype == XSM_BF16 ? 2 : 4;
   c->fast = g.dtype == XSM_BF16 && g.head_dim == 64 && g.d_model % 32 == 0 && g.d_ffn % 32 == 0 &&
             g.vocab % 16 == 0;
-  c->small_ok = c->fast && g.n_cond == 0 && small_supported(g.d_model, g.d_ffn) && g.vocab <= 65536;
+  c->small_ok = c->fast && g.n_cond == 0 && small_supported(g.d_model, g.d_ffn) && g.vocab <= 65536 &&
+                g.n_layers <= 48;
   build_weight_offsets(c);
   build_work_offsets(c);
   c->cap_self = (g.max_ctx + 63) / 64 * 64;
@@ -551,7 +555,18 @@ int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params
 int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value) {
   if (!ctx) return XSM_EINVAL;
   if (option == XSM_OPT_SINGLE_LAUNCH) { ctx->use_small = value != 0; return XSM_OK; }
+  if (option == XSM_OPT_TIMELINE) { ctx->timeline = value != 0; return XSM_OK; }
   return fail(ctx, XSM_EINVAL, "unknown option");
+}
+
+int xsm_debug_timeline(xsm_ctx* ctx, uint64_t* h_out, size_t n_words) {
+  if (!ctx || !h_out) return XSM_EINVAL;
+  if (!ctx->small_ok || !ctx->d_ws) return fail(ctx, XSM_ESTATE, "no single-launch step for this model");
+  const size_t have = (size_t)256 * (ctx->cfg.n_layers * 8 + 8);
+  if (n_words < have) return fail(ctx, XSM_EINVAL, "timeline buffer too small");
+  XSM_HIP(hipDeviceSynchronize());
+  XSM_HIP(hipMemcpy(h_out, ctx->d_ws + ctx->ws.tlog, have * 8, hipMemcpyDeviceToHost));
+  return XSM_OK;
 }
 
 int xsm_check_device(xsm_ctx* ctx) {

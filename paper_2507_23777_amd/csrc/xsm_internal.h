@@ -29,7 +29,7 @@ struct WorkOff {
   size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
   size_t Qbf, AObf, Ubf, Rkbf;                           // bf16 activations of the MFMA path
   size_t part, tickets;                                  // split-key attention partials
-  size_t ll, ctrl, head_all;                             // single-launch step: exchange buffers
+  size_t ll, ctrl, head_all, tlog;                       // single-launch step: exchange buffers
   size_t total;
 };
 
@@ -62,6 +62,7 @@ struct xsm_ctx {
   bool fast = false;       // bf16 MFMA path (head_dim 64, values cached transposed)
   bool small_ok = false;   // single-launch step available for this model shape
   bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
+  bool timeline = false;   // xsm_set_option(XSM_OPT_TIMELINE)
   size_t layer_tab_off = 0;              // byte offset of the LayerTab array in the weights buffer
   std::vector<xsm::LayerTab> layer_tab;  // host copy (source of the upload)
   xsm::TiledOff toff;
@@ -171,6 +172,7 @@ struct SmallArgs {
   const int32_t* slot; int32_t* kv_len; int32_t* block; int32_t* out_tokens; int32_t* n_accepted;
   uint32_t* flags;
   float* logits_dbg; float* head_logits_dbg; float* head_all_dbg; int32_t* acc_out;
+  uint64_t* tlog;                        // optional stage timeline [256][L*8 + 8] clock stamps
   int n_seq, R, S, V, max_batch, max_ctx, bound, cap;
   float eps, scale_log2;
 };

@@ -1,6 +1,6 @@
 // One speculative (or plain) decoding step as ONE persistent kernel, for the
 // latency regime: at most 16 block rows in total (batch x (K+1) <= 16), bf16,
-// d_model 1024-class models with head_dim 64, greedy verification.
+// d_model 1024 / FFN 4096 / head_dim 64 models, greedy verification.
 //
 // At batch 1 a step streams every weight once (hundreds of MB) through ~150 dependent
 // stages of a few MB each, so what bounds it is not bandwidth inside a stage but the
@@ -16,6 +16,10 @@
 // step; the epoch makes last step's contents invalid.  Every wait is bounded: a
 // workgroup that does not see its inputs within the spin budget raises the error word
 // and leaves, and so does every workgroup waiting on it.
+//
+// Coherent loads bypass the caches, so they are issued fully coalesced (a wavefront reads
+// 1 KB of consecutive words) and the activation block is re-laid through LDS into MFMA
+// operand order; a lane-scattered read of the same words costs an order of magnitude more.
 //
 // Weights never depend on activations, so each workgroup requests the fragments of the
 // tile it will need one layer ahead and holds them in registers; HBM stays busy while
@@ -43,6 +47,7 @@ namespace {
 
 constexpr int kSpinBudget = 150000;         // polls before a wait gives up (a fraction of a second)
 constexpr float kTieMarginS = 1e-2f;
+constexpr int kQS = 72;                     // LDS row stride (bf16) of the attention q / new-k / new-v tiles
 
 __device__ __forceinline__ uint64_t ll_ld(const uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -53,38 +58,94 @@ __device__ __forceinline__ void ll_st(uint64_t* p, uint32_t payload, uint32_t ta
 __device__ __forceinline__ uint32_t pk2(float a, float b) {
   return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
 }
+__device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// Wait for NG groups of GW consecutive tagged words (groups gstride words apart); all loads
-// of a round are issued before any is checked.  Payloads go to out.  On timeout, or when an
-// earlier wait of this lane already failed, ok is false and out is zero.
-template <int NG, int GW>
-__device__ __forceinline__ void ll_wait_groups(const uint64_t* p, size_t gstride, uint32_t tag,
-                                               uint32_t (&out)[NG * GW], bool& ok) {
-  if (ok) {
-    for (int spin = 0; spin < kSpinBudget; ++spin) {
-      uint64_t w[NG * GW];
+// Wait for up to N tagged words at p + off[i] (i < n); payloads to out.  The lane first
+// spins on its last word only (producers of a stage finish together; re-reading every word
+// while nothing has arrived would flood the coherent path), then reads all of them in one
+// round and repeats that round until every tag matches.  On timeout, or when an earlier
+// wait of this lane already failed, ok is false and out is zero.
+template <int N>
+__device__ __forceinline__ void ll_wait_list(const uint64_t* p, const int (&off)[N], int n, uint32_t tag,
+                                             uint32_t (&out)[N], bool& ok) {
+  if (ok && n > 0) {
+    int spin = 0;
+    // one lane per wavefront watches one word; the others join when it has arrived
+    if (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) == 0) {
+      const uint64_t* last = p + off[n - 1];
+      while ((uint32_t)(ll_ld(last) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
+    }
+    for (; spin < kSpinBudget; ++spin) {
+      uint64_t w[N];
 #pragma unroll
-      for (int gi = 0; gi < NG; ++gi)
-#pragma unroll
-        for (int e = 0; e < GW; ++e) w[gi * GW + e] = ll_ld(p + gi * gstride + e);
+      for (int i = 0; i < N; ++i)
+        if (i < n) w[i] = ll_ld(p + off[i]);
       bool good = true;
 #pragma unroll
-      for (int i = 0; i < NG * GW; ++i) good &= (uint32_t)(w[i] >> 32) == tag;
+      for (int i = 0; i < N; ++i)
+        if (i < n) good &= (uint32_t)(w[i] >> 32) == tag;
       if (good) {
 #pragma unroll
-        for (int i = 0; i < NG * GW; ++i) out[i] = (uint32_t)w[i];
+        for (int i = 0; i < N; ++i) out[i] = i < n ? (uint32_t)w[i] : 0u;
         return;
       }
-      __builtin_amdgcn_s_sleep(1);
+      __builtin_amdgcn_s_sleep(8);
     }
     ok = false;
   }
 #pragma unroll
-  for (int i = 0; i < NG * GW; ++i) out[i] = 0u;
+  for (int i = 0; i < N; ++i) out[i] = 0u;
 }
-template <int N>
-__device__ __forceinline__ void ll_wait(const uint64_t* p, uint32_t tag, uint32_t (&out)[N], bool& ok) {
-  ll_wait_groups<1, N>(p, 0, tag, out, ok);
+__device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bool& ok) {
+  const int off[1] = {0};
+  uint32_t out[1];
+  ll_wait_list<1>(p, off, 1, tag, out, ok);
+  return out[0];
+}
+
+// Cooperative, coalesced wait for rows [m0, m0 + ROWS) (clipped to nrows) of a block of tagged
+// words with W words per row: thread t takes the word pairs 2(t + 256 j), +1, j < W/512, of
+// every row, so a wavefront instruction covers 1 KB of consecutive words.
+template <int W, int ROWS>
+__device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows, int tid, uint32_t tag,
+                                          uint32_t (&pay)[ROWS * (W / 512) * 2], bool& ok) {
+  constexpr int PP = W / 512, N = ROWS * PP * 2;
+  const int rows = min(ROWS, nrows - m0);
+  const uint64_t* base = buf + (size_t)m0 * W + 2 * tid;
+  if (ok && rows > 0) {
+    int spin = 0;
+    if ((tid & 63) == 0) {                 // one lane per wavefront watches one word
+      const uint64_t* last = base + (size_t)(rows - 1) * W + (PP - 1) * 512 + 1;
+      while ((uint32_t)(ll_ld(last) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
+    }
+    for (; spin < kSpinBudget; ++spin) {
+      uint64_t w[N];
+#pragma unroll
+      for (int m = 0; m < ROWS; ++m)
+#pragma unroll
+        for (int j = 0; j < PP; ++j)
+          if (m < rows) {
+            w[(m * PP + j) * 2] = ll_ld(base + (size_t)m * W + j * 512);
+            w[(m * PP + j) * 2 + 1] = ll_ld(base + (size_t)m * W + j * 512 + 1);
+          }
+      bool good = true;
+#pragma unroll
+      for (int m = 0; m < ROWS; ++m)
+#pragma unroll
+        for (int j = 0; j < PP * 2; ++j)
+          if (m < rows) good &= (uint32_t)(w[m * PP * 2 + j] >> 32) == tag;
+      if (good) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) pay[i] = (i / (PP * 2)) < rows ? (uint32_t)w[i] : 0u;
+        return;
+      }
+      __builtin_amdgcn_s_sleep(8);
+    }
+    ok = false;
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) pay[i] = 0u;
 }
 
 template <int N>
@@ -98,6 +159,7 @@ __device__ __forceinline__ void load_frags(uint4 (&w)[N], const uint4* Wt, int n
 struct Shared {
   float red[4][64][4];          // cross-wavefront tile reduction
   float rowsum[4][16];          // RMSNorm partial sums
+  float inv[16];
   float att_ml[4][2][16];
   float att_o[4][4][64][4];
   int len[16], slot[16];
@@ -106,9 +168,8 @@ struct Shared {
   int fail;
   float st_max[80], st_sec[80];  // FINAL: per-row reductions
   int st_idx[80];
+  LayerTab tab[48];
 };
-
-}  // namespace
 
 // Sum the four wavefronts' partial 16x16 tiles; thread (wave i, lane) gets element
 // D[nrow = (lane>>4)*4 + i][m = lane & 15].
@@ -119,29 +180,80 @@ __device__ __forceinline__ float tile_reduce(Shared& sm, f32x4 acc, int wave, in
   return (sm.red[0][lane][wave] + sm.red[1][lane][wave]) + (sm.red[2][lane][wave] + sm.red[3][lane][wave]);
 }
 
-// B-operand fragments (activation rows) of one wavefront's NKT k-tiles from fp32 tagged
-// words: lane (m = lane&15, g = lane>>4) takes columns (kt0 + i)*32 + g*8 .. +8 of row m.
-// vals keeps the fp32 values (for the RMSNorm), ss their sum of squares.
-template <int NKT>
-__device__ __forceinline__ void poll_rows_f32(const uint64_t* buf, int ld, int m, bool live, int kt0,
-                                              int g, uint32_t tag, float (&vals)[NKT][8], float& ss,
-                                              bool& ok) {
-  ss = 0.f;
-  uint32_t pw[NKT * 8];
-  if (live) {
-    ll_wait_groups<NKT, 8>(buf + (size_t)m * ld + kt0 * 32 + g * 8, 32, tag, pw, ok);
-  } else {
+// Stage rows [0, M) of an fp32-payload block (D words per row) into LDS as bf16 rows of
+// stride D + 8.  NORM: RMSNorm with the gain pairs gpair[j] (columns 2(tid + 256 j), +1); the
+// fp32 result is also kept in f32dst when given.
+template <int D, bool NORM>
+__device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, float* f32dst, const uint64_t* buf,
+                                               int M, const uint32_t (&gpair)[D / 512], float eps, int tid,
+                                               uint32_t tag, bool& ok) {
+  constexpr int PP = D / 512, ST = D + 8;
+  const int wave = tid >> 6, lane = tid & 63;
+  for (int m0 = 0; m0 < M; m0 += 8) {
+    uint32_t pay[8 * PP * 2];
+    coop_wait<D, 8>(buf, m0, M, tid, tag, pay, ok);
+    if (NORM) {
+      __syncthreads();                                   // earlier readers of rowsum / inv are done
 #pragma unroll
-    for (int i = 0; i < NKT * 8; ++i) pw[i] = 0u;
-  }
+      for (int m = 0; m < 8; ++m) {
+        float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < NKT; ++i)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      vals[i][e] = __uint_as_float(pw[i * 8 + e]);
-      ss += vals[i][e] * vals[i][e];
+        for (int j = 0; j < PP * 2; ++j) {
+          const float x = __uint_as_float(pay[m * PP * 2 + j]);
+          ss += x * x;
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) sm.rowsum[wave][m] = ss;
+      }
+      __syncthreads();
+      if (tid < 8)
+        sm.inv[tid] = 1.0f / sqrtf(((sm.rowsum[0][tid] + sm.rowsum[1][tid]) + (sm.rowsum[2][tid] + sm.rowsum[3][tid])) / (float)D + eps);
+      __syncthreads();
     }
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      if (m0 + m < M) {
+        const float sc = NORM ? sm.inv[m] : 1.0f;
+#pragma unroll
+        for (int j = 0; j < PP; ++j) {
+          float x0 = __uint_as_float(pay[(m * PP + j) * 2]), x1 = __uint_as_float(pay[(m * PP + j) * 2 + 1]);
+          if (NORM) { x0 *= sc * lo_bf(gpair[j]); x1 *= sc * hi_bf(gpair[j]); }
+          const int c = 2 * (tid + 256 * j);
+          *reinterpret_cast<uint32_t*>(As + (size_t)(m0 + m) * ST + c) = pk2(x0, x1);
+          if (f32dst) *reinterpret_cast<float2*>(f32dst + (size_t)(m0 + m) * D + c) = float2{x0, x1};
+        }
+      }
+    }
+  }
+  __syncthreads();
 }
+
+// Stage nrows rows of a bf16x2-payload block (W words = 2W elements per row) into LDS rows
+// starting at dst_row, stride ST elements.
+template <int W>
+__device__ __forceinline__ void stage_rows_bf16(uint16_t* As, int ST, int dst_row, const uint64_t* buf,
+                                                int nrows, int tid, uint32_t tag, bool& ok) {
+  constexpr int PP = W / 512, RB = PP >= 4 ? 4 : 8;     // rows per round: at most 32 words in flight per thread
+  for (int m0 = 0; m0 < nrows; m0 += RB) {
+    uint32_t pay[RB * PP * 2];
+    coop_wait<W, RB>(buf, m0, nrows, tid, tag, pay, ok);
+#pragma unroll
+    for (int m = 0; m < RB; ++m)
+      if (m0 + m < nrows) {
+#pragma unroll
+        for (int j = 0; j < PP; ++j)
+          *reinterpret_cast<uint2*>(As + (size_t)(dst_row + m0 + m) * ST + 4 * (tid + 256 * j)) =
+              uint2{pay[(m * PP + j) * 2], pay[(m * PP + j) * 2 + 1]};
+      }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ uint4 lds_frag(const uint16_t* As, int ST, int row, int kt, int g) {
+  return *reinterpret_cast<const uint4*>(As + (size_t)row * ST + kt * 32 + g * 8);
+}
+
+}  // namespace
 
 template <int D, int F>
 __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
@@ -150,18 +262,24 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   constexpr int KD = KTD / 4, KF = KTF / 4;          // per wavefront
   constexpr int NQ = 3 * D / 16, NO = D / 16, NU = F / 16;
   constexpr int O_BASE = NQ, DN_BASE = 128;
+  constexpr int STD = D + 8, STF = F + 8;            // LDS row strides (bf16 elements)
   static_assert(NQ + NO <= 256 && DN_BASE + NO <= 256 && NU <= 256, "tile roles must fit 256 workgroups");
+  static_assert(D % 512 == 0 && F % 1024 == 0, "cooperative staging needs whole pair rounds");
   __shared__ Shared sm;
+  extern __shared__ __align__(16) unsigned char dyn[];
+  uint16_t* const As = reinterpret_cast<uint16_t*>(dyn);     // activation tile(s), several layouts
 
   const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
   const int R = a.R, K = R - 1, M = a.n_seq * R, S = a.S, V = a.V;
 
-  // ---- set-up: epoch and per-sequence validation (every workgroup, redundantly) ----
+  // ---- set-up: epoch, layer table, per-sequence validation (every workgroup, redundantly) ----
   if (tid == 0) {
     sm.tag = __hip_atomic_load(a.ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     sm.fail = (int)__hip_atomic_load(a.ctrl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  for (int i = tid; i < a.L * (int)(sizeof(LayerTab) / 8); i += 256)
+    reinterpret_cast<uint64_t*>(sm.tab)[i] = reinterpret_cast<const uint64_t*>(a.layers)[i];
   if (tid < 16) {
     int len = -1, sl = 0;
     uint32_t f = 0;
@@ -197,10 +315,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   const bool has_q = w < NQ, has_o = w >= O_BASE && w < O_BASE + NO, has_u = w < NU,
              has_d = w >= DN_BASE && w < DN_BASE + NO;
   uint4 wq[KD], wo[KD], wu[KD], wd[KF];
-  if (has_q) load_frags<KD>(wq, a.layers[0].Wqkv, w, KTD, wave * KD, lane);
-  if (has_o) load_frags<KD>(wo, a.layers[0].Wo, w - O_BASE, KTD, wave * KD, lane);
-  if (has_u) load_frags<KD>(wu, a.layers[0].W1, w, KTD, wave * KD, lane);
-  if (has_d) load_frags<KF>(wd, a.layers[0].W2, w - DN_BASE, KTF, wave * KF, lane);
+  if (has_q) load_frags<KD>(wq, sm.tab[0].Wqkv, w, KTD, wave * KD, lane);
+  if (has_o) load_frags<KD>(wo, sm.tab[0].Wo, w - O_BASE, KTD, wave * KD, lane);
+  if (has_u) load_frags<KD>(wu, sm.tab[0].W1, w, KTD, wave * KD, lane);
 
   // ---- EMBED: layer-0 residual rows as tagged words ----
   for (int idx = w * 256 + tid; idx < M * D; idx += 256 * 256) {
@@ -209,55 +326,47 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     ll_st(llb + OFF_X + (size_t)m * D + c, __float_as_uint(x), tag);
   }
 
+  // optional timeline: thread 0 of every workgroup stamps the 100 MHz clock at stage boundaries
+  uint64_t* const tl = a.tlog ? a.tlog + (size_t)w * (a.L * 8 + 8) : nullptr;
+#define XSM_STAMP(idx) do { if (tl && tid == 0) tl[idx] = wall_clock64(); } while (0)
   bool ok = true;
   for (int l = 0; l < a.L; ++l) {
     uint64_t* const lb = llb + (size_t)l * LS;
-    const LayerTab lt = a.layers[l];
+    const LayerTab& lt = sm.tab[l];
+    XSM_STAMP(l * 8 + 0);
 
     // ================= QKV =================
     if (has_q) {
-      float xv[KD][8];
-      float ss;
-      poll_rows_f32<KD>(lb + OFF_X, D, r, live, wave * KD, g, tag, xv, ss, ok);
-      ss += __shfl_xor(ss, 16, WAVE);
-      ss += __shfl_xor(ss, 32, WAVE);
-      if (g == 0) sm.rowsum[wave][r] = ss;
-      __syncthreads();
-      const float inv = 1.0f / sqrtf(((sm.rowsum[0][r] + sm.rowsum[1][r]) + (sm.rowsum[2][r] + sm.rowsum[3][r])) / (float)D + a.eps);
+      uint32_t gp[D / 512];                            // gain pairs and rotary entry: requested before waiting
+#pragma unroll
+      for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g1 + 2 * (tid + 256 * j));
+      const int q_sec = w / (D / 16), q_ts = w % (D / 16), q_h = q_ts >> 2, q_tt = q_ts & 3;
+      float2 cs = float2{1.f, 0.f};
+      if (live && q_sec < 2) cs = a.rope[(size_t)(len_m + mj) * 32 + q_tt * 8 + (nrow & 7)];
+      stage_rows_f32<D, true>(sm, As, nullptr, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i) {
-        const uint4 gg = *reinterpret_cast<const uint4*>(lt.g1 + (wave * KD + i) * 32 + g * 8);
-        const uint32_t gw[4] = {gg.x, gg.y, gg.z, gg.w};
-        uint32_t bw[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          bw[e] = pk2(xv[i][2 * e] * inv * __uint_as_float(gw[e] << 16),
-                      xv[i][2 * e + 1] * inv * __uint_as_float(gw[e] & 0xFFFF0000u));
+      for (int i = 0; i < KD; ++i)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wq[i]),
-                                                      __builtin_bit_cast(bf16x8, uint4{bw[0], bw[1], bw[2], bw[3]}), acc, 0, 0, 0);
-      }
-      if (l + 1 < a.L) load_frags<KD>(wq, a.layers[l + 1].Wqkv, w, KTD, wave * KD, lane);
+                                                      __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
       const float v = tile_reduce(sm, acc, wave, lane);
       const float partner = __shfl_xor(v, 32, WAVE);
       if (live) {
         const int pos = len_m + mj;
-        const int sec = w / (D / 16), ts = w % (D / 16), h = ts >> 2, tt = ts & 3;
         float o = v;
         int dim;
-        if (sec < 2) {
-          const int pi = tt * 8 + (nrow & 7);
-          const float2 cs = a.rope[(size_t)pos * 32 + pi];
+        if (q_sec < 2) {
+          const int pi = q_tt * 8 + (nrow & 7);
           if (nrow < 8) { dim = pi; o = v * cs.x - partner * cs.y; }
           else { dim = 32 + pi; o = partner * cs.y + v * cs.x; }
         } else {
-          dim = tt * 16 + nrow;
+          dim = q_tt * 16 + nrow;
         }
-        const size_t col = (size_t)r * D + h * 64 + dim;
-        const size_t head = (size_t)sm.slot[mb] * H + h;
-        if (sec == 0) {
+        const size_t col = (size_t)r * D + q_h * 64 + dim;
+        const size_t head = (size_t)sm.slot[mb] * H + q_h;
+        if (q_sec == 0) {
           ll_st(lb + OFF_Q + col, __float_as_uint(o), tag);
-        } else if (sec == 1) {
+        } else if (q_sec == 1) {
           ll_st(lb + OFF_KN + col, __float_as_uint(o), tag);
           lt.Kc[(head * a.cap + pos) * 64 + dim] = f2bf(o);
         } else {
@@ -266,6 +375,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         }
       }
     }
+    XSM_STAMP(l * 8 + 1);
 
     // ================= ATT =================
     const int n_units = a.n_seq * H * S;
@@ -278,19 +388,58 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const size_t head = (size_t)sm.slot[b] * H + h;
       const uint16_t* kb = lt.Kc + head * (size_t)a.cap * 64;
       const uint16_t* vb = lt.Vt + head * 64 * (size_t)a.cap;
-      // queries of this sequence: MFMA column r is query j = r (r < R)
-      uint4 qf[2] = {uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
-      const bool qlive = r < R && n >= 0;
-      if (qlive) {
+      // this step's q, k, v rows of (sequence b, head h): [R][64] each, staged as bf16 tiles
+      uint16_t* const qs = As;
+      uint16_t* const kns = As + 16 * kQS;
+      uint16_t* const vns = As + 32 * kQS;
+      // the first chunk of cached keys/values does not depend on this step: request it before waiting
+      uint4 kn_[4][2], vn_[4][2];
+      auto load_kv = [&](int c) {
+        const int key0 = c << 6;
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          uint32_t pw[8];
-          ll_wait<8>(lb + OFF_Q + (size_t)(b * R + r) * D + h * 64 + hf * 32 + g * 8, tag, pw, ok);
-          qf[hf] = uint4{pk2(__uint_as_float(pw[0]), __uint_as_float(pw[1])), pk2(__uint_as_float(pw[2]), __uint_as_float(pw[3])),
-                         pk2(__uint_as_float(pw[4]), __uint_as_float(pw[5])), pk2(__uint_as_float(pw[6]), __uint_as_float(pw[7]))};
+        for (int t = 0; t < 4; ++t) {
+          const uint16_t* kr = kb + (size_t)(key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 64 + g * 8;
+          kn_[t][0] = *reinterpret_cast<const uint4*>(kr);
+          kn_[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
+        }
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
+          vn_[dt][0] = *reinterpret_cast<const uint4*>(vr);
+          vn_[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
+        }
+      };
+      if (c_lo + wave < c_hi) load_kv(c_lo + wave);
+      __syncthreads();
+      if (n >= 0) {
+        const int j0 = tid >> 6, c = tid & 63;            // rows j0, j0+4, j0+8, j0+12
+        int off[12];
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int j = j0 + 4 * q;
+          if (j < R) {
+            const int base = (b * R + j) * D + h * 64 + c;
+            off[cnt] = (int)OFF_Q + base; off[cnt + 1] = (int)OFF_KN + base; off[cnt + 2] = (int)OFF_VN + base;
+            cnt += 3;
+          }
+        }
+        uint32_t pw[12];
+        ll_wait_list<12>(lb, off, cnt, tag, pw, ok);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int j = j0 + 4 * q;
+          if (j < R) {
+            qs[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q]));
+            kns[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q + 1]));
+            vns[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q + 2]));
+          }
         }
       }
-      const bf16x8 q0 = __builtin_bit_cast(bf16x8, qf[0]), q1 = __builtin_bit_cast(bf16x8, qf[1]);
+      __syncthreads();
+      const bool qlive = r < R && n >= 0;                 // MFMA column r is query j = r
+      const bf16x8 q0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qs + r * kQS + g * 8));
+      const bf16x8 q1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qs + r * kQS + 32 + g * 8));
       float m_run = -INFINITY, l_run = 0.f;
       f32x4 o[4];
 #pragma unroll
@@ -301,17 +450,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         const int key0 = c << 6;
         uint4 kf[4][2], vf[4][2];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const uint16_t* kr = kb + (size_t)(key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 64 + g * 8;
-          kf[t][0] = *reinterpret_cast<const uint4*>(kr);
-          kf[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
-        }
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
-          vf[dt][0] = *reinterpret_cast<const uint4*>(vr);
-          vf[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
-        }
+        for (int t = 0; t < 4; ++t) { kf[t][0] = kn_[t][0]; kf[t][1] = kn_[t][1]; vf[t][0] = vn_[t][0]; vf[t][1] = vn_[t][1]; }
+        if (c + 4 < c_hi) load_kv(c + 4);                 // next chunk's cache lines are in flight during this one
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -376,21 +516,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
 
       // the R new keys of this step (positions n..n+R-1): one 16-key tile, taken by wavefront 3
-      // of slice 0, straight from the tagged k/v words; query j sees new key i iff i <= j
+      // of slice 0; query j sees new key i iff i <= j
       if (s == 0 && wave == 3 && n >= 0) {
         // A operand of S^T: lane (key r, g) holds k_new[r][hf*32 + g*8 .. +8]
-        uint4 kn[2] = {uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
-        if (r < R) {
-#pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            uint32_t pw[8];
-            ll_wait<8>(lb + OFF_KN + (size_t)(b * R + r) * D + h * 64 + hf * 32 + g * 8, tag, pw, ok);
-            kn[hf] = uint4{pk2(__uint_as_float(pw[0]), __uint_as_float(pw[1])), pk2(__uint_as_float(pw[2]), __uint_as_float(pw[3])),
-                           pk2(__uint_as_float(pw[4]), __uint_as_float(pw[5])), pk2(__uint_as_float(pw[6]), __uint_as_float(pw[7]))};
-          }
-        }
-        f32x4 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kn[0]), q0, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kn[1]), q1, sc, 0, 0, 0);
+        const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kns + r * kQS + g * 8));
+        const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kns + r * kQS + 32 + g * 8));
+        f32x4 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, q0, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, q1, sc, 0, 0, 0);
         // lane (query r, g) holds new keys g*4 + i
         float cmax = -INFINITY;
 #pragma unroll
@@ -422,17 +554,14 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
           // A operand: lane (dim dt*16 + r, g) holds v_new[key g*4 + e][dim], e < 4
-          float vv[4] = {0.f, 0.f, 0.f, 0.f};
+          uint32_t vw[2] = {0u, 0u};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int key = g * 4 + e;
-            if (key < R) {
-              uint32_t pw[1];
-              ll_wait<1>(lb + OFF_VN + (size_t)(b * R + key) * D + h * 64 + dt * 16 + r, tag, pw, ok);
-              vv[e] = __uint_as_float(pw[0]);
-            }
+            const uint32_t x = key < R ? (uint32_t)vns[key * kQS + dt * 16 + r] : 0u;
+            vw[e >> 1] |= x << ((e & 1) * 16);
           }
-          const uint4 vfrag = uint4{pk2(vv[0], vv[1]), pk2(vv[2], vv[3]), 0u, 0u};
+          const uint4 vfrag = uint4{vw[0], vw[1], 0u, 0u};
           o[dt] = o[dt] * alpha;
           o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vfrag),
                                                           __builtin_bit_cast(bf16x8, pfrag), o[dt], 0, 0, 0);
@@ -440,7 +569,6 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
 
       // merge the four wavefronts; wavefront i finishes dim tile i
-      __syncthreads();
       if (g == 0) { sm.att_ml[wave][0][r] = m_run; sm.att_ml[wave][1][r] = l_run; }
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) *reinterpret_cast<f32x4*>(&sm.att_o[wave][dt][lane][0]) = o[dt];
@@ -476,83 +604,92 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           ll_st(part + 32 + (size_t)(wave * 16 + g * 4 + i) * 16 + r, __float_as_uint(acc[i]), tag);
       }
     }
+    XSM_STAMP(l * 8 + 2);
 
     // ================= COMB =================
     if (S > 1 && w < n_units) {
       const int b = w / (H * S), h = (w / S) % H, s = w % S;
       const int dps = 64 / S;                               // dims finished by this unit
+      const int P = 32 + dps * 16;                          // words needed from each slice: m, l, O^T rows
+      const uint64_t* p0 = lb + OFF_P + (size_t)(w - s) * 1056;
+      float* const cb = reinterpret_cast<float*>(As);       // [S][P]
+      __syncthreads();
+      {
+        int off[6];
+        int cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+          const int i = tid + 256 * q;
+          if (i < S * P) {
+            const int k = i / P, j = i % P;
+            off[q] = k * 1056 + (j < 32 ? j : 32 + s * dps * 16 + (j - 32));
+            cnt = q + 1;
+          } else {
+            off[q] = 0;
+          }
+        }
+        uint32_t pw[6];
+        ll_wait_list<6>(p0, off, cnt, tag, pw, ok);
+#pragma unroll
+        for (int q = 0; q < 6; ++q)
+          if (q < cnt) cb[tid + 256 * q] = __uint_as_float(pw[q]);
+      }
+      __syncthreads();
       for (int qd = tid >> 4; qd < dps; qd += 16) {
-        if (r >= R) break;
-        const int dim = s * dps + qd;
-        const uint64_t* p0 = lb + OFF_P + (size_t)(w - s) * 1056;
-        float Mg = -INFINITY, mk[16];
-        for (int k = 0; k < S; ++k) {
-          uint32_t pw[1];
-          ll_wait<1>(p0 + (size_t)k * 1056 + r, tag, pw, ok);
-          mk[k] = __uint_as_float(pw[0]);
-          Mg = fmaxf(Mg, mk[k]);
+        const int rq = tid & 15;
+        if (rq < R) {
+          float Mg = -INFINITY;
+          for (int k = 0; k < S; ++k) Mg = fmaxf(Mg, cb[k * P + rq]);
+          float Lg = 0.f, og = 0.f;
+          for (int k = 0; k < S; ++k) {
+            const float mk = cb[k * P + rq];
+            const float f = mk == -INFINITY ? 0.f : exp2f(mk - Mg);
+            Lg += cb[k * P + 16 + rq] * f;
+            og += cb[k * P + 32 + qd * 16 + rq] * f;
+          }
+          const float outv = sm.len[b] >= 0 ? og / Lg : 0.f;
+          ll_st(lb + OFF_O + (size_t)(b * R + rq) * D + h * 64 + s * dps + qd, __float_as_uint(outv), tag);
         }
-        float Lg = 0.f, og = 0.f;
-        for (int k = 0; k < S; ++k) {
-          uint32_t pl[1], po[1];
-          ll_wait<1>(p0 + (size_t)k * 1056 + 16 + r, tag, pl, ok);
-          ll_wait<1>(p0 + (size_t)k * 1056 + 32 + (size_t)dim * 16 + r, tag, po, ok);
-          const float f = mk[k] == -INFINITY ? 0.f : exp2f(mk[k] - Mg);
-          Lg += __uint_as_float(pl[0]) * f;
-          og += __uint_as_float(po[0]) * f;
-        }
-        const float outv = sm.len[b] >= 0 ? og / Lg : 0.f;
-        ll_st(lb + OFF_O + (size_t)(b * R + r) * D + h * 64 + dim, __float_as_uint(outv), tag);
       }
     }
+    XSM_STAMP(l * 8 + 3);
+    // the FFN-down tile is 4x larger than the others: its fragments are requested here, two
+    // stages ahead of their use, rather than a layer ahead, to stay out of the attention
+    // stage's register budget
+    if (has_d) load_frags<KF>(wd, lt.W2, w - DN_BASE, KTF, wave * KF, lane);
 
     // ================= OPROJ =================
     if (has_o) {
       const int nt = w - O_BASE;
-      float xv[KD][8];
-      float ss;
-      poll_rows_f32<KD>(lb + OFF_O, D, r, row_in, wave * KD, g, tag, xv, ss, ok);
+      // residual entering the layer: published a stage ago
+      const uint32_t px = row_in ? ll_wait1(lb + OFF_X + (size_t)r * D + nt * 16 + nrow, tag, ok) : 0u;
+      const uint32_t nogain[D / 512] = {};
+      __syncthreads();
+      stage_rows_f32<D, false>(sm, As, nullptr, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i) {
-        const uint4 bfrag = uint4{pk2(xv[i][0], xv[i][1]), pk2(xv[i][2], xv[i][3]), pk2(xv[i][4], xv[i][5]), pk2(xv[i][6], xv[i][7])};
+      for (int i = 0; i < KD; ++i)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wo[i]),
-                                                      __builtin_bit_cast(bf16x8, bfrag), acc, 0, 0, 0);
-      }
-      if (l + 1 < a.L) load_frags<KD>(wo, a.layers[l + 1].Wo, nt, KTD, wave * KD, lane);
+                                                      __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
       const float v = tile_reduce(sm, acc, wave, lane);
-      if (row_in) {
-        uint32_t px[1];
-        ll_wait<1>(lb + OFF_X + (size_t)r * D + nt * 16 + nrow, tag, px, ok);
-        ll_st(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px[0]) + v), tag);
-      }
+      if (row_in)
+        ll_st(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px) + v), tag);
     }
+    XSM_STAMP(l * 8 + 4);
 
     // ================= UP =================
     if (has_u) {
-      float xv[KD][8];
-      float ss;
-      poll_rows_f32<KD>(lb + OFF_XM, D, r, row_in, wave * KD, g, tag, xv, ss, ok);
-      ss += __shfl_xor(ss, 16, WAVE);
-      ss += __shfl_xor(ss, 32, WAVE);
+      uint32_t gp[D / 512];
+#pragma unroll
+      for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g2 + 2 * (tid + 256 * j));
       __syncthreads();
-      if (g == 0) sm.rowsum[wave][r] = ss;
-      __syncthreads();
-      const float inv = 1.0f / sqrtf(((sm.rowsum[0][r] + sm.rowsum[1][r]) + (sm.rowsum[2][r] + sm.rowsum[3][r])) / (float)D + a.eps);
+      stage_rows_f32<D, true>(sm, As, nullptr, lb + OFF_XM, M, gp, a.eps, tid, tag, ok);
+      XSM_STAMP(l * 8 + 7);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i) {
-        const uint4 gg = *reinterpret_cast<const uint4*>(lt.g2 + (wave * KD + i) * 32 + g * 8);
-        const uint32_t gw[4] = {gg.x, gg.y, gg.z, gg.w};
-        uint32_t bw[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          bw[e] = pk2(xv[i][2 * e] * inv * __uint_as_float(gw[e] << 16),
-                      xv[i][2 * e + 1] * inv * __uint_as_float(gw[e] & 0xFFFF0000u));
+      for (int i = 0; i < KD; ++i)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wu[i]),
-                                                      __builtin_bit_cast(bf16x8, uint4{bw[0], bw[1], bw[2], bw[3]}), acc, 0, 0, 0);
-      }
-      if (l + 1 < a.L) load_frags<KD>(wu, a.layers[l + 1].W1, w, KTD, wave * KD, lane);
+                                                      __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
       __syncthreads();
       *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
       __syncthreads();
@@ -569,33 +706,34 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         ll_st(lb + OFF_U + (size_t)r * (F / 2) + w * 8 + p, pk2(v2[0], v2[1]), tag);
       }
     }
+    XSM_STAMP(l * 8 + 5);
 
     // ================= DOWN =================
     if (has_d) {
       const int nt = w - DN_BASE;
+      const uint32_t px = row_in ? ll_wait1(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, tag, ok) : 0u;
+      __syncthreads();
+      stage_rows_bf16<F / 2>(As, STF, 0, lb + OFF_U, M, tid, tag, ok);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i0 = 0; i0 < KF; i0 += 8) {
-        uint32_t pw[32];
-        if (row_in) {
-          ll_wait_groups<8, 4>(lb + OFF_U + (size_t)r * (F / 2) + (wave * KF + i0) * 16 + g * 4, 16, tag, pw, ok);
-        } else {
+      for (int i0 = 0; i0 < KF; i0 += 8) {               // eight k-tiles at a time keeps the operand reads short-lived
 #pragma unroll
-          for (int i = 0; i < 32; ++i) pw[i] = 0u;
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8, wd[i0 + i]),
-              __builtin_bit_cast(bf16x8, uint4{pw[4 * i], pw[4 * i + 1], pw[4 * i + 2], pw[4 * i + 3]}), acc, 0, 0, 0);
+        for (int i = i0; i < i0 + 8; ++i)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wd[i]),
+                                                        __builtin_bit_cast(bf16x8, lds_frag(As, STF, r, wave * KF + i, g)), acc, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      if (l + 1 < a.L) load_frags<KF>(wd, a.layers[l + 1].W2, nt, KTF, wave * KF, lane);
       const float v = tile_reduce(sm, acc, wave, lane);
-      if (row_in) {
-        uint32_t px[1];
-        ll_wait<1>(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, tag, px, ok);
-        ll_st(lb + LS + OFF_X + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px[0]) + v), tag);
-      }
+      if (row_in)
+        ll_st(lb + LS + OFF_X + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px) + v), tag);
+    }
+    XSM_STAMP(l * 8 + 6);
+    // next layer's projection tiles: requested now, a whole layer of dependency hops ahead of use
+    // (for the workgroups that just ran DOWN: right behind it, so the registers do not overlap)
+    if (l + 1 < a.L) {
+      if (has_q) load_frags<KD>(wq, sm.tab[l + 1].Wqkv, w, KTD, wave * KD, lane);
+      if (has_o) load_frags<KD>(wo, sm.tab[l + 1].Wo, w - O_BASE, KTD, wave * KD, lane);
+      if (has_u) load_frags<KD>(wu, sm.tab[l + 1].W1, w, KTD, wave * KD, lane);
     }
 
     // a workgroup that timed out anywhere leaves (its consumers will time out in turn)
@@ -611,45 +749,37 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   const size_t OFF_ST = OFF_RB + (size_t)16 * 15 * (D / 2); // per (tile, row) top-2 statistics: 4 words
   const int NTV = V / 16;                                  // vocabulary tiles
   const int rows_all = M + M * K;                          // backbone rows, then head rows (m, k)
+  uint16_t* const T0 = As;                                 // rows 0..15 of the unembedding input
+  uint16_t* const T1 = As + 16 * STD;                      // later row tiles, one at a time
+  float* const Hf32 = reinterpret_cast<float*>(As + 32 * STD);   // fp32 final-normed hidden [16][D]
 
-  // final-normed hidden state of every row, as this lane's B fragments (all workgroups need it)
-  uint4 hfrag[KD];
-  float hval[KD][8];
+  // first tiles of the head and unembedding matrices: requested before the last residual arrives
+  uint4 wh[KD], wv[KD];
+  if (w < K * (D / 16)) load_frags<KD>(wh, a.Wh, w, KTD, wave * KD, lane);
+  if (w < NTV) load_frags<KD>(wv, a.WU, w, KTD, wave * KD, lane);
+
+  XSM_STAMP(a.L * 8 + 0);
   {
-    float ss;
-    poll_rows_f32<KD>(tb + OFF_X, D, r, row_in, wave * KD, g, tag, hval, ss, ok);
-    ss += __shfl_xor(ss, 16, WAVE);
-    ss += __shfl_xor(ss, 32, WAVE);
-    __syncthreads();
-    if (g == 0) sm.rowsum[wave][r] = ss;
-    __syncthreads();
-    const float inv = 1.0f / sqrtf(((sm.rowsum[0][r] + sm.rowsum[1][r]) + (sm.rowsum[2][r] + sm.rowsum[3][r])) / (float)D + a.eps);
+    uint32_t gp[D / 512];
 #pragma unroll
-    for (int i = 0; i < KD; ++i) {
-      const uint4 gg = *reinterpret_cast<const uint4*>(a.gf + (wave * KD + i) * 32 + g * 8);
-      const uint32_t gw[4] = {gg.x, gg.y, gg.z, gg.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        hval[i][2 * e] *= inv * __uint_as_float(gw[e] << 16);
-        hval[i][2 * e + 1] *= inv * __uint_as_float(gw[e] & 0xFFFF0000u);
-      }
-      hfrag[i] = uint4{pk2(hval[i][0], hval[i][1]), pk2(hval[i][2], hval[i][3]), pk2(hval[i][4], hval[i][5]), pk2(hval[i][6], hval[i][7])};
-    }
+    for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(a.gf + 2 * (tid + 256 * j));
+    __syncthreads();
+    stage_rows_f32<D, true>(sm, T0, Hf32, tb + OFF_X, M, gp, a.eps, tid, tag, ok);
   }
+  XSM_STAMP(a.L * 8 + 1);
 
   // ---- HEADS on every row: r_k = g + SiLU(W_k g + b_k)  (Eq. 4, MLP variant) ----
   for (int t = w; t < K * (D / 16); t += 256) {
-    uint4 wh[KD];
-    load_frags<KD>(wh, a.Wh, t, KTD, wave * KD, lane);
+    if (t != w) load_frags<KD>(wh, a.Wh, t, KTD, wave * KD, lane);
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < KD; ++i)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wh[i]), __builtin_bit_cast(bf16x8, hfrag[i]), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wh[i]),
+                                                    __builtin_bit_cast(bf16x8, lds_frag(T0, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
     __syncthreads();
     *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
-    // the normalised hidden values of the 16 output columns of this tile, for the residual
-    const int kh = t / (D / 16), c0 = (t % (D / 16)) * 16;   // head index, first column
     __syncthreads();
+    const int kh = t / (D / 16), c0 = (t % (D / 16)) * 16;   // head index, first column
     if (tid < 128 && r < M) {
       const int p = tid >> 4;
       float v2[2];
@@ -658,58 +788,42 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         const int nr = 2 * p + q, ln = (nr >> 2) * 16 + r, ii = nr & 3;
         const float y = (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
         const float pre = y + bf2f(a.hb[(size_t)kh * D + c0 + nr]);
-        // g[c] recomputed from the tagged residual words (fp32), same arithmetic as above
-        uint32_t px[1];
-        ll_wait<1>(tb + OFF_X + (size_t)r * D + c0 + nr, tag, px, ok);
-        const float tot = (sm.rowsum[0][r] + sm.rowsum[1][r]) + (sm.rowsum[2][r] + sm.rowsum[3][r]);
-        const float gn = __uint_as_float(px[0]) * (1.0f / sqrtf(tot / (float)D + a.eps)) * bf2f(a.gf[c0 + nr]);
-        v2[q] = gn + pre / (1.0f + __expf(-pre));
+        v2[q] = Hf32[(size_t)r * D + c0 + nr] + pre / (1.0f + __expf(-pre));
       }
       ll_st(tb + OFF_RB + ((size_t)r * K + kh) * (D / 2) + (c0 >> 1) + p, pk2(v2[0], v2[1]), tag);
     }
   }
+  XSM_STAMP(a.L * 8 + 2);
 
   // ---- UNEMBED over backbone rows and head rows, per-tile top-2 per row ----
-  for (int t = w; t < NTV; t += 256) {
-    uint4 wv[KD];
-    load_frags<KD>(wv, a.WU, t, KTD, wave * KD, lane);
-    for (int mt = 0; mt * 16 < rows_all; ++mt) {
-      // rows of this m-tile: global row q = mt*16 + r; q < M: backbone row q; else head row q - M
-      const int qrow = mt * 16 + r;
-      uint4 bfr[KD];
-      if (qrow < M) {                       // backbone rows lead tile 0: fragments are at hand
-#pragma unroll
-        for (int i = 0; i < KD; ++i) bfr[i] = hfrag[i];
-      } else {
-        uint32_t pw[KD * 4];
-        if (qrow < rows_all) {
-          ll_wait_groups<KD, 4>(tb + OFF_RB + (size_t)(qrow - M) * (D / 2) + wave * KD * 16 + g * 4, 16, tag, pw, ok);
-        } else {
-#pragma unroll
-          for (int i = 0; i < KD * 4; ++i) pw[i] = 0u;
-        }
-#pragma unroll
-        for (int i = 0; i < KD; ++i) bfr[i] = uint4{pw[4 * i], pw[4 * i + 1], pw[4 * i + 2], pw[4 * i + 3]};
-      }
+  // row q < M: backbone row q (already in T0); row q >= M: head row q - M = m*K + k
+  const int n_mt = (rows_all + 15) / 16;
+  for (int mt = 0; mt < n_mt; ++mt) {
+    uint16_t* const T = mt == 0 ? T0 : T1;
+    const int q_lo = mt == 0 ? M : mt * 16, q_hi = min(rows_all, mt * 16 + 16);
+    if (w < NTV) {                                     // only workgroups with a vocabulary tile need the rows
+      __syncthreads();
+      if (q_hi > q_lo)
+        stage_rows_bf16<D / 2>(T, STD, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * (D / 2), q_hi - q_lo, tid, tag, ok);
+    }
+    for (int t = w; t < NTV; t += 256) {
+      if (t != w) load_frags<KD>(wv, a.WU, t, KTD, wave * KD, lane);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[i]), __builtin_bit_cast(bf16x8, bfr[i]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[i]),
+                                                      __builtin_bit_cast(bf16x8, lds_frag(T, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
       __syncthreads();
       *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
       __syncthreads();
-      // threads 0..15: row qrow = mt*16 + tid; scan the tile's 16 vocabulary entries in order
+      // threads 0..15: row q = mt*16 + tid; scan the tile's 16 vocabulary entries in order
       if (tid < 16 && mt * 16 + tid < rows_all) {
         const int q = mt * 16 + tid;
         float bv = -INFINITY, sv = -INFINITY;
         int bi = 0;
         float* dbg = nullptr;
         if (q < M) { if (a.logits_dbg) dbg = a.logits_dbg + (size_t)q * V; }
-        else if (a.head_logits_dbg) {
-          // head rows are ordered (m, k); the debug array wants the heads of the accepted row only,
-          // which is not known yet: the full [M][K][V] block is written to the workspace copy
-          dbg = a.head_all_dbg + (size_t)(q - M) * V;
-        }
+        else if (a.head_logits_dbg) dbg = a.head_all_dbg + (size_t)(q - M) * V;
 #pragma unroll
         for (int nr = 0; nr < 16; ++nr) {
           const int ln = (nr >> 2) * 16 + tid, ii = nr & 3;
@@ -724,7 +838,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         ll_st(st + 2, __float_as_uint(sv), tag);
       }
     }
+    // a workgroup with several vocabulary tiles starts the next row tile from its first again
+    if (NTV > 256 && w < NTV && mt + 1 < n_mt) load_frags<KD>(wv, a.WU, w, KTD, wave * KD, lane);
   }
+  XSM_STAMP(a.L * 8 + 3);
 
   // ---- FINAL: workgroup b finishes sequence b ----
   if (w < a.n_seq) {
@@ -737,8 +854,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       float bv = -INFINITY, sv = -INFINITY;
       int bi = 0x7FFFFFFF;
       for (int t = lane; t < NTV; t += 64) {
+        const int off[3] = {0, 1, 2};
         uint32_t pw[3];
-        ll_wait<3>(tb + OFF_ST + ((size_t)t * 80 + grow) * 4, tag, pw, ok);
+        ll_wait_list<3>(tb + OFF_ST + ((size_t)t * 80 + grow) * 4, off, 3, tag, pw, ok);
         const float tv = __uint_as_float(pw[0]), ts = __uint_as_float(pw[2]);
         const int ti = (int)pw[1];
         if (tv > bv || (tv == bv && ti < bi)) { sv = fmaxf(bv, fmaxf(sv, ts)); bv = tv; bi = ti; }
@@ -788,6 +906,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
     }
   }
+  XSM_STAMP(a.L * 8 + 4);
   if (__syncthreads_or(!ok)) {
     if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return;
@@ -796,6 +915,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   // workgroup has long since read the epoch
   if (w == 0 && tid == 0)
     __hip_atomic_store(a.ctrl, tag + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#undef XSM_STAMP
 }
 
 size_t small_ll_words(int n_layers, int D, int F, int K) {
@@ -812,8 +932,19 @@ bool small_supported(int D, int F) { return D == 1024 && F == 4096; }
 
 void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
   TraceScope trace_("step_small", s);
-  if (D == 1024 && F == 4096)
-    hipLaunchKernelGGL((k_step_small<1024, 4096>), dim3(256), dim3(256), 0, s, a);
+  if (D == 1024 && F == 4096) {
+    auto kfn = k_step_small<1024, 4096>;
+    // activation tiles: 16 rows of FFN width in bf16, or two 16-row model-width tiles plus an
+    // fp32 copy of the final hidden state
+    const size_t a1 = (size_t)16 * (4096 + 8) * 2, a2 = (size_t)32 * (1024 + 8) * 2 + (size_t)16 * 1024 * 4;
+    const size_t lds = a1 > a2 ? a1 : a2;
+    static bool configured = false;
+    if (!configured) {
+      (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      configured = true;
+    }
+    hipLaunchKernelGGL(kfn, dim3(256), dim3(256), lds, s, a);
+  }
 }
 
 }  // namespace xsm
