@@ -61,36 +61,32 @@ __device__ __forceinline__ uint32_t pk2(float a, float b) {
 __device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// Wait for up to N tagged words at p + off[i] (i < n); payloads to out.  The lane first
-// spins on its last word only (producers of a stage finish together; re-reading every word
-// while nothing has arrived would flood the coherent path), then reads all of them in one
-// round and repeats that round until every tag matches.  On timeout, or when an earlier
-// wait of this lane already failed, ok is false and out is zero.
+// Wait for the tagged words at p + off[i] (entries with off[i] < 0 are skipped); payloads to
+// out.  Meant for small blocks: the words are simply re-read together until every tag
+// matches, one round trip from arrival to use.  On timeout, or when an earlier wait of this
+// lane already failed, ok is false and out is zero.
 template <int N>
-__device__ __forceinline__ void ll_wait_list(const uint64_t* p, const int (&off)[N], int n, uint32_t tag,
+__device__ __forceinline__ void ll_wait_list(const uint64_t* p, const int (&off)[N], uint32_t tag,
                                              uint32_t (&out)[N], bool& ok) {
-  if (ok && n > 0) {
-    int spin = 0;
-    // one lane per wavefront watches one word; the others join when it has arrived
-    if (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) == 0) {
-      const uint64_t* last = p + off[n - 1];
-      while ((uint32_t)(ll_ld(last) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
-    }
-    for (; spin < kSpinBudget; ++spin) {
+  bool any = false;
+#pragma unroll
+  for (int i = 0; i < N; ++i) any |= off[i] >= 0;
+  if (ok && any) {
+    for (int spin = 0; spin < kSpinBudget; ++spin) {
       uint64_t w[N];
 #pragma unroll
       for (int i = 0; i < N; ++i)
-        if (i < n) w[i] = ll_ld(p + off[i]);
+        if (off[i] >= 0) w[i] = ll_ld(p + off[i]);
       bool good = true;
 #pragma unroll
       for (int i = 0; i < N; ++i)
-        if (i < n) good &= (uint32_t)(w[i] >> 32) == tag;
+        if (off[i] >= 0) good &= (uint32_t)(w[i] >> 32) == tag;
       if (good) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) out[i] = i < n ? (uint32_t)w[i] : 0u;
+        for (int i = 0; i < N; ++i) out[i] = off[i] >= 0 ? (uint32_t)w[i] : 0u;
         return;
       }
-      __builtin_amdgcn_s_sleep(8);
+      __builtin_amdgcn_s_sleep(4);
     }
     ok = false;
   }
@@ -100,7 +96,7 @@ __device__ __forceinline__ void ll_wait_list(const uint64_t* p, const int (&off)
 __device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bool& ok) {
   const int off[1] = {0};
   uint32_t out[1];
-  ll_wait_list<1>(p, off, 1, tag, out, ok);
+  ll_wait_list<1>(p, off, tag, out, ok);
   return out[0];
 }
 
@@ -140,7 +136,7 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
         for (int i = 0; i < N; ++i) pay[i] = (i / (PP * 2)) < rows ? (uint32_t)w[i] : 0u;
         return;
       }
-      __builtin_amdgcn_s_sleep(8);
+      __builtin_amdgcn_s_sleep(4);
     }
     ok = false;
   }
@@ -314,10 +310,16 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 
   const bool has_q = w < NQ, has_o = w >= O_BASE && w < O_BASE + NO, has_u = w < NU,
              has_d = w >= DN_BASE && w < DN_BASE + NO;
-  uint4 wq[KD], wo[KD], wu[KD], wd[KF];
+  // Weight fragments live in registers and are requested ahead of use.  A wavefront's loads
+  // return in order, so a bulk request delays whatever wait is issued right behind it; each
+  // request is therefore placed where its workgroup is about to sit out a stage:
+  //   workgroups with QKV (+ DOWN): next layer's QKV tile, this layer's DOWN tile (and, for the
+  //     DOWN owners, this layer's UP tile) after COMB - they have no OPROJ tile;
+  //   the others: next layer's UP / OPROJ tiles after UP - they have no DOWN tile.
+  uint4 wq[KD], wu[KD], wd[KF];            // wq doubles as the OPROJ tile (disjoint workgroups)
   if (has_q) load_frags<KD>(wq, sm.tab[0].Wqkv, w, KTD, wave * KD, lane);
-  if (has_o) load_frags<KD>(wo, sm.tab[0].Wo, w - O_BASE, KTD, wave * KD, lane);
-  if (has_u) load_frags<KD>(wu, sm.tab[0].W1, w, KTD, wave * KD, lane);
+  if (has_o) load_frags<KD>(wq, sm.tab[0].Wo, w - O_BASE, KTD, wave * KD, lane);
+  if (has_u && !has_d) load_frags<KD>(wu, sm.tab[0].W1, w, KTD, wave * KD, lane);
 
   // ---- EMBED: layer-0 residual rows as tagged words ----
   for (int idx = w * 256 + tid; idx < M * D; idx += 256 * 256) {
@@ -393,20 +395,20 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       uint16_t* const kns = As + 16 * kQS;
       uint16_t* const vns = As + 32 * kQS;
       // the first chunk of cached keys/values does not depend on this step: request it before waiting
-      uint4 kn_[4][2], vn_[4][2];
+      uint4 kf[4][2], vf[4][2];
       auto load_kv = [&](int c) {
         const int key0 = c << 6;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const uint16_t* kr = kb + (size_t)(key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 64 + g * 8;
-          kn_[t][0] = *reinterpret_cast<const uint4*>(kr);
-          kn_[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
+          kf[t][0] = *reinterpret_cast<const uint4*>(kr);
+          kf[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
         }
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
           const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
-          vn_[dt][0] = *reinterpret_cast<const uint4*>(vr);
-          vn_[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
+          vf[dt][0] = *reinterpret_cast<const uint4*>(vr);
+          vf[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
         }
       };
       if (c_lo + wave < c_hi) load_kv(c_lo + wave);
@@ -414,18 +416,16 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       if (n >= 0) {
         const int j0 = tid >> 6, c = tid & 63;            // rows j0, j0+4, j0+8, j0+12
         int off[12];
-        int cnt = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int j = j0 + 4 * q;
-          if (j < R) {
-            const int base = (b * R + j) * D + h * 64 + c;
-            off[cnt] = (int)OFF_Q + base; off[cnt + 1] = (int)OFF_KN + base; off[cnt + 2] = (int)OFF_VN + base;
-            cnt += 3;
-          }
+          const int base = (b * R + j) * D + h * 64 + c;
+          off[3 * q] = j < R ? (int)OFF_Q + base : -1;
+          off[3 * q + 1] = j < R ? (int)OFF_KN + base : -1;
+          off[3 * q + 2] = j < R ? (int)OFF_VN + base : -1;
         }
         uint32_t pw[12];
-        ll_wait_list<12>(lb, off, cnt, tag, pw, ok);
+        ll_wait_list<12>(lb, off, tag, pw, ok);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int j = j0 + 4 * q;
@@ -448,10 +448,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       // cached keys 0..n-1: every live query sees all of them
       for (int c = c_lo + wave; c < c_hi; c += 4) {
         const int key0 = c << 6;
-        uint4 kf[4][2], vf[4][2];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) { kf[t][0] = kn_[t][0]; kf[t][1] = kn_[t][1]; vf[t][0] = vn_[t][0]; vf[t][1] = vn_[t][1]; }
-        if (c + 4 < c_hi) load_kv(c + 4);                 // next chunk's cache lines are in flight during this one
+        if (c != c_lo + wave) load_kv(c);                  // (the first chunk was requested before the q wait)
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -616,23 +613,17 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
       {
         int off[6];
-        int cnt = 0;
 #pragma unroll
         for (int q = 0; q < 6; ++q) {
           const int i = tid + 256 * q;
-          if (i < S * P) {
-            const int k = i / P, j = i % P;
-            off[q] = k * 1056 + (j < 32 ? j : 32 + s * dps * 16 + (j - 32));
-            cnt = q + 1;
-          } else {
-            off[q] = 0;
-          }
+          const int k = i / P, j = i % P;
+          off[q] = i < S * P ? k * 1056 + (j < 32 ? j : 32 + s * dps * 16 + (j - 32)) : -1;
         }
         uint32_t pw[6];
-        ll_wait_list<6>(p0, off, cnt, tag, pw, ok);
+        ll_wait_list<6>(p0, off, tag, pw, ok);
 #pragma unroll
         for (int q = 0; q < 6; ++q)
-          if (q < cnt) cb[tid + 256 * q] = __uint_as_float(pw[q]);
+          if (off[q] >= 0) cb[tid + 256 * q] = __uint_as_float(pw[q]);
       }
       __syncthreads();
       for (int qd = tid >> 4; qd < dps; qd += 16) {
@@ -653,10 +644,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
     }
     XSM_STAMP(l * 8 + 3);
-    // the FFN-down tile is 4x larger than the others: its fragments are requested here, two
-    // stages ahead of their use, rather than a layer ahead, to stay out of the attention
-    // stage's register budget
-    if (has_d) load_frags<KF>(wd, lt.W2, w - DN_BASE, KTF, wave * KF, lane);
+    if (has_q && l + 1 < a.L) load_frags<KD>(wq, sm.tab[l + 1].Wqkv, w, KTD, wave * KD, lane);
+    if (has_d) {
+      load_frags<KD>(wu, lt.W1, w, KTD, wave * KD, lane);
+      load_frags<KF>(wd, lt.W2, w - DN_BASE, KTF, wave * KF, lane);
+    }
 
     // ================= OPROJ =================
     if (has_o) {
@@ -669,7 +661,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wo[i]),
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wq[i]),
                                                       __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
       const float v = tile_reduce(sm, acc, wave, lane);
       if (row_in)
@@ -707,6 +699,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
     }
     XSM_STAMP(l * 8 + 5);
+    if (l + 1 < a.L && !has_d) {
+      if (has_o) load_frags<KD>(wq, sm.tab[l + 1].Wo, w - O_BASE, KTD, wave * KD, lane);
+      if (has_u) load_frags<KD>(wu, sm.tab[l + 1].W1, w, KTD, wave * KD, lane);
+    }
 
     // ================= DOWN =================
     if (has_d) {
@@ -728,14 +724,6 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         ll_st(lb + LS + OFF_X + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px) + v), tag);
     }
     XSM_STAMP(l * 8 + 6);
-    // next layer's projection tiles: requested now, a whole layer of dependency hops ahead of use
-    // (for the workgroups that just ran DOWN: right behind it, so the registers do not overlap)
-    if (l + 1 < a.L) {
-      if (has_q) load_frags<KD>(wq, sm.tab[l + 1].Wqkv, w, KTD, wave * KD, lane);
-      if (has_o) load_frags<KD>(wo, sm.tab[l + 1].Wo, w - O_BASE, KTD, wave * KD, lane);
-      if (has_u) load_frags<KD>(wu, sm.tab[l + 1].W1, w, KTD, wave * KD, lane);
-    }
-
     // a workgroup that timed out anywhere leaves (its consumers will time out in turn)
     if (__syncthreads_or(!ok)) {
       if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u + (uint32_t)l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -856,7 +844,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       for (int t = lane; t < NTV; t += 64) {
         const int off[3] = {0, 1, 2};
         uint32_t pw[3];
-        ll_wait_list<3>(tb + OFF_ST + ((size_t)t * 80 + grow) * 4, off, 3, tag, pw, ok);
+        ll_wait_list<3>(tb + OFF_ST + ((size_t)t * 80 + grow) * 4, off, tag, pw, ok);
         const float tv = __uint_as_float(pw[0]), ts = __uint_as_float(pw[2]);
         const int ti = (int)pw[1];
         if (tv > bv || (tv == bv && ti < bi)) { sv = fmaxf(bv, fmaxf(sv, ts)); bv = tv; bi = ti; }
