@@ -24,6 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this same command, scaled by a plain copy of known size (see profiles/ and the design doc);
+# measured for k_step_small on the default workload with --steps 60 (context 282..370), where the
+# algorithmic figure is 653 MB: 763.4 MB read + 96.1 MB written.
+TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 859.5e6}
 
 
 def algorithmic_bytes(cfg: dict, n_seq: int, sum_ctx: float) -> float:
@@ -71,6 +76,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy five times and exit (scale for the PMC byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (sequences are independent; "
@@ -87,6 +94,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         return 2
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.ones(n // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
+        return 0
     cfg = si.get_config(args.config)
     B, K, P = cfg["batch"], cfg["n_draft"], cfg["prefix"]
     R = K + 1
@@ -111,43 +127,44 @@ def main() -> int:
     run(args.warmup, 0)
     torch.cuda.synchronize()
     len0 = buf.kv_len.clone()
-    # ---- timed region: exactly `steps` steps, untraced ---------------------------------
+    # ---- timed region: exactly `steps` steps; every kernel launch is bracketed by a pair of HIP
+    # events recorded on the launch stream (two event records per launch)
+    xsm.xsm_debug_trace_enable(True)
+    xsm.xsm_debug_trace_report()                 # drop anything recorded so far
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(args.steps, args.warmup)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    trace = xsm.xsm_debug_trace_report()
+    xsm.xsm_debug_trace_enable(False)
     sec = t1 - t0
     len1 = buf.kv_len.clone()
+    eng.xsm_check_device()
     accepted = int((len1 - len0).sum())
     ms_per_step = 1e3 * sec / args.steps
     verified_tps = B * R * args.steps / sec
     mean_ctx = float((len0.float().mean() + len1.float().mean()) / 2)
 
-    # ---- same steps again with per-kernel HIP events (on the launch stream) ---------------
-    buf.kv_len.copy_(len0)
-    torch.cuda.synchronize()
-    xsm.xsm_debug_trace_enable(True)
-    tr_steps = min(args.steps, 200)
-    run(tr_steps, args.warmup)
-    trace = xsm.xsm_debug_trace_report()
-    xsm.xsm_debug_trace_enable(False)
-    dom = max(trace.items(), key=lambda kv: kv[1][1])
-    dom_name, (dom_cnt, dom_ms) = dom
+    dom_name, (dom_cnt, dom_ms) = max(trace.items(), key=lambda kv: kv[1][1])
     tot_ms = sum(v[1] for v in trace.values())
-    # dominant kernel class: algorithmic bytes it must move per step / its time per step
     step_bytes = algorithmic_bytes(cfg, B, B * mean_ctx)
-    kernels = {k: {"launches_per_step": v[0] / tr_steps, "us_per_step": round(1e3 * v[1] / tr_steps, 2)}
+    kernels = {k: {"launches_per_step": v[0] / args.steps, "us_per_launch": round(1e3 * v[1] / v[0], 2)}
                for k, v in sorted(trace.items(), key=lambda kv: -kv[1][1])}
     e = 2 if cfg["dtype"] == "bf16" else 4
     L, d, F, V = cfg["n_layers"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"]
-    gemm_bytes = e * (L * (4 * d * d + 2 * d * F) + V * d + K * d * d + V * d)
-    dom_bytes = gemm_bytes if dom_name == "gemm" else step_bytes
-    achieved = dom_bytes / (1e6 * dom_ms / tr_steps)           # GB/s
+    if dom_name == "step_small":       # the whole step is one kernel: all of the step's bytes
+        dom_bytes_per_launch = step_bytes
+    elif dom_name == "fgemm":          # every weight matrix once per step, spread over its launches
+        dom_bytes_per_launch = e * (L * (4 * d * d + 2 * d * F) + 2 * V * d + K * d * d) * args.steps / dom_cnt
+    else:
+        dom_bytes_per_launch = step_bytes * args.steps / dom_cnt
+    avg_us = 1e3 * dom_ms / dom_cnt
+    achieved = dom_bytes_per_launch / (1e3 * avg_us)           # GB/s
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 3),
-                "bytes_per_step": dom_bytes, "step_frac_whole": round(step_bytes / (1e6 * ms_per_step) / HBM_PEAK_GBS, 4)}
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(dom_name),
+                "avg_launch_us": round(avg_us, 3), "algorithmic_bytes_per_launch": int(dom_bytes_per_launch),
+                "launches_per_step": dom_cnt / args.steps}
 
     out = {"metric": "verified tok/s/GPU per spec step", "value": round(verified_tps, 1), "unit": "tok/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -158,8 +175,8 @@ def main() -> int:
                                   f"free-running generation",
                       "batch": B, "n_draft": K, "ctx_start": int(len0.max()), "ctx_end": int(len1.max())},
            "accepted_tok_per_s": round(accepted / sec, 1), "scr": round(accepted / (B * args.steps), 4),
-           "roofline": roofline, "kernels_us_per_step": kernels,
-           "traced_ms_per_step": round(tot_ms / tr_steps, 4)}
+           "roofline": roofline, "kernels": kernels,
+           "kernel_ms_per_step": round(tot_ms / args.steps, 4)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, prefix, first)
     print(json.dumps(out))
