@@ -71,6 +71,7 @@ void build_work_offsets(xsm_ctx* c) {
   w.rowidx = take(g.max_batch * 4);
   w.Qbf = take(Mmax * d * 2); w.AObf = take(Mmax * d * 2); w.Ubf = take(Mmax * F * 2);
   w.Rkbf = take((size_t)g.max_batch * (K ? K : 1) * d * 2);
+  w.Nbf = take(Mmax * d * 2);
   c->part_entries = (size_t)g.max_batch * g.n_heads;
   if (c->part_entries < 1024) c->part_entries = 1024;
   w.part = take(fattn_part_bytes(c->part_entries));
@@ -160,7 +161,7 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     FastGemm q{};
     q.Wt = (const uint4*)(c->d_w + T.Wqkv); q.N = 3 * d; q.K = d; q.M = M;
     q.X = X; q.ldx = d; q.gain = (const uint16_t*)P.g1; q.eps = g.rms_eps;
-    q.Ybf = Qbf; q.ldyb = d;
+    q.Ybf = Qbf; q.ldyb = d; q.nscratch = (uint16_t*)(ws + c->ws.Nbf);
     q.rope = rope; q.eff_len = eff; q.slot = slot; q.R = R; q.H = H; q.hd = hd; q.cap = c->cap_self;
     q.v_transposed = 1; q.Kc = (uint16_t*)self_cache(c, l, 0); q.Vc = (uint16_t*)self_cache(c, l, 1);
     launch_fgemm(PRO_NORM, FEPI_QKV, q, s);
@@ -175,14 +176,14 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
 
     FastGemm o{};
     o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
-    o.Abf = AObf; o.lda = d; o.Y = X; o.ldy = d;
+    o.Abf = AObf; o.lda = d; o.Y = X; o.ldy = d; o.nscratch = (uint16_t*)(ws + c->ws.Nbf);
     launch_fgemm(PRO_BF16, FEPI_ADD, o, s);
 
     if (g.n_cond > 0) {
       FastGemm cq{};
       cq.Wt = (const uint4*)(c->d_w + T.Wcq); cq.N = d; cq.K = d; cq.M = M;
       cq.X = X; cq.ldx = d; cq.gain = (const uint16_t*)P.gc; cq.eps = g.rms_eps;
-      cq.Ybf = Qbf; cq.ldyb = d;
+      cq.Ybf = Qbf; cq.ldyb = d; cq.nscratch = (uint16_t*)(ws + c->ws.Nbf);
       launch_fgemm(PRO_NORM, FEPI_BF16, cq, s);
       FastAttn ca = a;
       ca.Kc = (const uint16_t*)cross_cache(c, l, 0); ca.Vt = (const uint16_t*)cross_cache(c, l, 1);
@@ -196,12 +197,12 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     FastGemm u{};
     u.Wt = (const uint4*)(c->d_w + T.W1); u.N = F; u.K = d; u.M = M;
     u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
-    u.Ybf = Ubf; u.ldyb = F;
+    u.Ybf = Ubf; u.ldyb = F; u.nscratch = (uint16_t*)(ws + c->ws.Nbf);
     launch_fgemm(PRO_NORM, FEPI_GELU_BF16, u, s);
 
     FastGemm dn{};
     dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
-    dn.Abf = Ubf; dn.lda = F; dn.Y = X; dn.ldy = d;
+    dn.Abf = Ubf; dn.lda = F; dn.Y = X; dn.ldy = d; dn.nscratch = (uint16_t*)(ws + c->ws.Nbf);
     launch_fgemm(PRO_BF16, FEPI_ADD, dn, s);
   }
 }
@@ -331,7 +332,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     FastGemm z{};
     z.Wt = (const uint4*)(wb + ctx->toff.WU); z.N = V; z.K = d; z.M = M;
     z.X = X; z.ldx = d; z.gain = (const uint16_t*)(wb + ctx->woff.gf * e); z.eps = g.rms_eps;
-    z.Y = Z0; z.ldy = V;
+    z.Y = Z0; z.ldy = V; z.nscratch = (uint16_t*)(ws + ctx->ws.Nbf);
     launch_fgemm(PRO_NORM, FEPI_STORE, z, s);
     if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
     launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
@@ -343,10 +344,11 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
       hg.Wt = (const uint4*)(wb + ctx->toff.Wh); hg.N = K * d; hg.K = d; hg.M = n_seq;
       hg.X = X; hg.ldx = d; hg.gain = z.gain; hg.eps = g.rms_eps; hg.row_index = rowidx;
       hg.Ybf = Rkbf; hg.ldyb = K * d; hg.bias = (const uint16_t*)(wb + ctx->toff.hb);
+      hg.nscratch = (uint16_t*)(ws + ctx->ws.Nbf); hg.X32n = Xn;
       launch_fgemm(PRO_NORM, FEPI_HEAD, hg, s);
       FastGemm zh{};
       zh.Wt = z.Wt; zh.N = V; zh.K = d; zh.M = n_seq * K;
-      zh.Abf = Rkbf; zh.lda = d; zh.Y = Zh; zh.ldy = V;
+      zh.Abf = Rkbf; zh.lda = d; zh.Y = Zh; zh.ldy = V; zh.nscratch = (uint16_t*)(ws + ctx->ws.Nbf);
       launch_fgemm(PRO_BF16, FEPI_STORE, zh, s);
       if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     }

@@ -20,6 +20,7 @@ namespace xsm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kBigMinM = 32;        // rows above which the row-blocked kernel is used
 
 // ---------------------------------------------------------------------------
 // canonical [N][K] -> fragment-ordered tiles.  rope_hd > 0: the first two thirds of the
@@ -238,6 +239,182 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// Larger M (tens to a thousand rows): two 16-row weight tiles x 128 activation rows per
+// workgroup, activations staged through LDS in 256-wide slices of the contraction index and
+// shared by the four wavefronts, weight fragments streamed from global memory (HBM once,
+// then the XCD's L2: all row blocks of one weight tile pair are placed on the same XCD).
+// RMSNorm is done once per row by k_norm_bf16 instead of once per workgroup.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_norm_bf16(const float* X, int ldx, const int32_t* row_index,
+                                                   const uint16_t* gain, float eps, uint16_t* out,
+                                                   float* out32, int K) {
+  __shared__ float red[8];
+  const int m = blockIdx.x;
+  const float* x = X + (size_t)(row_index ? row_index[m] : m) * ldx;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < K; c += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(x + c);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)K + eps);
+  for (int c = threadIdx.x * 4; c < K; c += 1024) {
+    float4 v = *reinterpret_cast<const float4*>(x + c);
+    const uint2 gg = *reinterpret_cast<const uint2*>(gain + c);
+    v.x *= inv * __uint_as_float(gg.x << 16); v.y *= inv * __uint_as_float(gg.x & 0xFFFF0000u);
+    v.z *= inv * __uint_as_float(gg.y << 16); v.w *= inv * __uint_as_float(gg.y & 0xFFFF0000u);
+    *reinterpret_cast<uint2*>(out + (size_t)m * K + c) = uint2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
+    if (out32) *reinterpret_cast<float4*>(out32 + (size_t)m * K + c) = v;
+  }
+}
+
+constexpr int kBigKC = 256, kBigBM = 128;
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_big(const FastGemm g) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int ST = kBigKC + 8;
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int KT = g.K / 32;
+  const int MB = (g.M + kBigBM - 1) / kBigBM;
+  // workgroup ids go round-robin over the 8 XCDs: keep the row blocks of one weight tile pair together
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int nb = xcd + 8 * (q / MB), mb = q % MB;
+  const int nt = nb * 2 + (wave >> 1);                  // this wavefront's 16-row weight tile
+  const int mh = wave & 1;                              // its half of the 128 rows: 4 tiles of 16
+  const int m0 = mb * kBigBM;
+  const uint4* wbase = g.Wt + (size_t)nt * KT * 64 + lane;
+  f32x4 acc[4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kc0 = 0; kc0 < g.K; kc0 += kBigKC) {
+    const int kc = min(kBigKC, g.K - kc0);
+    uint4 wa[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (i * 32 < kc) wa[i] = wbase[(size_t)(kc0 / 32 + i) * 64];
+    __syncthreads();
+    for (int idx = tid; idx < kBigBM * (kc / 8); idx += 256) {
+      const int row = idx / (kc / 8), c8 = idx % (kc / 8);
+      uint4 v = uint4{0, 0, 0, 0};
+      if (m0 + row < g.M) v = *reinterpret_cast<const uint4*>(g.Abf + (size_t)(m0 + row) * g.lda + kc0 + c8 * 8);
+      *reinterpret_cast<uint4*>(As + (size_t)row * ST + c8 * 8) = v;
+    }
+    __syncthreads();
+    const uint16_t* arow = As + (size_t)(mh * 64 + (lane & 15)) * ST + (lane >> 4) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (i * 32 < kc) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, wa[i]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(arow + (size_t)mt * 16 * ST + i * 32));
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[mt], 0, 0, 0);
+        }
+      }
+  }
+
+  // lane holds D[n0 + i][m], i = 0..3, n0 = nt*16 + (lane>>4)*4, for each of its 4 row tiles
+  const int n0 = nt * 16 + (lane >> 4) * 4;
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+    const int m = m0 + (mh * 4 + mt) * 16 + (lane & 15);
+    if (EPI == FEPI_QKV) {
+      float pr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pr[i] = __shfl_xor(acc[mt][i], 32, WAVE);
+      if (m < g.M) {
+        const int b = m / g.R, j = m % g.R;
+        const int len = g.eff_len[b];
+        if (len >= 0) {
+          const int d = g.H * g.hd, tps = d / 16, tph = g.hd / 16, half = g.hd / 2;
+          const int sec = nt / tps, ts = nt % tps, h = ts / tph, tt = ts % tph;
+          const int pos = len + j;
+          const size_t head = (size_t)g.slot[b] * g.H + h;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int nrow = (lane >> 4) * 4 + i;
+            const float v = acc[mt][i];
+            float o = v;
+            int dim;
+            if (sec < 2) {
+              const int pi = tt * 8 + (nrow & 7);
+              const float2 cs = g.rope[(size_t)pos * half + pi];
+              if (nrow < 8) { dim = pi; o = v * cs.x - pr[i] * cs.y; }
+              else { dim = half + pi; o = pr[i] * cs.y + v * cs.x; }
+            } else {
+              dim = tt * 16 + nrow;
+            }
+            if (sec == 0) g.Ybf[(size_t)m * g.ldyb + h * g.hd + dim] = f2bf(o);
+            else if (sec == 1) g.Kc[(head * g.cap + pos) * g.hd + dim] = f2bf(o);
+            else if (g.v_transposed) g.Vc[(head * g.hd + dim) * g.cap + pos] = f2bf(o);
+            else g.Vc[(head * g.cap + pos) * g.hd + dim] = f2bf(o);
+          }
+        }
+      }
+    } else if (m < g.M) {
+      const f32x4 v = acc[mt];
+      if (EPI == FEPI_STORE) {
+        *reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0) = v;
+      } else if (EPI == FEPI_ADD) {
+        f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
+        *y = *y + v;
+      } else if (EPI == FEPI_GELU_BF16) {
+        *reinterpret_cast<uint2*>(g.Ybf + (size_t)m * g.ldyb + n0) =
+            uint2{pack_bf16(gelu_erf_f(v[0]), gelu_erf_f(v[1])), pack_bf16(gelu_erf_f(v[2]), gelu_erf_f(v[3]))};
+      } else if (EPI == FEPI_BF16) {
+        *reinterpret_cast<uint2*>(g.Ybf + (size_t)m * g.ldyb + n0) = uint2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+      } else if (EPI == FEPI_HEAD) {
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int n = n0 + i, c = n % g.K;
+          const float pre = v[i] + bf2f(g.bias[n]);
+          o[i] = g.X32n[(size_t)m * g.K + c] + pre / (1.0f + __expf(-pre));
+        }
+        *reinterpret_cast<uint2*>(g.Ybf + (size_t)m * g.ldyb + n0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+      }
+    }
+  }
+}
+
+template <int EPI>
+static void big_launch(const FastGemm& g, hipStream_t s) {
+  const int MB = (g.M + kBigBM - 1) / kBigBM;
+  const size_t lds = (size_t)kBigBM * (kBigKC + 8) * 2;
+  auto kfn = k_gemm_big<EPI>;
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured = true;
+  }
+  hipLaunchKernelGGL(kfn, dim3((g.N / 32) * MB), dim3(256), lds, s, g);
+}
+
+static bool big_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
+  if (g.M <= kBigMinM || g.N % 256 != 0 || !g.nscratch) return false;
+  if (pro == PRO_F32) return false;
+  if (pro == PRO_NORM) {
+    hipLaunchKernelGGL(k_norm_bf16, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
+                       g.nscratch, epi == FEPI_HEAD ? g.X32n : nullptr, g.K);
+    g.Abf = g.nscratch; g.lda = g.K;
+  }
+  switch (epi) {
+    case FEPI_STORE: big_launch<FEPI_STORE>(g, s); break;
+    case FEPI_ADD: big_launch<FEPI_ADD>(g, s); break;
+    case FEPI_GELU_BF16: big_launch<FEPI_GELU_BF16>(g, s); break;
+    case FEPI_QKV: big_launch<FEPI_QKV>(g, s); break;
+    case FEPI_HEAD: big_launch<FEPI_HEAD>(g, s); break;
+    case FEPI_BF16: big_launch<FEPI_BF16>(g, s); break;
+    default: return false;
+  }
+  return true;
+}
+
 static size_t fgemm_lds(int MT, int KC) {
   return (size_t)16 * MT * (KC + 8) * 2 + (size_t)4 * MT * 256 * 4 + (size_t)16 * MT * 4;
 }
@@ -269,8 +446,12 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 }
 
 void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
-  TraceScope trace_("fgemm", s);
   if (g.M <= 0) return;
+  if (g.M > kBigMinM) {
+    TraceScope trace_("gemm_big", s);
+    if (big_gemm(pro, epi, g, s)) return;
+  }
+  TraceScope trace_("fgemm", s);
   if (pro == PRO_NORM && epi == FEPI_QKV) fgemm_launch<PRO_NORM, FEPI_QKV>(g, s);
   else if (pro == PRO_NORM && epi == FEPI_STORE) fgemm_launch<PRO_NORM, FEPI_STORE>(g, s);
   else if (pro == PRO_NORM && epi == FEPI_GELU_BF16) fgemm_launch<PRO_NORM, FEPI_GELU_BF16>(g, s);

@@ -27,7 +27,7 @@ struct WeightOff {
 struct WorkOff {
   size_t X, Xn, QKV, Qr, AO, U, Z0, G, Hh, Rk, Zh;
   size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
-  size_t Qbf, AObf, Ubf, Rkbf;                           // bf16 activations of the MFMA path
+  size_t Qbf, AObf, Ubf, Rkbf, Nbf;                      // bf16 activations of the MFMA path
   size_t part, tickets;                                  // split-key attention partials
   size_t ll, ctrl, head_all, tlog;                       // single-launch step: exchange buffers
   size_t total;
@@ -136,6 +136,8 @@ struct FastGemm {
   float* Y; int ldy;           // fp32 output (STORE, ADD)
   uint16_t* Ybf; int ldyb;     // bf16 output (GELU, HEAD, q of QKV)
   const uint16_t* bias;        // FEPI_HEAD: stacked biases [N]
+  uint16_t* nscratch;          // [M][K] bf16: normalised rows for the row-blocked kernel
+  float* X32n;                 // [M][K] fp32 normalised rows (FEPI_HEAD residual on that kernel)
   // FEPI_QKV
   const float2* rope; const int32_t* eff_len; const int32_t* slot;
   int R, H, hd, cap, v_transposed;

@@ -180,6 +180,18 @@ def test_config1_shape_bf16(X):
     _report(tal, "c1 lockstep")
 
 
+def test_large_batch_row_blocked_gemm(X):
+    """M = 200 block rows and 40 head rows: the row-blocked MFMA GEMM (all epilogues), ragged lengths."""
+    cfg = _mid_cfg(seed=29, vocab=1024, n_layers=2)
+    lens = [37 - (b % 9) * 3 for b in range(40)]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 40, prefix_lens=lens)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 40))
+    _report(tal, "B40 row-blocked")
+    vp = VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=77)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 2, si.first_block(cfg, 40))
+    _report(tal, "B40 row-blocked top-8")
+
+
 def _c1_small(**kw):
     """The latency model's shape (d=1024, FFN 4096, 16 heads, vocab 4096) with few layers: the
     shape the single-launch step kernel is built for."""
