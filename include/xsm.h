@@ -177,6 +177,10 @@ XSM_API int xsm_debug_kv_export(xsm_ctx* ctx, int32_t layer, int32_t which, int3
 XSM_API int xsm_debug_kv_import(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, int32_t pos0,
                         int32_t n_pos, const float* h_in);
 
+/* Test only, synchronous: copy every layer's cache contents (self- and cross-attention) of
+ * slot src to slot dst, device to device. */
+XSM_API int xsm_debug_kv_clone(xsm_ctx* ctx, int32_t src_slot, int32_t dst_slot);
+
 /* Benchmark only: per-kernel timing with HIP events recorded on the launch stream around
  * every kernel the library enqueues (process-wide switch, off by default; adds two event
  * records per launch).  xsm_debug_trace_report synchronises the device, writes one text line

@@ -69,9 +69,6 @@ void build_work_offsets(xsm_ctx* c) {
   w.y0 = take(g.max_batch * 4); w.wflags = take(g.max_batch * 4);
   w.toks = take((size_t)g.max_batch * kMaxRows * 4);
   w.rowidx = take(g.max_batch * 4);
-  w.Qbf = take(Mmax * d * 2); w.AObf = take(Mmax * d * 2); w.Ubf = take(Mmax * F * 2);
-  w.Rkbf = take((size_t)g.max_batch * (K ? K : 1) * d * 2);
-  w.Nbf = take(Mmax * d * 2);
   c->part_entries = (size_t)g.max_batch * g.n_heads;
   if (c->part_entries < 1024) c->part_entries = 1024;
   w.part = take(fattn_part_bytes(c->part_entries));
@@ -148,9 +145,10 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
   const int M = n_seq * R;
   char* ws = c->d_ws;
   float* X = (float*)(ws + c->ws.X);
-  uint16_t* Qbf = (uint16_t*)(ws + c->ws.Qbf);
-  uint16_t* AObf = (uint16_t*)(ws + c->ws.AObf);
-  uint16_t* Ubf = (uint16_t*)(ws + c->ws.Ubf);
+  float* Xn = (float*)(ws + c->ws.Xn);            // normalised rows of the row-blocked GEMM
+  float* Qr = (float*)(ws + c->ws.Qr);
+  float* AO = (float*)(ws + c->ws.AO);
+  float* U = (float*)(ws + c->ws.U);
   const int32_t* eff = (const int32_t*)(ws + c->ws.eff_len);
   const int32_t* slot = (const int32_t*)(ws + c->ws.slot);
   const float2* rope = (const float2*)(c->d_w + c->rope_off);
@@ -161,14 +159,14 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     FastGemm q{};
     q.Wt = (const uint4*)(c->d_w + T.Wqkv); q.N = 3 * d; q.K = d; q.M = M;
     q.X = X; q.ldx = d; q.gain = (const uint16_t*)P.g1; q.eps = g.rms_eps;
-    q.Ybf = Qbf; q.ldyb = d; q.nscratch = (uint16_t*)(ws + c->ws.Nbf);
+    q.Y = Qr; q.ldy = d; q.nscratch = Xn;
     q.rope = rope; q.eff_len = eff; q.slot = slot; q.R = R; q.H = H; q.hd = hd; q.cap = c->cap_self;
     q.v_transposed = 1; q.Kc = (uint16_t*)self_cache(c, l, 0); q.Vc = (uint16_t*)self_cache(c, l, 1);
     launch_fgemm(PRO_NORM, FEPI_QKV, q, s);
 
     FastAttn a{};
-    a.Q = Qbf; a.ldq = d; a.Kc = (const uint16_t*)self_cache(c, l, 0); a.Vt = (const uint16_t*)self_cache(c, l, 1);
-    a.eff_len = eff; a.slot = slot; a.O = AObf; a.ldo = d;
+    a.Q = Qr; a.ldq = d; a.Kc = (const uint16_t*)self_cache(c, l, 0); a.Vt = (const uint16_t*)self_cache(c, l, 1);
+    a.eff_len = eff; a.slot = slot; a.O = AO; a.ldo = d;
     a.part = (float*)(ws + c->ws.part); a.tickets = (uint32_t*)(ws + c->ws.tickets);
     a.R = R; a.H = H; a.cap = c->cap_self; a.S = attn_splits(c, n_seq, len_bound + R); a.fixed_limit = 0;
     a.scale_log2 = scale_log2;
@@ -176,34 +174,34 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
 
     FastGemm o{};
     o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
-    o.Abf = AObf; o.lda = d; o.Y = X; o.ldy = d; o.nscratch = (uint16_t*)(ws + c->ws.Nbf);
-    launch_fgemm(PRO_BF16, FEPI_ADD, o, s);
+    o.X = AO; o.ldx = d; o.Y = X; o.ldy = d; o.nscratch = Xn;
+    launch_fgemm(PRO_F32, FEPI_ADD, o, s);
 
     if (g.n_cond > 0) {
       FastGemm cq{};
       cq.Wt = (const uint4*)(c->d_w + T.Wcq); cq.N = d; cq.K = d; cq.M = M;
       cq.X = X; cq.ldx = d; cq.gain = (const uint16_t*)P.gc; cq.eps = g.rms_eps;
-      cq.Ybf = Qbf; cq.ldyb = d; cq.nscratch = (uint16_t*)(ws + c->ws.Nbf);
-      launch_fgemm(PRO_NORM, FEPI_BF16, cq, s);
+      cq.Y = Qr; cq.ldy = d; cq.nscratch = Xn;
+      launch_fgemm(PRO_NORM, FEPI_STORE, cq, s);
       FastAttn ca = a;
       ca.Kc = (const uint16_t*)cross_cache(c, l, 0); ca.Vt = (const uint16_t*)cross_cache(c, l, 1);
       ca.cap = c->cap_cross; ca.fixed_limit = g.n_cond; ca.S = attn_splits(c, n_seq, g.n_cond);
       launch_fattn(ca, n_seq, s);
       FastGemm co = o;
       co.Wt = (const uint4*)(c->d_w + T.Wco);
-      launch_fgemm(PRO_BF16, FEPI_ADD, co, s);
+      launch_fgemm(PRO_F32, FEPI_ADD, co, s);
     }
 
     FastGemm u{};
     u.Wt = (const uint4*)(c->d_w + T.W1); u.N = F; u.K = d; u.M = M;
     u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
-    u.Ybf = Ubf; u.ldyb = F; u.nscratch = (uint16_t*)(ws + c->ws.Nbf);
-    launch_fgemm(PRO_NORM, FEPI_GELU_BF16, u, s);
+    u.Y = U; u.ldy = F; u.nscratch = Xn;
+    launch_fgemm(PRO_NORM, FEPI_GELU, u, s);
 
     FastGemm dn{};
     dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
-    dn.Abf = Ubf; dn.lda = F; dn.Y = X; dn.ldy = d; dn.nscratch = (uint16_t*)(ws + c->ws.Nbf);
-    launch_fgemm(PRO_BF16, FEPI_ADD, dn, s);
+    dn.X = U; dn.ldx = F; dn.Y = X; dn.ldy = d; dn.nscratch = Xn;
+    launch_fgemm(PRO_F32, FEPI_ADD, dn, s);
   }
 }
 
@@ -332,24 +330,23 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     FastGemm z{};
     z.Wt = (const uint4*)(wb + ctx->toff.WU); z.N = V; z.K = d; z.M = M;
     z.X = X; z.ldx = d; z.gain = (const uint16_t*)(wb + ctx->woff.gf * e); z.eps = g.rms_eps;
-    z.Y = Z0; z.ldy = V; z.nscratch = (uint16_t*)(ws + ctx->ws.Nbf);
+    z.Y = Z0; z.ldy = V; z.nscratch = Xn;
     launch_fgemm(PRO_NORM, FEPI_STORE, z, s);
     if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
     launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
     if (K > 0) {
       int32_t* rowidx = (int32_t*)(ws + ctx->ws.rowidx);
-      uint16_t* Rkbf = (uint16_t*)(ws + ctx->ws.Rkbf);
       launch_head_rows(acc, rowidx, n_seq, R, s);
       FastGemm hg{};                               // all K heads at once: [K*d][d] stacked
       hg.Wt = (const uint4*)(wb + ctx->toff.Wh); hg.N = K * d; hg.K = d; hg.M = n_seq;
       hg.X = X; hg.ldx = d; hg.gain = z.gain; hg.eps = g.rms_eps; hg.row_index = rowidx;
-      hg.Ybf = Rkbf; hg.ldyb = K * d; hg.bias = (const uint16_t*)(wb + ctx->toff.hb);
-      hg.nscratch = (uint16_t*)(ws + ctx->ws.Nbf); hg.X32n = Xn;
+      hg.Y = Rk; hg.ldy = K * d; hg.bias = (const uint16_t*)(wb + ctx->toff.hb);
+      hg.nscratch = Xn;
       launch_fgemm(PRO_NORM, FEPI_HEAD, hg, s);
       FastGemm zh{};
       zh.Wt = z.Wt; zh.N = V; zh.K = d; zh.M = n_seq * K;
-      zh.Abf = Rkbf; zh.lda = d; zh.Y = Zh; zh.ldy = V; zh.nscratch = (uint16_t*)(ws + ctx->ws.Nbf);
-      launch_fgemm(PRO_BF16, FEPI_STORE, zh, s);
+      zh.X = Rk; zh.ldx = d; zh.Y = Zh; zh.ldy = V; zh.nscratch = Xn;
+      launch_fgemm(PRO_F32, FEPI_STORE, zh, s);
       if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     }
   } else {
@@ -624,6 +621,29 @@ static int kv_debug(xsm_ctx* ctx, int32_t layer, int32_t which, int32_t slot, in
                (size_t)np * g.head_dim * 4);
     }
   }
+  return XSM_OK;
+}
+
+int xsm_debug_kv_clone(xsm_ctx* ctx, int32_t src_slot, int32_t dst_slot) {
+  if (!ctx) return XSM_EINVAL;
+  if (!ctx->d_kv) return fail(ctx, XSM_ESTATE, "buffers not bound");
+  const xsm_config& g = ctx->cfg;
+  if (src_slot < 0 || dst_slot < 0 || src_slot >= g.max_batch || dst_slot >= g.max_batch)
+    return fail(ctx, XSM_EINVAL, "slot out of range");
+  XSM_HIP(hipDeviceSynchronize());
+  if (src_slot == dst_slot) return XSM_OK;
+  for (int l = 0; l < g.n_layers; ++l)
+    for (int which = 0; which < 2; ++which) {
+      const size_t per = (size_t)g.n_heads * ctx->cap_self * g.head_dim * ctx->esz;
+      char* base = self_cache(ctx, l, which);
+      XSM_HIP(hipMemcpy(base + dst_slot * per, base + src_slot * per, per, hipMemcpyDeviceToDevice));
+      if (g.n_cond > 0) {
+        const size_t perc = (size_t)g.n_heads * ctx->cap_cross * g.head_dim * ctx->esz;
+        char* cb = cross_cache(ctx, l, which);
+        XSM_HIP(hipMemcpy(cb + dst_slot * perc, cb + src_slot * perc, perc, hipMemcpyDeviceToDevice));
+      }
+    }
+  XSM_HIP(hipDeviceSynchronize());
   return XSM_OK;
 }
 

@@ -10,7 +10,9 @@
 // A wavefront takes 64 keys at a time.  The 16-key score tiles are formed from keys
 // {g*16 + t*4 + i}, so that the probabilities a lane holds after the first product are
 // exactly the 16 consecutive keys it must supply as the "B" operand of the second one, and no
-// cross-lane movement is needed.  Online softmax in fp32 (base 2); the key range of one
+// cross-lane movement is needed.  The fp32 queries and probabilities enter the MFMAs as bf16
+// hi + lo operand pairs, so the only bf16 rounding left in attention is the cache's own.
+// Online softmax in fp32 (base 2); the key range of one
 // (sequence, head) is split over S workgroups whose partial (max, sum, O) are merged in
 // fixed order by the last one to finish.
 #include "xsm_device.h"
@@ -31,6 +33,12 @@ __device__ __forceinline__ float ld_coherent(const float* p) {
 }
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+}
+
+// (a, b) -> packed bf16 pair of the rounded values and of what the rounding dropped
+__device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {
+  hi = pack2(a, b);
+  lo = pack2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 
 __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
@@ -58,13 +66,23 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   const int lim = r < R ? (a.fixed_limit > 0 ? Ltot : n + r + 1) : 0;
   const int first_masked = a.fixed_limit > 0 ? Ltot : n + 1;     // below this every live query sees the key
 
-  uint4 qf[2] = {uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
-  if (r < R) {
-    const uint16_t* q = a.Q + (size_t)(b * R + r) * a.ldq + h * 64 + g * 8;
-    qf[0] = *reinterpret_cast<const uint4*>(q);
-    qf[1] = *reinterpret_cast<const uint4*>(q + 32);
+  // query operand halves (dims g*8.. and 32 + g*8..), each as bf16 hi and lo parts
+  bf16x8 qh[2], ql[2];
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    float qv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (r < R) {
+      const float* q = a.Q + (size_t)(b * R + r) * a.ldq + h * 64 + half * 32 + g * 8;
+      const float4 x0 = *reinterpret_cast<const float4*>(q), x1 = *reinterpret_cast<const float4*>(q + 4);
+      qv[0] = x0.x; qv[1] = x0.y; qv[2] = x0.z; qv[3] = x0.w;
+      qv[4] = x1.x; qv[5] = x1.y; qv[6] = x1.z; qv[7] = x1.w;
+    }
+    uint32_t hw[4], lw[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split2(qv[2 * e], qv[2 * e + 1], hw[e], lw[e]);
+    qh[half] = __builtin_bit_cast(bf16x8, uint4{hw[0], hw[1], hw[2], hw[3]});
+    ql[half] = __builtin_bit_cast(bf16x8, uint4{lw[0], lw[1], lw[2], lw[3]});
   }
-  const bf16x8 q0 = __builtin_bit_cast(bf16x8, qf[0]), q1 = __builtin_bit_cast(bf16x8, qf[1]);
 
   float m_run = -INFINITY, l_run = 0.f;
   f32x4 o[4];
@@ -89,9 +107,13 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
     f32x4 sc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][0]), q0,
-                                                      f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-      sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][1]), q1, sc[t], 0, 0, 0);
+      sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const bf16x8 kk = __builtin_bit_cast(bf16x8, kf[t][half]);
+        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[half], sc[t], 0, 0, 0);
+        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[half], sc[t], 0, 0, 0);
+      }
     }
     // this lane's 16 scores belong to keys key0 + g*16 + t*4 + i
     const int kbase = key0 + g * 16;
@@ -138,17 +160,22 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
           }
         }
     }
-    uint4 pf[2];
+    uint4 ph[2], pl[2];
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-      pf[jj] = uint4{pack2(sc[2 * jj][0], sc[2 * jj][1]), pack2(sc[2 * jj][2], sc[2 * jj][3]),
-                     pack2(sc[2 * jj + 1][0], sc[2 * jj + 1][1]), pack2(sc[2 * jj + 1][2], sc[2 * jj + 1][3])};
+    for (int jj = 0; jj < 2; ++jj) {
+      split2(sc[2 * jj][0], sc[2 * jj][1], ph[jj].x, pl[jj].x);
+      split2(sc[2 * jj][2], sc[2 * jj][3], ph[jj].y, pl[jj].y);
+      split2(sc[2 * jj + 1][0], sc[2 * jj + 1][1], ph[jj].z, pl[jj].z);
+      split2(sc[2 * jj + 1][2], sc[2 * jj + 1][3], ph[jj].w, pl[jj].w);
+    }
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
-        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt][jj]),
-                                                        __builtin_bit_cast(bf16x8, pf[jj]), o[dt], 0, 0, 0);
+      for (int jj = 0; jj < 2; ++jj) {
+        const bf16x8 vv = __builtin_bit_cast(bf16x8, vf[dt][jj]);
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, pl[jj]), o[dt], 0, 0, 0);
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, ph[jj]), o[dt], 0, 0, 0);
+      }
   }
 
   // merge the four wavefronts (fixed order); wavefront w finishes dim tile w
@@ -172,8 +199,8 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   if (S == 1) {
     if (r < R) {
       const float inv = 1.0f / L;
-      uint16_t* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
-      *reinterpret_cast<uint2*>(dst) = uint2{pack2(acc[0] * inv, acc[1] * inv), pack2(acc[2] * inv, acc[3] * inv)};
+      float* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
+      *reinterpret_cast<float4*>(dst) = float4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
     }
     return;
   }
@@ -207,8 +234,8 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   }
   if (r < R) {
     const float inv = 1.0f / Lg;
-    uint16_t* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
-    *reinterpret_cast<uint2*>(dst) = uint2{pack2(og[0] * inv, og[1] * inv), pack2(og[2] * inv, og[3] * inv)};
+    float* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
+    *reinterpret_cast<float4*>(dst) = float4{og[0] * inv, og[1] * inv, og[2] * inv, og[3] * inv};
   }
 }
 

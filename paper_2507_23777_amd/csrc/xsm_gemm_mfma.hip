@@ -74,13 +74,49 @@ __device__ __forceinline__ float gelu_erf_f(float x) {
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
 }
+// An fp32 activation enters the bf16 MFMA as two operands, hi = bf16(x) and lo = bf16(x - hi),
+// multiplied against the same weight fragment: the activation keeps ~16 mantissa bits, so what
+// is left of the bf16 format in a projection is the weights' own rounding (which the model
+// definition shares).  At these M the second MFMA is free.
+__device__ __forceinline__ void split4(const float4 v, uint2& hi, uint2& lo) {
+  hi = uint2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
+  lo = uint2{pack_bf16(v.x - __uint_as_float(hi.x << 16), v.y - __uint_as_float(hi.x & 0xFFFF0000u)),
+             pack_bf16(v.z - __uint_as_float(hi.y << 16), v.w - __uint_as_float(hi.y & 0xFFFF0000u))};
+}
+
+// shared epilogue of the fused QKV projection for one element: rotary pair (v, partner), then
+// q to the fp32 query buffer, k / v to the bf16 cache
+__device__ __forceinline__ void qkv_store(const FastGemm& g, int nt, int nrow, int m, float v, float partner) {
+  const int b = m / g.R, j = m % g.R;
+  const int len = g.eff_len[b];
+  if (len < 0) return;
+  const int d = g.H * g.hd, tps = d / 16, tph = g.hd / 16, half = g.hd / 2;
+  const int sec = nt / tps, ts = nt % tps, h = ts / tph, tt = ts % tph;
+  const int pos = len + j;
+  int dim;
+  float o = v;
+  if (sec < 2) {
+    const int pi = tt * 8 + (nrow & 7);
+    const float2 cs = g.rope[(size_t)pos * half + pi];
+    if (nrow < 8) { dim = pi; o = v * cs.x - partner * cs.y; }
+    else { dim = half + pi; o = partner * cs.y + v * cs.x; }
+  } else {
+    dim = tt * 16 + nrow;
+  }
+  const size_t head = (size_t)g.slot[b] * g.H + h;
+  if (sec == 0) g.Y[(size_t)m * g.ldy + h * g.hd + dim] = o;
+  else if (sec == 1) g.Kc[(head * g.cap + pos) * g.hd + dim] = f2bf(o);
+  else if (g.v_transposed) g.Vc[(head * g.hd + dim) * g.cap + pos] = f2bf(o);
+  else g.Vc[(head * g.cap + pos) * g.hd + dim] = f2bf(o);
+}
 
 template <int PRO, int EPI, int MT>
 __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int KC = g.KC, stride = KC + 8;                 // LDS row stride in bf16 elements
+  const size_t plane = (size_t)16 * MT * stride;        // hi plane, then lo plane
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);
-  float* red = reinterpret_cast<float*>(smem + (size_t)16 * MT * stride * 2);
+  float* red = reinterpret_cast<float*>(smem + 2 * plane * 2);
   float* srms = red + 4 * MT * 256;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nt = blockIdx.x, KT = g.K / 32;
@@ -118,16 +154,15 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
         }
         __syncthreads();
       }
-      // stage the activation chunk as bf16
+      // stage the activation chunk as bf16 hi / lo planes
       for (int r = wave; r < 16 * MT; r += 4) {
         const int m = m0 + r;
         uint16_t* dst = As + (size_t)r * stride;
         if (m >= g.M) {
-          for (int c = lane * 8; c < kc; c += 512) *reinterpret_cast<uint4*>(dst + c) = uint4{0, 0, 0, 0};
-        } else if (PRO == PRO_BF16) {
-          const uint16_t* a = g.Abf + (size_t)m * g.lda + kc0;
-          for (int c = lane * 8; c < kc; c += 512)
-            *reinterpret_cast<uint4*>(dst + c) = *reinterpret_cast<const uint4*>(a + c);
+          for (int c = lane * 4; c < kc; c += 256) {
+            *reinterpret_cast<uint2*>(dst + c) = uint2{0, 0};
+            *reinterpret_cast<uint2*>(dst + plane + c) = uint2{0, 0};
+          }
         } else {
           const float* x = g.X + (size_t)(g.row_index ? g.row_index[m] : m) * g.ldx + kc0;
           const float sc = PRO == PRO_NORM ? srms[r] : 1.0f;
@@ -138,42 +173,40 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
               v.x *= sc * __uint_as_float(gg.x << 16); v.y *= sc * __uint_as_float(gg.x & 0xFFFF0000u);
               v.z *= sc * __uint_as_float(gg.y << 16); v.w *= sc * __uint_as_float(gg.y & 0xFFFF0000u);
             }
-            *reinterpret_cast<uint2*>(dst + c) = uint2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
+            uint2 hi, lo;
+            split4(v, hi, lo);
+            *reinterpret_cast<uint2*>(dst + c) = hi;
+            *reinterpret_cast<uint2*>(dst + plane + c) = lo;
           }
         }
       }
       __syncthreads();
 
-      const uint16_t* arow = As + (size_t)(lane & 15) * stride + (lane >> 4) * 8 - kc0;
+      const uint16_t* arow = As + (size_t)(lane & 15) * stride + (lane >> 4) * 8;
+      auto mac = [&](const uint4& wfrag, int kt) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, wfrag);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint16_t* bp = arow + (size_t)mt * 16 * stride + (kt * 32 - kc0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              a, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp)), acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              a, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + plane)), acc[mt], 0, 0, 0);
+        }
+      };
       for (int kt = kt_lo; kt < kt_hi; kt += 16) {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
           if (kt + 8 + i < kt_hi) wb[i] = wbase[(size_t)(kt + 8 + i) * 64];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-          if (kt + i < kt_hi) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, wa[i]);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              const bf16x8 b = __builtin_bit_cast(
-                  bf16x8, *reinterpret_cast<const uint4*>(arow + (size_t)mt * 16 * stride + (kt + i) * 32));
-              acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[mt], 0, 0, 0);
-            }
-          }
+          if (kt + i < kt_hi) mac(wa[i], kt + i);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
           if (kt + 16 + i < kt_hi) wa[i] = wbase[(size_t)(kt + 16 + i) * 64];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-          if (kt + 8 + i < kt_hi) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, wb[i]);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              const bf16x8 b = __builtin_bit_cast(
-                  bf16x8, *reinterpret_cast<const uint4*>(arow + (size_t)mt * 16 * stride + (kt + 8 + i) * 32));
-              acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[mt], 0, 0, 0);
-            }
-          }
+          if (kt + 8 + i < kt_hi) mac(wb[i], kt + 8 + i);
       }
     }
 
@@ -193,63 +226,33 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
       const int m = m0 + mt * 16 + mcol;
       if (EPI == FEPI_QKV) {
         const float partner = __shfl_xor(v, 32, WAVE);    // row nrow +- 8 of the same tile
-        if (m < g.M) {
-          const int b = m / g.R, j = m % g.R;
-          const int len = g.eff_len[b];
-          if (len >= 0) {
-            const int d = g.H * g.hd, tps = d / 16, tph = g.hd / 16, half = g.hd / 2;
-            const int sec = nt / tps, ts = nt % tps, h = ts / tph, tt = ts % tph;
-            const int pos = len + j;
-            int dim;
-            float o = v;
-            if (sec < 2) {
-              const int pi = tt * 8 + (nrow & 7);
-              const float2 cs = g.rope[(size_t)pos * half + pi];
-              if (nrow < 8) { dim = pi; o = v * cs.x - partner * cs.y; }
-              else { dim = half + pi; o = partner * cs.y + v * cs.x; }
-            } else {
-              dim = tt * 16 + nrow;
-            }
-            if (sec == 0) {
-              g.Ybf[(size_t)m * g.ldyb + h * g.hd + dim] = f2bf(o);
-            } else if (sec == 1) {
-              g.Kc[(((size_t)g.slot[b] * g.H + h) * g.cap + pos) * g.hd + dim] = f2bf(o);
-            } else if (g.v_transposed) {
-              g.Vc[(((size_t)g.slot[b] * g.H + h) * g.hd + dim) * g.cap + pos] = f2bf(o);
-            } else {
-              g.Vc[(((size_t)g.slot[b] * g.H + h) * g.cap + pos) * g.hd + dim] = f2bf(o);
-            }
-          }
-        }
+        if (m < g.M) qkv_store(g, nt, nrow, m, v, partner);
       } else if (m < g.M) {
         if (EPI == FEPI_STORE) g.Y[(size_t)m * g.ldy + n] = v;
         else if (EPI == FEPI_ADD) g.Y[(size_t)m * g.ldy + n] += v;
-        else if (EPI == FEPI_GELU_BF16) g.Ybf[(size_t)m * g.ldyb + n] = f2bf(gelu_erf_f(v));
-        else if (EPI == FEPI_BF16) g.Ybf[(size_t)m * g.ldyb + n] = f2bf(v);
+        else if (EPI == FEPI_GELU) g.Y[(size_t)m * g.ldy + n] = gelu_erf_f(v);
         else if (EPI == FEPI_HEAD) {
           // n = k*d + c: head k, column c; r = g + SiLU(y + b_k[c]) with g the normalised row
           const int c = n % g.K;
           const float pre = v + bf2f(g.bias[n]);
           const float x = g.X[(size_t)(g.row_index ? g.row_index[m] : m) * g.ldx + c];
           const float gn = x * bf2f(g.gain[c]) * srms[mt * 16 + mcol];
-          g.Ybf[(size_t)m * g.ldyb + n] = f2bf(gn + pre / (1.0f + __expf(-pre)));
+          g.Y[(size_t)m * g.ldy + n] = gn + pre / (1.0f + __expf(-pre));
         }
       }
     }
   }
 }
 
-
 // ---------------------------------------------------------------------------
-// Larger M (tens to a thousand rows): two 16-row weight tiles x 128 activation rows per
-// workgroup, activations staged through LDS in 256-wide slices of the contraction index and
-// shared by the four wavefronts, weight fragments streamed from global memory (HBM once,
-// then the XCD's L2: all row blocks of one weight tile pair are placed on the same XCD).
-// RMSNorm is done once per row by k_norm_bf16 instead of once per workgroup.
+// Larger M (tens to a thousand rows): two 16-row weight tiles x 64 or 128 activation rows per
+// workgroup, activations staged through LDS (hi / lo planes) in 128-wide slices of the
+// contraction index and shared by the four wavefronts, weight fragments streamed from global
+// memory (HBM once, then the XCD's L2: all row blocks of one weight tile pair are placed on the
+// same XCD).  RMSNorm is done once per row by k_norm_rows instead of once per workgroup.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_norm_bf16(const float* X, int ldx, const int32_t* row_index,
-                                                   const uint16_t* gain, float eps, uint16_t* out,
-                                                   float* out32, int K) {
+__global__ __launch_bounds__(256) void k_norm_rows(const float* X, int ldx, const int32_t* row_index,
+                                                   const uint16_t* gain, float eps, float* out, int K) {
   __shared__ float red[8];
   const int m = blockIdx.x;
   const float* x = X + (size_t)(row_index ? row_index[m] : m) * ldx;
@@ -265,165 +268,170 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* X, int ldx, cons
     const uint2 gg = *reinterpret_cast<const uint2*>(gain + c);
     v.x *= inv * __uint_as_float(gg.x << 16); v.y *= inv * __uint_as_float(gg.x & 0xFFFF0000u);
     v.z *= inv * __uint_as_float(gg.y << 16); v.w *= inv * __uint_as_float(gg.y & 0xFFFF0000u);
-    *reinterpret_cast<uint2*>(out + (size_t)m * K + c) = uint2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
-    if (out32) *reinterpret_cast<float4*>(out32 + (size_t)m * K + c) = v;
+    *reinterpret_cast<float4*>(out + (size_t)m * K + c) = v;
   }
 }
 
-constexpr int kBigKC = 256, kBigBM = 128;
+constexpr int kBigKC = 128;
 
-template <int EPI>
+// MTW: 16-row activation tiles per wavefront; a workgroup covers BM = 32*MTW rows
+// (two wavefronts per weight tile, each taking half of the rows) and two weight tiles.
+template <int EPI, int MTW>
 __global__ __launch_bounds__(256) void k_gemm_big(const FastGemm g) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int ST = kBigKC + 8;
+  constexpr int ST = kBigKC + 8, BM = 32 * MTW;
+  constexpr int NPF = BM * (kBigKC / 4) / 256;          // float4 pieces of one slice per thread
+  constexpr int PLANE = BM * ST;
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KT = g.K / 32;
-  const int MB = (g.M + kBigBM - 1) / kBigBM;
+  const int MB = (g.M + BM - 1) / BM;
   // workgroup ids go round-robin over the 8 XCDs: keep the row blocks of one weight tile pair together
   const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
   const int nb = xcd + 8 * (q / MB), mb = q % MB;
   const int nt = nb * 2 + (wave >> 1);                  // this wavefront's 16-row weight tile
-  const int mh = wave & 1;                              // its half of the 128 rows: 4 tiles of 16
-  const int m0 = mb * kBigBM;
+  const int mh = wave & 1;                              // its half of the rows
+  const int m0 = mb * BM;
   const uint4* wbase = g.Wt + (size_t)nt * KT * 64 + lane;
-  f32x4 acc[4];
+  f32x4 acc[MTW];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int mt = 0; mt < MTW; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // software pipeline: the next slice's weight fragments and activation pieces are in
+  // registers while the current slice is multiplied out of LDS
+  uint4 wa[4];
+  float4 ap[NPF];
+  auto fetch = [&](int kc0) {
+    const int kc = min(kBigKC, g.K - kc0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i * 32 < kc) wa[i] = wbase[(size_t)(kc0 / 32 + i) * 64];
+#pragma unroll
+    for (int p = 0; p < NPF; ++p) {
+      const int idx = tid + 256 * p, row = idx / (kBigKC / 4), c4 = idx % (kBigKC / 4);
+      ap[p] = float4{0.f, 0.f, 0.f, 0.f};
+      if (m0 + row < g.M && c4 * 4 < kc)
+        ap[p] = *reinterpret_cast<const float4*>(g.X + (size_t)(m0 + row) * g.ldx + kc0 + c4 * 4);
+    }
+  };
+  fetch(0);
   for (int kc0 = 0; kc0 < g.K; kc0 += kBigKC) {
     const int kc = min(kBigKC, g.K - kc0);
-    uint4 wa[8];
+    __syncthreads();                                     // previous slice fully consumed
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      if (i * 32 < kc) wa[i] = wbase[(size_t)(kc0 / 32 + i) * 64];
-    __syncthreads();
-    for (int idx = tid; idx < kBigBM * (kc / 8); idx += 256) {
-      const int row = idx / (kc / 8), c8 = idx % (kc / 8);
-      uint4 v = uint4{0, 0, 0, 0};
-      if (m0 + row < g.M) v = *reinterpret_cast<const uint4*>(g.Abf + (size_t)(m0 + row) * g.lda + kc0 + c8 * 8);
-      *reinterpret_cast<uint4*>(As + (size_t)row * ST + c8 * 8) = v;
+    for (int p = 0; p < NPF; ++p) {
+      const int idx = tid + 256 * p, row = idx / (kBigKC / 4), c4 = idx % (kBigKC / 4);
+      uint2 hi, lo;
+      split4(ap[p], hi, lo);
+      *reinterpret_cast<uint2*>(As + (size_t)row * ST + c4 * 4) = hi;
+      *reinterpret_cast<uint2*>(As + PLANE + (size_t)row * ST + c4 * 4) = lo;
     }
+    uint4 wc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wc[i] = wa[i];
     __syncthreads();
-    const uint16_t* arow = As + (size_t)(mh * 64 + (lane & 15)) * ST + (lane >> 4) * 8;
+    if (kc0 + kBigKC < g.K) fetch(kc0 + kBigKC);
+    const uint16_t* arow = As + (size_t)(mh * 16 * MTW + (lane & 15)) * ST + (lane >> 4) * 8;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 4; ++i)
       if (i * 32 < kc) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, wa[i]);
+        const bf16x8 a = __builtin_bit_cast(bf16x8, wc[i]);
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(arow + (size_t)mt * 16 * ST + i * 32));
-          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[mt], 0, 0, 0);
+        for (int mt = 0; mt < MTW; ++mt) {
+          const uint16_t* bp = arow + (size_t)mt * 16 * ST + i * 32;
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              a, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp)), acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              a, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + PLANE)), acc[mt], 0, 0, 0);
         }
       }
   }
 
-  // lane holds D[n0 + i][m], i = 0..3, n0 = nt*16 + (lane>>4)*4, for each of its 4 row tiles
+  // lane holds D[n0 + i][m], i = 0..3, n0 = nt*16 + (lane>>4)*4, for each of its row tiles
   const int n0 = nt * 16 + (lane >> 4) * 4;
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
-    const int m = m0 + (mh * 4 + mt) * 16 + (lane & 15);
+  for (int mt = 0; mt < MTW; ++mt) {
+    const int m = m0 + (mh * MTW + mt) * 16 + (lane & 15);
     if (EPI == FEPI_QKV) {
       float pr[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) pr[i] = __shfl_xor(acc[mt][i], 32, WAVE);
       if (m < g.M) {
-        const int b = m / g.R, j = m % g.R;
-        const int len = g.eff_len[b];
-        if (len >= 0) {
-          const int d = g.H * g.hd, tps = d / 16, tph = g.hd / 16, half = g.hd / 2;
-          const int sec = nt / tps, ts = nt % tps, h = ts / tph, tt = ts % tph;
-          const int pos = len + j;
-          const size_t head = (size_t)g.slot[b] * g.H + h;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int nrow = (lane >> 4) * 4 + i;
-            const float v = acc[mt][i];
-            float o = v;
-            int dim;
-            if (sec < 2) {
-              const int pi = tt * 8 + (nrow & 7);
-              const float2 cs = g.rope[(size_t)pos * half + pi];
-              if (nrow < 8) { dim = pi; o = v * cs.x - pr[i] * cs.y; }
-              else { dim = half + pi; o = pr[i] * cs.y + v * cs.x; }
-            } else {
-              dim = tt * 16 + nrow;
-            }
-            if (sec == 0) g.Ybf[(size_t)m * g.ldyb + h * g.hd + dim] = f2bf(o);
-            else if (sec == 1) g.Kc[(head * g.cap + pos) * g.hd + dim] = f2bf(o);
-            else if (g.v_transposed) g.Vc[(head * g.hd + dim) * g.cap + pos] = f2bf(o);
-            else g.Vc[(head * g.cap + pos) * g.hd + dim] = f2bf(o);
-          }
-        }
+        for (int i = 0; i < 4; ++i) qkv_store(g, nt, (lane >> 4) * 4 + i, m, acc[mt][i], pr[i]);
       }
     } else if (m < g.M) {
       const f32x4 v = acc[mt];
+      f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
       if (EPI == FEPI_STORE) {
-        *reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0) = v;
+        *y = v;
       } else if (EPI == FEPI_ADD) {
-        f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
         *y = *y + v;
-      } else if (EPI == FEPI_GELU_BF16) {
-        *reinterpret_cast<uint2*>(g.Ybf + (size_t)m * g.ldyb + n0) =
-            uint2{pack_bf16(gelu_erf_f(v[0]), gelu_erf_f(v[1])), pack_bf16(gelu_erf_f(v[2]), gelu_erf_f(v[3]))};
-      } else if (EPI == FEPI_BF16) {
-        *reinterpret_cast<uint2*>(g.Ybf + (size_t)m * g.ldyb + n0) = uint2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+      } else if (EPI == FEPI_GELU) {
+        *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
       } else if (EPI == FEPI_HEAD) {
-        float o[4];
+        f32x4 o;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int n = n0 + i, c = n % g.K;
           const float pre = v[i] + bf2f(g.bias[n]);
-          o[i] = g.X32n[(size_t)m * g.K + c] + pre / (1.0f + __expf(-pre));
+          o[i] = g.X[(size_t)m * g.ldx + c] + pre / (1.0f + __expf(-pre));   // X: normalised rows here
         }
-        *reinterpret_cast<uint2*>(g.Ybf + (size_t)m * g.ldyb + n0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+        *y = o;
       }
     }
   }
 }
 
-template <int EPI>
-static void big_launch(const FastGemm& g, hipStream_t s) {
-  const int MB = (g.M + kBigBM - 1) / kBigBM;
-  const size_t lds = (size_t)kBigBM * (kBigKC + 8) * 2;
-  auto kfn = k_gemm_big<EPI>;
+template <int EPI, int MTW>
+static void big_launch_t(const FastGemm& g, hipStream_t s) {
+  constexpr int BM = 32 * MTW;
+  const int MB = (g.M + BM - 1) / BM;
+  const size_t lds = (size_t)2 * BM * (kBigKC + 8) * 2;
+  auto kfn = k_gemm_big<EPI, MTW>;
   static bool configured = false;
-  if (!configured) {
+  if (!configured && lds > 64 * 1024) {
     (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = true;
   }
   hipLaunchKernelGGL(kfn, dim3((g.N / 32) * MB), dim3(256), lds, s, g);
 }
+template <int EPI>
+static void big_launch(const FastGemm& g, hipStream_t s) {
+  // row block: 64 rows when that covers M or is needed to fill the chip, else 128
+  const long tiles128 = (long)(g.N / 32) * ((g.M + 127) / 128);
+  if (g.M <= 64) big_launch_t<EPI, 2>(g, s);
+  else if (g.M > 128 && tiles128 < 512) big_launch_t<EPI, 2>(g, s);
+  else big_launch_t<EPI, 4>(g, s);
+}
 
 static bool big_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
   if (g.M <= kBigMinM || g.N % 256 != 0 || !g.nscratch) return false;
-  if (pro == PRO_F32) return false;
   if (pro == PRO_NORM) {
-    hipLaunchKernelGGL(k_norm_bf16, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
-                       g.nscratch, epi == FEPI_HEAD ? g.X32n : nullptr, g.K);
-    g.Abf = g.nscratch; g.lda = g.K;
+    hipLaunchKernelGGL(k_norm_rows, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
+                       g.nscratch, g.K);
+    g.X = g.nscratch; g.ldx = g.K; g.row_index = nullptr;
   }
   switch (epi) {
     case FEPI_STORE: big_launch<FEPI_STORE>(g, s); break;
     case FEPI_ADD: big_launch<FEPI_ADD>(g, s); break;
-    case FEPI_GELU_BF16: big_launch<FEPI_GELU_BF16>(g, s); break;
+    case FEPI_GELU: big_launch<FEPI_GELU>(g, s); break;
     case FEPI_QKV: big_launch<FEPI_QKV>(g, s); break;
     case FEPI_HEAD: big_launch<FEPI_HEAD>(g, s); break;
-    case FEPI_BF16: big_launch<FEPI_BF16>(g, s); break;
     default: return false;
   }
   return true;
 }
 
 static size_t fgemm_lds(int MT, int KC) {
-  return (size_t)16 * MT * (KC + 8) * 2 + (size_t)4 * MT * 256 * 4 + (size_t)16 * MT * 4;
+  return (size_t)2 * 16 * MT * (KC + 8) * 2 + (size_t)4 * MT * 256 * 4 + (size_t)16 * MT * 4;
 }
 
 bool fgemm_supported(int N, int K) { return N % 16 == 0 && K % 32 == 0; }
 
 template <int PRO, int EPI>
 static void fgemm_launch(FastGemm g, hipStream_t s) {
-  const int MT = g.M <= 16 ? 1 : g.M <= 32 ? 2 : g.M <= 64 ? 4 : 8;
+  const int MT = g.M <= 16 ? 1 : g.M <= 32 ? 2 : 4;
   // largest chunk of the contraction index (multiple of 128) whose staging fits 160 KB of LDS
   const size_t budget = 160 * 1024;
   int KC = g.K;
@@ -441,7 +449,7 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
     }                                                                                           \
     hipLaunchKernelGGL(kfn, grid, blk, lds, s, g);                                              \
   }
-  if (MT == 1) XSM_FG(1) else if (MT == 2) XSM_FG(2) else if (MT == 4) XSM_FG(4) else XSM_FG(8)
+  if (MT == 1) XSM_FG(1) else if (MT == 2) XSM_FG(2) else XSM_FG(4)
 #undef XSM_FG
 }
 
@@ -454,12 +462,10 @@ void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   TraceScope trace_("fgemm", s);
   if (pro == PRO_NORM && epi == FEPI_QKV) fgemm_launch<PRO_NORM, FEPI_QKV>(g, s);
   else if (pro == PRO_NORM && epi == FEPI_STORE) fgemm_launch<PRO_NORM, FEPI_STORE>(g, s);
-  else if (pro == PRO_NORM && epi == FEPI_GELU_BF16) fgemm_launch<PRO_NORM, FEPI_GELU_BF16>(g, s);
+  else if (pro == PRO_NORM && epi == FEPI_GELU) fgemm_launch<PRO_NORM, FEPI_GELU>(g, s);
   else if (pro == PRO_NORM && epi == FEPI_HEAD) fgemm_launch<PRO_NORM, FEPI_HEAD>(g, s);
-  else if (pro == PRO_NORM && epi == FEPI_BF16) fgemm_launch<PRO_NORM, FEPI_BF16>(g, s);
   else if (pro == PRO_F32 && epi == FEPI_ADD) fgemm_launch<PRO_F32, FEPI_ADD>(g, s);
-  else if (pro == PRO_BF16 && epi == FEPI_ADD) fgemm_launch<PRO_BF16, FEPI_ADD>(g, s);
-  else if (pro == PRO_BF16 && epi == FEPI_STORE) fgemm_launch<PRO_BF16, FEPI_STORE>(g, s);
+  else if (pro == PRO_F32 && epi == FEPI_STORE) fgemm_launch<PRO_F32, FEPI_STORE>(g, s);
 }
 
 }  // namespace xsm

@@ -27,7 +27,6 @@ struct WeightOff {
 struct WorkOff {
   size_t X, Xn, QKV, Qr, AO, U, Z0, G, Hh, Rk, Zh;
   size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
-  size_t Qbf, AObf, Ubf, Rkbf, Nbf;                      // bf16 activations of the MFMA path
   size_t part, tickets;                                  // split-key attention partials
   size_t ll, ctrl, head_all, tlog;                       // single-launch step: exchange buffers
   size_t total;
@@ -123,21 +122,18 @@ void launch_attention(int dtype, const float* Q, const void* Kc, const void* Vc,
                       int H, int hd, int cap, int fixed_limit, hipStream_t s);
 
 // ---- MFMA path (xsm_gemm_mfma.hip, xsm_attn_mfma.hip) ----------------------------
-enum { PRO_NORM = 0, PRO_F32 = 1, PRO_BF16 = 2 };
-enum { FEPI_STORE = 0, FEPI_ADD = 1, FEPI_GELU_BF16 = 2, FEPI_QKV = 3, FEPI_HEAD = 4, FEPI_BF16 = 5 };
+enum { PRO_NORM = 0, PRO_F32 = 1 };
+enum { FEPI_STORE = 0, FEPI_ADD = 1, FEPI_GELU = 2, FEPI_QKV = 3, FEPI_HEAD = 4 };
 struct FastGemm {
   const uint4* Wt;             // fragment-ordered weights [N/16][K/32][64 lanes][8]
   int N, K, M, KC;
-  const float* X; int ldx;     // fp32 input rows (PRO_NORM, PRO_F32; FEPI_HEAD residual)
-  const uint16_t* gain;        // bf16 RMSNorm gain [K]
+  const float* X; int ldx;     // fp32 input rows
+  const uint16_t* gain;        // bf16 RMSNorm gain [K] (PRO_NORM)
   float eps;
   const int32_t* row_index;    // optional gather: input row of output row m
-  const uint16_t* Abf; int lda;   // bf16 input rows (PRO_BF16)
-  float* Y; int ldy;           // fp32 output (STORE, ADD)
-  uint16_t* Ybf; int ldyb;     // bf16 output (GELU, HEAD, q of QKV)
+  float* Y; int ldy;           // fp32 output (for FEPI_QKV: the rotated queries [M][d])
   const uint16_t* bias;        // FEPI_HEAD: stacked biases [N]
-  uint16_t* nscratch;          // [M][K] bf16: normalised rows for the row-blocked kernel
-  float* X32n;                 // [M][K] fp32 normalised rows (FEPI_HEAD residual on that kernel)
+  float* nscratch;             // [M][K] fp32: normalised rows for the row-blocked kernel
   // FEPI_QKV
   const float2* rope; const int32_t* eff_len; const int32_t* slot;
   int R, H, hd, cap, v_transposed;
@@ -149,11 +145,11 @@ void launch_tile_weights(const void* W, void* out, int N, int K, int rope_d, int
 void launch_copy_u16(const void* src, void* dst, int n, hipStream_t s);
 
 struct FastAttn {
-  const uint16_t* Q; int ldq;         // bf16 rotated queries [M][d]
+  const float* Q; int ldq;            // fp32 rotated queries [M][d]
   const uint16_t* Kc;                 // layer's keys [slot][H][cap][64]
   const uint16_t* Vt;                 // layer's values, transposed [slot][H][64][cap]
   const int32_t* eff_len; const int32_t* slot;
-  uint16_t* O; int ldo;               // bf16 output [M][d]
+  float* O; int ldo;                  // fp32 output [M][d]
   float* part; uint32_t* tickets;     // split-key partials and arrival counters
   int R, H, cap, S, fixed_limit;
   float scale_log2;                   // log2(e) / sqrt(head_dim)

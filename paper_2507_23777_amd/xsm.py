@@ -17,7 +17,7 @@ API = ["xsm_create", "xsm_destroy", "xsm_last_error", "xsm_weights_bytes", "xsm_
        "xsm_workspace_bytes", "xsm_canonical_weight_elems", "xsm_bind", "xsm_load_weights",
        "xsm_prefill", "xsm_spec_step", "xsm_plain_step", "xsm_debug_kv_export",
        "xsm_debug_kv_import", "xsm_debug_trace_enable", "xsm_debug_trace_report", "xsm_set_option",
-       "xsm_check_device", "xsm_debug_timeline"]
+       "xsm_check_device", "xsm_debug_timeline", "xsm_debug_kv_clone"]
 
 
 class XsmError(RuntimeError):
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
     for f in ("xsm_debug_kv_export", "xsm_debug_kv_import"):
         getattr(L, f).argtypes, getattr(L, f).restype = [vp, i32, i32, i32, i32, i32, vp], C.c_int
     L.xsm_set_option.argtypes, L.xsm_set_option.restype = [vp, i32, i32], C.c_int
+    L.xsm_debug_kv_clone.argtypes, L.xsm_debug_kv_clone.restype = [vp, i32, i32], C.c_int
     L.xsm_debug_timeline.argtypes, L.xsm_debug_timeline.restype = [vp, vp, sz], C.c_int
     L.xsm_check_device.argtypes, L.xsm_check_device.restype = [vp], C.c_int
     L.xsm_debug_trace_enable.argtypes, L.xsm_debug_trace_enable.restype = [C.c_int], None
@@ -207,6 +208,9 @@ class Engine:
 
     def xsm_set_option(self, option: int, value: int):
         self._check(self.L.xsm_set_option(self.h, option, value), "xsm_set_option")
+
+    def xsm_debug_kv_clone(self, src_slot: int, dst_slot: int):
+        self._check(self.L.xsm_debug_kv_clone(self.h, src_slot, dst_slot), "xsm_debug_kv_clone")
 
     def xsm_debug_timeline(self) -> np.ndarray:
         out = np.zeros((256, self.c_cfg.n_layers * 8 + 8), np.uint64)
