@@ -161,7 +161,7 @@ XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
 
 /* Tuning aid.  With XSM_OPT_TIMELINE = 1 every workgroup of the single-launch step stamps the
  * device's 100 MHz clock at its stage boundaries; this copies the stamps of the last step to
- * h_out as [256 workgroups][n_layers*8 + 8] words (synchronises the device). */
+ * h_out as [256 workgroups][n_layers*16 + 8] words (synchronises the device). */
 XSM_API int xsm_debug_timeline(xsm_ctx* ctx, uint64_t* h_out, size_t n_words);
 
 /* Synchronises the device and reports whether a bounded device-side wait of the

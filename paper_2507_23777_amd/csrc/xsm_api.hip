@@ -78,7 +78,7 @@ void build_work_offsets(xsm_ctx* c) {
     w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
     w.ctrl = take(256);
     w.head_all = take((size_t)80 * V * 4);
-    w.tlog = take((size_t)256 * (g.n_layers * 8 + 8) * 8);
+    w.tlog = take((size_t)256 * (g.n_layers * 16 + 8) * 8);
   }
   w.total = p;
 }
@@ -308,11 +308,11 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     a.n_seq = n_seq; a.R = R; a.V = V; a.max_batch = g.max_batch; a.max_ctx = g.max_ctx;
     a.bound = bt->kv_len_bound; a.cap = ctx->cap_self;
     a.eps = g.rms_eps; a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
-    // key-range slices per (sequence, head): up to two 64-key chunks per wavefront before the
-    // range is split (a split costs one more exchange stage for the merge)
+    // key-range slices per (sequence, head): one 64-key chunk per wavefront (requested before
+    // the queries arrive) before the range is split further
     const int chunks = (bt->kv_len_bound + 63) / 64;
     int S = 1;
-    while (S < 16 && S * 8 < chunks && 2 * S * n_seq * g.n_heads <= 256) S *= 2;
+    while (S < 16 && S * 4 < chunks && 2 * S * n_seq * g.n_heads <= 256) S *= 2;
     a.S = S;
     launch_step_small(a, d, g.d_ffn, s);
     if (bt->head_logits_dbg && K > 0)
@@ -561,7 +561,7 @@ int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value) {
 int xsm_debug_timeline(xsm_ctx* ctx, uint64_t* h_out, size_t n_words) {
   if (!ctx || !h_out) return XSM_EINVAL;
   if (!ctx->small_ok || !ctx->d_ws) return fail(ctx, XSM_ESTATE, "no single-launch step for this model");
-  const size_t have = (size_t)256 * (ctx->cfg.n_layers * 8 + 8);
+  const size_t have = (size_t)256 * (ctx->cfg.n_layers * 16 + 8);
   if (n_words < have) return fail(ctx, XSM_EINVAL, "timeline buffer too small");
   XSM_HIP(hipDeviceSynchronize());
   XSM_HIP(hipMemcpy(h_out, ctx->d_ws + ctx->ws.tlog, have * 8, hipMemcpyDeviceToHost));

@@ -170,7 +170,7 @@ struct SmallArgs {
   const int32_t* slot; int32_t* kv_len; int32_t* block; int32_t* out_tokens; int32_t* n_accepted;
   uint32_t* flags;
   float* logits_dbg; float* head_logits_dbg; float* head_all_dbg; int32_t* acc_out;
-  uint64_t* tlog;                        // optional stage timeline [256][L*8 + 8] clock stamps
+  uint64_t* tlog;                        // optional stage timeline [256][L*16 + 8] clock stamps
   int n_seq, R, S, V, max_batch, max_ctx, bound, cap;
   float eps, scale_log2;
 };

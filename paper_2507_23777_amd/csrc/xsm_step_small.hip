@@ -8,7 +8,7 @@
 // stage's consumers.  Kernel boundaries cost several microseconds each; here all 256
 // workgroups (one per compute unit) stay resident for the whole step and exchange
 // activations through memory with a flag in every 8-byte word:
-//     word = { 32-bit payload (one fp32 or two bf16), 32-bit tag }, tag = step epoch.
+//     word = { 32-bit payload (one fp32 value), 32-bit tag }, tag = step epoch.
 // A producer writes words with device-coherent stores; a consumer loads the words it
 // needs with device-coherent loads and retries until every tag equals the current
 // epoch, so arrival of the data IS the synchronisation (no barrier, no second round
@@ -21,6 +21,10 @@
 // 1 KB of consecutive words) and the activation block is re-laid through LDS into MFMA
 // operand order; a lane-scattered read of the same words costs an order of magnitude more.
 //
+// Activations travel as fp32 and enter the bf16 MFMAs as two operands, hi = bf16(x) and
+// lo = bf16(x - hi), against the same weight fragment, so the result carries the weights'
+// bf16 rounding (part of the model) but not a second one from the activations.
+//
 // Weights never depend on activations, so each workgroup requests the fragments of the
 // tile it will need one layer ahead and holds them in registers; HBM stays busy while
 // the dependency chain is waiting.  Stages per layer (Sec. 4.1 block = self-attention +
@@ -30,7 +34,9 @@
 //   COMB  merge of the S slices (skipped when S == 1)
 //   OPROJ 64 tiles   output projection + residual
 //   UP    256 tiles  RMSNorm + W1 + erf-GELU
-//   DOWN  64 tiles   W2 + residual
+//   DOWN  64 tiles x 4 slices of the FFN width: W2 partial products on all 256 workgroups;
+//         the workgroup of the last slice (which also made the tile's OPROJ output) adds the
+//         other three and the residual
 // then the decoding heads on every block row (Alg. 1 runs each head on h_{s:s+D}), the
 // shared unembedding over backbone and head rows with a per-tile top-2 reduction, and one
 // workgroup per sequence that does the accept scan, picks the tokens at the first rejected
@@ -100,19 +106,19 @@ __device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bo
   return out[0];
 }
 
-// Cooperative, coalesced wait for rows [m0, m0 + ROWS) (clipped to nrows) of a block of tagged
-// words with W words per row: thread t takes the word pairs 2(t + 256 j), +1, j < W/512, of
+// Cooperative, coalesced wait for rows [m0, m0 + ROWS) (clipped to nrows), W words of each, of a
+// block of tagged words with row stride RS: thread t takes the word pairs 2(t + 256 j), +1, j < W/512, of
 // every row, so a wavefront instruction covers 1 KB of consecutive words.
-template <int W, int ROWS>
+template <int W, int RS, int ROWS>
 __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows, int tid, uint32_t tag,
                                           uint32_t (&pay)[ROWS * (W / 512) * 2], bool& ok) {
   constexpr int PP = W / 512, N = ROWS * PP * 2;
   const int rows = min(ROWS, nrows - m0);
-  const uint64_t* base = buf + (size_t)m0 * W + 2 * tid;
+  const uint64_t* base = buf + (size_t)m0 * RS + 2 * tid;
   if (ok && rows > 0) {
     int spin = 0;
     if ((tid & 63) == 0) {                 // one lane per wavefront watches one word
-      const uint64_t* last = base + (size_t)(rows - 1) * W + (PP - 1) * 512 + 1;
+      const uint64_t* last = base + (size_t)(rows - 1) * RS + (PP - 1) * 512 + 1;
       while ((uint32_t)(ll_ld(last) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
     }
     for (; spin < kSpinBudget; ++spin) {
@@ -122,8 +128,8 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
 #pragma unroll
         for (int j = 0; j < PP; ++j)
           if (m < rows) {
-            w[(m * PP + j) * 2] = ll_ld(base + (size_t)m * W + j * 512);
-            w[(m * PP + j) * 2 + 1] = ll_ld(base + (size_t)m * W + j * 512 + 1);
+            w[(m * PP + j) * 2] = ll_ld(base + (size_t)m * RS + j * 512);
+            w[(m * PP + j) * 2 + 1] = ll_ld(base + (size_t)m * RS + j * 512 + 1);
           }
       bool good = true;
 #pragma unroll
@@ -176,22 +182,29 @@ __device__ __forceinline__ float tile_reduce(Shared& sm, f32x4 acc, int wave, in
   return (sm.red[0][lane][wave] + sm.red[1][lane][wave]) + (sm.red[2][lane][wave] + sm.red[3][lane][wave]);
 }
 
-// Stage rows [0, M) of an fp32-payload block (D words per row) into LDS as bf16 rows of
-// stride D + 8.  NORM: RMSNorm with the gain pairs gpair[j] (columns 2(tid + 256 j), +1); the
-// fp32 result is also kept in f32dst when given.
-template <int D, bool NORM>
-__device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, float* f32dst, const uint64_t* buf,
-                                               int M, const uint32_t (&gpair)[D / 512], float eps, int tid,
+// bf16 pair of (a, b) and of what that rounding dropped
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  hi = pk2(x0, x1);
+  lo = pk2(x0 - lo_bf(hi), x1 - hi_bf(hi));
+}
+
+// Stage nrows rows, D columns each, of an fp32-payload block with row stride RS words into LDS
+// rows dst_row.. as two bf16 planes of row stride D + 8: hi at As, lo at As + 16 * (D + 8).
+// NORM: RMSNorm over the D columns with the gain pairs gpair[j] (columns 2(tid + 256 j), +1).
+template <int D, int RS, bool NORM>
+__device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst_row, const uint64_t* buf,
+                                               int nrows, const uint32_t (&gpair)[D / 512], float eps, int tid,
                                                uint32_t tag, bool& ok) {
-  constexpr int PP = D / 512, ST = D + 8;
+  constexpr int PP = D / 512, ST = D + 8, LO = 16 * ST;
+  constexpr int RB = PP >= 4 ? 4 : 8;                    // rows per round: at most 32 words in flight per thread
   const int wave = tid >> 6, lane = tid & 63;
-  for (int m0 = 0; m0 < M; m0 += 8) {
-    uint32_t pay[8 * PP * 2];
-    coop_wait<D, 8>(buf, m0, M, tid, tag, pay, ok);
+  for (int m0 = 0; m0 < nrows; m0 += RB) {
+    uint32_t pay[RB * PP * 2];
+    coop_wait<D, RS, RB>(buf, m0, nrows, tid, tag, pay, ok);
     if (NORM) {
       __syncthreads();                                   // earlier readers of rowsum / inv are done
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
+      for (int m = 0; m < RB; ++m) {
         float ss = 0.f;
 #pragma unroll
         for (int j = 0; j < PP * 2; ++j) {
@@ -202,21 +215,23 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, float* 
         if (lane == 0) sm.rowsum[wave][m] = ss;
       }
       __syncthreads();
-      if (tid < 8)
+      if (tid < RB)
         sm.inv[tid] = 1.0f / sqrtf(((sm.rowsum[0][tid] + sm.rowsum[1][tid]) + (sm.rowsum[2][tid] + sm.rowsum[3][tid])) / (float)D + eps);
       __syncthreads();
     }
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      if (m0 + m < M) {
+    for (int m = 0; m < RB; ++m) {
+      if (m0 + m < nrows) {
         const float sc = NORM ? sm.inv[m] : 1.0f;
 #pragma unroll
         for (int j = 0; j < PP; ++j) {
           float x0 = __uint_as_float(pay[(m * PP + j) * 2]), x1 = __uint_as_float(pay[(m * PP + j) * 2 + 1]);
           if (NORM) { x0 *= sc * lo_bf(gpair[j]); x1 *= sc * hi_bf(gpair[j]); }
-          const int c = 2 * (tid + 256 * j);
-          *reinterpret_cast<uint32_t*>(As + (size_t)(m0 + m) * ST + c) = pk2(x0, x1);
-          if (f32dst) *reinterpret_cast<float2*>(f32dst + (size_t)(m0 + m) * D + c) = float2{x0, x1};
+          uint32_t hi, lo;
+          split2(x0, x1, hi, lo);
+          uint16_t* dst = As + (size_t)(dst_row + m0 + m) * ST + 2 * (tid + 256 * j);
+          *reinterpret_cast<uint32_t*>(dst) = hi;
+          *reinterpret_cast<uint32_t*>(dst + LO) = lo;
         }
       }
     }
@@ -224,29 +239,14 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, float* 
   __syncthreads();
 }
 
-// Stage nrows rows of a bf16x2-payload block (W words = 2W elements per row) into LDS rows
-// starting at dst_row, stride ST elements.
-template <int W>
-__device__ __forceinline__ void stage_rows_bf16(uint16_t* As, int ST, int dst_row, const uint64_t* buf,
-                                                int nrows, int tid, uint32_t tag, bool& ok) {
-  constexpr int PP = W / 512, RB = PP >= 4 ? 4 : 8;     // rows per round: at most 32 words in flight per thread
-  for (int m0 = 0; m0 < nrows; m0 += RB) {
-    uint32_t pay[RB * PP * 2];
-    coop_wait<W, RB>(buf, m0, nrows, tid, tag, pay, ok);
-#pragma unroll
-    for (int m = 0; m < RB; ++m)
-      if (m0 + m < nrows) {
-#pragma unroll
-        for (int j = 0; j < PP; ++j)
-          *reinterpret_cast<uint2*>(As + (size_t)(dst_row + m0 + m) * ST + 4 * (tid + 256 * j)) =
-              uint2{pay[(m * PP + j) * 2], pay[(m * PP + j) * 2 + 1]};
-      }
-  }
-  __syncthreads();
-}
-
-__device__ __forceinline__ uint4 lds_frag(const uint16_t* As, int ST, int row, int kt, int g) {
-  return *reinterpret_cast<const uint4*>(As + (size_t)row * ST + kt * 32 + g * 8);
+// acc += Wfrag . (hi + lo) for activation row `row`, k-tile kt of an LDS tile staged by
+// stage_rows_f32 (row stride ST, lo plane 16 rows further)
+__device__ __forceinline__ f32x4 mac2(f32x4 acc, const uint4& wfrag, const uint16_t* As, int ST, int row,
+                                      int kt, int g) {
+  const uint16_t* p = As + (size_t)row * ST + kt * 32 + g * 8;
+  const bf16x8 wa = __builtin_bit_cast(bf16x8, wfrag);
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + 16 * ST)), acc, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p)), acc, 0, 0, 0);
 }
 
 }  // namespace
@@ -255,11 +255,14 @@ template <int D, int F>
 __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   constexpr int H = D / 64;
   constexpr int KTD = D / 32, KTF = F / 32;          // k-tiles of the two contraction lengths
-  constexpr int KD = KTD / 4, KF = KTF / 4;          // per wavefront
+  constexpr int KD = KTD / 4;                        // per wavefront
   constexpr int NQ = 3 * D / 16, NO = D / 16, NU = F / 16;
-  constexpr int O_BASE = NQ, DN_BASE = 128;
-  constexpr int STD = D + 8, STF = F + 8;            // LDS row strides (bf16 elements)
-  static_assert(NQ + NO <= 256 && DN_BASE + NO <= 256 && NU <= 256, "tile roles must fit 256 workgroups");
+  constexpr int O_BASE = NQ;
+  constexpr int FS = F / 4;                          // DOWN: slice of the FFN width per workgroup
+  constexpr int KFS = FS / 32 / 4;                   // its k-tiles per wavefront
+  constexpr int STD = D + 8, STS = FS + 8;           // LDS row strides (bf16 elements)
+  static_assert(NQ + NO <= 256 && NU <= 256 && NO * 4 == 256, "tile roles must fit 256 workgroups");
+  static_assert(FS % 512 == 0 && FS <= D, "DOWN slice is staged like a model-width row block");
   static_assert(D % 512 == 0 && F % 1024 == 0, "cooperative staging needs whole pair rounds");
   __shared__ Shared sm;
   extern __shared__ __align__(16) unsigned char dyn[];
@@ -306,20 +309,26 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   const size_t LS = a.ll_layer_stride;                 // words per layer
   uint64_t* const llb = a.ll;
   const size_t OFF_X = 0, OFF_Q = 16 * D, OFF_KN = 2 * 16 * D, OFF_VN = 3 * 16 * D, OFF_O = 4 * 16 * D,
-               OFF_XM = 5 * 16 * D, OFF_U = 6 * 16 * D, OFF_P = 6 * 16 * D + 16 * (F / 2);
+               OFF_XM = 5 * 16 * D, OFF_U = 6 * 16 * D, OFF_PD = OFF_U + 16 * F, OFF_P = OFF_PD + 3 * 16 * D;
 
-  const bool has_q = w < NQ, has_o = w >= O_BASE && w < O_BASE + NO, has_u = w < NU,
-             has_d = w >= DN_BASE && w < DN_BASE + NO;
+  const bool has_q = w < NQ, has_o = w >= O_BASE && w < O_BASE + NO, has_u = w < NU;
+  const int d_nt = w % NO, d_ks = w / NO;              // DOWN: output tile and slice of the FFN width
   // Weight fragments live in registers and are requested ahead of use.  A wavefront's loads
   // return in order, so a bulk request delays whatever wait is issued right behind it; each
   // request is therefore placed where its workgroup is about to sit out a stage:
-  //   workgroups with QKV (+ DOWN): next layer's QKV tile, this layer's DOWN tile (and, for the
-  //     DOWN owners, this layer's UP tile) after COMB - they have no OPROJ tile;
-  //   the others: next layer's UP / OPROJ tiles after UP - they have no DOWN tile.
-  uint4 wq[KD], wu[KD], wd[KF];            // wq doubles as the OPROJ tile (disjoint workgroups)
+  //   workgroups with a QKV tile: this layer's UP and DOWN tiles and next layer's QKV tile after
+  //     COMB - they have no OPROJ tile;
+  //   the OPROJ workgroups: next layer's OPROJ, UP and DOWN tiles after DOWN - they sit out QKV
+  //     and attention.
+  uint4 wq[KD], wu[KD], wd[KFS];           // wq doubles as the OPROJ tile (disjoint workgroups)
+  auto load_down = [&](const uint4* W2) { load_frags<KFS>(wd, W2, d_nt, KTF, d_ks * (FS / 32) + wave * KFS, lane); };
   if (has_q) load_frags<KD>(wq, sm.tab[0].Wqkv, w, KTD, wave * KD, lane);
-  if (has_o) load_frags<KD>(wq, sm.tab[0].Wo, w - O_BASE, KTD, wave * KD, lane);
-  if (has_u && !has_d) load_frags<KD>(wu, sm.tab[0].W1, w, KTD, wave * KD, lane);
+  if (has_o) {
+    load_frags<KD>(wq, sm.tab[0].Wo, w - O_BASE, KTD, wave * KD, lane);
+    load_frags<KD>(wu, sm.tab[0].W1, w, KTD, wave * KD, lane);
+    load_down(sm.tab[0].W2);
+  }
+  float xm = 0.f;                          // OPROJ workgroups: their element of the mid-layer residual
 
   // ---- EMBED: layer-0 residual rows as tagged words ----
   for (int idx = w * 256 + tid; idx < M * D; idx += 256 * 256) {
@@ -329,13 +338,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
 
   // optional timeline: thread 0 of every workgroup stamps the 100 MHz clock at stage boundaries
-  uint64_t* const tl = a.tlog ? a.tlog + (size_t)w * (a.L * 8 + 8) : nullptr;
+  uint64_t* const tl = a.tlog ? a.tlog + (size_t)w * (a.L * 16 + 8) : nullptr;
 #define XSM_STAMP(idx) do { if (tl && tid == 0) tl[idx] = wall_clock64(); } while (0)
   bool ok = true;
   for (int l = 0; l < a.L; ++l) {
     uint64_t* const lb = llb + (size_t)l * LS;
     const LayerTab& lt = sm.tab[l];
-    XSM_STAMP(l * 8 + 0);
+    XSM_STAMP(l * 16 + 0);
 
     // ================= QKV =================
     if (has_q) {
@@ -345,12 +354,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const int q_sec = w / (D / 16), q_ts = w % (D / 16), q_h = q_ts >> 2, q_tt = q_ts & 3;
       float2 cs = float2{1.f, 0.f};
       if (live && q_sec < 2) cs = a.rope[(size_t)(len_m + mj) * 32 + q_tt * 8 + (nrow & 7)];
-      stage_rows_f32<D, true>(sm, As, nullptr, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
+      stage_rows_f32<D, D, true>(sm, As, 0, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
+      XSM_STAMP(l * 16 + 8);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wq[i]),
-                                                      __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
+      for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
       const float v = tile_reduce(sm, acc, wave, lane);
       const float partner = __shfl_xor(v, 32, WAVE);
       if (live) {
@@ -377,7 +385,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         }
       }
     }
-    XSM_STAMP(l * 8 + 1);
+    XSM_STAMP(l * 16 + 1);
 
     // ================= ATT =================
     const int n_units = a.n_seq * H * S;
@@ -391,9 +399,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const uint16_t* kb = lt.Kc + head * (size_t)a.cap * 64;
       const uint16_t* vb = lt.Vt + head * 64 * (size_t)a.cap;
       // this step's q, k, v rows of (sequence b, head h): [R][64] each, staged as bf16 tiles
-      uint16_t* const qs = As;
-      uint16_t* const kns = As + 16 * kQS;
-      uint16_t* const vns = As + 32 * kQS;
+      uint16_t* const qs = As;                            // q: hi plane, lo plane 16 rows further
+      uint16_t* const kns = As + 32 * kQS;                // new k / v: as the cache will hold them
+      uint16_t* const vns = As + 48 * kQS;
       // the first chunk of cached keys/values does not depend on this step: request it before waiting
       uint4 kf[4][2], vf[4][2];
       auto load_kv = [&](int c) {
@@ -430,16 +438,24 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         for (int q = 0; q < 4; ++q) {
           const int j = j0 + 4 * q;
           if (j < R) {
-            qs[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q]));
+            const float qv = __uint_as_float(pw[3 * q]);
+            const uint16_t qh = f2bf(qv);
+            qs[j * kQS + c] = qh;
+            qs[(16 + j) * kQS + c] = f2bf(qv - bf2f(qh));
             kns[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q + 1]));
             vns[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q + 2]));
           }
         }
       }
       __syncthreads();
+      XSM_STAMP(l * 16 + 9);
       const bool qlive = r < R && n >= 0;                 // MFMA column r is query j = r
-      const bf16x8 q0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qs + r * kQS + g * 8));
-      const bf16x8 q1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qs + r * kQS + 32 + g * 8));
+      bf16x8 qh[2], ql[2];                                // dims g*8.. and 32 + g*8.., hi and lo parts
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        qh[hf] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qs + r * kQS + hf * 32 + g * 8));
+        ql[hf] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qs + (16 + r) * kQS + hf * 32 + g * 8));
+      }
       float m_run = -INFINITY, l_run = 0.f;
       f32x4 o[4];
 #pragma unroll
@@ -452,8 +468,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][0]), q0, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-          sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][1]), q1, sc[t], 0, 0, 0);
+          sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            const bf16x8 kk = __builtin_bit_cast(bf16x8, kf[t][hf]);
+            sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[hf], sc[t], 0, 0, 0);
+            sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[hf], sc[t], 0, 0, 0);
+          }
         }
         const int kbase = key0 + g * 16;
         const bool edge = key0 + 64 > nn || !qlive;
@@ -499,17 +520,22 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
                 if (kbase + jj * 8 + e >= nn) wv[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
             }
         }
-        uint4 pf[2];
+        uint4 ph[2], pl[2];
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-          pf[jj] = uint4{pk2(sc[2 * jj][0], sc[2 * jj][1]), pk2(sc[2 * jj][2], sc[2 * jj][3]),
-                         pk2(sc[2 * jj + 1][0], sc[2 * jj + 1][1]), pk2(sc[2 * jj + 1][2], sc[2 * jj + 1][3])};
+        for (int jj = 0; jj < 2; ++jj) {
+          split2(sc[2 * jj][0], sc[2 * jj][1], ph[jj].x, pl[jj].x);
+          split2(sc[2 * jj][2], sc[2 * jj][3], ph[jj].y, pl[jj].y);
+          split2(sc[2 * jj + 1][0], sc[2 * jj + 1][1], ph[jj].z, pl[jj].z);
+          split2(sc[2 * jj + 1][2], sc[2 * jj + 1][3], ph[jj].w, pl[jj].w);
+        }
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-          for (int jj = 0; jj < 2; ++jj)
-            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dt][jj]),
-                                                            __builtin_bit_cast(bf16x8, pf[jj]), o[dt], 0, 0, 0);
+          for (int jj = 0; jj < 2; ++jj) {
+            const bf16x8 vv = __builtin_bit_cast(bf16x8, vf[dt][jj]);
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, pl[jj]), o[dt], 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, ph[jj]), o[dt], 0, 0, 0);
+          }
       }
 
       // the R new keys of this step (positions n..n+R-1): one 16-key tile, taken by wavefront 3
@@ -518,8 +544,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         // A operand of S^T: lane (key r, g) holds k_new[r][hf*32 + g*8 .. +8]
         const bf16x8 k0 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kns + r * kQS + g * 8));
         const bf16x8 k1 = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kns + r * kQS + 32 + g * 8));
-        f32x4 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, q0, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, q1, sc, 0, 0, 0);
+        f32x4 sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[1], sc, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qh[0], sc, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qh[1], sc, 0, 0, 0);
         // lane (query r, g) holds new keys g*4 + i
         float cmax = -INFINITY;
 #pragma unroll
@@ -547,7 +575,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         l_run = l_run * alpha + psum;
         m_run = m_new;
         // contraction index of the second product: k = g*8 + e  <->  new key g*4 + e (e < 4)
-        const uint4 pfrag = uint4{pk2(sc[0], sc[1]), pk2(sc[2], sc[3]), 0u, 0u};
+        uint4 pfh = uint4{0u, 0u, 0u, 0u}, pfl = uint4{0u, 0u, 0u, 0u};
+        split2(sc[0], sc[1], pfh.x, pfl.x);
+        split2(sc[2], sc[3], pfh.y, pfl.y);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
           // A operand: lane (dim dt*16 + r, g) holds v_new[key g*4 + e][dim], e < 4
@@ -561,10 +591,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           const uint4 vfrag = uint4{vw[0], vw[1], 0u, 0u};
           o[dt] = o[dt] * alpha;
           o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vfrag),
-                                                          __builtin_bit_cast(bf16x8, pfrag), o[dt], 0, 0, 0);
+                                                          __builtin_bit_cast(bf16x8, pfl), o[dt], 0, 0, 0);
+          o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vfrag),
+                                                          __builtin_bit_cast(bf16x8, pfh), o[dt], 0, 0, 0);
         }
       }
 
+      XSM_STAMP(l * 16 + 10);
       // merge the four wavefronts; wavefront i finishes dim tile i
       if (g == 0) { sm.att_ml[wave][0][r] = m_run; sm.att_ml[wave][1][r] = l_run; }
 #pragma unroll
@@ -601,7 +634,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           ll_st(part + 32 + (size_t)(wave * 16 + g * 4 + i) * 16 + r, __float_as_uint(acc[i]), tag);
       }
     }
-    XSM_STAMP(l * 8 + 2);
+    XSM_STAMP(l * 16 + 2);
 
     // ================= COMB =================
     if (S > 1 && w < n_units) {
@@ -643,11 +676,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         }
       }
     }
-    XSM_STAMP(l * 8 + 3);
-    if (has_q && l + 1 < a.L) load_frags<KD>(wq, sm.tab[l + 1].Wqkv, w, KTD, wave * KD, lane);
-    if (has_d) {
+    XSM_STAMP(l * 16 + 3);
+    if (has_q) {
       load_frags<KD>(wu, lt.W1, w, KTD, wave * KD, lane);
-      load_frags<KF>(wd, lt.W2, w - DN_BASE, KTF, wave * KF, lane);
+      load_down(lt.W2);
+      if (l + 1 < a.L) load_frags<KD>(wq, sm.tab[l + 1].Wqkv, w, KTD, wave * KD, lane);
     }
 
     // ================= OPROJ =================
@@ -657,17 +690,16 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const uint32_t px = row_in ? ll_wait1(lb + OFF_X + (size_t)r * D + nt * 16 + nrow, tag, ok) : 0u;
       const uint32_t nogain[D / 512] = {};
       __syncthreads();
-      stage_rows_f32<D, false>(sm, As, nullptr, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
+      stage_rows_f32<D, D, false>(sm, As, 0, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
+      XSM_STAMP(l * 16 + 14);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wq[i]),
-                                                      __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
+      for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
       const float v = tile_reduce(sm, acc, wave, lane);
-      if (row_in)
-        ll_st(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px) + v), tag);
+      xm = __uint_as_float(px) + v;
+      if (row_in) ll_st(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, __float_as_uint(xm), tag);
     }
-    XSM_STAMP(l * 8 + 4);
+    XSM_STAMP(l * 16 + 4);
 
     // ================= UP =================
     if (has_u) {
@@ -675,55 +707,46 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
       for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g2 + 2 * (tid + 256 * j));
       __syncthreads();
-      stage_rows_f32<D, true>(sm, As, nullptr, lb + OFF_XM, M, gp, a.eps, tid, tag, ok);
-      XSM_STAMP(l * 8 + 7);
+      stage_rows_f32<D, D, true>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok);
+      XSM_STAMP(l * 16 + 7);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wu[i]),
-                                                      __builtin_bit_cast(bf16x8, lds_frag(As, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
-      __syncthreads();
-      *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
-      __syncthreads();
-      // threads 0..127: row m = tid&15, output pair (2p, 2p+1), p = tid>>4
-      if (tid < 128 && r < M) {
-        const int p = tid >> 4;
-        float v2[2];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int nr = 2 * p + q, ln = (nr >> 2) * 16 + r, ii = nr & 3;
-          const float v = (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
-          v2[q] = 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
-        }
-        ll_st(lb + OFF_U + (size_t)r * (F / 2) + w * 8 + p, pk2(v2[0], v2[1]), tag);
-      }
-    }
-    XSM_STAMP(l * 8 + 5);
-    if (l + 1 < a.L && !has_d) {
-      if (has_o) load_frags<KD>(wq, sm.tab[l + 1].Wo, w - O_BASE, KTD, wave * KD, lane);
-      if (has_u) load_frags<KD>(wu, sm.tab[l + 1].W1, w, KTD, wave * KD, lane);
-    }
-
-    // ================= DOWN =================
-    if (has_d) {
-      const int nt = w - DN_BASE;
-      const uint32_t px = row_in ? ll_wait1(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, tag, ok) : 0u;
-      __syncthreads();
-      stage_rows_bf16<F / 2>(As, STF, 0, lb + OFF_U, M, tid, tag, ok);
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i0 = 0; i0 < KF; i0 += 8) {               // eight k-tiles at a time keeps the operand reads short-lived
-#pragma unroll
-        for (int i = i0; i < i0 + 8; ++i)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wd[i]),
-                                                        __builtin_bit_cast(bf16x8, lds_frag(As, STF, r, wave * KF + i, g)), acc, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      for (int i = 0; i < KD; ++i) acc = mac2(acc, wu[i], As, STD, r, wave * KD + i, g);
       const float v = tile_reduce(sm, acc, wave, lane);
       if (row_in)
-        ll_st(lb + LS + OFF_X + (size_t)r * D + nt * 16 + nrow, __float_as_uint(__uint_as_float(px) + v), tag);
+        ll_st(lb + OFF_U + (size_t)r * F + w * 16 + nrow,
+              __float_as_uint(0.5f * v * (1.0f + erff(v * 0.70710678118654752f))), tag);
     }
-    XSM_STAMP(l * 8 + 6);
+    XSM_STAMP(l * 16 + 5);
+
+    // ================= DOWN =================
+    {
+      const uint32_t nogain[FS / 512] = {};
+      __syncthreads();
+      stage_rows_f32<FS, F, false>(sm, As, 0, lb + OFF_U + d_ks * FS, M, nogain, a.eps, tid, tag, ok);
+      XSM_STAMP(l * 16 + 12);
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < KFS; ++i) acc = mac2(acc, wd[i], As, STS, r, wave * KFS + i, g);
+      const float v = tile_reduce(sm, acc, wave, lane);
+      const size_t col = (size_t)r * D + d_nt * 16 + nrow;
+      if (d_ks < 3) {
+        if (row_in) ll_st(lb + OFF_PD + (size_t)d_ks * 16 * D + col, __float_as_uint(v), tag);
+      } else {
+        // last slice: the other three partial products, then the residual this workgroup made in OPROJ
+        const int off[3] = {row_in ? (int)col : -1, row_in ? (int)(16 * D + col) : -1, row_in ? (int)(32 * D + col) : -1};
+        uint32_t pw[3];
+        ll_wait_list<3>(lb + OFF_PD, off, tag, pw, ok);
+        const float x = xm + ((__uint_as_float(pw[0]) + __uint_as_float(pw[1])) + (__uint_as_float(pw[2]) + v));
+        if (row_in) ll_st(lb + LS + OFF_X + col, __float_as_uint(x), tag);
+      }
+    }
+    XSM_STAMP(l * 16 + 6);
+    if (has_o && l + 1 < a.L) {
+      load_frags<KD>(wq, sm.tab[l + 1].Wo, w - O_BASE, KTD, wave * KD, lane);
+      load_frags<KD>(wu, sm.tab[l + 1].W1, w, KTD, wave * KD, lane);
+      load_down(sm.tab[l + 1].W2);
+    }
     // a workgroup that timed out anywhere leaves (its consumers will time out in turn)
     if (__syncthreads_or(!ok)) {
       if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u + (uint32_t)l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -733,55 +756,43 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 
   // =========================== tail ===========================
   uint64_t* const tb = llb + (size_t)a.L * LS;             // XB[L] lives at the start of this block
-  const size_t OFF_RB = 16 * D;                            // head outputs: [16*K rows][D/2] bf16x2 words
-  const size_t OFF_ST = OFF_RB + (size_t)16 * 15 * (D / 2); // per (tile, row) top-2 statistics: 4 words
+  const size_t OFF_RB = 16 * D;                            // head outputs: [16*K rows][D] fp32 words
+  const size_t OFF_ST = OFF_RB + (size_t)16 * 15 * D;      // per (tile, row) top-2 statistics: 4 words
   const int NTV = V / 16;                                  // vocabulary tiles
   const int rows_all = M + M * K;                          // backbone rows, then head rows (m, k)
-  uint16_t* const T0 = As;                                 // rows 0..15 of the unembedding input
-  uint16_t* const T1 = As + 16 * STD;                      // later row tiles, one at a time
-  float* const Hf32 = reinterpret_cast<float*>(As + 32 * STD);   // fp32 final-normed hidden [16][D]
+  uint16_t* const T0 = As;                                 // rows 0..15 of the unembedding input (hi, lo planes)
+  uint16_t* const T1 = As + 32 * STD;                      // later row tiles, one at a time
 
   // first tiles of the head and unembedding matrices: requested before the last residual arrives
   uint4 wh[KD], wv[KD];
   if (w < K * (D / 16)) load_frags<KD>(wh, a.Wh, w, KTD, wave * KD, lane);
   if (w < NTV) load_frags<KD>(wv, a.WU, w, KTD, wave * KD, lane);
 
-  XSM_STAMP(a.L * 8 + 0);
+  XSM_STAMP(a.L * 16 + 0);
   {
     uint32_t gp[D / 512];
 #pragma unroll
     for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(a.gf + 2 * (tid + 256 * j));
     __syncthreads();
-    stage_rows_f32<D, true>(sm, T0, Hf32, tb + OFF_X, M, gp, a.eps, tid, tag, ok);
+    stage_rows_f32<D, D, true>(sm, T0, 0, tb + OFF_X, M, gp, a.eps, tid, tag, ok);
   }
-  XSM_STAMP(a.L * 8 + 1);
+  XSM_STAMP(a.L * 16 + 1);
 
   // ---- HEADS on every row: r_k = g + SiLU(W_k g + b_k)  (Eq. 4, MLP variant) ----
   for (int t = w; t < K * (D / 16); t += 256) {
     if (t != w) load_frags<KD>(wh, a.Wh, t, KTD, wave * KD, lane);
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < KD; ++i)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wh[i]),
-                                                    __builtin_bit_cast(bf16x8, lds_frag(T0, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
-    __syncthreads();
-    *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
-    __syncthreads();
-    const int kh = t / (D / 16), c0 = (t % (D / 16)) * 16;   // head index, first column
-    if (tid < 128 && r < M) {
-      const int p = tid >> 4;
-      float v2[2];
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int nr = 2 * p + q, ln = (nr >> 2) * 16 + r, ii = nr & 3;
-        const float y = (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
-        const float pre = y + bf2f(a.hb[(size_t)kh * D + c0 + nr]);
-        v2[q] = Hf32[(size_t)r * D + c0 + nr] + pre / (1.0f + __expf(-pre));
-      }
-      ll_st(tb + OFF_RB + ((size_t)r * K + kh) * (D / 2) + (c0 >> 1) + p, pk2(v2[0], v2[1]), tag);
+    for (int i = 0; i < KD; ++i) acc = mac2(acc, wh[i], T0, STD, r, wave * KD + i, g);
+    const float y = tile_reduce(sm, acc, wave, lane);
+    const int kh = t / (D / 16), c = (t % (D / 16)) * 16 + nrow;   // head index, column
+    if (row_in) {
+      const float pre = y + bf2f(a.hb[(size_t)kh * D + c]);
+      const float gn = bf2f(T0[(size_t)r * STD + c]) + bf2f(T0[(size_t)(16 + r) * STD + c]);
+      ll_st(tb + OFF_RB + ((size_t)r * K + kh) * D + c, __float_as_uint(gn + pre / (1.0f + __expf(-pre))), tag);
     }
   }
-  XSM_STAMP(a.L * 8 + 2);
+  XSM_STAMP(a.L * 16 + 2);
 
   // ---- UNEMBED over backbone rows and head rows, per-tile top-2 per row ----
   // row q < M: backbone row q (already in T0); row q >= M: head row q - M = m*K + k
@@ -791,16 +802,17 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     const int q_lo = mt == 0 ? M : mt * 16, q_hi = min(rows_all, mt * 16 + 16);
     if (w < NTV) {                                     // only workgroups with a vocabulary tile need the rows
       __syncthreads();
-      if (q_hi > q_lo)
-        stage_rows_bf16<D / 2>(T, STD, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * (D / 2), q_hi - q_lo, tid, tag, ok);
+      if (q_hi > q_lo) {
+        const uint32_t nogain[D / 512] = {};
+        stage_rows_f32<D, D, false>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, q_hi - q_lo, nogain,
+                                    a.eps, tid, tag, ok);
+      }
     }
     for (int t = w; t < NTV; t += 256) {
       if (t != w) load_frags<KD>(wv, a.WU, t, KTD, wave * KD, lane);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KD; ++i)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[i]),
-                                                      __builtin_bit_cast(bf16x8, lds_frag(T, STD, r, wave * KD + i, g)), acc, 0, 0, 0);
+      for (int i = 0; i < KD; ++i) acc = mac2(acc, wv[i], T, STD, r, wave * KD + i, g);
       __syncthreads();
       *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
       __syncthreads();
@@ -829,7 +841,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     // a workgroup with several vocabulary tiles starts the next row tile from its first again
     if (NTV > 256 && w < NTV && mt + 1 < n_mt) load_frags<KD>(wv, a.WU, w, KTD, wave * KD, lane);
   }
-  XSM_STAMP(a.L * 8 + 3);
+  XSM_STAMP(a.L * 16 + 3);
 
   // ---- FINAL: workgroup b finishes sequence b ----
   if (w < a.n_seq) {
@@ -894,7 +906,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
     }
   }
-  XSM_STAMP(a.L * 8 + 4);
+  XSM_STAMP(a.L * 16 + 4);
   if (__syncthreads_or(!ok)) {
     if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return;
@@ -907,13 +919,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 }
 
 size_t small_ll_words(int n_layers, int D, int F, int K) {
-  const size_t layer = (size_t)6 * 16 * D + (size_t)16 * (F / 2) + (size_t)256 * 1056;
-  const size_t tail = (size_t)16 * D + (size_t)16 * 15 * (D / 2) + (size_t)4096 * 80 * 4;
+  const size_t layer = small_ll_layer_stride(D, F);
+  const size_t tail = (size_t)16 * D + (size_t)16 * 15 * D + (size_t)4096 * 80 * 4;
   (void)K;
   return layer * n_layers + (tail > layer ? tail : layer);
 }
 size_t small_ll_layer_stride(int D, int F) {
-  return (size_t)6 * 16 * D + (size_t)16 * (F / 2) + (size_t)256 * 1056;
+  return (size_t)6 * 16 * D + (size_t)16 * F + (size_t)3 * 16 * D + (size_t)256 * 1056;
 }
 
 bool small_supported(int D, int F) { return D == 1024 && F == 4096; }
@@ -922,10 +934,8 @@ void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
   TraceScope trace_("step_small", s);
   if (D == 1024 && F == 4096) {
     auto kfn = k_step_small<1024, 4096>;
-    // activation tiles: 16 rows of FFN width in bf16, or two 16-row model-width tiles plus an
-    // fp32 copy of the final hidden state
-    const size_t a1 = (size_t)16 * (4096 + 8) * 2, a2 = (size_t)32 * (1024 + 8) * 2 + (size_t)16 * 1024 * 4;
-    const size_t lds = a1 > a2 ? a1 : a2;
+    // activation tiles as bf16 hi + lo planes: two 16-row model-width tiles in the tail
+    const size_t lds = (size_t)4 * 16 * (1024 + 8) * 2;
     static bool configured = false;
     if (!configured) {
       (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -213,7 +213,7 @@ class Engine:
         self._check(self.L.xsm_debug_kv_clone(self.h, src_slot, dst_slot), "xsm_debug_kv_clone")
 
     def xsm_debug_timeline(self) -> np.ndarray:
-        out = np.zeros((256, self.c_cfg.n_layers * 8 + 8), np.uint64)
+        out = np.zeros((256, self.c_cfg.n_layers * 16 + 8), np.uint64)
         self._check(self.L.xsm_debug_timeline(self.h, out.ctypes.data, out.size), "xsm_debug_timeline")
         return out
 
