@@ -73,6 +73,19 @@ void build_work_offsets(xsm_ctx* c) {
   if (c->part_entries < 1024) c->part_entries = 1024;
   w.part = take(fattn_part_bytes(c->part_entries));
   w.tickets = take((size_t)g.max_batch * g.n_heads * 4);
+  w.gpart = w.gtickets = 0;
+  if (c->fast) {
+    // partial products of the split-contraction GEMM, for the largest projection it may run
+    const int shapes[6][2] = {{(int)(3 * d), (int)d}, {(int)d, (int)d}, {(int)F, (int)d}, {(int)d, (int)F},
+                              {(int)V, (int)d}, {(int)((K ? K : 1) * d), (int)d}};
+    size_t fl = 0;
+    for (auto& sh : shapes) {
+      const size_t need = ws_gemm_part_floats((int)(Mmax > Mb ? Mmax : Mb), sh[0], sh[1]);
+      if (need > fl) fl = need;
+    }
+    w.gpart = take(fl * 4);
+    w.gtickets = take(kWsTickets * 4);
+  }
   w.ll = w.ctrl = w.head_all = w.tlog = 0;
   if (c->small_ok) {
     w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
@@ -145,7 +158,10 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
   const int M = n_seq * R;
   char* ws = c->d_ws;
   float* X = (float*)(ws + c->ws.X);
-  float* Xn = (float*)(ws + c->ws.Xn);            // normalised rows of the row-blocked GEMM
+  float* Xn = (float*)(ws + c->ws.Xn);            // normalised rows for the GEMMs that do not fuse the norm
+  float* gpart = (float*)(ws + c->ws.gpart);
+  uint32_t* gtick = (uint32_t*)(ws + c->ws.gtickets);
+  PendingAdd* const PEND = &c->pend;
   float* Qr = (float*)(ws + c->ws.Qr);
   float* AO = (float*)(ws + c->ws.AO);
   float* U = (float*)(ws + c->ws.U);
@@ -159,7 +175,7 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     FastGemm q{};
     q.Wt = (const uint4*)(c->d_w + T.Wqkv); q.N = 3 * d; q.K = d; q.M = M;
     q.X = X; q.ldx = d; q.gain = (const uint16_t*)P.g1; q.eps = g.rms_eps;
-    q.Y = Qr; q.ldy = d; q.nscratch = Xn;
+    q.Y = Qr; q.ldy = d; q.nscratch = Xn; q.ws_part = gpart; q.ws_tickets = gtick; q.pend = PEND;
     q.rope = rope; q.eff_len = eff; q.slot = slot; q.R = R; q.H = H; q.hd = hd; q.cap = c->cap_self;
     q.v_transposed = 1; q.Kc = (uint16_t*)self_cache(c, l, 0); q.Vc = (uint16_t*)self_cache(c, l, 1);
     launch_fgemm(PRO_NORM, FEPI_QKV, q, s);
@@ -174,14 +190,14 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
 
     FastGemm o{};
     o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
-    o.X = AO; o.ldx = d; o.Y = X; o.ldy = d; o.nscratch = Xn;
+    o.X = AO; o.ldx = d; o.Y = X; o.ldy = d; o.nscratch = Xn; o.ws_part = gpart; o.ws_tickets = gtick; o.pend = PEND;
     launch_fgemm(PRO_F32, FEPI_ADD, o, s);
 
     if (g.n_cond > 0) {
       FastGemm cq{};
       cq.Wt = (const uint4*)(c->d_w + T.Wcq); cq.N = d; cq.K = d; cq.M = M;
       cq.X = X; cq.ldx = d; cq.gain = (const uint16_t*)P.gc; cq.eps = g.rms_eps;
-      cq.Y = Qr; cq.ldy = d; cq.nscratch = Xn;
+      cq.Y = Qr; cq.ldy = d; cq.nscratch = Xn; cq.ws_part = gpart; cq.ws_tickets = gtick; cq.pend = PEND;
       launch_fgemm(PRO_NORM, FEPI_STORE, cq, s);
       FastAttn ca = a;
       ca.Kc = (const uint16_t*)cross_cache(c, l, 0); ca.Vt = (const uint16_t*)cross_cache(c, l, 1);
@@ -195,14 +211,15 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     FastGemm u{};
     u.Wt = (const uint4*)(c->d_w + T.W1); u.N = F; u.K = d; u.M = M;
     u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
-    u.Y = U; u.ldy = F; u.nscratch = Xn;
+    u.Y = U; u.ldy = F; u.nscratch = Xn; u.ws_part = gpart; u.ws_tickets = gtick; u.pend = PEND;
     launch_fgemm(PRO_NORM, FEPI_GELU, u, s);
 
     FastGemm dn{};
     dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
-    dn.X = U; dn.ldx = F; dn.Y = X; dn.ldy = d; dn.nscratch = Xn;
+    dn.X = U; dn.ldx = F; dn.Y = X; dn.ldy = d; dn.nscratch = Xn; dn.ws_part = gpart; dn.ws_tickets = gtick; dn.pend = PEND;
     launch_fgemm(PRO_F32, FEPI_ADD, dn, s);
   }
+  flush_pending_add(PEND, s);                     // the residual rows are read by the caller next
 }
 
 // All decoder blocks over M = n_seq*R rows held in ws.X; row m = b*R + j sits at position
@@ -277,6 +294,9 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   float* X = (float*)(ws + ctx->ws.X);
   float* Xn = (float*)(ws + ctx->ws.Xn);
   float* Z0 = (float*)(ws + ctx->ws.Z0);
+  float* gpart = (float*)(ws + ctx->ws.gpart);
+  uint32_t* gtick = (uint32_t*)(ws + ctx->ws.gtickets);
+  PendingAdd* const PEND = &ctx->pend;
   float* G = (float*)(ws + ctx->ws.G);
   float* Hh = (float*)(ws + ctx->ws.Hh);
   float* Rk = (float*)(ws + ctx->ws.Rk);
@@ -330,7 +350,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     FastGemm z{};
     z.Wt = (const uint4*)(wb + ctx->toff.WU); z.N = V; z.K = d; z.M = M;
     z.X = X; z.ldx = d; z.gain = (const uint16_t*)(wb + ctx->woff.gf * e); z.eps = g.rms_eps;
-    z.Y = Z0; z.ldy = V; z.nscratch = Xn;
+    z.Y = Z0; z.ldy = V; z.nscratch = Xn; z.ws_part = gpart; z.ws_tickets = gtick; z.pend = PEND;
     launch_fgemm(PRO_NORM, FEPI_STORE, z, s);
     if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
     launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
@@ -341,11 +361,11 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
       hg.Wt = (const uint4*)(wb + ctx->toff.Wh); hg.N = K * d; hg.K = d; hg.M = n_seq;
       hg.X = X; hg.ldx = d; hg.gain = z.gain; hg.eps = g.rms_eps; hg.row_index = rowidx;
       hg.Y = Rk; hg.ldy = K * d; hg.bias = (const uint16_t*)(wb + ctx->toff.hb);
-      hg.nscratch = Xn;
+      hg.nscratch = Xn; hg.ws_part = gpart; hg.ws_tickets = gtick; hg.pend = PEND;
       launch_fgemm(PRO_NORM, FEPI_HEAD, hg, s);
       FastGemm zh{};
       zh.Wt = z.Wt; zh.N = V; zh.K = d; zh.M = n_seq * K;
-      zh.X = Rk; zh.ldx = d; zh.Y = Zh; zh.ldy = V; zh.nscratch = Xn;
+      zh.X = Rk; zh.ldx = d; zh.Y = Zh; zh.ldy = V; zh.nscratch = Xn; zh.ws_part = gpart; zh.ws_tickets = gtick; zh.pend = PEND;
       launch_fgemm(PRO_F32, FEPI_STORE, zh, s);
       if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     }
@@ -470,6 +490,7 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
       launch_copy_u16(wb + ctx->woff.hb[k] * 2, wb + ctx->toff.hb + (size_t)k * d * 2, d, s);
     }
     launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), g.max_batch * g.n_heads, 0, s);
+    launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.gtickets), (int)kWsTickets, 0, s);
     if (ctx->small_ok) {
       ctx->layer_tab.resize(g.n_layers);
       for (int l = 0; l < g.n_layers; ++l) {

@@ -10,9 +10,16 @@
 // first weight fragments are requested before the activation prologue runs, because they
 // do not depend on it.
 //
-// Prologues: RMSNorm of fp32 rows (optionally gathered by a row index), fp32 rows, bf16 rows.
-// Epilogues: store, residual add, erf-GELU to bf16, rotary + q / cache write (fused QKV),
+// Prologues: RMSNorm of fp32 rows (optionally gathered by a row index), fp32 rows.
+// Epilogues: store, residual add, erf-GELU, rotary + q / cache write (fused QKV),
 // decoding-head activation r = g + SiLU(y + b).
+//
+// Three kernels share the fragment layout and the epilogues:
+//   k_fgemm     M <= 32: one tile per workgroup, whole contraction length, norm fused
+//   k_gemm_ws   M <= 256: 64 weight rows x 256 of the contraction index per workgroup, all
+//               held in registers from one request; partial products merged by the last
+//               workgroup to finish (fixed order)
+//   k_gemm_big  larger M: row-blocked, weights re-read from the XCD's L2 per row block
 #include "xsm_device.h"
 #include "xsm_internal.h"
 
@@ -423,6 +430,345 @@ static bool big_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
   return true;
 }
 
+// ---------------------------------------------------------------------------
+// Mid-size M (17..256 rows).  A weight matrix of a few MB is smaller than what the memory
+// system holds in flight, so the only way to stream it at speed is to have it requested all at
+// once: every workgroup takes 64 weight rows x 256 of the contraction index (32 KB, eight
+// fragments per lane and tile) in one go, the activation slice [M][256] is staged through LDS
+// (hi / lo planes) and shared by the four wavefronts (2 weight tiles x 4 row tiles each), and
+// the K/256 partial products of an output block are summed in slice order by whichever
+// workgroup finishes last, which also applies the epilogue.
+// ---------------------------------------------------------------------------
+constexpr int kWsKS = 256, kWsBM = 128, kWsST = kWsKS + 8, kWsPlane = kWsBM * kWsST;
+constexpr int kWsMaxM = 256;
+
+__device__ __forceinline__ void ws_st2(uint64_t* p, float a, float b) {
+  __hip_atomic_store(p, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Partial products live as contiguous blocks [column group][slice][row][64] so that both sides
+// address them as (uniform base) + (one per-thread offset): with dozens of loads in flight the
+// address registers, not the data, would otherwise run the register file over.
+//
+// RED = false (residual-add projections only): the kernel stops after writing its partial
+// block; the RMSNorm pass that always follows such a projection adds the slices to the residual
+// rows while it reads them anyway (k_norm_rows with a pending sum).
+
+// fused-QKV epilogue for the column pair (n, n + 1) of row m; everything that depends on n only
+// is precomputed in QkvCols
+struct QkvCols { int sec, h, dim0, pi0; bool low; };
+__device__ __forceinline__ QkvCols qkv_cols(const FastGemm& g, int n) {
+  const int d = g.H * g.hd, nt = n >> 4, nrow = n & 15;
+  const int tps = d / 16, tph = g.hd / 16;
+  QkvCols c;
+  c.sec = nt / tps;
+  const int ts = nt % tps, tt = ts % tph;
+  c.h = ts / tph;
+  c.low = nrow < 8;
+  c.pi0 = tt * 8 + (nrow & 7);
+  c.dim0 = c.sec < 2 ? (c.low ? c.pi0 : g.hd / 2 + c.pi0) : tt * 16 + nrow;
+  return c;
+}
+__device__ __forceinline__ void qkv_pair_store(const FastGemm& g, const QkvCols& c, int m, float2 v, float2 partner) {
+  const int b = m / g.R, j = m - b * g.R;
+  const int len = g.eff_len[b];
+  if (len < 0) return;
+  const int pos = len + j;
+  float2 o = v;
+  if (c.sec < 2) {
+    const float4 cs = *reinterpret_cast<const float4*>(&g.rope[(size_t)pos * (g.hd / 2) + c.pi0]);   // (cos, sin) x 2
+    if (c.low) { o.x = v.x * cs.x - partner.x * cs.y; o.y = v.y * cs.z - partner.y * cs.w; }
+    else { o.x = partner.x * cs.y + v.x * cs.x; o.y = partner.y * cs.w + v.y * cs.z; }
+  }
+  const size_t head = (size_t)g.slot[b] * g.H + c.h;
+  if (c.sec == 0) {
+    *reinterpret_cast<float2*>(g.Y + (size_t)m * g.ldy + c.h * g.hd + c.dim0) = o;
+  } else if (c.sec == 1) {
+    *reinterpret_cast<uint32_t*>(g.Kc + (head * g.cap + pos) * g.hd + c.dim0) = pack_bf16(o.x, o.y);
+  } else if (g.v_transposed) {
+    g.Vc[(head * g.hd + c.dim0) * g.cap + pos] = f2bf(o.x);
+    g.Vc[(head * g.hd + c.dim0 + 1) * g.cap + pos] = f2bf(o.y);
+  } else {
+    *reinterpret_cast<uint32_t*>(g.Vc + (head * g.cap + pos) * g.hd + c.dim0) = pack_bf16(o.x, o.y);
+  }
+}
+
+template <int EPI, bool RED>
+__global__ __launch_bounds__(256) void k_gemm_ws(const FastGemm g) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int sm_last;
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, gq = lane >> 4;
+  const int KT = g.K / 32, KSPL = g.K / kWsKS, NG = g.N / 64, total = NG * KSPL;
+  // workgroup ids go round-robin over the 8 XCDs; make the workgroups of one slice of the
+  // contraction index neighbours on one XCD, whose L2 then holds that activation slice once
+  int id = blockIdx.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int ks = id / NG, ng = id % NG;
+  const int wn = wave & 1, wm = wave >> 1;            // weight tiles 2wn, 2wn+1; row tiles 4wm..4wm+3
+  const int MB = (g.M + kWsBM - 1) / kWsBM;
+
+  // activation pieces (row, 4 columns) p = tid + 256 j, row = tid/64 + 4j: a whole row block
+  // (up to 32 pieces per thread) is requested at once, the next block while this one is multiplied
+  const unsigned st_off = (unsigned)(tid >> 6) * (unsigned)g.ldx * 4u + (unsigned)(tid & 63) * 16u;
+  float4 v[32];
+  auto request = [&](int mb) {
+    const int m0 = mb * kWsBM, rows = min(kWsBM, g.M - m0);
+    const char* xb = reinterpret_cast<const char*>(g.X + (size_t)m0 * g.ldx + ks * kWsKS);
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      v[j] = float4{0.f, 0.f, 0.f, 0.f};
+      if (4 * j + (tid >> 6) < rows) v[j] = *reinterpret_cast<const float4*>(xb + (size_t)j * 16 * g.ldx + st_off);
+    }
+  };
+  request(0);
+  uint4 wf[2][8];                                      // the workgroup's weights: one request, kept
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint4* wb = g.Wt + ((size_t)(ng * 4 + wn * 2 + t) * KT + ks * (kWsKS / 32)) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wf[t][i] = wb[(size_t)i * 64];
+  }
+
+  const size_t blk = (size_t)g.M * 64;                 // floats of one (column group, slice) block
+  float* const part_ng = g.ws_part + (size_t)ng * KSPL * blk;
+  for (int mb = 0; mb < MB; ++mb) {
+    const int m0 = mb * kWsBM, rows = min(kWsBM, g.M - m0), rows16 = (rows + 15) & ~15;
+    __syncthreads();                                   // LDS and sm_last of the previous block are free
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const int row = 4 * j + (tid >> 6);
+      if (row < rows16) {
+        uint2 hi, lo;
+        split4(v[j], hi, lo);
+        uint16_t* dst = As + (size_t)row * kWsST + (tid & 63) * 4;
+        *reinterpret_cast<uint2*>(dst) = hi;
+        *reinterpret_cast<uint2*>(dst + kWsPlane) = lo;
+      }
+    }
+    __syncthreads();
+    if (mb + 1 < MB) request(mb + 1);
+
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[t][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int mt = wm * 4 + q;
+      if (mt * 16 < rows16) {
+        const uint16_t* bp = As + (size_t)(mt * 16 + r) * kWsST + gq * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + i * 32));
+          const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + kWsPlane + i * 32));
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wf[t][i]);
+            acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[t][q], 0, 0, 0);
+            acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[t][q], 0, 0, 0);
+          }
+        }
+      }
+    }
+    // partial products of this slice: lane holds D[n0 + e][m], e = 0..3
+    {
+      char* pb = reinterpret_cast<char*>(part_ng + (size_t)ks * blk + (size_t)m0 * 64);
+      const unsigned po = ((unsigned)(wm * 64 + r) * 64u + (unsigned)(wn * 32 + gq * 4)) * 4u;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (m0 + (wm * 4 + q) * 16 + r < g.M) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            char* dst = pb + (size_t)(q * 16 * 64 + t * 16) * 4 + po;
+            if (RED) {
+              ws_st2(reinterpret_cast<uint64_t*>(dst), acc[t][q][0], acc[t][q][1]);
+              ws_st2(reinterpret_cast<uint64_t*>(dst) + 1, acc[t][q][2], acc[t][q][3]);
+            } else {
+              *reinterpret_cast<f32x4*>(dst) = acc[t][q];
+            }
+          }
+        }
+      }
+    }
+    if (!RED) continue;
+    __builtin_amdgcn_s_waitcnt(0);                     // this workgroup's partial is in memory
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t* tk = g.ws_tickets + ng * MB + mb;
+      const uint32_t old = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sm_last = old == (uint32_t)(KSPL - 1);
+      if (sm_last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!sm_last) continue;
+    // last to arrive: sum the slices in order, finish the block [rows][64 columns]; a thread
+    // takes column pairs, sixteen at a time with four slices each in flight
+    const int npairs = rows * 32;
+    const int n = ng * 64 + (tid & 31) * 2;            // this thread's column pair, the same in every round
+    QkvCols qc{};
+    if (EPI == FEPI_QKV) qc = qkv_cols(g, n);
+    for (int i0 = 0; i0 < npairs; i0 += 256 * 16) {
+      float2 sum[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) sum[u] = float2{0.f, 0.f};
+      for (int k0 = 0; k0 < KSPL; k0 += 4) {
+        uint64_t t[16][4];
+        const char* sb = reinterpret_cast<const char*>(part_ng + (size_t)k0 * blk + (size_t)m0 * 64) + (size_t)i0 * 8;
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+          if (i0 + 256 * u + tid < npairs) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (k0 + j < KSPL)
+                t[u][j] = __hip_atomic_load(reinterpret_cast<const uint64_t*>(sb + (size_t)j * blk * 4 + (size_t)u * 2048 + (unsigned)tid * 8u),
+                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+          if (i0 + 256 * u + tid < npairs) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (k0 + j < KSPL) {
+                sum[u].x += __uint_as_float((uint32_t)t[u][j]);
+                sum[u].y += __uint_as_float((uint32_t)(t[u][j] >> 32));
+              }
+          }
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int idx = i0 + 256 * u + tid;
+        if (idx < npairs) {
+          const int m = m0 + (idx >> 5);
+          if (EPI == FEPI_QKV) {
+            // rows n +- 8 of the same 16-row tile sit four column pairs away
+            const float2 partner = float2{__shfl_xor(sum[u].x, 4, WAVE), __shfl_xor(sum[u].y, 4, WAVE)};
+            qkv_pair_store(g, qc, m, sum[u], partner);
+          } else {
+            float2* y = reinterpret_cast<float2*>(g.Y + (size_t)m * g.ldy + n);
+            if (EPI == FEPI_STORE) {
+              *y = sum[u];
+            } else if (EPI == FEPI_ADD) {
+              const float2 o = *y;
+              *y = float2{o.x + sum[u].x, o.y + sum[u].y};
+            } else if (EPI == FEPI_GELU) {
+              *y = float2{gelu_erf_f(sum[u].x), gelu_erf_f(sum[u].y)};
+            } else if (EPI == FEPI_HEAD) {
+              const int c = n % g.K;                     // X: normalised rows here
+              const float p0 = sum[u].x + bf2f(g.bias[n]), p1 = sum[u].y + bf2f(g.bias[n + 1]);
+              const float2 gn = *reinterpret_cast<const float2*>(g.X + (size_t)m * g.ldx + c);
+              *y = float2{gn.x + p0 / (1.0f + __expf(-p0)), gn.y + p1 / (1.0f + __expf(-p1))};
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// One workgroup per row: adds the pending partial products of a residual-add projection to the
+// row (slices in order), writes it back, and (out != nullptr) writes its RMSNorm to out.
+__global__ __launch_bounds__(256) void k_norm_rows_pending(float* X, int ldx, const float* part, int kspl, int Mtot,
+                                                           const uint16_t* gain, float eps, float* out, int K) {
+  __shared__ float red[8];
+  const int m = blockIdx.x;
+  float* x = X + (size_t)m * ldx;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < K; c += 1024) {
+    float4 a = *reinterpret_cast<const float4*>(x + c);
+    const float* pp = part + ((size_t)(c >> 6) * kspl * Mtot + m) * 64 + (c & 63);
+    for (int k0 = 0; k0 < kspl; k0 += 8) {
+      float4 t[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (k0 + j < kspl) t[j] = *reinterpret_cast<const float4*>(pp + (size_t)(k0 + j) * Mtot * 64);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (k0 + j < kspl) { a.x += t[j].x; a.y += t[j].y; a.z += t[j].z; a.w += t[j].w; }
+    }
+    *reinterpret_cast<float4*>(x + c) = a;
+    ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+  }
+  if (!out) return;
+  ss = block_sum(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)K + eps);
+  for (int c = threadIdx.x * 4; c < K; c += 1024) {
+    float4 a = *reinterpret_cast<const float4*>(x + c);       // this thread's own stores
+    const uint2 gg = *reinterpret_cast<const uint2*>(gain + c);
+    a.x *= inv * __uint_as_float(gg.x << 16); a.y *= inv * __uint_as_float(gg.x & 0xFFFF0000u);
+    a.z *= inv * __uint_as_float(gg.y << 16); a.w *= inv * __uint_as_float(gg.y & 0xFFFF0000u);
+    *reinterpret_cast<float4*>(out + (size_t)m * K + c) = a;
+  }
+}
+
+void flush_pending_add(PendingAdd* p, hipStream_t s) {
+  if (!p || !p->active) return;
+  hipLaunchKernelGGL(k_norm_rows_pending, dim3(p->M), dim3(256), 0, s, p->Y, p->ldy, p->part, p->kspl, p->M, nullptr,
+                     0.f, nullptr, p->N);
+  p->active = false;
+}
+
+bool ws_gemm_shape_ok(int M, int N, int K) {
+  return M > 16 && M <= kWsMaxM && K % kWsKS == 0 && K >= 2 * kWsKS && N % 64 == 0;
+}
+size_t ws_gemm_part_floats(int M, int N, int K) {
+  return (size_t)(K / kWsKS) * (size_t)(M < kWsMaxM ? M : kWsMaxM) * N;
+}
+
+template <int EPI, bool RED>
+static void ws_launch(const FastGemm& g, hipStream_t s) {
+  const size_t lds = (size_t)2 * kWsPlane * 2;
+  auto kfn = k_gemm_ws<EPI, RED>;
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured = true;
+  }
+  hipLaunchKernelGGL(kfn, dim3((g.N / 64) * (g.K / kWsKS)), dim3(256), lds, s, g);
+}
+
+static bool ws_gemm_usable(const FastGemm& g) {
+  return ws_gemm_shape_ok(g.M, g.N, g.K) && g.ws_part && g.ws_tickets && g.nscratch &&
+         (size_t)(g.N / 64) * ((g.M + kWsBM - 1) / kWsBM) <= kWsTickets;
+}
+
+static void ws_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
+  PendingAdd* pend = g.pend;
+  if (pro == PRO_NORM) {
+    if (pend && pend->active && pend->Y == g.X && pend->M == g.M && pend->N == g.K && !g.row_index) {
+      // the rows still lack the previous projection's output: add it while normalising
+      hipLaunchKernelGGL(k_norm_rows_pending, dim3(g.M), dim3(256), 0, s, pend->Y, pend->ldy, pend->part, pend->kspl,
+                         pend->M, g.gain, g.eps, g.nscratch, g.K);
+      pend->active = false;
+    } else {
+      flush_pending_add(pend, s);
+      hipLaunchKernelGGL(k_norm_rows, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
+                         g.nscratch, g.K);
+    }
+    g.X = g.nscratch; g.ldx = g.K; g.row_index = nullptr;
+  } else {
+    flush_pending_add(pend, s);
+  }
+  switch (epi) {
+    case FEPI_STORE: ws_launch<FEPI_STORE, true>(g, s); break;
+    case FEPI_ADD:
+      if (pend) {                                      // leave the sum to the RMSNorm pass that follows
+        ws_launch<FEPI_ADD, false>(g, s);
+        *pend = PendingAdd{true, g.ws_part, g.K / kWsKS, g.M, g.N, g.Y, g.ldy};
+      } else {
+        ws_launch<FEPI_ADD, true>(g, s);
+      }
+      break;
+    case FEPI_GELU: ws_launch<FEPI_GELU, true>(g, s); break;
+    case FEPI_QKV: ws_launch<FEPI_QKV, true>(g, s); break;
+    case FEPI_HEAD: ws_launch<FEPI_HEAD, true>(g, s); break;
+    default: break;
+  }
+}
+
 static size_t fgemm_lds(int MT, int KC) {
   return (size_t)2 * 16 * MT * (KC + 8) * 2 + (size_t)4 * MT * 256 * 4 + (size_t)16 * MT * 4;
 }
@@ -455,6 +801,12 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 
 void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   if (g.M <= 0) return;
+  if (ws_gemm_usable(g)) {
+    TraceScope trace_("gemm_ws", s);
+    ws_gemm(pro, epi, g, s);
+    return;
+  }
+  flush_pending_add(g.pend, s);                        // the other kernels read finished rows
   if (g.M > kBigMinM) {
     TraceScope trace_("gemm_big", s);
     if (big_gemm(pro, epi, g, s)) return;

@@ -27,7 +27,7 @@ struct WeightOff {
 struct WorkOff {
   size_t X, Xn, QKV, Qr, AO, U, Z0, G, Hh, Rk, Zh;
   size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
-  size_t part, tickets;                                  // split-key attention partials
+  size_t part, tickets, gpart, gtickets;                                  // split-key attention partials
   size_t ll, ctrl, head_all, tlog;                       // single-launch step: exchange buffers
   size_t total;
 };
@@ -41,6 +41,17 @@ struct TiledOff {
 };
 
 // Per-layer pointers of the single-launch step (uploaded to the device at load time).
+// Output of a residual-add projection that is still in split-contraction partial blocks
+// [N/64][kspl][M][64]; the next RMSNorm pass over Y (or flush_pending_add) adds it in.
+struct PendingAdd {
+  bool active = false;
+  const float* part = nullptr;
+  int kspl = 0, M = 0, N = 0;
+  float* Y = nullptr;
+  int ldy = 0;
+};
+void flush_pending_add(PendingAdd* p, hipStream_t s);
+
 struct LayerTab {
   const uint4 *Wqkv, *Wo, *W1, *W2;     // fragment-ordered weights
   const uint16_t *g1, *g2;              // RMSNorm gains (bf16)
@@ -66,6 +77,7 @@ struct xsm_ctx {
   std::vector<xsm::LayerTab> layer_tab;  // host copy (source of the upload)
   xsm::TiledOff toff;
   int cap_self = 0, cap_cross = 0;   // cache capacities in positions, padded to 64
+  xsm::PendingAdd pend;              // see PendingAdd
   size_t part_entries = 0;           // (sequence, head, split) partial slots in the workspace
   char* d_w = nullptr;
   char* d_kv = nullptr;
@@ -133,13 +145,18 @@ struct FastGemm {
   const int32_t* row_index;    // optional gather: input row of output row m
   float* Y; int ldy;           // fp32 output (for FEPI_QKV: the rotated queries [M][d])
   const uint16_t* bias;        // FEPI_HEAD: stacked biases [N]
-  float* nscratch;             // [M][K] fp32: normalised rows for the row-blocked kernel
+  float* nscratch;             // [M][K] fp32: normalised rows for the kernels that do not fuse the norm
+  float* ws_part; uint32_t* ws_tickets;   // split-contraction partial products and arrival counters
+  PendingAdd* pend;            // host-side: where a residual-add projection may leave its sum pending
   // FEPI_QKV
   const float2* rope; const int32_t* eff_len; const int32_t* slot;
   int R, H, hd, cap, v_transposed;
   uint16_t* Kc; uint16_t* Vc;
 };
 bool fgemm_supported(int N, int K);
+constexpr size_t kWsTickets = 4096;      // arrival counters of the split-contraction GEMM
+bool ws_gemm_shape_ok(int M, int N, int K);
+size_t ws_gemm_part_floats(int M, int N, int K);
 void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s);
 void launch_tile_weights(const void* W, void* out, int N, int K, int rope_d, int rope_hd, hipStream_t s);
 void launch_copy_u16(const void* src, void* dst, int n, hipStream_t s);
