@@ -258,8 +258,21 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
 // memory (HBM once, then the XCD's L2: all row blocks of one weight tile pair are placed on the
 // same XCD).  RMSNorm is done once per row by k_norm_rows instead of once per workgroup.
 // ---------------------------------------------------------------------------
+// normalised row piece -> fp32 row of out, or (split) bf16 hi / lo planes [M][K] laid over the same buffer
+__device__ __forceinline__ void norm_out(float* out, bool split, int M, int m, int K, int c, float4 v) {
+  if (!split) {
+    *reinterpret_cast<float4*>(out + (size_t)m * K + c) = v;
+  } else {
+    uint2 hi, lo;
+    split4(v, hi, lo);
+    uint16_t* hp = reinterpret_cast<uint16_t*>(out) + (size_t)m * K + c;
+    *reinterpret_cast<uint2*>(hp) = hi;
+    *reinterpret_cast<uint2*>(hp + (size_t)M * K) = lo;
+  }
+}
+
 __global__ __launch_bounds__(256) void k_norm_rows(const float* X, int ldx, const int32_t* row_index,
-                                                   const uint16_t* gain, float eps, float* out, int K) {
+                                                   const uint16_t* gain, float eps, float* out, int K, int split) {
   __shared__ float red[8];
   const int m = blockIdx.x;
   const float* x = X + (size_t)(row_index ? row_index[m] : m) * ldx;
@@ -275,7 +288,7 @@ __global__ __launch_bounds__(256) void k_norm_rows(const float* X, int ldx, cons
     const uint2 gg = *reinterpret_cast<const uint2*>(gain + c);
     v.x *= inv * __uint_as_float(gg.x << 16); v.y *= inv * __uint_as_float(gg.x & 0xFFFF0000u);
     v.z *= inv * __uint_as_float(gg.y << 16); v.w *= inv * __uint_as_float(gg.y & 0xFFFF0000u);
-    *reinterpret_cast<float4*>(out + (size_t)m * K + c) = v;
+    norm_out(out, split != 0, gridDim.x, m, K, c, v);
   }
 }
 
@@ -416,7 +429,7 @@ static bool big_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
   if (g.M <= kBigMinM || g.N % 256 != 0 || !g.nscratch) return false;
   if (pro == PRO_NORM) {
     hipLaunchKernelGGL(k_norm_rows, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
-                       g.nscratch, g.K);
+                       g.nscratch, g.K, 0);
     g.X = g.nscratch; g.ldx = g.K; g.row_index = nullptr;
   }
   switch (epi) {
@@ -672,7 +685,8 @@ __global__ __launch_bounds__(256) void k_gemm_ws(const FastGemm g) {
 // One workgroup per row: adds the pending partial products of a residual-add projection to the
 // row (slices in order), writes it back, and (out != nullptr) writes its RMSNorm to out.
 __global__ __launch_bounds__(256) void k_norm_rows_pending(float* X, int ldx, const float* part, int kspl, int Mtot,
-                                                           const uint16_t* gain, float eps, float* out, int K) {
+                                                           const uint16_t* gain, float eps, float* out, int K,
+                                                           int split) {
   __shared__ float red[8];
   const int m = blockIdx.x;
   float* x = X + (size_t)m * ldx;
@@ -700,14 +714,14 @@ __global__ __launch_bounds__(256) void k_norm_rows_pending(float* X, int ldx, co
     const uint2 gg = *reinterpret_cast<const uint2*>(gain + c);
     a.x *= inv * __uint_as_float(gg.x << 16); a.y *= inv * __uint_as_float(gg.x & 0xFFFF0000u);
     a.z *= inv * __uint_as_float(gg.y << 16); a.w *= inv * __uint_as_float(gg.y & 0xFFFF0000u);
-    *reinterpret_cast<float4*>(out + (size_t)m * K + c) = a;
+    norm_out(out, split != 0, gridDim.x, m, K, c, a);
   }
 }
 
 void flush_pending_add(PendingAdd* p, hipStream_t s) {
   if (!p || !p->active) return;
   hipLaunchKernelGGL(k_norm_rows_pending, dim3(p->M), dim3(256), 0, s, p->Y, p->ldy, p->part, p->kspl, p->M, nullptr,
-                     0.f, nullptr, p->N);
+                     0.f, nullptr, p->N, 0);
   p->active = false;
 }
 
@@ -735,23 +749,178 @@ static bool ws_gemm_usable(const FastGemm& g) {
          (size_t)(g.N / 64) * ((g.M + kWsBM - 1) / kWsBM) <= kWsTickets;
 }
 
-static void ws_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
-  PendingAdd* pend = g.pend;
-  if (pro == PRO_NORM) {
-    if (pend && pend->active && pend->Y == g.X && pend->M == g.M && pend->N == g.K && !g.row_index) {
-      // the rows still lack the previous projection's output: add it while normalising
-      hipLaunchKernelGGL(k_norm_rows_pending, dim3(g.M), dim3(256), 0, s, pend->Y, pend->ldy, pend->part, pend->kspl,
-                         pend->M, g.gain, g.eps, g.nscratch, g.K);
-      pend->active = false;
-    } else {
-      flush_pending_add(pend, s);
-      hipLaunchKernelGGL(k_norm_rows, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
-                         g.nscratch, g.K);
+// ---------------------------------------------------------------------------
+// Same M range, projections whose input is a normalised row block and that have at least 128
+// column tiles (QKV, FFN up, unembedding, stacked heads): no split of the contraction index
+// across workgroups and no LDS staging.  The norm pass writes the rows as bf16 hi / lo planes;
+// one workgroup owns one 16-row weight tile over the whole contraction length (its four
+// wavefronts take a quarter each, fragments in registers from one request) and reads the
+// MFMA "B" fragments of all row tiles straight from the planes, 16 bytes per lane, two
+// k-tiles in flight.  The four partial tiles are summed through LDS in a fixed order.
+// ---------------------------------------------------------------------------
+constexpr int kWtMaxKW = 16;                           // k-tiles per wavefront: K <= 2048
+
+// 16-byte load that does not allocate in the compute unit's vector cache (policy bit sc1):
+// activation blocks are read once per workgroup out of L2, and going through the vector cache
+// more than halves the rate a compute unit sustains on such a stream.  Reads past the end of the
+// buffer return zero.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t stream_rsrc(const void* base, size_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 stream_ld16(__amdgpu_buffer_rsrc_t rs, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, 16);
+  return uint4{v.x, v.y, v.z, v.w};
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
+  __shared__ __align__(16) float red[4][8][64][4];      // [wavefront][row tile][lane][4]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, gq = lane >> 4;
+  const int nt = blockIdx.x, KT = g.K / 32, KW = KT / 4;
+  const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);          // [M][K] bf16 hi, then lo
+  const size_t lo_off = (size_t)g.M * g.K;
+  const __amdgpu_buffer_rsrc_t brs = stream_rsrc(Bh, lo_off * 4);
+
+  uint4 wf[kWtMaxKW];
+  {
+    const uint4* wb = g.Wt + ((size_t)nt * KT + wave * KW) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < kWtMaxKW; ++i)
+      if (i < KW) wf[i] = wb[(size_t)i * 64];
+  }
+  for (int m0 = 0; m0 < g.M; m0 += 128) {
+    const int rows = min(128, g.M - m0), ntile = (rows + 15) >> 4;
+    // lane's row in row tile mt (rows past M are clamped: their columns are never stored)
+    const unsigned bp = (unsigned)(wave * KW * 32 + gq * 8) * 2u;      // byte offsets into the hi plane
+    unsigned roff[8];
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) roff[mt] = (unsigned)min(m0 + mt * 16 + r, g.M - 1) * (unsigned)g.K * 2u;
+    f32x4 acc[8];
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 b0[8][2], b1[8][2];
+    auto fetch = [&](uint4 (&b)[8][2], int i) {
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+        if (mt < ntile) {
+          const unsigned o = bp + roff[mt] + (unsigned)i * 64u;
+          b[mt][0] = stream_ld16(brs, o);
+          b[mt][1] = stream_ld16(brs, o + (unsigned)lo_off * 2u);
+        }
+    };
+    auto mac = [&](const uint4 (&b)[8][2], const uint4& w) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+        if (mt < ntile) {
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[mt][1]), acc[mt], 0, 0, 0);
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[mt][0]), acc[mt], 0, 0, 0);
+        }
+    };
+    fetch(b0, 0);
+#pragma unroll
+    for (int i = 0; i < kWtMaxKW; i += 2) {
+      if (i < KW) {
+        if (i + 1 < KW) fetch(b1, i + 1);
+        mac(b0, wf[i]);
+        if (i + 1 < KW) {
+          if (i + 2 < KW) fetch(b0, i + 2);
+          mac(b1, wf[i + 1]);
+        }
+      }
     }
-    g.X = g.nscratch; g.ldx = g.K; g.row_index = nullptr;
+    __syncthreads();                                   // red is free (previous row block finished)
+#pragma unroll
+    for (int mt = 0; mt < 8; ++mt)
+      if (mt < ntile) *reinterpret_cast<f32x4*>(&red[wave][mt][lane][0]) = acc[mt];
+    __syncthreads();
+    // thread: row tile tid/32, lanes 2(tid%32), +1 of it
+    const int mt = tid >> 5;
+    if (mt < ntile) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int ll = (tid & 31) * 2 + q, lr = ll & 15, lg = ll >> 4;
+        f32x4 v = *reinterpret_cast<const f32x4*>(&red[0][mt][ll][0]);
+        v += *reinterpret_cast<const f32x4*>(&red[1][mt][ll][0]);
+        f32x4 v2 = *reinterpret_cast<const f32x4*>(&red[2][mt][ll][0]);
+        v2 += *reinterpret_cast<const f32x4*>(&red[3][mt][ll][0]);
+        v += v2;
+        const int m = m0 + mt * 16 + lr, n0 = nt * 16 + lg * 4;
+        if (EPI == FEPI_QKV) {
+          float pr[4];                                  // rows +- 8 of the tile: lane ll ^ 32, thread ^ 16
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(v[e], 16, WAVE);
+          if (m < g.M) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) qkv_store(g, nt, lg * 4 + e, m, v[e], pr[e]);
+          }
+        } else if (m < g.M) {
+          f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
+          if (EPI == FEPI_STORE) {
+            *y = v;
+          } else if (EPI == FEPI_ADD) {
+            *y = *y + v;
+          } else if (EPI == FEPI_GELU) {
+            *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
+          } else if (EPI == FEPI_HEAD) {
+            f32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int n = n0 + e, c = n % g.K;
+              const float pre = v[e] + bf2f(g.bias[n]);
+              const float gn = bf2f(Bh[(size_t)m * g.K + c]) + bf2f(Bh[lo_off + (size_t)m * g.K + c]);
+              o[e] = gn + pre / (1.0f + __expf(-pre));
+            }
+            *y = o;
+          }
+        }
+      }
+    }
+  }
+}
+
+static bool wt_gemm_usable(int pro, const FastGemm& g) {
+  return pro == PRO_NORM && g.M > 16 && g.M <= kWsMaxM && g.N % 16 == 0 && g.N / 16 >= 128 && g.K % 128 == 0 &&
+         g.K / 128 <= kWtMaxKW && g.nscratch;
+}
+
+template <int EPI>
+static void wt_launch(const FastGemm& g, hipStream_t s) {
+  hipLaunchKernelGGL(k_gemm_wt<EPI>, dim3(g.N / 16), dim3(256), 0, s, g);
+}
+
+// the RMSNorm pass in front of a projection; takes in a pending residual sum when there is one
+static void norm_pass(FastGemm& g, int split, hipStream_t s) {
+  PendingAdd* pend = g.pend;
+  if (pend && pend->active && pend->Y == g.X && pend->M == g.M && pend->N == g.K && !g.row_index) {
+    hipLaunchKernelGGL(k_norm_rows_pending, dim3(g.M), dim3(256), 0, s, pend->Y, pend->ldy, pend->part, pend->kspl,
+                       pend->M, g.gain, g.eps, g.nscratch, g.K, split);
+    pend->active = false;
   } else {
     flush_pending_add(pend, s);
+    hipLaunchKernelGGL(k_norm_rows, dim3(g.M), dim3(256), 0, s, g.X, g.ldx, g.row_index, g.gain, g.eps,
+                       g.nscratch, g.K, split);
   }
+  g.X = g.nscratch; g.ldx = g.K; g.row_index = nullptr;
+}
+
+static void wt_gemm(int epi, FastGemm g, hipStream_t s) {
+  norm_pass(g, 1, s);
+  switch (epi) {
+    case FEPI_STORE: wt_launch<FEPI_STORE>(g, s); break;
+    case FEPI_GELU: wt_launch<FEPI_GELU>(g, s); break;
+    case FEPI_QKV: wt_launch<FEPI_QKV>(g, s); break;
+    case FEPI_HEAD: wt_launch<FEPI_HEAD>(g, s); break;
+    default: break;
+  }
+}
+
+static void ws_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
+  PendingAdd* pend = g.pend;
+  if (pro == PRO_NORM) norm_pass(g, 0, s);
+  else flush_pending_add(pend, s);
   switch (epi) {
     case FEPI_STORE: ws_launch<FEPI_STORE, true>(g, s); break;
     case FEPI_ADD:
@@ -801,6 +970,11 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 
 void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   if (g.M <= 0) return;
+  if (wt_gemm_usable(pro, g) && epi != FEPI_ADD) {
+    TraceScope trace_("gemm_wt", s);
+    wt_gemm(epi, g, s);
+    return;
+  }
   if (ws_gemm_usable(g)) {
     TraceScope trace_("gemm_ws", s);
     ws_gemm(pro, epi, g, s);
