@@ -90,7 +90,7 @@ void build_work_offsets(xsm_ctx* c) {
   if (c->small_ok) {
     w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
     w.ctrl = take(256);
-    w.head_all = take((size_t)80 * V * 4);
+    w.head_all = take((size_t)kSmallMaxRows * V * 4);
     w.tlog = take((size_t)256 * (g.n_layers * 16 + 8) * 8);
   }
   w.total = p;
@@ -309,7 +309,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   const char* wb = ctx->d_w;
   const size_t e = ctx->esz;
 
-  if (ctx->small_ok && ctx->use_small && M <= 16 && M + M * K <= 80 && n_seq * g.n_heads <= 256 &&
+  if (ctx->small_ok && ctx->use_small && M <= 16 && M + M * K <= kSmallMaxRows && n_seq * g.n_heads <= 256 &&
       vp->mode == XSM_VERIFY_GREEDY && vp->sample == 0) {
     // the whole step as one persistent kernel
     SmallArgs a{};

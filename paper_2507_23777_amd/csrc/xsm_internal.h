@@ -191,6 +191,7 @@ struct SmallArgs {
   int n_seq, R, S, V, max_batch, max_ctx, bound, cap;
   float eps, scale_log2;
 };
+constexpr int kSmallMaxRows = 144;     // backbone rows + head rows (M + M K) of one single-launch step
 bool small_supported(int D, int F);
 size_t small_ll_words(int n_layers, int D, int F, int K);
 size_t small_ll_layer_stride(int D, int F);

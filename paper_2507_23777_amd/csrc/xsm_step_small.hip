@@ -168,8 +168,8 @@ struct Shared {
   uint32_t flag[16];
   uint32_t tag;
   int fail;
-  float st_max[80], st_sec[80];  // FINAL: per-row reductions
-  int st_idx[80];
+  float st_max[kSmallMaxRows], st_sec[kSmallMaxRows];  // FINAL: per-row reductions
+  int st_idx[kSmallMaxRows];
   LayerTab tab[48];
 };
 
@@ -832,7 +832,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           if (z > bv) { sv = bv; bv = z; bi = t * 16 + nr; }
           else sv = fmaxf(sv, z);
         }
-        uint64_t* st = tb + OFF_ST + ((size_t)t * 80 + q) * 4;
+        uint64_t* st = tb + OFF_ST + ((size_t)t * kSmallMaxRows + q) * 4;
         ll_st(st, __float_as_uint(bv), tag);
         ll_st(st + 1, (uint32_t)bi, tag);
         ll_st(st + 2, __float_as_uint(sv), tag);
@@ -856,7 +856,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       for (int t = lane; t < NTV; t += 64) {
         const int off[3] = {0, 1, 2};
         uint32_t pw[3];
-        ll_wait_list<3>(tb + OFF_ST + ((size_t)t * 80 + grow) * 4, off, tag, pw, ok);
+        ll_wait_list<3>(tb + OFF_ST + ((size_t)t * kSmallMaxRows + grow) * 4, off, tag, pw, ok);
         const float tv = __uint_as_float(pw[0]), ts = __uint_as_float(pw[2]);
         const int ti = (int)pw[1];
         if (tv > bv || (tv == bv && ti < bi)) { sv = fmaxf(bv, fmaxf(sv, ts)); bv = tv; bi = ti; }
@@ -920,7 +920,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 
 size_t small_ll_words(int n_layers, int D, int F, int K) {
   const size_t layer = small_ll_layer_stride(D, F);
-  const size_t tail = (size_t)16 * D + (size_t)16 * 15 * D + (size_t)4096 * 80 * 4;
+  const size_t tail = (size_t)16 * D + (size_t)16 * 15 * D + (size_t)4096 * kSmallMaxRows * 4;
   (void)K;
   return layer * n_layers + (tail > layer ? tail : layer);
 }

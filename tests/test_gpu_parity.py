@@ -226,6 +226,26 @@ def test_single_launch_step_matches_oracle_and_per_stage_kernels(X, single_launc
     eng.xsm_check_device()
 
 
+def test_single_launch_eight_draft_heads(X):
+    """K = 8 at batch 1: 9 backbone rows + 72 head rows in the persistent kernel (several row
+    tiles in the unembedding), every acceptance length forced once."""
+    cfg = _c1_small(n_layers=2, n_draft=8)
+    K = cfg["n_draft"]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1, perturb=True)
+
+    def forced(step, b, st, blk):
+        full = X.H.true_continuation(orc, st, blk[0], K, GREEDY)
+        j = step % (K + 1)
+        if j < K:
+            full[j + 1] = (full[j + 1] + 1) % cfg["vocab"]
+        return full
+
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, K + 1, si.first_block(cfg, 1), forced=forced)
+    _report(tal, "c1-shape B1 K8 single launch")
+    assert set(tal.accept_hist) == set(range(1, K + 2))
+    eng.xsm_check_device()
+
+
 def test_single_launch_long_context_split_keys(X):
     cfg = _c1_small(n_layers=2, max_ctx=4608, prefix=0)
     n_pos = 4352
