@@ -111,6 +111,7 @@ def main() -> int:
     w = si.make_weights(cfg)
     eng = pkg.Engine(cfg, max_batch=B, max_ctx=max_ctx)
     eng.xsm_load_weights(si.pack_canonical(cfg, w))
+    eng.d_kv.zero_()                             # fixed-context points read slots no step has written
     prefix = si.make_prefix(cfg, B)
     first = si.first_block(cfg, B)
     eng.xsm_prefill(list(range(B)), eng.to_device(prefix))
@@ -166,6 +167,36 @@ def main() -> int:
                 "avg_launch_us": round(avg_us, 3), "algorithmic_bytes_per_launch": int(dom_bytes_per_launch),
                 "launches_per_step": dom_cnt / args.steps}
 
+    # ---- extras (outside the timed region): per-step latency spread, fixed-context points and
+    # accepted tokens/s under given acceptance lengths (step latency depends on shapes only)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(201)]
+    ctx_mid = int(len0[0])
+    evs[0].record()
+    for i in range(200):
+        buf.kv_len.fill_(ctx_mid)
+        eng.xsm_spec_step(buf, vp, ctx_mid)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(200))
+    spread = {"context": ctx_mid, "p10": round(per[20], 4), "p50": round(per[100], 4), "p90": round(per[180], 4)}
+    fixed = []
+    for ctx in (257, 2048, 4353):
+        if ctx + R > max_ctx:
+            continue
+        for _ in range(5):
+            buf.kv_len.fill_(ctx); eng.xsm_spec_step(buf, vp, ctx)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(100):
+            buf.kv_len.fill_(ctx); eng.xsm_spec_step(buf, vp, ctx)
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t2) / 100
+        by = algorithmic_bytes(cfg, B, B * ctx)
+        fixed.append({"context": ctx, "ms_per_step": round(ms, 4), "verified_tok_per_s": round(B * R / ms * 1e3, 1),
+                      "hbm_frac": round(by / (ms * 1e6) / HBM_PEAK_GBS, 4)})
+    eng.xsm_check_device()
+    forced = {f"{a:g}": round(B * a / ms_per_step * 1e3, 1) for a in (1.0, 2.02, float(R))}
+
     out = {"metric": "verified tok/s/GPU per spec step", "value": round(verified_tps, 1), "unit": "tok/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -176,7 +207,11 @@ def main() -> int:
                       "batch": B, "n_draft": K, "ctx_start": int(len0.max()), "ctx_end": int(len1.max())},
            "accepted_tok_per_s": round(accepted / sec, 1), "scr": round(accepted / (B * args.steps), 4),
            "roofline": roofline, "kernels": kernels,
-           "kernel_ms_per_step": round(tot_ms / args.steps, 4)}
+           "kernel_ms_per_step": round(tot_ms / args.steps, 4),
+           "step_ms_spread": spread, "fixed_context": fixed,
+           "accepted_tok_per_s_at_accept_length": dict(
+               forced, note="synthetic acceptance profiles: measured step latency x a given mean number of accepted "
+                            "tokens per step (1 = no draft accepted, 2.02 = the paper's Table 3 row E, K+1 = all)")}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, prefix, first)
     print(json.dumps(out))

@@ -106,6 +106,19 @@ __device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bo
   return out[0];
 }
 
+// Every poll of a word that another XCD is about to write costs fabric traffic that slows the
+// writes everybody is waiting for, so a workgroup polls with one lane: it watches one word of the
+// block until it carries the tag while the rest sit at the barrier; the block is read afterwards
+// (and re-read in the rare case that other producers' words lag).  Must be reached by every
+// thread of the workgroup.
+__device__ __forceinline__ void watch_then_sync(const uint64_t* word, uint32_t tag, bool active, int tid) {
+  if (tid == 0 && active) {
+    int spin = 0;
+    while ((uint32_t)(ll_ld(word) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
+  }
+  __syncthreads();
+}
+
 // Cooperative, coalesced wait for rows [m0, m0 + ROWS) (clipped to nrows), W words of each, of a
 // block of tagged words with row stride RS: thread t takes the word pairs 2(t + 256 j), +1, j < W/512, of
 // every row, so a wavefront instruction covers 1 KB of consecutive words.
@@ -115,12 +128,9 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
   constexpr int PP = W / 512, N = ROWS * PP * 2;
   const int rows = min(ROWS, nrows - m0);
   const uint64_t* base = buf + (size_t)m0 * RS + 2 * tid;
+  watch_then_sync(base + (size_t)(rows > 0 ? rows - 1 : 0) * RS + (PP - 1) * 512 + 1, tag, ok && rows > 0, tid);
   if (ok && rows > 0) {
     int spin = 0;
-    if ((tid & 63) == 0) {                 // one lane per wavefront watches one word
-      const uint64_t* last = base + (size_t)(rows - 1) * RS + (PP - 1) * 512 + 1;
-      while ((uint32_t)(ll_ld(last) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
-    }
     for (; spin < kSpinBudget; ++spin) {
       uint64_t w[N];
 #pragma unroll
@@ -420,7 +430,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         }
       };
       if (c_lo + wave < c_hi) load_kv(c_lo + wave);
-      __syncthreads();
+      watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, tag, ok && n >= 0, tid);
       if (n >= 0) {
         const int j0 = tid >> 6, c = tid & 63;            // rows j0, j0+4, j0+8, j0+12
         int off[12];
@@ -643,7 +653,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const int P = 32 + dps * 16;                          // words needed from each slice: m, l, O^T rows
       const uint64_t* p0 = lb + OFF_P + (size_t)(w - s) * 1056;
       float* const cb = reinterpret_cast<float*>(As);       // [S][P]
-      __syncthreads();
+      watch_then_sync(p0 + (size_t)(S - 1) * 1056 + 32 + (s * dps + dps - 1) * 16, tag, ok, tid);
       {
         int off[6];
 #pragma unroll
@@ -736,6 +746,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         // last slice: the other three partial products, then the residual this workgroup made in OPROJ
         const int off[3] = {row_in ? (int)col : -1, row_in ? (int)(16 * D + col) : -1, row_in ? (int)(32 * D + col) : -1};
         uint32_t pw[3];
+        watch_then_sync(lb + OFF_PD + (size_t)32 * D + d_nt * 16, tag, ok, tid);
         ll_wait_list<3>(lb + OFF_PD, off, tag, pw, ok);
         const float x = xm + ((__uint_as_float(pw[0]) + __uint_as_float(pw[1])) + (__uint_as_float(pw[2]) + v));
         if (row_in) ll_st(lb + LS + OFF_X + col, __float_as_uint(x), tag);
