@@ -114,7 +114,7 @@ __device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bo
 __device__ __forceinline__ void watch_then_sync(const uint64_t* word, uint32_t tag, bool active, int tid) {
   if (tid == 0 && active) {
     int spin = 0;
-    while ((uint32_t)(ll_ld(word) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
+    while ((uint32_t)(ll_ld(word) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(4);
   }
   __syncthreads();
 }
