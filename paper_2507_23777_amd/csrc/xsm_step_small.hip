@@ -183,13 +183,15 @@ struct Shared {
   LayerTab tab[48];
 };
 
-// Sum the four wavefronts' partial 16x16 tiles; thread (wave i, lane) gets element
-// D[nrow = (lane>>4)*4 + i][m = lane & 15].
-__device__ __forceinline__ float tile_reduce(Shared& sm, f32x4 acc, int wave, int lane) {
+// Sum the four wavefronts' partial 16x16 tiles; thread t gets element D[column t % 16][row t / 16],
+// so that the 16 words of one row's tile leave in one 128-byte store.
+__device__ __forceinline__ float tile_reduce(Shared& sm, f32x4 acc, int wave, int lane, int tid) {
   __syncthreads();
   *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
   __syncthreads();
-  return (sm.red[0][lane][wave] + sm.red[1][lane][wave]) + (sm.red[2][lane][wave] + sm.red[3][lane][wave]);
+  const int oc = tid & 15, om = tid >> 4;
+  const int ln = (oc >> 2) * 16 + om, ii = oc & 3;        // MFMA lane and slot that hold D[oc][om]
+  return (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
 }
 
 // bf16 pair of (a, b) and of what that rounding dropped
@@ -309,12 +311,12 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   if (sm.fail != 0) return;                 // an earlier step timed out: stay down until reset
   const uint32_t tag = sm.tag;
   // this lane's activation row (MFMA column) m = r
-  const int mb = r / R, mj = r % R;
-  const bool row_in = r < M;
+  // the output element this thread finishes after tile_reduce: tile column nrow of row om
+  const int om = tid >> 4, nrow = tid & 15;
+  const int mb = om / R, mj = om % R;
+  const bool row_in = om < M;
   const int len_m = row_in ? sm.len[mb] : -1;
   const bool live = row_in && len_m >= 0;              // rows of skipped sequences carry zeros
-  // the output element this thread finishes after tile_reduce: (nrow, m = r)
-  const int nrow = g * 4 + wave;
 
   const size_t LS = a.ll_layer_stride;                 // words per layer
   uint64_t* const llb = a.ll;
@@ -369,8 +371,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
-      const float v = tile_reduce(sm, acc, wave, lane);
-      const float partner = __shfl_xor(v, 32, WAVE);
+      const float v = tile_reduce(sm, acc, wave, lane, tid);
+      const float partner = __shfl_xor(v, 8, WAVE);        // tile column nrow +- 8
       if (live) {
         const int pos = len_m + mj;
         float o = v;
@@ -382,7 +384,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         } else {
           dim = q_tt * 16 + nrow;
         }
-        const size_t col = (size_t)r * D + q_h * 64 + dim;
+        const size_t col = (size_t)om * D + q_h * 64 + dim;
         const size_t head = (size_t)sm.slot[mb] * H + q_h;
         if (q_sec == 0) {
           ll_st(lb + OFF_Q + col, __float_as_uint(o), tag);
@@ -697,7 +699,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (has_o) {
       const int nt = w - O_BASE;
       // residual entering the layer: published a stage ago
-      const uint32_t px = row_in ? ll_wait1(lb + OFF_X + (size_t)r * D + nt * 16 + nrow, tag, ok) : 0u;
+      const uint32_t px = row_in ? ll_wait1(lb + OFF_X + (size_t)om * D + nt * 16 + nrow, tag, ok) : 0u;
       const uint32_t nogain[D / 512] = {};
       __syncthreads();
       stage_rows_f32<D, D, false>(sm, As, 0, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
@@ -705,9 +707,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
-      const float v = tile_reduce(sm, acc, wave, lane);
+      const float v = tile_reduce(sm, acc, wave, lane, tid);
       xm = __uint_as_float(px) + v;
-      if (row_in) ll_st(lb + OFF_XM + (size_t)r * D + nt * 16 + nrow, __float_as_uint(xm), tag);
+      if (row_in) ll_st(lb + OFF_XM + (size_t)om * D + nt * 16 + nrow, __float_as_uint(xm), tag);
     }
     XSM_STAMP(l * 16 + 4);
 
@@ -722,9 +724,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i) acc = mac2(acc, wu[i], As, STD, r, wave * KD + i, g);
-      const float v = tile_reduce(sm, acc, wave, lane);
+      const float v = tile_reduce(sm, acc, wave, lane, tid);
       if (row_in)
-        ll_st(lb + OFF_U + (size_t)r * F + w * 16 + nrow,
+        ll_st(lb + OFF_U + (size_t)om * F + w * 16 + nrow,
               __float_as_uint(0.5f * v * (1.0f + erff(v * 0.70710678118654752f))), tag);
     }
     XSM_STAMP(l * 16 + 5);
@@ -738,8 +740,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KFS; ++i) acc = mac2(acc, wd[i], As, STS, r, wave * KFS + i, g);
-      const float v = tile_reduce(sm, acc, wave, lane);
-      const size_t col = (size_t)r * D + d_nt * 16 + nrow;
+      const float v = tile_reduce(sm, acc, wave, lane, tid);
+      const size_t col = (size_t)om * D + d_nt * 16 + nrow;
       if (d_ks < 3) {
         if (row_in) ll_st(lb + OFF_PD + (size_t)d_ks * 16 * D + col, __float_as_uint(v), tag);
       } else {
@@ -795,12 +797,12 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < KD; ++i) acc = mac2(acc, wh[i], T0, STD, r, wave * KD + i, g);
-    const float y = tile_reduce(sm, acc, wave, lane);
+    const float y = tile_reduce(sm, acc, wave, lane, tid);
     const int kh = t / (D / 16), c = (t % (D / 16)) * 16 + nrow;   // head index, column
     if (row_in) {
       const float pre = y + bf2f(a.hb[(size_t)kh * D + c]);
-      const float gn = bf2f(T0[(size_t)r * STD + c]) + bf2f(T0[(size_t)(16 + r) * STD + c]);
-      ll_st(tb + OFF_RB + ((size_t)r * K + kh) * D + c, __float_as_uint(gn + pre / (1.0f + __expf(-pre))), tag);
+      const float gn = bf2f(T0[(size_t)om * STD + c]) + bf2f(T0[(size_t)(16 + om) * STD + c]);
+      ll_st(tb + OFF_RB + ((size_t)om * K + kh) * D + c, __float_as_uint(gn + pre / (1.0f + __expf(-pre))), tag);
     }
   }
   XSM_STAMP(a.L * 16 + 2);
