@@ -31,9 +31,7 @@ __device__ __forceinline__ void st_coherent(float* p, float v) {
 __device__ __forceinline__ float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return f2bf_pair(a, b); }
 
 // (a, b) -> packed bf16 pair of the rounded values and of what the rounding dropped
 __device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {

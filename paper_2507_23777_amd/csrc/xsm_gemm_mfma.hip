@@ -78,9 +78,7 @@ void launch_copy_u16(const void* src, void* dst, int n, hipStream_t s) {
 __device__ __forceinline__ float gelu_erf_f(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
 }
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return f2bf_pair(a, b); }
 // An fp32 activation enters the bf16 MFMA as two operands, hi = bf16(x) and lo = bf16(x - hi),
 // multiplied against the same weight fragment: the activation keeps ~16 mantissa bits, so what
 // is left of the bf16 format in a projection is the weights' own rounding (which the model

@@ -61,9 +61,7 @@ __device__ __forceinline__ uint64_t ll_ld(const uint64_t* p) {
 __device__ __forceinline__ void ll_st(uint64_t* p, uint32_t payload, uint32_t tag) {
   __hip_atomic_store(p, ((uint64_t)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint32_t pk2(float a, float b) {
-  return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
-}
+__device__ __forceinline__ uint32_t pk2(float a, float b) { return f2bf_pair(a, b); }
 __device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -124,11 +122,12 @@ __device__ __forceinline__ void watch_then_sync(const uint64_t* word, uint32_t t
 // every row, so a wavefront instruction covers 1 KB of consecutive words.
 template <int W, int RS, int ROWS>
 __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows, int tid, uint32_t tag,
-                                          uint32_t (&pay)[ROWS * (W / 512) * 2], bool& ok) {
+                                          uint32_t (&pay)[ROWS * (W / 512) * 2], bool& ok, uint64_t* stamp = nullptr) {
   constexpr int PP = W / 512, N = ROWS * PP * 2;
   const int rows = min(ROWS, nrows - m0);
   const uint64_t* base = buf + (size_t)m0 * RS + 2 * tid;
   watch_then_sync(base + (size_t)(rows > 0 ? rows - 1 : 0) * RS + (PP - 1) * 512 + 1, tag, ok && rows > 0, tid);
+  if (stamp && tid == 0) stamp[0] = wall_clock64();
   if (ok && rows > 0) {
     int spin = 0;
     for (; spin < kSpinBudget; ++spin) {
@@ -150,6 +149,7 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
       if (good) {
 #pragma unroll
         for (int i = 0; i < N; ++i) pay[i] = (i / (PP * 2)) < rows ? (uint32_t)w[i] : 0u;
+        if (stamp && tid == 0) stamp[1] = wall_clock64();
         return;
       }
       __builtin_amdgcn_s_sleep(4);
@@ -206,26 +206,40 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_
 template <int D, int RS, bool NORM>
 __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst_row, const uint64_t* buf,
                                                int nrows, const uint32_t (&gpair)[D / 512], float eps, int tid,
-                                               uint32_t tag, bool& ok) {
+                                               uint32_t tag, bool& ok, uint64_t* stamp = nullptr) {
   constexpr int PP = D / 512, ST = D + 8, LO = 16 * ST;
   constexpr int RB = PP >= 4 ? 4 : 8;                    // rows per round: at most 32 words in flight per thread
   const int wave = tid >> 6, lane = tid & 63;
   for (int m0 = 0; m0 < nrows; m0 += RB) {
     uint32_t pay[RB * PP * 2];
-    coop_wait<D, RS, RB>(buf, m0, nrows, tid, tag, pay, ok);
+    coop_wait<D, RS, RB>(buf, m0, nrows, tid, tag, pay, ok, stamp);
     if (NORM) {
       __syncthreads();                                   // earlier readers of rowsum / inv are done
+      // eight row sums per wavefront in ten lane exchanges instead of forty-eight: each exchange
+      // step halves the rows a lane carries (lane bits 5, 4, 3 pick the row), then three steps
+      // finish the one row left.  Cross-lane moves cost LDS-like latency at one wavefront per SIMD.
+      static_assert(RB == 8, "row-sum exchange is written for eight rows");
+      float ss[8];
 #pragma unroll
-      for (int m = 0; m < RB; ++m) {
-        float ss = 0.f;
+      for (int m = 0; m < 8; ++m) {
+        ss[m] = 0.f;
 #pragma unroll
         for (int j = 0; j < PP * 2; ++j) {
           const float x = __uint_as_float(pay[m * PP * 2 + j]);
-          ss += x * x;
+          ss[m] += x * x;
         }
-        ss = wave_sum(ss);
-        if (lane == 0) sm.rowsum[wave][m] = ss;
       }
+      const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
+      float s4[4], s2[2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s4[i] = (b5 ? ss[4 + i] : ss[i]) + __shfl_xor(b5 ? ss[i] : ss[4 + i], 32, WAVE);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) s2[i] = (b4 ? s4[2 + i] : s4[i]) + __shfl_xor(b4 ? s4[i] : s4[2 + i], 16, WAVE);
+      float s1 = (b3 ? s2[1] : s2[0]) + __shfl_xor(b3 ? s2[0] : s2[1], 8, WAVE);
+      s1 += __shfl_xor(s1, 4, WAVE);
+      s1 += __shfl_xor(s1, 2, WAVE);
+      s1 += __shfl_xor(s1, 1, WAVE);
+      if ((lane & 7) == 0) sm.rowsum[wave][(b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
       __syncthreads();
       if (tid < RB)
         sm.inv[tid] = 1.0f / sqrtf(((sm.rowsum[0][tid] + sm.rowsum[1][tid]) + (sm.rowsum[2][tid] + sm.rowsum[3][tid])) / (float)D + eps);
@@ -719,7 +733,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
       for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g2 + 2 * (tid + 256 * j));
       __syncthreads();
-      stage_rows_f32<D, D, true>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok);
+      stage_rows_f32<D, D, true>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok, tl ? tl + l * 16 + 13 : nullptr);
       XSM_STAMP(l * 16 + 7);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
