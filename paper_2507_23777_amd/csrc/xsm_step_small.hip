@@ -171,7 +171,6 @@ __device__ __forceinline__ void load_frags(uint4 (&w)[N], const uint4* Wt, int n
 struct Shared {
   float red[4][64][4];          // cross-wavefront tile reduction
   float rowsum[4][16];          // RMSNorm partial sums
-  float inv[16];
   float att_ml[4][2][16];
   float att_o[4][4][64][4];
   int len[16], slot[16];
@@ -214,7 +213,7 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
     uint32_t pay[RB * PP * 2];
     coop_wait<D, RS, RB>(buf, m0, nrows, tid, tag, pay, ok, stamp);
     if (NORM) {
-      __syncthreads();                                   // earlier readers of rowsum / inv are done
+      if (m0 > 0) __syncthreads();                       // this call's earlier readers of rowsum are done
       // eight row sums per wavefront in ten lane exchanges instead of forty-eight: each exchange
       // step halves the rows a lane carries (lane bits 5, 4, 3 pick the row), then three steps
       // finish the one row left.  Cross-lane moves cost LDS-like latency at one wavefront per SIMD.
@@ -241,14 +240,14 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
       s1 += __shfl_xor(s1, 1, WAVE);
       if ((lane & 7) == 0) sm.rowsum[wave][(b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
       __syncthreads();
-      if (tid < RB)
-        sm.inv[tid] = 1.0f / sqrtf(((sm.rowsum[0][tid] + sm.rowsum[1][tid]) + (sm.rowsum[2][tid] + sm.rowsum[3][tid])) / (float)D + eps);
-      __syncthreads();
     }
 #pragma unroll
     for (int m = 0; m < RB; ++m) {
       if (m0 + m < nrows) {
-        const float sc = NORM ? sm.inv[m] : 1.0f;
+        // every thread forms the scale itself (hardware reciprocal square root, 1 ulp): cheaper
+        // than a round through LDS and a barrier
+        const float sc = NORM ? __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / (float)D) + eps)
+                              : 1.0f;
 #pragma unroll
         for (int j = 0; j < PP; ++j) {
           float x0 = __uint_as_float(pay[(m * PP + j) * 2]), x1 = __uint_as_float(pay[(m * PP + j) * 2 + 1]);
