@@ -11,7 +11,13 @@ What is computed, with the passage it follows:
 * backbone distribution p^(0)_{s+1} = softmax(W^(0) h_s) (Eq. 3);
 * D decoding heads reading the same final hidden state h_s, head d predicting
   position s+d+1 (Eq. 4), here in the MLP variant of the ablation (Table 3 rows
-  B/C): r = h + SiLU(W_d h + b_d), logits through the shared unembedding;
+  B/C): r = h + SiLU(W_d h + b_d), logits through the shared unembedding; or
+  (head_kind "ca", Table 3 rows D/E) Eq. 4 as printed: a cross-attention layer
+  of the hidden state over the condition tokens, then the head's own
+  unembedding W^(d).  The paper does not spell the layer out; the reading here
+  is one multi-head attention with a residual connection and no extra norm:
+  q = Wq_d h, keys/values = Wk_d c, Wv_d c (cached at prefill),
+  r = h + Wo_d softmax(q k^T / sqrt(hd)) v, logits = W^(d) r;
 * verification: accept candidates while the criterion holds, stop at the first
   failure, then resample D+1 tokens from p^(0) and the heads at the first
   rejected position (Sec. 4.2; Alg. 1 inner while and the resample line);
@@ -37,7 +43,9 @@ slots; block causality; forced drafts hit every accept length; K_a = V accepts
 all; delta > 1 equals plain sampled decoding; incremental cached forward equals
 a full-sequence causal forward built from torch's library attention; building
 blocks against scipy/torch routines; Philox against an independent big-int
-implementation and published known-answer values.
+implementation and published known-answer values; the cross-attention head
+against its closed forms (zero output projection, one condition token, zero query
+projection) and torch's library attention.
 The stochastic path's exact sampled sequences have no external pin beyond the
 chi-square test of the sampler's distribution: parity unpinned for those.
 """
@@ -144,6 +152,8 @@ class SeqState:
     v: list
     ck: list = field(default_factory=list)     # cross-attention condition keys per layer
     cv: list = field(default_factory=list)
+    hk: list = field(default_factory=list)     # condition keys / values of the cross-attention heads
+    hv: list = field(default_factory=list)
     seq_id: int = 0
 
 
@@ -155,6 +165,8 @@ class Oracle:
         self.n_cond = cfg["n_cond"]
         self.theta, self.eps = float(cfg["rope_theta"]), float(cfg["rms_eps"])
         self.kv_dtype = kv_dtype
+        self.head_kind = cfg.get("head_kind", "mlp")
+        assert self.head_kind in ("mlp", "ca") and (self.head_kind == "mlp" or self.n_cond > 0)
         self.w = {k: np.asarray(v, dtype=F64) for k, v in weights.items()}
 
     # -- state -----------------------------------------------------------------
@@ -204,13 +216,19 @@ class Oracle:
         Hf = rmsnorm(X, w["gf"], self.eps)
         return Hf, Hf @ w["WU"].T
 
-    def head_logits(self, g: np.ndarray) -> np.ndarray:
-        """Logits of the K decoding heads from one hidden state g [d] -> [K, V]."""
+    def head_logits(self, g: np.ndarray, st: SeqState | None = None) -> np.ndarray:
+        """Logits of the K decoding heads from one hidden state g [d] -> [K, V] (Eq. 4)."""
         w = self.w
         out = np.empty((self.K, self.V), dtype=F64)
         for k in range(1, self.K + 1):
-            r = g + silu(w[f"h{k}.W"] @ g + w[f"h{k}.b"])
-            out[k - 1] = w["WU"] @ r
+            if self.head_kind == "ca":
+                q = (w[f"h{k}.Wq"] @ g).reshape(1, self.H, self.hd)
+                o = self._attend(q, st.hk[k - 1], st.hv[k - 1], np.array([self.n_cond]))
+                r = g + w[f"h{k}.Wo"] @ o.reshape(self.d)
+                out[k - 1] = w[f"h{k}.WU"] @ r
+            else:
+                r = g + silu(w[f"h{k}.W"] @ g + w[f"h{k}.b"])
+                out[k - 1] = w["WU"] @ r
         return out
 
     # -- entry points --------------------------------------------------------------
@@ -224,6 +242,12 @@ class Oracle:
                 kv = c @ self.w[f"l{l}.Wckv"].T
                 st.ck.append(kv[:, :self.d].reshape(-1, self.H, self.hd).astype(self.kv_dtype))
                 st.cv.append(kv[:, self.d:].reshape(-1, self.H, self.hd).astype(self.kv_dtype))
+            if self.head_kind == "ca":
+                st.hk, st.hv = [], []
+                for k in range(1, self.K + 1):
+                    kv = c @ self.w[f"h{k}.Wkv"].T
+                    st.hk.append(kv[:, :self.d].reshape(-1, self.H, self.hd).astype(self.kv_dtype))
+                    st.hv.append(kv[:, self.d:].reshape(-1, self.H, self.hd).astype(self.kv_dtype))
         st.n = 0
         P = 0 if prefix_emb is None else prefix_emb.shape[0]
         if P > 0:
@@ -244,9 +268,9 @@ class Oracle:
             a += 1
         y0, diag0 = sample(Z0[a], vp, n + a + 1, 0, st.seq_id)
         if heads_on_all_rows:      # Alg. 1's literal for-loop over heads on h_{s:s+D}
-            Zh = np.stack([self.head_logits(Hf[j]) for j in range(K + 1)])[a]
+            Zh = np.stack([self.head_logits(Hf[j], st) for j in range(K + 1)])[a]
         else:                      # only h_{s*-1} is consumed by the resample line
-            Zh = self.head_logits(Hf[a])
+            Zh = self.head_logits(Hf[a], st)
         ys, diags = [], [diag0]
         for k in range(1, K + 1):
             y, dg = sample(Zh[k - 1], vp, n + a + 1 + k, k, st.seq_id)

@@ -20,7 +20,8 @@ import numpy as np
 
 # --- model/workload shapes -------------------------------------------------
 # Shapes of the synthetic workloads.  K (n_draft) is the paper's D, the number
-# of decoding heads (Sec. 4.1); vocabularies are mesh-sized (Table 1).
+# of decoding heads (Sec. 4.1); vocabularies are mesh-sized (Table 1).  Optional
+# key head_kind: "mlp" (default) or "ca" (cross-attention heads, needs n_cond > 0).
 CONFIGS = {
     # tiny fp32 correctness model
     "c0": dict(n_layers=2, d_model=128, n_heads=4, head_dim=32, d_ffn=512, vocab=512,
@@ -106,7 +107,10 @@ def tensor_order(cfg: dict) -> list[tuple[str, tuple[int, ...]]]:
         out += [(f"l{l}.g2", (d,)), (f"l{l}.W1", (F, d)), (f"l{l}.W2", (d, F))]
     out += [("gf", (d,)), ("WU", (V, d))]
     for k in range(1, K + 1):
-        out += [(f"h{k}.W", (d, d)), (f"h{k}.b", (d,))]
+        if cfg.get("head_kind", "mlp") == "ca":     # cross-attention decoding head with its own unembedding (Eq. 4)
+            out += [(f"h{k}.Wq", (d, d)), (f"h{k}.Wkv", (2 * d, d)), (f"h{k}.Wo", (d, d)), (f"h{k}.WU", (V, d))]
+        else:
+            out += [(f"h{k}.W", (d, d)), (f"h{k}.b", (d,))]
     return out
 
 

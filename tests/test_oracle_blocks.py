@@ -150,3 +150,64 @@ def test_head_reduces_to_closed_form_with_identity_weights():
     r = torch.tensor(g) + TF.silu(TF.linear(torch.tensor(g), tw, torch.tensor(np.asarray(w2["h2.b"], np.float64))))
     np.testing.assert_allclose(Zh2[1], TF.linear(r, torch.tensor(np.asarray(w2["WU"], np.float64))).numpy(),
                                rtol=1e-12, atol=1e-14)
+
+
+# ---- cross-attention decoding heads (Eq. 4; Table 3 rows D/E) ---------------------------------
+def _ca_setup(n_cond=9, seed=5, **kw):
+    cfg = si.tiny_config(n_cond=n_cond, head_kind="ca", prefix=3, **kw)
+    w = si.make_weights(cfg, perturb=True)
+    orc = Oracle(cfg, w)
+    st = orc.new_state()
+    cond = si.make_cond(cfg, 1)[0]
+    orc.prefill(st, si.make_prefix(cfg, 1)[0], cond)
+    g = np.random.default_rng(seed).standard_normal(cfg["d_model"])
+    return cfg, w, orc, st, cond, g
+
+
+def test_ca_head_closed_forms():
+    f64 = lambda x: np.asarray(x, np.float64)
+    # zero output projection: the attention branch vanishes, logits = W^(d) h
+    cfg, w, orc, st, cond, g = _ca_setup()
+    for k in range(1, cfg["n_draft"] + 1):
+        w[f"h{k}.Wo"] = np.zeros_like(w[f"h{k}.Wo"])
+    orc0 = Oracle(cfg, w)
+    Zh = orc0.head_logits(g, st)
+    for k in range(cfg["n_draft"]):
+        np.testing.assert_allclose(Zh[k], f64(w[f"h{k + 1}.WU"]) @ g, rtol=1e-12, atol=1e-14)
+    # one condition token: the softmax is 1, r = h + Wo Wv c
+    cfg, w, orc, st, cond, g = _ca_setup(n_cond=1)
+    Zh = orc.head_logits(g, st)
+    d = cfg["d_model"]
+    for k in range(1, cfg["n_draft"] + 1):
+        v = f64(w[f"h{k}.Wkv"])[d:] @ f64(cond[0])
+        r = g + f64(w[f"h{k}.Wo"]) @ v
+        np.testing.assert_allclose(Zh[k - 1], f64(w[f"h{k}.WU"]) @ r, rtol=1e-12, atol=1e-14)
+    # zero query projection: uniform attention, r = h + Wo mean_t(Wv c_t)
+    cfg, w, orc, st, cond, g = _ca_setup(n_cond=7)
+    for k in range(1, cfg["n_draft"] + 1):
+        w[f"h{k}.Wq"] = np.zeros_like(w[f"h{k}.Wq"])
+    Zh = Oracle(cfg, w).head_logits(g, st)
+    for k in range(1, cfg["n_draft"] + 1):
+        vbar = (f64(cond) @ f64(w[f"h{k}.Wkv"])[d:].T).mean(0)
+        r = g + f64(w[f"h{k}.Wo"]) @ vbar
+        np.testing.assert_allclose(Zh[k - 1], f64(w[f"h{k}.WU"]) @ r, rtol=1e-12, atol=1e-13)
+
+
+def test_ca_head_against_torch_attention():
+    cfg, w, orc, st, cond, g = _ca_setup(n_cond=13, seed=11)
+    H, hd, d = cfg["n_heads"], cfg["head_dim"], cfg["d_model"]
+    t = lambda x: torch.tensor(np.asarray(x, np.float64))
+    Zh = orc.head_logits(g, st)
+    for k in range(1, cfg["n_draft"] + 1):
+        q = TF.linear(t(g), t(w[f"h{k}.Wq"])).reshape(1, H, 1, hd)
+        kv = TF.linear(t(cond), t(w[f"h{k}.Wkv"]))
+        kk = kv[:, :d].reshape(-1, H, hd).permute(1, 0, 2)[None]
+        vv = kv[:, d:].reshape(-1, H, hd).permute(1, 0, 2)[None]
+        o = TF.scaled_dot_product_attention(q, kk, vv).reshape(d)
+        r = t(g) + TF.linear(o, t(w[f"h{k}.Wo"]))
+        np.testing.assert_allclose(Zh[k - 1], TF.linear(r, t(w[f"h{k}.WU"])).numpy(), rtol=1e-10, atol=1e-12)
+    # heads differ from each other and depend on the condition
+    assert np.abs(Zh[0] - Zh[1]).max() > 1e-6
+    st2 = orc.new_state()
+    orc.prefill(st2, si.make_prefix(cfg, 1)[0], cond[::-1].copy() * 0.5)
+    assert np.abs(orc.head_logits(g, st2)[0] - Zh[0]).max() > 1e-6

@@ -176,3 +176,22 @@ def test_categorical_sampler_distribution():
         u = philox.uniform24(7, pos, 0, 0)
         tok, _ = sample(z2, VerifyParams(sample=1, seed=7), pos, 0, 0)
         assert tok == (0 if u < 0.25 else 1 if u < 0.5 else 2)
+
+
+@pytest.mark.parametrize("K", [2, 4])
+def test_greedy_spec_equals_plain_greedy_with_cross_attention_heads(K):
+    """The invariant does not depend on what the heads are (Sec. 4.2): with cross-attention
+    heads reading the condition, greedy speculative output is still plain greedy decoding, and
+    the heads on all rows vs on the accepted row agree."""
+    cfg = si.tiny_config(n_draft=K, n_cond=6, head_kind="ca", seed=21)
+    orc, st = _setup(cfg)
+    st2, st3 = copy.deepcopy(st), copy.deepcopy(st)
+    blk = si.first_block(cfg, 1)[0]
+    spec, steps, hist = orc.generate_spec(st, blk, 40, GREEDY)
+    plain = orc.generate_plain(st2, blk[0], 40, GREEDY)
+    assert spec == plain
+    assert all(1 <= a <= K + 1 for a in hist)
+    a = orc.spec_step(copy.deepcopy(st3), blk, GREEDY)
+    b = orc.spec_step(st3, blk, GREEDY, heads_on_all_rows=True)
+    assert a["next_block"] == b["next_block"]
+    np.testing.assert_allclose(a["Zh"], b["Zh"], rtol=1e-12, atol=1e-14)
