@@ -54,6 +54,12 @@ typedef enum {
 } xsm_status;
 
 enum { XSM_F32 = 0, XSM_BF16 = 1 };
+/* Decoding-head architecture (Eq. 4; Table 3).  MLP: r = g + SiLU(W_k g + b_k), logits through
+ * the shared unembedding.  CA: one multi-head cross-attention of the final hidden state g over the
+ * n_cond condition tokens (keys/values W_kv,k c cached by xsm_prefill, no mask, no rotary
+ * embedding, scale 1/sqrt(head_dim)), r = g + W_o,k attn(W_q,k g), logits through the head's own
+ * unembedding W^(k); needs n_cond > 0. */
+enum { XSM_HEAD_MLP = 0, XSM_HEAD_CA = 1 };
 
 /* Model and capacity.  Pre-RMSNorm decoder, multi-head attention with rotary
  * embedding (pair (i, i+head_dim/2), angle pos*theta^(-2i/head_dim)), FFN
@@ -67,6 +73,7 @@ typedef struct {
   int32_t n_cond;                 /* cross-attention condition tokens per sequence, 0 = none */
   int32_t dtype;                  /* XSM_F32 | XSM_BF16: storage of weights, cache, embeddings */
   float rope_theta, rms_eps;
+  int32_t head_kind;              /* XSM_HEAD_MLP | XSM_HEAD_CA */
 } xsm_config;
 
 /* Acceptance criterion and sampling rule (Sec. 5.4 "Verification criterion";
@@ -127,7 +134,8 @@ XSM_API int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspac
  * (bf16 bit patterns or float), all matrices [out][in] row-major, in this order:
  * E[V][d]; per layer g1[d], Wqkv[3d][d] (q rows, k rows, v rows), Wo[d][d],
  * (if n_cond: gc[d], Wcq[d][d], Wckv[2d][d], Wco[d][d]), g2[d], W1[F][d], W2[d][F];
- * gf[d]; WU[V][d]; per head Wh[d][d], bh[d].  Copies to the device, re-lays the
+ * gf[d]; WU[V][d]; per head Wh[d][d], bh[d] (XSM_HEAD_MLP) or Wq[d][d], Wkv[2d][d] (key rows,
+ * value rows), Wo[d][d], WU_k[V][d] (XSM_HEAD_CA).  Copies to the device, re-lays the
  * matrices for the kernels and builds the rotary table, all on `stream`; the host
  * array may be reused once the stream has been synchronised. */
 XSM_API int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_stream stream);

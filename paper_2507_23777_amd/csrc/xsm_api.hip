@@ -46,7 +46,11 @@ void build_weight_offsets(xsm_ctx* c) {
   }
   o.gf = take(d); o.WU = take(V * d);
   o.hW.resize(g.n_draft); o.hb.resize(g.n_draft);
-  for (int k = 0; k < g.n_draft; ++k) { o.hW[k] = take(d * d); o.hb[k] = take(d); }
+  o.hq.resize(g.n_draft); o.hkv.resize(g.n_draft); o.ho.resize(g.n_draft); o.hU.resize(g.n_draft);
+  for (int k = 0; k < g.n_draft; ++k) {
+    if (g.head_kind == XSM_HEAD_CA) { o.hq[k] = take(d * d); o.hkv[k] = take(2 * d * d); o.ho[k] = take(d * d); o.hU[k] = take(V * d); }
+    else { o.hW[k] = take(d * d); o.hb[k] = take(d); }
+  }
   o.total = p;
 }
 
@@ -69,10 +73,12 @@ void build_work_offsets(xsm_ctx* c) {
   w.y0 = take(g.max_batch * 4); w.wflags = take(g.max_batch * 4);
   w.toks = take((size_t)g.max_batch * kMaxRows * 4);
   w.rowidx = take(g.max_batch * 4);
-  c->part_entries = (size_t)g.max_batch * g.n_heads;
-  if (c->part_entries < 1024) c->part_entries = 1024;
+  w.eff2 = take((size_t)g.max_batch * (K ? K : 1) * 4); w.slot2 = take((size_t)g.max_batch * (K ? K : 1) * 4);
+  // (sequence, head) pairs of one attention call: the backbone's, or all cross-attention decoding heads at once
+  const size_t attn_pairs = (size_t)g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && K ? K : 1);
+  c->part_entries = attn_pairs < 1024 ? 1024 : attn_pairs;
   w.part = take(fattn_part_bytes(c->part_entries));
-  w.tickets = take((size_t)g.max_batch * g.n_heads * 4);
+  w.tickets = take(attn_pairs * 4);
   w.gpart = w.gtickets = 0;
   if (c->fast) {
     // partial products of the split-contraction GEMM, for the largest projection it may run
@@ -113,6 +119,9 @@ size_t build_tiled_offsets(xsm_ctx* c, size_t start) {
   t.WU = take(V * d);
   t.Wh = take((K ? K : 1) * d * d);
   t.hb = take((K ? K : 1) * d);
+  t.Who.assign(K, 0); t.WhU.assign(K, 0);
+  if (g.head_kind == XSM_HEAD_CA)
+    for (size_t k = 0; k < K; ++k) { t.Who[k] = take(d * d); t.WhU[k] = take(V * d); }
   return p;
 }
 
@@ -138,6 +147,13 @@ char* cross_cache(const xsm_ctx* c, int layer, int which) {
   const xsm_config& g = c->cfg;
   const size_t per = (size_t)g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
   return c->d_kv + (c->kv_self_elems + ((size_t)layer * 2 + which) * per) * c->esz;
+}
+// condition cache of the cross-attention decoding heads: [2][K][max_batch][H][n_cond][hd], so that
+// (head k, slot s) is "slot" k*max_batch + s of one attention call over all heads
+char* head_cache(const xsm_ctx* c, int k, int which) {
+  const xsm_config& g = c->cfg;
+  const size_t per = (size_t)g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
+  return c->d_kv + (c->kv_self_elems + c->kv_cross_elems + ((size_t)which * g.n_draft + k) * per) * c->esz;
 }
 
 // split count of the key range per (sequence, head): enough workgroups to fill the chip, at
@@ -354,7 +370,45 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     launch_fgemm(PRO_NORM, FEPI_STORE, z, s);
     if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
     launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
-    if (K > 0) {
+    if (K > 0 && g.head_kind == XSM_HEAD_CA) {
+      // Eq. 4 with cross-attention heads, all heads of all sequences at once: q = Wq_k g (one
+      // stacked GEMM), one attention call over the heads' cached condition keys/values with
+      // (sequence, head) as the batch index, then per head the output projection onto the
+      // residual g and the head's own unembedding.
+      int32_t* rowidx = (int32_t*)(ws + ctx->ws.rowidx);
+      int32_t* eff2 = (int32_t*)(ws + ctx->ws.eff2);
+      int32_t* slot2 = (int32_t*)(ws + ctx->ws.slot2);
+      float* Qh = Hh;                                        // [n_seq][K][d]
+      float* Oh = (float*)(ws + ctx->ws.Qr);                 // [n_seq][K][d]
+      launch_head_rows(acc, rowidx, n_seq, R, s);
+      launch_norm_rows(X, d, rowidx, z.gain, g.rms_eps, G, n_seq, d, s);
+      launch_head_ca_prep(G, Rk, eff, slot, eff2, slot2, n_seq, K, d, g.max_batch, s);
+      FastGemm hq{};
+      hq.Wt = (const uint4*)(wb + ctx->toff.Wh); hq.N = K * d; hq.K = d; hq.M = n_seq;
+      hq.X = G; hq.ldx = d; hq.Y = Qh; hq.ldy = K * d;
+      hq.nscratch = Xn; hq.ws_part = gpart; hq.ws_tickets = gtick; hq.pend = PEND;
+      launch_fgemm(PRO_F32, FEPI_STORE, hq, s);
+      FastAttn ha{};
+      ha.Q = Qh; ha.ldq = d; ha.Kc = (const uint16_t*)head_cache(ctx, 0, 0); ha.Vt = (const uint16_t*)head_cache(ctx, 0, 1);
+      ha.eff_len = eff2; ha.slot = slot2; ha.O = Oh; ha.ldo = d;
+      ha.part = (float*)(ws + ctx->ws.part); ha.tickets = (uint32_t*)(ws + ctx->ws.tickets);
+      ha.R = 1; ha.H = g.n_heads; ha.cap = ctx->cap_cross; ha.S = attn_splits(ctx, n_seq * K, g.n_cond);
+      ha.fixed_limit = g.n_cond; ha.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
+      launch_fattn(ha, n_seq * K, s);
+      for (int k = 0; k < K; ++k) {
+        FastGemm ho{};
+        ho.Wt = (const uint4*)(wb + ctx->toff.Who[k]); ho.N = d; ho.K = d; ho.M = n_seq;
+        ho.X = Oh + (size_t)k * d; ho.ldx = K * d; ho.Y = Rk + (size_t)k * d; ho.ldy = K * d;
+        ho.nscratch = Xn; ho.ws_part = gpart; ho.ws_tickets = gtick; ho.pend = nullptr;
+        launch_fgemm(PRO_F32, FEPI_ADD, ho, s);
+        FastGemm zu{};
+        zu.Wt = (const uint4*)(wb + ctx->toff.WhU[k]); zu.N = V; zu.K = d; zu.M = n_seq;
+        zu.X = Rk + (size_t)k * d; zu.ldx = K * d; zu.Y = Zh + (size_t)k * V; zu.ldy = K * V;
+        zu.nscratch = Xn; zu.ws_part = gpart; zu.ws_tickets = gtick; zu.pend = PEND;
+        launch_fgemm(PRO_F32, FEPI_STORE, zu, s);
+      }
+      if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
+    } else if (K > 0) {
       int32_t* rowidx = (int32_t*)(ws + ctx->ws.rowidx);
       launch_head_rows(acc, rowidx, n_seq, R, s);
       FastGemm hg{};                               // all K heads at once: [K*d][d] stacked
@@ -375,7 +429,24 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
     launch_verify(Z0, Xn, bt->block, eff, slot, *vp, acc, y0, wfl, K > 0 ? G : nullptr, n_seq, R, V,
                   d, s);
-    if (K > 0) {
+    if (K > 0 && g.head_kind == XSM_HEAD_CA) {
+      int32_t* eff2 = (int32_t*)(ws + ctx->ws.eff2);
+      int32_t* slot2 = (int32_t*)(ws + ctx->ws.slot2);
+      float* Qh = Hh;
+      float* Oh = (float*)(ws + ctx->ws.Qr);
+      launch_head_ca_prep(G, Rk, eff, slot, eff2, slot2, n_seq, K, d, g.max_batch, s);
+      for (int k = 0; k < K; ++k)
+        launch_gemm(dt, EPI_STORE, G, d, wb + ctx->woff.hq[k] * e, Qh + (size_t)k * d, K * d, n_seq, d, d, s);
+      launch_attention(dt, Qh, head_cache(ctx, 0, 0), head_cache(ctx, 0, 1), eff2, slot2, Oh, n_seq * K, 1,
+                       g.n_heads, g.head_dim, ctx->cap_cross, g.n_cond, s);
+      for (int k = 0; k < K; ++k) {
+        launch_gemm(dt, EPI_ADD, Oh + (size_t)k * d, K * d, wb + ctx->woff.ho[k] * e, Rk + (size_t)k * d, K * d,
+                    n_seq, d, d, s);
+        launch_gemm(dt, EPI_STORE, Rk + (size_t)k * d, K * d, wb + ctx->woff.hU[k] * e, Zh + (size_t)k * V, K * V,
+                    n_seq, V, d, s);
+      }
+      if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
+    } else if (K > 0) {
       const void* bias[16];
       for (int k = 0; k < K; ++k) {
         launch_gemm(dt, EPI_STORE, G, d, wb + ctx->woff.hW[k] * e, Hh + (size_t)k * d, K * d, n_seq, d,
@@ -411,6 +482,8 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
   if (g.n_draft < 0 || g.n_draft + 1 > kMaxRows) return bad("n_draft must be in [0, 15]");
   if (g.max_batch < 1 || g.max_ctx < kMaxRows) return bad("max_batch < 1 or max_ctx < 16");
   if (g.n_cond < 0) return bad("n_cond < 0");
+  if (g.head_kind != XSM_HEAD_MLP && g.head_kind != XSM_HEAD_CA) return bad("head_kind must be XSM_HEAD_MLP or XSM_HEAD_CA");
+  if (g.head_kind == XSM_HEAD_CA && g.n_cond < 1) return bad("cross-attention heads need condition tokens (n_cond > 0)");
   if (g.dtype != XSM_F32 && g.dtype != XSM_BF16) return bad("dtype must be XSM_F32 or XSM_BF16");
   if (!(g.rope_theta > 1.f) || !(g.rms_eps > 0.f)) return bad("rope_theta must be > 1, rms_eps > 0");
   xsm_ctx* c = new (std::nothrow) xsm_ctx();
@@ -434,8 +507,10 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
     c->weights_bytes += align_up(sizeof(LayerTab) * g.n_layers);
   }
   c->kv_self_elems = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_self * g.head_dim;
-  const size_t cross = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
-  c->kv_bytes = align_up((c->kv_self_elems + cross) * c->esz);
+  c->kv_cross_elems = (size_t)g.n_layers * 2 * g.max_batch * g.n_heads * c->cap_cross * g.head_dim;
+  const size_t hcross = g.head_kind == XSM_HEAD_CA
+                            ? (size_t)g.n_draft * 2 * g.max_batch * g.n_heads * c->cap_cross * g.head_dim : 0;
+  c->kv_bytes = align_up((c->kv_self_elems + c->kv_cross_elems + hcross) * c->esz);
   *out = c;
   return XSM_OK;
 }
@@ -486,10 +561,17 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
     }
     launch_tile_weights(wb + ctx->woff.WU * 2, wb + ctx->toff.WU, V, d, 0, 0, s);
     for (int k = 0; k < g.n_draft; ++k) {
-      launch_tile_weights(wb + ctx->woff.hW[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
-      launch_copy_u16(wb + ctx->woff.hb[k] * 2, wb + ctx->toff.hb + (size_t)k * d * 2, d, s);
+      if (g.head_kind == XSM_HEAD_CA) {
+        launch_tile_weights(wb + ctx->woff.hq[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
+        launch_tile_weights(wb + ctx->woff.ho[k] * 2, wb + ctx->toff.Who[k], d, d, 0, 0, s);
+        launch_tile_weights(wb + ctx->woff.hU[k] * 2, wb + ctx->toff.WhU[k], V, d, 0, 0, s);
+      } else {
+        launch_tile_weights(wb + ctx->woff.hW[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
+        launch_copy_u16(wb + ctx->woff.hb[k] * 2, wb + ctx->toff.hb + (size_t)k * d * 2, d, s);
+      }
     }
-    launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), g.max_batch * g.n_heads, 0, s);
+    launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets),
+                    g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && g.n_draft ? g.n_draft : 1), 0, s);
     launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.gtickets), (int)kWsTickets, 0, s);
     if (ctx->small_ok) {
       ctx->layer_tab.resize(g.n_layers);
@@ -547,6 +629,12 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
         launch_store_cond(dt, QKV, slot, cross_cache(ctx, l, 0), cross_cache(ctx, l, 1), n_seq, C,
                           r0, g.n_heads, g.head_dim, ctx->cap_cross, ctx->fast ? 1 : 0, s);
       }
+      if (g.head_kind == XSM_HEAD_CA)          // the decoding heads' own keys/values of the condition
+        for (int k = 0; k < g.n_draft; ++k) {
+          launch_gemm(dt, EPI_STORE, X, d, ctx->d_w + ctx->woff.hkv[k] * ctx->esz, QKV, 2 * d, n_seq * C, 2 * d, d, s);
+          launch_store_cond(dt, QKV, slot, head_cache(ctx, k, 0), head_cache(ctx, k, 1), n_seq, C, r0,
+                            g.n_heads, g.head_dim, ctx->cap_cross, ctx->fast ? 1 : 0, s);
+        }
     }
   }
   for (int r0 = 0; r0 < P; r0 += kPrefillChunk) {
@@ -664,6 +752,13 @@ int xsm_debug_kv_clone(xsm_ctx* ctx, int32_t src_slot, int32_t dst_slot) {
         XSM_HIP(hipMemcpy(cb + dst_slot * perc, cb + src_slot * perc, perc, hipMemcpyDeviceToDevice));
       }
     }
+  if (g.head_kind == XSM_HEAD_CA)
+    for (int k = 0; k < g.n_draft; ++k)
+      for (int which = 0; which < 2; ++which) {
+        const size_t perc = (size_t)g.n_heads * ctx->cap_cross * g.head_dim * ctx->esz;
+        char* hb = head_cache(ctx, k, which);
+        XSM_HIP(hipMemcpy(hb + dst_slot * perc, hb + src_slot * perc, perc, hipMemcpyDeviceToDevice));
+      }
   XSM_HIP(hipDeviceSynchronize());
   return XSM_OK;
 }

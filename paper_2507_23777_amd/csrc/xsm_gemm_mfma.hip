@@ -716,6 +716,12 @@ __global__ __launch_bounds__(256) void k_norm_rows_pending(float* X, int ldx, co
   }
 }
 
+void launch_norm_rows(const float* X, int ldx, const int32_t* row_index, const uint16_t* gain, float eps, float* out,
+                      int M, int K, hipStream_t s) {
+  TraceScope trace_("norm_rows", s);
+  hipLaunchKernelGGL(k_norm_rows, dim3(M), dim3(256), 0, s, X, ldx, row_index, gain, eps, out, K, 0);
+}
+
 void flush_pending_add(PendingAdd* p, hipStream_t s) {
   if (!p || !p->active) return;
   hipLaunchKernelGGL(k_norm_rows_pending, dim3(p->M), dim3(256), 0, s, p->Y, p->ldy, p->part, p->kspl, p->M, nullptr,

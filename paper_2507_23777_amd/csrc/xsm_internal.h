@@ -20,13 +20,14 @@ struct LayerOff {
 struct WeightOff {
   size_t E, gf, WU, total;
   std::vector<LayerOff> layer;
-  std::vector<size_t> hW, hb;
+  std::vector<size_t> hW, hb;                 // MLP heads
+  std::vector<size_t> hq, hkv, ho, hU;        // cross-attention heads
 };
 
 // Byte offsets inside the caller's workspace buffer.
 struct WorkOff {
   size_t X, Xn, QKV, Qr, AO, U, Z0, G, Hh, Rk, Zh;
-  size_t eff_len, slot, acc, y0, wflags, toks, rowidx;   // int32 arrays
+  size_t eff_len, slot, acc, y0, wflags, toks, rowidx, eff2, slot2;   // int32 arrays
   size_t part, tickets, gpart, gtickets;                                  // split-key attention partials
   size_t ll, ctrl, head_all, tlog;                       // single-launch step: exchange buffers
   size_t total;
@@ -36,7 +37,8 @@ struct WorkOff {
 struct TiledLayer { size_t Wqkv, Wo, Wcq, Wco, W1, W2; };
 struct TiledOff {
   std::vector<TiledLayer> layer;
-  size_t WU, Wh, hb;       // unembedding, stacked head matrices [K*d][d], stacked head biases [K][d]
+  size_t WU, Wh, hb;       // unembedding, stacked head matrices [K*d][d] (MLP: W_k, CA: Wq_k), stacked head biases [K][d]
+  std::vector<size_t> Who, WhU;   // cross-attention heads: output projections and unembeddings
   bool wu_ok;              // vocabulary is a multiple of 16
 };
 
@@ -69,6 +71,7 @@ struct xsm_ctx {
   size_t rope_off;         // byte offset of the rotary table in the weights buffer
   size_t weights_bytes, kv_bytes;
   size_t kv_self_elems;    // elements of the self-attention cache (cross cache follows)
+  size_t kv_cross_elems;   // elements of the layers' cross cache (the heads' condition cache follows)
   bool fast = false;       // bf16 MFMA path (head_dim 64, values cached transposed)
   bool small_ok = false;   // single-launch step available for this model shape
   bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
@@ -175,6 +178,11 @@ void launch_fattn(const FastAttn& a, int n_seq, hipStream_t s);
 size_t fattn_part_bytes(size_t entries);
 // row_index[b] = b*R + acc[b] (the hidden state the decoding heads read)
 void launch_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R, hipStream_t s);
+void launch_head_ca_prep(const float* G, float* Rk, const int32_t* eff, const int32_t* slot, int32_t* eff2,
+                         int32_t* slot2, int n_seq, int K, int d, int max_batch, hipStream_t s);
+// out[m][:] = RMSNorm(X[row_index ? row_index[m] : m][:]) * gain (fp32 in and out, bf16 gain)
+void launch_norm_rows(const float* X, int ldx, const int32_t* row_index, const uint16_t* gain, float eps, float* out,
+                      int M, int K, hipStream_t s);
 
 // ---- single-launch step for <= 16 block rows (xsm_step_small.hip) -------------------
 struct SmallArgs {

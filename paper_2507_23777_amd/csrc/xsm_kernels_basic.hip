@@ -468,4 +468,19 @@ void launch_head_rows(const int32_t* acc, int32_t* row_index, int n_seq, int R, 
   hipLaunchKernelGGL(k_head_rows, dim3((n_seq + 63) / 64), dim3(64), 0, s, acc, row_index, n_seq, R);
 }
 
+// Cross-attention heads: residual rows Rk[b][k][:] = G[b][:] and the (sequence, head) -> cache
+// "slot" / skip-flag arrays of the one attention call over all heads.
+__global__ void k_head_ca_prep(const float* G, float* Rk, const int32_t* eff, const int32_t* slot,
+                               int32_t* eff2, int32_t* slot2, int n_seq, int K, int d, int max_batch) {
+  const int bk = blockIdx.x, b = bk / K, k = bk % K;
+  if (threadIdx.x == 0) { eff2[bk] = eff[b] < 0 ? -1 : 0; slot2[bk] = k * max_batch + slot[b]; }
+  for (int c = threadIdx.x; c < d; c += blockDim.x) Rk[(size_t)bk * d + c] = G[(size_t)b * d + c];
+}
+void launch_head_ca_prep(const float* G, float* Rk, const int32_t* eff, const int32_t* slot, int32_t* eff2,
+                         int32_t* slot2, int n_seq, int K, int d, int max_batch, hipStream_t s) {
+  TraceScope trace_("head_ca_prep", s);
+  hipLaunchKernelGGL(k_head_ca_prep, dim3(n_seq * K), dim3(256), 0, s, G, Rk, eff, slot, eff2, slot2, n_seq, K, d,
+                     max_batch);
+}
+
 }  // namespace xsm

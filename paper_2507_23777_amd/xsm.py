@@ -9,6 +9,7 @@ import os
 import numpy as np
 
 XSM_F32, XSM_BF16 = 0, 1
+XSM_HEAD_MLP, XSM_HEAD_CA = 0, 1
 XSM_OPT_SINGLE_LAUNCH = 1
 XSM_OPT_TIMELINE = 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -27,7 +28,8 @@ class XsmError(RuntimeError):
 class xsm_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn",
                                          "vocab", "n_draft", "max_batch", "max_ctx", "n_cond",
-                                         "dtype")] + [("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+                                         "dtype")] + [("rope_theta", C.c_float), ("rms_eps", C.c_float),
+                                                      ("head_kind", C.c_int32)]
 
 
 class xsm_verify_params(C.Structure):
@@ -101,7 +103,7 @@ def make_config(cfg: dict, max_batch: int | None = None, max_ctx: int | None = N
     return xsm_config(cfg["n_layers"], cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"],
                       cfg["vocab"], cfg["n_draft"], max_batch or cfg["batch"], max_ctx or cfg["max_ctx"],
                       cfg["n_cond"], XSM_BF16 if cfg["dtype"] == "bf16" else XSM_F32,
-                      cfg["rope_theta"], cfg["rms_eps"])
+                      cfg["rope_theta"], cfg["rms_eps"], XSM_HEAD_CA if cfg.get("head_kind", "mlp") == "ca" else XSM_HEAD_MLP)
 
 
 class StepBuffers:

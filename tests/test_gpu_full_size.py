@@ -137,6 +137,16 @@ def test_config3_cross_attention_full_size(X):
     _run_sampled(X, cfg, B, 16300, lens, [B - 1], GREEDY, steps=2)
 
 
+def test_config3_shape_with_cross_attention_heads(X):
+    """Config 3's shape (d=1536, 2048 condition tokens, vocabulary 8192, batch 8, long context) with
+    cross-attention decoding heads and per-head unembeddings; 6 layers keep the oracle within
+    seconds."""
+    cfg = si.get_config("c3", head_kind="ca", n_layers=6)
+    B = cfg["batch"]
+    lens = [16300 - 501 * b for b in range(B)]
+    _run_sampled(X, cfg, B, 16300, lens, [0, B - 1], GREEDY, steps=2)
+
+
 def test_config4_large_batch(X):
     cfg = si.get_config("c4", batch=128, n_draft=8)
     lens = [10000 - 7 * b for b in range(128)]

@@ -131,6 +131,40 @@ def test_cross_attention_backbone(X):
     assert tal.max_rel < 1e-5
 
 
+def test_cross_attention_decoding_heads(X):
+    """Eq. 4 with cross-attention heads and per-head unembeddings (Table 3 rows D/E): fp32 general
+    kernels, bf16 MFMA kernels at a small batch, and a batch large enough for the
+    split-contraction GEMMs; condition length not a multiple of the 64-key chunk."""
+    cfg = _mid_cfg(n_cond=19, prefix=9, seed=31, n_layers=2, dtype="f32", d_model=128, head_dim=32, d_ffn=256,
+                   head_kind="ca", n_draft=3)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 6, si.first_block(cfg, 2))
+    _report(tal, "CA heads f32")
+    assert tal.max_rel < 1e-5
+    cfg = _mid_cfg(n_cond=150, prefix=0, seed=32, n_layers=2, head_kind="ca")
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3)
+    K = cfg["n_draft"]
+
+    def forced(step, b, st, blk):
+        full = X.H.true_continuation(orc, st, blk[0], K, GREEDY)
+        j = (step + b) % (K + 1)
+        if j < K:
+            full[j + 1] = (full[j + 1] + 1) % cfg["vocab"]
+        return full
+
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, K + 2, si.first_block(cfg, 3), forced=forced)
+    _report(tal, "CA heads bf16 B3")
+    assert set(tal.accept_hist) == set(range(1, K + 2))
+    top8 = VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=77)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, top8, 4, si.first_block(cfg, 3))
+    _report(tal, "CA heads bf16 top-8 categorical")
+    cfg = _mid_cfg(n_cond=130, prefix=5, seed=33, n_layers=1, d_model=512, n_heads=8, d_ffn=1024, vocab=1024,
+                   head_kind="ca", n_draft=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 20)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 20))
+    _report(tal, "CA heads bf16 B20")
+
+
 def test_cache_contents_and_rollback(X):
     cfg = _mid_cfg(seed=26, n_layers=2)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
