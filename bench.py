@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, scaled by a plain copy of known size (see profiles/ and the design doc);
 # measured for k_step_small on the default workload with --steps 60 (context 282..370), where the
-# algorithmic figure is 653 MB: 772.1 MB read + 71.6 MB written.
-TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 843.7e6}
+# algorithmic figure is 653 MB: 733.3 MB read + 22.9 MB written.
+TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 756.2e6}
 
 
 def algorithmic_bytes(cfg: dict, n_seq: int, sum_ctx: float) -> float:
@@ -76,6 +76,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the untimed extras (latency spread, fixed-context points): profiling runs then see "
+                         "only the warm-up and timed steps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy five times and exit (scale for the PMC byte counters)")
     args = ap.parse_args()
@@ -169,19 +172,20 @@ def main() -> int:
 
     # ---- extras (outside the timed region): per-step latency spread, fixed-context points and
     # accepted tokens/s under given acceptance lengths (step latency depends on shapes only)
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(201)]
-    ctx_mid = int(len0[0])
-    evs[0].record()
-    for i in range(200):
-        buf.kv_len.fill_(ctx_mid)
-        eng.xsm_spec_step(buf, vp, ctx_mid)
-        evs[i + 1].record()
-    torch.cuda.synchronize()
-    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(200))
-    spread = {"context": ctx_mid, "p10": round(per[20], 4), "p50": round(per[100], 4), "p90": round(per[180], 4)}
-    fixed = []
+    spread, fixed = None, []
+    if not args.no_extras:
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(201)]
+        ctx_mid = int(len0[0])
+        evs[0].record()
+        for i in range(200):
+            buf.kv_len.fill_(ctx_mid)
+            eng.xsm_spec_step(buf, vp, ctx_mid)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(200))
+        spread = {"context": ctx_mid, "p10": round(per[20], 4), "p50": round(per[100], 4), "p90": round(per[180], 4)}
     for ctx in (257, 2048, 4353):
-        if ctx + R > max_ctx:
+        if args.no_extras or ctx + R > max_ctx:
             continue
         for _ in range(5):
             buf.kv_len.fill_(ctx); eng.xsm_spec_step(buf, vp, ctx)
