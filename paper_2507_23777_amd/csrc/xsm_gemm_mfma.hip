@@ -921,6 +921,255 @@ static void wt_gemm(int epi, FastGemm g, hipStream_t s) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Large M (more than 256 rows): register-blocked.  A workgroup computes 32 WN weight rows x
+// 32 WM activation rows, its four wavefronts 2 x 2 with WN x WM MFMA tiles each (16 accumulator
+// tiles at 4 x 4), so every operand fragment feeds four MFMA pairs and the kernel is bound by the
+// matrix cores rather than by LDS reads.  Weight fragments go from global memory / L2 straight to
+// registers (they are stored in fragment order), one stage of 64 k ahead; activations are staged
+// through double-buffered LDS as bf16 hi / lo planes (copied from the norm pass's planes, or split
+// from fp32 rows on the way in), one barrier per stage.  No split of the contraction index; row
+// blocks of one weight block run next to each other on one XCD.
+// ---------------------------------------------------------------------------
+struct QkvRow { int m, pos; size_t head0; bool ok; };
+__device__ __forceinline__ QkvRow qkv_row(const FastGemm& g, int m) {
+  QkvRow q{m, 0, 0, false};
+  if (m < g.M) {
+    const int b = m / g.R, j = m - b * g.R;
+    const int len = g.eff_len[b];
+    if (len >= 0) { q.pos = len + j; q.head0 = (size_t)g.slot[b] * g.H; q.ok = true; }
+  }
+  return q;
+}
+// four consecutive tile rows (n..n+3, n a multiple of 4) of row q.m: v and the values 8 tile rows away
+__device__ __forceinline__ void qkv_quad_store(const FastGemm& g, const QkvCols& c, const QkvRow& q, f32x4 v, f32x4 partner) {
+  if (!q.ok) return;
+  f32x4 o = v;
+  if (c.sec < 2) {
+    const float4* rp = reinterpret_cast<const float4*>(&g.rope[(size_t)q.pos * (g.hd / 2) + c.pi0]);
+    const float4 cs0 = rp[0], cs1 = rp[1];             // (cos, sin) of pi0, pi0+1 | pi0+2, pi0+3
+    const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = c.low ? v[e] * co[e] - partner[e] * si[e] : partner[e] * si[e] + v[e] * co[e];
+  }
+  const size_t head = q.head0 + c.h;
+  if (c.sec == 0) {
+    *reinterpret_cast<f32x4*>(g.Y + (size_t)q.m * g.ldy + c.h * g.hd + c.dim0) = o;
+  } else if (c.sec == 1) {
+    *reinterpret_cast<uint2*>(g.Kc + (head * g.cap + q.pos) * g.hd + c.dim0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+  } else if (g.v_transposed) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) g.Vc[(head * g.hd + c.dim0 + e) * g.cap + q.pos] = f2bf(o[e]);
+  } else {
+    *reinterpret_cast<uint2*>(g.Vc + (head * g.cap + q.pos) * g.hd + c.dim0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+  }
+}
+
+constexpr int kBlkKC = 64, kBlkST = kBlkKC + 8;        // contraction slice per stage, LDS row stride (bf16)
+constexpr int kBlkKT = kBlkKC / 32;
+
+template <int EPI, bool PLANES, int WN, int WM>
+__global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
+  constexpr int BN = 32 * WN, BM = 32 * WM;
+  constexpr int PLANE = BM * kBlkST, BUF = 2 * PLANE;   // hi plane, lo plane; two buffers
+  constexpr int NPC = PLANES ? BM * (kBlkKC / 8) / 256 : BM * (kBlkKC / 4) / 256;   // 16-byte pieces per thread, plane and stage
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, gq = lane >> 4;
+  const int KT = g.K / 32, NS = g.K / kBlkKC, MBk = (g.M + BM - 1) / BM, total = (g.N / BN) * MBk;
+  int id = blockIdx.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int nb = id / MBk, mb = id % MBk;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int nt0 = nb * (BN / 16) + wn * WN, m0 = mb * BM, m_base = m0 + wm * WM * 16;
+  const uint4* wbase = g.Wt + (size_t)nt0 * KT * 64 + lane;
+
+  f32x4 acc[WN][WM];
+#pragma unroll
+  for (int t = 0; t < WN; ++t)
+#pragma unroll
+    for (int q = 0; q < WM; ++q) acc[t][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // staging pieces: PLANES piece p = (row p/8, 8 columns), fp32 piece p = (row p/16, 4 columns)
+  uint4 wreg[WN][kBlkKT];
+  uint4 breg[PLANES ? 2 * NPC : NPC];
+  auto request = [&](int st) {
+    const int k0 = st * kBlkKC;
+#pragma unroll
+    for (int t = 0; t < WN; ++t)
+#pragma unroll
+      for (int i = 0; i < kBlkKT; ++i) wreg[t][i] = wbase[((size_t)t * KT + st * kBlkKT + i) * 64];
+#pragma unroll
+    for (int j = 0; j < NPC; ++j) {
+      const int p = tid + 256 * j;
+      if (PLANES) {
+        const int row = p / (kBlkKC / 8), c8 = p % (kBlkKC / 8);
+        breg[2 * j] = uint4{0, 0, 0, 0}; breg[2 * j + 1] = uint4{0, 0, 0, 0};
+        if (m0 + row < g.M) {
+          const uint16_t* src = reinterpret_cast<const uint16_t*>(g.X) + (size_t)(m0 + row) * g.K + k0 + c8 * 8;
+          breg[2 * j] = *reinterpret_cast<const uint4*>(src);
+          breg[2 * j + 1] = *reinterpret_cast<const uint4*>(src + (size_t)g.M * g.K);
+        }
+      } else {
+        const int row = p / (kBlkKC / 4), c4 = p % (kBlkKC / 4);
+        breg[j] = uint4{0, 0, 0, 0};
+        if (m0 + row < g.M) breg[j] = *reinterpret_cast<const uint4*>(g.X + (size_t)(m0 + row) * g.ldx + k0 + c4 * 4);
+      }
+    }
+  };
+  auto deposit = [&](int buf) {
+    uint16_t* dst = As + buf * BUF;
+#pragma unroll
+    for (int j = 0; j < NPC; ++j) {
+      const int p = tid + 256 * j;
+      if (PLANES) {
+        const int row = p / (kBlkKC / 8), c8 = p % (kBlkKC / 8);
+        *reinterpret_cast<uint4*>(dst + row * kBlkST + c8 * 8) = breg[2 * j];
+        *reinterpret_cast<uint4*>(dst + PLANE + row * kBlkST + c8 * 8) = breg[2 * j + 1];
+      } else {
+        const int row = p / (kBlkKC / 4), c4 = p % (kBlkKC / 4);
+        uint2 hi, lo;
+        split4(__builtin_bit_cast(float4, breg[j]), hi, lo);
+        *reinterpret_cast<uint2*>(dst + row * kBlkST + c4 * 4) = hi;
+        *reinterpret_cast<uint2*>(dst + PLANE + row * kBlkST + c4 * 4) = lo;
+      }
+    }
+  };
+  request(0);
+  deposit(0);
+  uint4 wcur[WN][kBlkKT];
+#pragma unroll
+  for (int t = 0; t < WN; ++t)
+#pragma unroll
+    for (int i = 0; i < kBlkKT; ++i) wcur[t][i] = wreg[t][i];
+  __syncthreads();
+  for (int st = 0; st < NS; ++st) {
+    if (st + 1 < NS) request(st + 1);
+    const uint16_t* bp = As + (st & 1) * BUF + (size_t)(wm * WM * 16 + r) * kBlkST + gq * 8;
+#pragma unroll
+    for (int i = 0; i < kBlkKT; ++i)
+#pragma unroll
+      for (int q = 0; q < WM; ++q) {
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + q * 16 * kBlkST + i * 32));
+        const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + PLANE + q * 16 * kBlkST + i * 32));
+        // the two products into one accumulator are kept WN MFMAs apart (a dependent MFMA issued
+        // back to back waits out the first one's latency)
+#pragma unroll
+        for (int t = 0; t < WN; ++t)
+          acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[t][i]), bl, acc[t][q], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < WN; ++t)
+          acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[t][i]), bh, acc[t][q], 0, 0, 0);
+      }
+    if (st + 1 < NS) {
+      deposit((st + 1) & 1);                           // that buffer was last read one stage ago
+#pragma unroll
+      for (int t = 0; t < WN; ++t)
+#pragma unroll
+        for (int i = 0; i < kBlkKT; ++i) wcur[t][i] = wreg[t][i];
+    }
+    __syncthreads();
+  }
+
+  // lane holds D[n0 + e][m], e = 0..3, n0 = (nt0 + t)*16 + gq*4, m = m_base + q*16 + r
+  if (EPI == FEPI_QKV) {
+    QkvRow rows[WM];
+#pragma unroll
+    for (int q = 0; q < WM; ++q) rows[q] = qkv_row(g, m_base + q * 16 + r);
+#pragma unroll
+    for (int t = 0; t < WN; ++t) {
+      const QkvCols c = qkv_cols(g, (nt0 + t) * 16 + gq * 4);
+#pragma unroll
+      for (int q = 0; q < WM; ++q) {
+        f32x4 pr;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(acc[t][q][e], 32, WAVE);   // tile row +- 8
+        qkv_quad_store(g, c, rows[q], acc[t][q], pr);
+      }
+    }
+    return;
+  }
+#pragma unroll
+  for (int q = 0; q < WM; ++q) {
+    const int m = m_base + q * 16 + r;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int t = 0; t < WN; ++t) {
+      const int n0 = (nt0 + t) * 16 + gq * 4;
+      const f32x4 v = acc[t][q];
+      f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
+      if (EPI == FEPI_STORE) {
+        *y = v;
+      } else if (EPI == FEPI_ADD) {
+        *y = *y + v;
+      } else if (EPI == FEPI_GELU) {
+        *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
+      } else if (EPI == FEPI_HEAD) {
+        const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);      // PLANES only: the normalised rows
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int n = n0 + e, c = n % g.K;
+          const float pre = v[e] + bf2f(g.bias[n]);
+          const float gn = bf2f(Bh[(size_t)m * g.K + c]) + bf2f(Bh[(size_t)g.M * g.K + (size_t)m * g.K + c]);
+          o[e] = gn + pre / (1.0f + __expf(-pre));
+        }
+        *y = o;
+      }
+    }
+  }
+}
+
+static bool blk_gemm_usable(int pro, int epi, const FastGemm& g) {
+  if (g.M <= kWsMaxM || g.N % 64 != 0 || g.K % kBlkKC != 0 || !g.nscratch) return false;
+  if (epi == FEPI_HEAD && pro != PRO_NORM) return false;
+  if ((size_t)g.M * (pro == PRO_NORM ? g.K : g.ldx) * 4 >= (1ull << 31)) return false;   // 32-bit buffer offsets
+  return true;
+}
+
+template <int EPI, bool PLANES, int WN, int WM>
+static void blk_launch_t(const FastGemm& g, hipStream_t s) {
+  constexpr int BN = 32 * WN, BM = 32 * WM;
+  const size_t lds = (size_t)2 * 2 * BM * kBlkST * 2;
+  auto kfn = k_gemm_blk<EPI, PLANES, WN, WM>;
+  static bool configured = false;
+  if (!configured && lds > 64 * 1024) {
+    (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured = true;
+  }
+  hipLaunchKernelGGL(kfn, dim3((g.N / BN) * ((g.M + BM - 1) / BM)), dim3(256), lds, s, g);
+}
+template <int EPI, bool PLANES>
+static void blk_launch(const FastGemm& g, hipStream_t s) {
+  // 128 x 128 blocks when they fill the chip, else 64 weight rows x 128 activation rows
+  const long blocks128 = (long)(g.N / 128) * ((g.M + 127) / 128);
+  if (g.N % 128 == 0 && blocks128 >= 200) blk_launch_t<EPI, PLANES, 4, 4>(g, s);
+  else blk_launch_t<EPI, PLANES, 2, 4>(g, s);
+}
+
+static void blk_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
+  if (pro == PRO_NORM) {
+    norm_pass(g, 1, s);
+    switch (epi) {
+      case FEPI_STORE: blk_launch<FEPI_STORE, true>(g, s); break;
+      case FEPI_GELU: blk_launch<FEPI_GELU, true>(g, s); break;
+      case FEPI_QKV: blk_launch<FEPI_QKV, true>(g, s); break;
+      case FEPI_HEAD: blk_launch<FEPI_HEAD, true>(g, s); break;
+      case FEPI_ADD: blk_launch<FEPI_ADD, true>(g, s); break;
+      default: break;
+    }
+  } else {
+    flush_pending_add(g.pend, s);
+    switch (epi) {
+      case FEPI_STORE: blk_launch<FEPI_STORE, false>(g, s); break;
+      case FEPI_GELU: blk_launch<FEPI_GELU, false>(g, s); break;
+      case FEPI_ADD: blk_launch<FEPI_ADD, false>(g, s); break;
+      default: break;
+    }
+  }
+}
+
 static void ws_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
   PendingAdd* pend = g.pend;
   if (pro == PRO_NORM) norm_pass(g, 0, s);
@@ -974,6 +1223,12 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 
 void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   if (g.M <= 0) return;
+  // (the residual-add projections read fp32 rows and have few column blocks: k_gemm_big is faster there)
+  if (blk_gemm_usable(pro, epi, g) && pro == PRO_NORM) {
+    TraceScope trace_("gemm_blk", s);
+    blk_gemm(pro, epi, g, s);
+    return;
+  }
   if (wt_gemm_usable(pro, g) && epi != FEPI_ADD) {
     TraceScope trace_("gemm_wt", s);
     wt_gemm(epi, g, s);
