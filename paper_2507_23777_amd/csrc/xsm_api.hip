@@ -57,7 +57,9 @@ void build_weight_offsets(xsm_ctx* c) {
 void build_work_offsets(xsm_ctx* c) {
   const xsm_config& g = c->cfg;
   const size_t d = g.d_model, F = g.d_ffn, V = g.vocab, K = g.n_draft;
-  const size_t Mmax = (size_t)g.max_batch * kMaxRows;     // rows of one backbone pass
+  size_t Mmax = (size_t)g.max_batch * kMaxRows;           // rows of one backbone pass
+  if (c->fast && Mmax < (size_t)kFastPassRows) Mmax = kFastPassRows;   // prefill chunks of few sequences
+  c->rows_max = Mmax;
   const size_t Mb = (size_t)g.max_batch * (K + 1);        // rows of one step
   WorkOff& w = c->ws;
   size_t p = 0;
@@ -75,7 +77,8 @@ void build_work_offsets(xsm_ctx* c) {
   w.rowidx = take(g.max_batch * 4);
   w.eff2 = take((size_t)g.max_batch * (K ? K : 1) * 4); w.slot2 = take((size_t)g.max_batch * (K ? K : 1) * 4);
   // (sequence, head) pairs of one attention call: the backbone's, or all cross-attention decoding heads at once
-  const size_t attn_pairs = (size_t)g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && K ? K : 1);
+  size_t attn_pairs = (size_t)g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && K ? K : 1);
+  if (attn_pairs < Mmax / 16 * g.n_heads) attn_pairs = Mmax / 16 * g.n_heads;   // (sequence, head, query tile) units
   c->part_entries = attn_pairs < 1024 ? 1024 : attn_pairs;
   w.part = take(fattn_part_bytes(c->part_entries));
   w.tickets = take(attn_pairs * 4);
@@ -113,15 +116,15 @@ size_t build_tiled_offsets(xsm_ctx* c, size_t start) {
   for (int l = 0; l < g.n_layers; ++l) {
     TiledLayer& L = t.layer[l];
     L.Wqkv = take(3 * d * d); L.Wo = take(d * d);
-    if (g.n_cond > 0) { L.Wcq = take(d * d); L.Wco = take(d * d); } else { L.Wcq = L.Wco = 0; }
+    if (g.n_cond > 0) { L.Wcq = take(d * d); L.Wckv = take(2 * d * d); L.Wco = take(d * d); } else { L.Wcq = L.Wckv = L.Wco = 0; }
     L.W1 = take(F * d); L.W2 = take(d * F);
   }
   t.WU = take(V * d);
   t.Wh = take((K ? K : 1) * d * d);
   t.hb = take((K ? K : 1) * d);
-  t.Who.assign(K, 0); t.WhU.assign(K, 0);
+  t.Who.assign(K, 0); t.WhU.assign(K, 0); t.Whkv.assign(K, 0);
   if (g.head_kind == XSM_HEAD_CA)
-    for (size_t k = 0; k < K; ++k) { t.Who[k] = take(d * d); t.WhU[k] = take(V * d); }
+    for (size_t k = 0; k < K; ++k) { t.Who[k] = take(d * d); t.WhU[k] = take(V * d); t.Whkv[k] = take(2 * d * d); }
   return p;
 }
 
@@ -158,8 +161,8 @@ char* head_cache(const xsm_ctx* c, int k, int which) {
 
 // split count of the key range per (sequence, head): enough workgroups to fill the chip, at
 // least ~4 chunks of 64 keys each, bounded by the partial slots in the workspace
-int attn_splits(const xsm_ctx* c, int n_seq, int len_bound) {
-  const int BH = n_seq * c->cfg.n_heads;
+int attn_splits(const xsm_ctx* c, int n_units, int len_bound) {
+  const int BH = n_units * c->cfg.n_heads;           // n_units: sequences x query tiles
   const int chunks = (len_bound + 63) / 64;
   int S = 512 / BH;
   if (S > chunks / 4) S = chunks / 4;
@@ -200,7 +203,7 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     a.Q = Qr; a.ldq = d; a.Kc = (const uint16_t*)self_cache(c, l, 0); a.Vt = (const uint16_t*)self_cache(c, l, 1);
     a.eff_len = eff; a.slot = slot; a.O = AO; a.ldo = d;
     a.part = (float*)(ws + c->ws.part); a.tickets = (uint32_t*)(ws + c->ws.tickets);
-    a.R = R; a.H = H; a.cap = c->cap_self; a.S = attn_splits(c, n_seq, len_bound + R); a.fixed_limit = 0;
+    a.R = R; a.H = H; a.cap = c->cap_self; a.S = attn_splits(c, n_seq * ((R + 15) / 16), len_bound + R); a.fixed_limit = 0;
     a.scale_log2 = scale_log2;
     launch_fattn(a, n_seq, s);
 
@@ -217,7 +220,7 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
       launch_fgemm(PRO_NORM, FEPI_STORE, cq, s);
       FastAttn ca = a;
       ca.Kc = (const uint16_t*)cross_cache(c, l, 0); ca.Vt = (const uint16_t*)cross_cache(c, l, 1);
-      ca.cap = c->cap_cross; ca.fixed_limit = g.n_cond; ca.S = attn_splits(c, n_seq, g.n_cond);
+      ca.cap = c->cap_cross; ca.fixed_limit = g.n_cond; ca.S = attn_splits(c, n_seq * ((R + 15) / 16), g.n_cond);
       launch_fattn(ca, n_seq, s);
       FastGemm co = o;
       co.Wt = (const uint4*)(c->d_w + T.Wco);
@@ -554,6 +557,7 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
       launch_tile_weights(P.Wo, wb + T.Wo, d, d, 0, 0, s);
       if (g.n_cond > 0) {
         launch_tile_weights(P.Wcq, wb + T.Wcq, d, d, 0, 0, s);
+        launch_tile_weights(P.Wckv, wb + T.Wckv, 2 * d, d, 0, 0, s);
         launch_tile_weights(P.Wco, wb + T.Wco, d, d, 0, 0, s);
       }
       launch_tile_weights(P.W1, wb + T.W1, F, d, 0, 0, s);
@@ -565,13 +569,17 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
         launch_tile_weights(wb + ctx->woff.hq[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
         launch_tile_weights(wb + ctx->woff.ho[k] * 2, wb + ctx->toff.Who[k], d, d, 0, 0, s);
         launch_tile_weights(wb + ctx->woff.hU[k] * 2, wb + ctx->toff.WhU[k], V, d, 0, 0, s);
+        launch_tile_weights(wb + ctx->woff.hkv[k] * 2, wb + ctx->toff.Whkv[k], 2 * d, d, 0, 0, s);
       } else {
         launch_tile_weights(wb + ctx->woff.hW[k] * 2, wb + ctx->toff.Wh + (size_t)k * d * d * 2, d, d, 0, 0, s);
         launch_copy_u16(wb + ctx->woff.hb[k] * 2, wb + ctx->toff.hb + (size_t)k * d * 2, d, s);
       }
     }
-    launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets),
-                    g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && g.n_draft ? g.n_draft : 1), 0, s);
+    {
+      size_t attn_pairs = (size_t)g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && g.n_draft ? g.n_draft : 1);
+      if (attn_pairs < ctx->rows_max / 16 * g.n_heads) attn_pairs = ctx->rows_max / 16 * g.n_heads;
+      launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), (int)attn_pairs, 0, s);
+    }
     launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.gtickets), (int)kWsTickets, 0, s);
     if (ctx->small_ok) {
       ctx->layer_tab.resize(g.n_layers);
@@ -619,26 +627,46 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
   int32_t* eff = (int32_t*)(ws + ctx->ws.eff_len);
   int32_t* slot = (int32_t*)(ws + ctx->ws.slot);
   XSM_HIP(hipMemcpyAsync(slot, h_slot, (size_t)n_seq * 4, hipMemcpyHostToDevice, s));
+  // rows per sequence per pass: 16 on the general kernels; on the MFMA path as many as the
+  // workspace holds (whole query tiles), so that a pass streams the weights for up to 256 rows
+  int chunk = kPrefillChunk;
+  if (ctx->fast) {
+    chunk = (int)(ctx->rows_max / n_seq) / 16 * 16;
+    if (chunk > kFastPassRows) chunk = kFastPassRows;
+    if (chunk < 16) chunk = 16;
+  }
   if (g.n_cond > 0) {      // per-layer cross-attention keys/values of the condition tokens
-    for (int r0 = 0; r0 < g.n_cond; r0 += kPrefillChunk) {
-      const int C = g.n_cond - r0 < kPrefillChunk ? g.n_cond - r0 : kPrefillChunk;
+    float* Xn = (float*)(ws + ctx->ws.Xn);
+    float* gpart = (float*)(ws + ctx->ws.gpart);
+    uint32_t* gtick = (uint32_t*)(ws + ctx->ws.gtickets);
+    auto project = [&](const void* Wcanon, size_t Wtiled, int M, char* kc, char* vc, int C, int r0) {
+      if (ctx->fast) {
+        FastGemm p{};
+        p.Wt = (const uint4*)(ctx->d_w + Wtiled); p.N = 2 * d; p.K = d; p.M = M;
+        p.X = X; p.ldx = d; p.Y = QKV; p.ldy = 2 * d;
+        p.nscratch = Xn; p.ws_part = gpart; p.ws_tickets = gtick; p.pend = &ctx->pend;
+        launch_fgemm(PRO_F32, FEPI_STORE, p, s);
+      } else {
+        launch_gemm(dt, EPI_STORE, X, d, Wcanon, QKV, 2 * d, M, 2 * d, d, s);
+      }
+      launch_store_cond(dt, QKV, slot, kc, vc, n_seq, C, r0, g.n_heads, g.head_dim, ctx->cap_cross,
+                        ctx->fast ? 1 : 0, s);
+    };
+    for (int r0 = 0; r0 < g.n_cond; r0 += chunk) {
+      const int C = g.n_cond - r0 < chunk ? g.n_cond - r0 : chunk;
       launch_load_rows(dt, d_cond, X, n_seq, C, r0, g.n_cond, d, s);
       for (int l = 0; l < g.n_layers; ++l) {
         const LayerPtrs L = layer_ptrs(ctx, l);
-        launch_gemm(dt, EPI_STORE, X, d, L.Wckv, QKV, 2 * d, n_seq * C, 2 * d, d, s);
-        launch_store_cond(dt, QKV, slot, cross_cache(ctx, l, 0), cross_cache(ctx, l, 1), n_seq, C,
-                          r0, g.n_heads, g.head_dim, ctx->cap_cross, ctx->fast ? 1 : 0, s);
+        project(L.Wckv, ctx->fast ? ctx->toff.layer[l].Wckv : 0, n_seq * C, cross_cache(ctx, l, 0), cross_cache(ctx, l, 1), C, r0);
       }
       if (g.head_kind == XSM_HEAD_CA)          // the decoding heads' own keys/values of the condition
-        for (int k = 0; k < g.n_draft; ++k) {
-          launch_gemm(dt, EPI_STORE, X, d, ctx->d_w + ctx->woff.hkv[k] * ctx->esz, QKV, 2 * d, n_seq * C, 2 * d, d, s);
-          launch_store_cond(dt, QKV, slot, head_cache(ctx, k, 0), head_cache(ctx, k, 1), n_seq, C, r0,
-                            g.n_heads, g.head_dim, ctx->cap_cross, ctx->fast ? 1 : 0, s);
-        }
+        for (int k = 0; k < g.n_draft; ++k)
+          project(ctx->d_w + ctx->woff.hkv[k] * ctx->esz, ctx->fast ? ctx->toff.Whkv[k] : 0, n_seq * C,
+                  head_cache(ctx, k, 0), head_cache(ctx, k, 1), C, r0);
     }
   }
-  for (int r0 = 0; r0 < P; r0 += kPrefillChunk) {
-    const int C = P - r0 < kPrefillChunk ? P - r0 : kPrefillChunk;
+  for (int r0 = 0; r0 < P; r0 += chunk) {
+    const int C = P - r0 < chunk ? P - r0 : chunk;
     launch_fill_i32(eff, n_seq, r0, s);
     launch_load_rows(dt, d_prefix_emb, X, n_seq, C, r0, P, d, s);
     forward_blocks(ctx, n_seq, C, r0, s);

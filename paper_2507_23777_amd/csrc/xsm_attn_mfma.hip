@@ -1,6 +1,7 @@
-// Block-causal KV-cache attention for R <= 16 query rows per sequence on bf16 MFMA
-// (gfx950), head_dim 64.  Query row j of sequence b sits at position n_b + j and sees cache
-// positions 0..n_b + j (Sec. 4.2: causal mask inside the draft block x_{s:s+D}).
+// Block-causal KV-cache attention for R query rows per sequence on bf16 MFMA (gfx950),
+// head_dim 64.  Query row j of sequence b sits at position n_b + j and sees cache positions
+// 0..n_b + j (Sec. 4.2: causal mask inside the draft block x_{s:s+D}).  A workgroup takes one
+// tile of 16 query rows (a speculative step has one tile; prefill chunks have several).
 //
 // HBM-bound: every cached key and value is read once per step, so the layout is chosen for
 // the loads.  Keys are [position][64] (128 B rows); values are stored transposed,
@@ -43,17 +44,20 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   __shared__ float sm_ml[4][2][16];
   __shared__ __align__(16) float sm_o[4][4][64][4];
   __shared__ int sm_last;
-  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int S = a.S, QT = (a.R + 15) >> 4;
+  const int s = blockIdx.x % S, qt = blockIdx.x / S, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int R = a.R, S = a.S;
-  const int n = a.eff_len[b];
-  if (n < 0) {                                     // skipped sequence: defined (zero) output
+  const int R = min(16, a.R - qt * 16);            // query rows of this tile
+  const int row0 = b * a.R + qt * 16;              // its first row in Q / O
+  const int nseq = a.eff_len[b];
+  if (nseq < 0) {                                  // skipped sequence: defined (zero) output
     if (s == 0)
       for (int i = tid; i < R * 64; i += 256)
-        a.O[(size_t)(b * R + i / 64) * a.ldo + h * 64 + (i & 63)] = 0;
+        a.O[(size_t)(row0 + i / 64) * a.ldo + h * 64 + (i & 63)] = 0;
     return;
   }
+  const int n = nseq + qt * 16;                    // keys every query of this tile sees
   const int Ltot = a.fixed_limit > 0 ? a.fixed_limit : n + R;
   const int NC = (Ltot + 63) >> 6, CPS = (NC + S - 1) / S;
   const int c_lo = s * CPS, c_hi = min(NC, c_lo + CPS);
@@ -70,7 +74,7 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   for (int half = 0; half < 2; ++half) {
     float qv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (r < R) {
-      const float* q = a.Q + (size_t)(b * R + r) * a.ldq + h * 64 + half * 32 + g * 8;
+      const float* q = a.Q + (size_t)(row0 + r) * a.ldq + h * 64 + half * 32 + g * 8;
       const float4 x0 = *reinterpret_cast<const float4*>(q), x1 = *reinterpret_cast<const float4*>(q + 4);
       qv[0] = x0.x; qv[1] = x0.y; qv[2] = x0.z; qv[3] = x0.w;
       qv[4] = x1.x; qv[5] = x1.y; qv[6] = x1.z; qv[7] = x1.w;
@@ -197,27 +201,28 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   if (S == 1) {
     if (r < R) {
       const float inv = 1.0f / L;
-      float* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
+      float* dst = a.O + (size_t)(row0 + r) * a.ldo + h * 64 + dt * 16 + g * 4;
       *reinterpret_cast<float4*>(dst) = float4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
     }
     return;
   }
   // split keys: publish this workgroup's partial, the last one to arrive merges all S
-  float* part = a.part + ((size_t)(b * a.H + h) * S + s) * kPartFloats;
+  const size_t unit = (size_t)(b * a.H + h) * QT + qt;          // (sequence, head, query tile)
+  float* part = a.part + (unit * S + s) * kPartFloats;
   if (wave == 0 && g == 0) { st_coherent(part + r, M); st_coherent(part + 16 + r, L); }
 #pragma unroll
   for (int i = 0; i < 4; ++i) st_coherent(part + 32 + (dt * 16 + g * 4 + i) * 16 + r, acc[i]);
   __builtin_amdgcn_s_waitcnt(0);                      // partial is complete in memory
   __syncthreads();
   if (tid == 0) {
-    uint32_t* tk = a.tickets + b * a.H + h;
+    uint32_t* tk = a.tickets + unit;
     const uint32_t old = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     sm_last = old == (uint32_t)(S - 1);
     if (sm_last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   if (!sm_last) return;
-  const float* p0 = a.part + (size_t)(b * a.H + h) * S * kPartFloats;
+  const float* p0 = a.part + unit * S * kPartFloats;
   float Mg = -INFINITY;
   for (int k = 0; k < S; ++k) Mg = fmaxf(Mg, ld_coherent(p0 + (size_t)k * kPartFloats + r));
   float Lg = 0.f;
@@ -232,14 +237,14 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   }
   if (r < R) {
     const float inv = 1.0f / Lg;
-    float* dst = a.O + (size_t)(b * R + r) * a.ldo + h * 64 + dt * 16 + g * 4;
+    float* dst = a.O + (size_t)(row0 + r) * a.ldo + h * 64 + dt * 16 + g * 4;
     *reinterpret_cast<float4*>(dst) = float4{og[0] * inv, og[1] * inv, og[2] * inv, og[3] * inv};
   }
 }
 
 void launch_fattn(const FastAttn& a, int n_seq, hipStream_t s) {
   TraceScope trace_("fattn", s);
-  hipLaunchKernelGGL(k_fattn, dim3(a.S, a.H, n_seq), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(k_fattn, dim3(a.S * ((a.R + 15) / 16), a.H, n_seq), dim3(256), 0, s, a);
 }
 
 size_t fattn_part_bytes(size_t entries) { return entries * kPartFloats * sizeof(float); }

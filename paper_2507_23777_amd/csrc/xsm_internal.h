@@ -10,7 +10,8 @@
 
 namespace xsm {
 
-constexpr int kPrefillChunk = 16;   // prefix rows per sequence per backbone pass
+constexpr int kPrefillChunk = 16;   // prefix rows per sequence per backbone pass (general kernels)
+constexpr int kFastPassRows = 256;  // rows of one backbone pass the MFMA path's workspace always holds (prefill chunks)
 constexpr int kMaxRows = 16;        // rows per sequence per pass (K+1 <= 16)
 
 // Element offsets of the canonical weight tensors (same order as the weight file).
@@ -34,11 +35,11 @@ struct WorkOff {
 };
 
 // Byte offsets of the fragment-ordered (tiled) bf16 matrices inside the weights buffer.
-struct TiledLayer { size_t Wqkv, Wo, Wcq, Wco, W1, W2; };
+struct TiledLayer { size_t Wqkv, Wo, Wcq, Wckv, Wco, W1, W2; };
 struct TiledOff {
   std::vector<TiledLayer> layer;
   size_t WU, Wh, hb;       // unembedding, stacked head matrices [K*d][d] (MLP: W_k, CA: Wq_k), stacked head biases [K][d]
-  std::vector<size_t> Who, WhU;   // cross-attention heads: output projections and unembeddings
+  std::vector<size_t> Who, WhU, Whkv;   // cross-attention heads: output projections, unembeddings, key/value projections
   bool wu_ok;              // vocabulary is a multiple of 16
 };
 
@@ -81,7 +82,8 @@ struct xsm_ctx {
   xsm::TiledOff toff;
   int cap_self = 0, cap_cross = 0;   // cache capacities in positions, padded to 64
   xsm::PendingAdd pend;              // see PendingAdd
-  size_t part_entries = 0;           // (sequence, head, split) partial slots in the workspace
+  size_t part_entries = 0;           // (sequence, head, query tile, split) partial slots in the workspace
+  size_t rows_max = 0;               // rows of one backbone pass the workspace holds
   char* d_w = nullptr;
   char* d_kv = nullptr;
   char* d_ws = nullptr;

@@ -165,6 +165,26 @@ def test_cross_attention_decoding_heads(X):
     _report(tal, "CA heads bf16 B20")
 
 
+def test_prefill_in_large_chunks(X):
+    """Prefill on the MFMA path runs up to 256 prefix rows per pass (several 16-row query tiles per
+    sequence, causal inside the chunk): one sequence with a 300-token prefix (chunks 256 + 44) and
+    a ragged batch; the cache must match the oracle's and the steps after it too."""
+    cfg = _mid_cfg(prefix=300, seed=41, n_layers=2, max_ctx=512)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1)
+    for l in range(cfg["n_layers"]):
+        for which, ref in ((0, states[0].k[l]), (1, states[0].v[l])):
+            got = eng.xsm_debug_kv_export(l, which, 0, 0, 300)          # [H][pos][hd]
+            want = np.transpose(np.asarray(ref[:300], np.float64), (1, 0, 2))
+            err = np.abs(got - want).max() / np.abs(want).max()
+            assert err < 1e-2, (l, which, err)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 1))
+    _report(tal, "prefix 300 B1")
+    cfg = _mid_cfg(prefix=150, seed=42, n_layers=2, max_ctx=512)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, prefix_lens=[150, 97, 16])
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 3))
+    _report(tal, "prefix 150/97/16 B3")
+
+
 def test_cache_contents_and_rollback(X):
     cfg = _mid_cfg(seed=26, n_layers=2)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
