@@ -8,7 +8,8 @@ shares no code with the HIP kernels or their Python binding.
 """
 from .philox import philox4x32_10, uniform24
 from .xsm_oracle import (Oracle, SeqState, VerifyParams, rmsnorm, rope_rotate, gelu_erf, silu,
-                         softmax, accept, sample, rank_of)
+                         softmax, accept, sample, rank_of, pts_sample, PTS_HEAD)
 
 __all__ = ["philox4x32_10", "uniform24", "Oracle", "SeqState", "VerifyParams", "rmsnorm",
-           "rope_rotate", "gelu_erf", "silu", "softmax", "accept", "sample", "rank_of"]
+           "rope_rotate", "gelu_erf", "silu", "softmax", "accept", "sample", "rank_of", "pts_sample",
+           "PTS_HEAD"]

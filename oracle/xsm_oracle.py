@@ -23,6 +23,8 @@ What is computed, with the passage it follows:
   rejected position (Sec. 4.2; Alg. 1 inner while and the resample line);
 * criteria: probability threshold p^(0)_i(x_i) > delta, or top-K_a membership
   (Sec. 5.4 "Verification criterion"); K_a = 1 is greedy verification;
+* sampling of the heads' tokens: independent draws, or top-K_s probability-tree
+  sampling with pruning at 1e-5 (appendix "Sampling strategies", Table 5);
 * the cache "rollback" is implied by s <- s*: the next pass overwrites slots
   from the new s on, so only the length changes.
 
@@ -45,7 +47,9 @@ a full-sequence causal forward built from torch's library attention; building
 blocks against scipy/torch routines; Philox against an independent big-int
 implementation and published known-answer values; the cross-attention head
 against its closed forms (zero output projection, one condition token, zero query
-projection) and torch's library attention.
+projection) and torch's library attention; probability-tree sampling against the
+flattened outer product of the per-level weights (no pruning), a hand-made pruned tree,
+K_s = 1, and a chi-square test of its first-level marginal.
 The stochastic path's exact sampled sequences have no external pin beyond the
 chi-square test of the sampler's distribution: parity unpinned for those.
 """
@@ -105,8 +109,10 @@ class VerifyParams:
     top_ka: int = 1
     delta: float = 0.5
     temperature: float = 1.0
-    sample: int = 0          # 0 argmax, 1 categorical
+    sample: int = 0          # 0 argmax, 1 categorical (independent sampling), 2 probability-tree sampling
     seed: int = 0
+    top_ks: int = 2          # K_s of the probability tree
+    pts_prune: float = 1e-5  # branches whose cumulative weight falls below this are cut
 
 
 def rank_of(z: np.ndarray, x: int) -> int:
@@ -125,7 +131,8 @@ def accept(z: np.ndarray, x: int, vp: VerifyParams) -> bool:
 
 
 def sample(z: np.ndarray, vp: VerifyParams, pos: int, head: int, seq_id: int):
-    """Draw a token from logits z.  Returns (token, diagnostics)."""
+    """Draw a token from logits z (argmax, or categorical; under probability-tree sampling the
+    backbone's token is a categorical draw).  Returns (token, diagnostics)."""
     if vp.sample == 0:
         tok = int(np.argmax(z))                   # first index among equal maxima
         top2 = np.partition(z, -2)[-2:] if z.size > 1 else np.array([-np.inf, z[0]])
@@ -139,6 +146,49 @@ def sample(z: np.ndarray, vp: VerifyParams, pos: int, head: int, seq_id: int):
     edges = np.concatenate([[0.0], cdf])
     gap = float(np.min(np.abs(edges - u * S)) / S)
     return tok, {"kind": "cdf", "u": u, "gap": gap}
+
+
+PTS_HEAD = 254      # Philox "head" coordinate of the one uniform a probability-tree draw consumes
+
+
+def pts_sample(Zh: np.ndarray, vp: VerifyParams, pos: int, seq_id: int):
+    """Top-K_s probability-tree sampling of the K head tokens (appendix "Sampling strategies").
+
+    Level d of the tree holds the K_s most probable tokens of head d's distribution
+    softmax(z_d / T) (equal probabilities ordered by lower index) with their probabilities
+    m as edge weights; a path's weight is the product of its edges; a branch is cut as soon as
+    its cumulative weight falls below vp.pts_prune; one complete path is drawn with probability
+    proportional to its weight, by inverse CDF over the surviving paths in depth-first order
+    (most probable child first) with one uniform.  If no complete path survives, the path of
+    the most probable token of every head is taken.  Returns (tokens, diagnostics)."""
+    K = Zh.shape[0]
+    tops = []
+    for d in range(K):
+        p = softmax(np.asarray(Zh[d], F64) / vp.temperature)
+        order = np.lexsort((np.arange(p.size), -p))[:vp.top_ks]
+        tops.append([(int(v), float(p[v])) for v in order])
+    leaves = []
+
+    def grow(d, toks, w):
+        if d == K:
+            leaves.append((toks, w))
+            return
+        for v, m in tops[d]:
+            if w * m >= vp.pts_prune:
+                grow(d + 1, toks + [v], w * m)
+
+    grow(0, [], 1.0)
+    u = uniform24(vp.seed, pos, PTS_HEAD, seq_id)
+    if not leaves:
+        return [t[0][0] for t in tops], {"kind": "pts", "u": u, "gap": 1.0, "n_paths": 0}
+    cdf = np.cumsum([w for _, w in leaves])
+    S = cdf[-1]
+    hit = np.nonzero(cdf > u * S)[0]
+    i = int(hit[0]) if hit.size else len(leaves) - 1
+    edges = np.concatenate([[0.0], cdf])
+    gap = float(np.min(np.abs(edges - u * S)) / S)
+    # how close any cut decision or any top-K_s membership was (for near-tie flags of a comparison)
+    return list(leaves[i][0]), {"kind": "pts", "u": u, "gap": gap, "n_paths": len(leaves)}
 
 
 # ----------------------------------------------------------------------------
@@ -272,10 +322,14 @@ class Oracle:
         else:                      # only h_{s*-1} is consumed by the resample line
             Zh = self.head_logits(Hf[a], st)
         ys, diags = [], [diag0]
-        for k in range(1, K + 1):
-            y, dg = sample(Zh[k - 1], vp, n + a + 1 + k, k, st.seq_id)
-            ys.append(y)
-            diags.append(dg)
+        if vp.sample == 2 and K > 0:     # the backbone token is an independent draw; the heads' tokens one tree draw
+            ys, dg = pts_sample(Zh, vp, n + a + 1, st.seq_id)
+            diags += [dg] * K
+        else:
+            for k in range(1, K + 1):
+                y, dg = sample(Zh[k - 1], vp, n + a + 1 + k, k, st.seq_id)
+                ys.append(y)
+                diags.append(dg)
         st.n = n + a + 1
         return {"out_tokens": t[1:a + 1] + [y0], "n_accepted": a + 1, "next_block": [y0] + ys,
                 "Z0": Z0, "Zh": Zh, "Hf": Hf, "a": a, "diag": diags}

@@ -195,3 +195,84 @@ def test_greedy_spec_equals_plain_greedy_with_cross_attention_heads(K):
     b = orc.spec_step(st3, blk, GREEDY, heads_on_all_rows=True)
     assert a["next_block"] == b["next_block"]
     np.testing.assert_allclose(a["Zh"], b["Zh"], rtol=1e-12, atol=1e-14)
+
+
+# ---- top-K_s probability-tree sampling (appendix "Sampling strategies") ------------------------
+def test_pts_without_pruning_is_the_flattened_outer_product():
+    """With no pruning the leaves in depth-first order are the C-order flattening of the outer
+    product of the per-level top-K_s probabilities, so the draw must be the searchsorted index of
+    u*S in that table (built here with numpy's outer / ravel, not by recursion)."""
+    from oracle import pts_sample, PTS_HEAD, uniform24
+    rng = np.random.default_rng(3)
+    K, V, Ks, T = 3, 11, 3, 0.7
+    for trial in range(40):
+        Zh = rng.standard_normal((K, V)) * 2.0
+        vp = VerifyParams(sample=2, temperature=T, seed=900 + trial, top_ks=Ks, pts_prune=0.0)
+        toks, dg = pts_sample(Zh, vp, pos=17 + trial, seq_id=trial % 3)
+        P = [softmax(Zh[d] / T) for d in range(K)]
+        order = [sorted(range(V), key=lambda v: (-P[d][v], v))[:Ks] for d in range(K)]
+        table = np.array([1.0])
+        for d in range(K):
+            table = np.outer(table, P[d][order[d]]).ravel()
+        cdf = np.cumsum(table)
+        u = uniform24(vp.seed, 17 + trial, PTS_HEAD, trial % 3)
+        idx = int(np.searchsorted(cdf, u * cdf[-1], side="right"))
+        digits = np.unravel_index(idx, (Ks,) * K)
+        assert toks == [order[d][digits[d]] for d in range(K)]
+        assert dg["n_paths"] == Ks ** K
+
+
+def test_pts_special_cases_and_pruning():
+    from oracle import pts_sample
+    rng = np.random.default_rng(5)
+    Zh = rng.standard_normal((4, 9))
+    # K_s = 1: the path of the most probable tokens, whatever the uniform
+    for seed in range(5):
+        toks, _ = pts_sample(Zh, VerifyParams(sample=2, seed=seed, top_ks=1, pts_prune=0.0), 3, 0)
+        assert toks == [int(np.argmax(z)) for z in Zh]
+    # nothing survives: same fallback
+    toks, dg = pts_sample(Zh, VerifyParams(sample=2, seed=1, top_ks=3, pts_prune=2.0), 3, 0)
+    assert toks == [int(np.argmax(z)) for z in Zh] and dg["n_paths"] == 0
+    # hand-made tree: level probabilities (0.9, 0.1) and (0.8, 0.2); threshold 0.05 cuts only the
+    # path 0.1*0.2 = 0.02, leaving weights 0.72, 0.18, 0.08
+    z1 = np.log(np.array([0.9, 0.1])); z2 = np.log(np.array([0.2, 0.8]))
+    Z = np.stack([z1, z2])
+    seen = {}
+    for seed in range(400):
+        vp = VerifyParams(sample=2, seed=seed, top_ks=2, pts_prune=0.05)
+        toks, dg = pts_sample(Z, vp, 0, 0)
+        assert dg["n_paths"] == 3 and tuple(toks) != (1, 0)
+        seen[tuple(toks)] = seen.get(tuple(toks), 0) + 1
+    exp = np.array([0.72, 0.18, 0.08]); exp = exp / exp.sum() * 400
+    obs = np.array([seen.get((0, 1), 0), seen.get((0, 0), 0), seen.get((1, 1), 0)])
+    assert stats.chisquare(obs, exp).pvalue > 1e-3
+
+
+def test_pts_first_level_marginal_distribution():
+    """Without pruning the first token's marginal is head 1's distribution truncated to its top K_s."""
+    from oracle import pts_sample
+    rng = np.random.default_rng(8)
+    Zh = rng.standard_normal((3, 12)) * 1.5
+    Ks, T, N = 4, 0.8, 3000
+    p = softmax(Zh[0] / T)
+    top = sorted(range(12), key=lambda v: (-p[v], v))[:Ks]
+    counts = {v: 0 for v in top}
+    for i in range(N):
+        toks, _ = pts_sample(Zh, VerifyParams(sample=2, temperature=T, seed=31, top_ks=Ks, pts_prune=0.0), pos=i, seq_id=0)
+        counts[toks[0]] += 1
+    exp = np.array([p[v] for v in top]); exp = exp / exp.sum() * N
+    assert stats.chisquare(np.array([counts[v] for v in top]), exp).pvalue > 1e-3
+
+
+def test_spec_step_with_pts_keeps_the_backbone_token_an_independent_draw():
+    cfg = si.tiny_config(n_draft=3, seed=13)
+    orc, st = _setup(cfg)
+    blk = si.first_block(cfg, 1)[0]
+    vp_is = VerifyParams(mode=1, top_ka=4, temperature=0.9, sample=1, seed=5)
+    vp_pts = VerifyParams(mode=1, top_ka=4, temperature=0.9, sample=2, seed=5, top_ks=2)
+    a = orc.spec_step(copy.deepcopy(st), blk, vp_is)
+    b = orc.spec_step(copy.deepcopy(st), blk, vp_pts)
+    assert a["n_accepted"] == b["n_accepted"] and a["next_block"][0] == b["next_block"][0]
+    from oracle import pts_sample
+    toks, _ = pts_sample(b["Zh"], vp_pts, st.n + b["a"] + 1, st.seq_id)
+    assert b["next_block"][1:] == toks
