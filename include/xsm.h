@@ -89,8 +89,18 @@ typedef struct {
   int32_t sample;        /* 0: argmax (lowest index among equal maxima); 1: categorical over the
                             full vocabulary by inverse CDF in ascending token order, weights
                             exp((z - max z)/T), uniform u = (x0 >> 8) * 2^-24 with
-                            x = Philox4x32-10(counter = (position, head, slot, 0), key = seed) */
+                            x = Philox4x32-10(counter = (position, head, slot, 0), key = seed);
+                            2: top-K_s probability-tree sampling of the K head tokens (appendix
+                            "Sampling strategies"): level d = the top_ks most probable tokens of
+                            softmax(z_d/T) (equal ones by lower index) with their probabilities as
+                            edge weights, paths whose weight falls below pts_prune are cut, one
+                            surviving path is drawn in proportion to its weight by inverse CDF in
+                            depth-first order with one uniform (head coordinate 254); no survivor:
+                            every head's most probable token.  The backbone token is drawn as
+                            under 1.  Needs 1 <= top_ks <= 4 and top_ks^K <= 4096. */
   uint64_t seed;
+  int32_t top_ks;        /* K_s (sample == 2) */
+  float pts_prune;       /* path-weight cut-off (sample == 2); the paper uses 1e-5 */
 } xsm_verify_params;
 
 /* flags[b] bits */

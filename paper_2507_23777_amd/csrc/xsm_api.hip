@@ -304,7 +304,15 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   if (vp->mode == XSM_VERIFY_TOPK && vp->top_ka < 1) return fail(ctx, XSM_EINVAL, "top_ka < 1");
   if ((vp->sample == 1 || vp->mode == XSM_VERIFY_THRESHOLD) && !(vp->temperature > 0.f))
     return fail(ctx, XSM_EINVAL, "temperature must be > 0");
-  if (vp->sample != 0 && vp->sample != 1) return fail(ctx, XSM_EINVAL, "bad sample rule");
+  if (vp->sample < 0 || vp->sample > 2) return fail(ctx, XSM_EINVAL, "bad sample rule");
+  if (vp->sample == 2) {
+    if (!(vp->temperature > 0.f)) return fail(ctx, XSM_EINVAL, "temperature must be > 0");
+    if (vp->top_ks < 1 || vp->top_ks > 4) return fail(ctx, XSM_EINVAL, "top_ks must be in [1, 4]");
+    long paths = 1;
+    for (int k = 0; k < R - 1; ++k) paths *= vp->top_ks;
+    if (paths > 4096) return fail(ctx, XSM_EINVAL, "probability tree too large (top_ks^K > 4096)");
+    if (!(vp->pts_prune >= 0.f)) return fail(ctx, XSM_EINVAL, "pts_prune must be >= 0");
+  }
 
   hipStream_t s = (hipStream_t)stream;
   const int n_seq = bt->n_seq, K = R - 1, d = g.d_model, V = g.vocab, dt = g.dtype;

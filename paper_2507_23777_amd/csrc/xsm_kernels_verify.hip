@@ -238,6 +238,81 @@ void launch_head_act(int dtype, const float* G, const float* Hh, const void* con
     hipLaunchKernelGGL(k_head_act<float>, grid, blk, 0, s, G, Hh, bp, Rk, K, d, total);
 }
 
+// Top-K_s probability-tree sampling of the K head tokens (appendix "Sampling strategies"): level d
+// holds the ks most probable tokens of softmax(z_d / T) with their probabilities as edge weights;
+// a complete path survives if its weight (a product of numbers <= 1, so the smallest of its
+// prefixes' weights) is at least `prune`; one survivor is drawn in proportion to its weight by
+// inverse CDF in depth-first (= lexicographic) order.  cand[1..K] receives the tokens.
+__device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
+                         RowScratch& sm, int* cand) {
+  __shared__ int top_i[16][4];
+  __shared__ float top_p[16][4];
+  for (int k = 0; k < K; ++k) {
+    const float* z = Zh + (size_t)k * V;
+    float mx = -INFINITY;
+    for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+    mx = block_max(mx, sm.redf);
+    float sum = 0.f;
+    for (int v = threadIdx.x; v < V; v += 256) sum += expf((z[v] - mx) * invT);
+    sum = block_sum(sum, sm.redf);
+    for (int j = 0; j < ks; ++j) {                 // j-th largest logit, lower index among equals
+      float bv = -INFINITY;
+      int bi = 0x7FFFFFFF;
+      for (int v = threadIdx.x; v < V; v += 256) {
+        bool taken = false;
+        for (int q = 0; q < j; ++q) taken |= top_i[k][q] == v;
+        const float x = z[v];
+        if (!taken && (x > bv || (x == bv && v < bi))) { bv = x; bi = v; }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const float bv2 = __shfl_xor(bv, o, WAVE);
+        const int bi2 = __shfl_xor(bi, o, WAVE);
+        if (bv2 > bv || (bv2 == bv && bi2 < bi)) { bv = bv2; bi = bi2; }
+      }
+      __syncthreads();
+      if ((threadIdx.x & 63) == 0) { sm.bestv[threadIdx.x >> 6] = bv; sm.besti[threadIdx.x >> 6] = bi; }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+          if (sm.bestv[w] > bv || (sm.bestv[w] == bv && sm.besti[w] < bi)) { bv = sm.bestv[w]; bi = sm.besti[w]; }
+        top_i[k][j] = bi;
+        top_p[k][j] = bi == 0x7FFFFFFF ? 0.f : expf((bv - mx) * invT) / sum;     // V < ks: no such token
+      }
+      __syncthreads();
+    }
+  }
+  if (threadIdx.x == 0) {
+    int n_paths = 1;
+    for (int k = 0; k < K; ++k) n_paths *= ks;
+    auto weight = [&](int leaf) {                  // digits of `leaf` base ks, first head most significant
+      double w = 1.0;
+      int rem = leaf, div = n_paths;
+      for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
+      return w;
+    };
+    double S = 0.0;
+    int last = -1;
+    for (int leaf = 0; leaf < n_paths; ++leaf) {
+      const double w = weight(leaf);
+      if (w >= (double)prune && w > 0.0) { S += w; last = leaf; }
+    }
+    int pick = 0;                                   // no survivor: the most probable token of every head
+    if (last >= 0) {
+      const double target = (double)u * S;
+      double run = 0.0;
+      pick = last;
+      for (int leaf = 0; leaf <= last; ++leaf) {
+        const double w = weight(leaf);
+        if (w >= (double)prune && w > 0.0) { run += w; if (run > target) { pick = leaf; break; } }
+      }
+    }
+    int rem = pick, div = n_paths;
+    for (int k = 0; k < K; ++k) { div /= ks; cand[k + 1] = top_i[k][rem / div]; rem %= div; }
+  }
+  __syncthreads();
+}
+
 // draws from the K head rows, then emit: accepted tokens, count, next block, new length
 __global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params vp,
                                               const int32_t* eff_len, const int32_t* slot,
@@ -258,10 +333,15 @@ __global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params
   const int a = acc[b];
   if (threadIdx.x < R) old_block[threadIdx.x] = block[b * R + threadIdx.x];
   uint32_t flag = 0;
-  for (int k = 1; k <= K; ++k) {
-    const int t = row_sample(Zh + (size_t)(b * K + k - 1) * V, V, vp, (uint32_t)(n + a + 1 + k),
-                             (uint32_t)k, (uint32_t)slot[b], sm, &flag);
-    if (threadIdx.x == 0) cand[k] = t;
+  if (vp.sample == 2 && K > 0) {
+    const float u = philox_uniform(vp.seed, (uint32_t)(n + a + 1), 254u, (uint32_t)slot[b]);
+    pts_draw(Zh + (size_t)b * K * V, K, V, vp.top_ks, 1.0f / vp.temperature, vp.pts_prune, u, sm, cand);
+  } else {
+    for (int k = 1; k <= K; ++k) {
+      const int t = row_sample(Zh + (size_t)(b * K + k - 1) * V, V, vp, (uint32_t)(n + a + 1 + k),
+                               (uint32_t)k, (uint32_t)slot[b], sm, &flag);
+      if (threadIdx.x == 0) cand[k] = t;
+    }
   }
   __syncthreads();
   if (threadIdx.x == 0) {

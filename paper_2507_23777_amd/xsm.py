@@ -34,7 +34,8 @@ class xsm_config(C.Structure):
 
 class xsm_verify_params(C.Structure):
     _fields_ = [("mode", C.c_int32), ("top_ka", C.c_int32), ("delta", C.c_float),
-                ("temperature", C.c_float), ("sample", C.c_int32), ("seed", C.c_uint64)]
+                ("temperature", C.c_float), ("sample", C.c_int32), ("seed", C.c_uint64),
+                ("top_ks", C.c_int32), ("pts_prune", C.c_float)]
 
 
 class xsm_batch(C.Structure):

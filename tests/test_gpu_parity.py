@@ -112,6 +112,30 @@ def test_mid_bf16_topk_categorical(X):
     _report(tal, "mid threshold")
 
 
+def test_probability_tree_sampling(X):
+    """Top-K_s probability-tree sampling of the head tokens (appendix): K_s = 2 and 3 with the
+    paper's cut-off, K_s = 1 (always the most probable path), and a cut-off that removes paths."""
+    cfg = _mid_cfg(seed=51)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, prefix_lens=[37, 20, 9])
+    K = cfg["n_draft"]
+    seen = set()
+    # random-init heads are nearly uniform over the vocabulary (every path weight ~1e-12), so the
+    # temperature is what makes the tree non-trivial: sharp levels, partial cuts, no cuts, all cut
+    for ks, prune, T in ((2, 1e-5, 0.02), (3, 1e-5, 0.05), (4, 1e-5, 0.03), (3, 0.0, 0.8), (1, 1e-5, 0.8),
+                         (3, 1e-5, 0.8), (3, 1e-2, 0.03)):
+        vp = VerifyParams(mode=1, top_ka=8, temperature=T, sample=2, seed=100 + ks, top_ks=ks, pts_prune=prune)
+        tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 4, si.first_block(cfg, 3))
+        _report(tal, f"PTS K_s={ks} prune={prune} T={T} paths {sorted(set(tal.pts_paths))}")
+        for n in tal.pts_paths:
+            seen.add("none" if n == 0 else "all" if n == ks ** K else "some")
+    assert seen == {"none", "some", "all"}, seen
+    buf = eng.buffers(3, spec=True)
+    buf.kv_len.fill_(40); buf.block.fill_(1)
+    bad = X.xsm.xsm_verify_params(1, 8, 0.5, 0.8, 2, 1, 5, 1e-5)
+    with pytest.raises(X.xsm.XsmError, match="top_ks"):
+        eng.xsm_spec_step(buf, bad, 40)
+
+
 def test_plain_step_matches_oracle(X):
     cfg = _mid_cfg(seed=23, vocab=1000)        # vocabulary not a multiple of 16: general-shape kernels
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)

@@ -9,12 +9,13 @@ margin for it is within 1e-2 (logit gap) or 1e-3 (inverse-CDF gap)."""
 from __future__ import annotations
 
 import copy
+import dataclasses
 from dataclasses import dataclass, field
 
 import numpy as np
 
 import synth_inputs as si
-from oracle import Oracle, VerifyParams, sample
+from oracle import Oracle, VerifyParams, pts_sample, sample
 
 TIE = 1e-2
 # Categorical draws are decided on the same inputs on both sides: the oracle's float64
@@ -65,6 +66,24 @@ def check_draw(tal, where, what, dg: dict, tok_gpu: int, tok_oracle: int, z_gpu,
         tal.mismatches.append(f"{where}: {what} gpu {tok_gpu} oracle-on-gpu-logits {ref} (u={dg2['u']:.6f})")
 
 
+def check_pts(tal, where, toks_gpu, zh_gpu, vp, pos, seq_id):
+    """One probability-tree draw of the K head tokens: the oracle's sampler re-run on the GPU's
+    head logits; flagged when the uniform falls within CDF_TIE of a path boundary or a path's
+    weight within 1e-4 (relative) of the cut-off."""
+    tal.decisions += 1
+    ref, dg = pts_sample(np.asarray(zh_gpu, np.float64), vp, pos, seq_id)
+    lo = dataclasses.replace(vp, pts_prune=vp.pts_prune * (1 - 1e-4))
+    hi = dataclasses.replace(vp, pts_prune=vp.pts_prune * (1 + 1e-4))
+    stable = pts_sample(np.asarray(zh_gpu, np.float64), lo, pos, seq_id)[1]["n_paths"] == \
+        pts_sample(np.asarray(zh_gpu, np.float64), hi, pos, seq_id)[1]["n_paths"]
+    tal.pts_paths.append(dg["n_paths"])
+    if dg["gap"] <= CDF_TIE or not stable:
+        tal.flagged += 1
+    elif [int(t) for t in toks_gpu] != ref:
+        tal.mismatches.append(f"{where}: tree draw gpu {[int(t) for t in toks_gpu]} oracle-on-gpu-logits {ref} "
+                              f"(u={dg['u']:.6f}, paths {dg['n_paths']})")
+
+
 @dataclass
 class Tally:
     rows: int = 0
@@ -73,10 +92,12 @@ class Tally:
     mismatches: list = field(default_factory=list)
     max_rel: float = 0.0
     accept_hist: dict = field(default_factory=dict)
+    pts_paths: list = field(default_factory=list)      # surviving paths of every probability-tree draw
 
 
 def to_vp_gpu(xsm, vp: VerifyParams):
-    return xsm.xsm_verify_params(vp.mode, vp.top_ka, vp.delta, vp.temperature, vp.sample, vp.seed)
+    return xsm.xsm_verify_params(vp.mode, vp.top_ka, vp.delta, vp.temperature, vp.sample, vp.seed,
+                                 vp.top_ks, vp.pts_prune)
 
 
 def setup_pair(cfg, engine_cls, n_seq, prefix_lens=None, perturb=True, max_ctx=None, kv_dtype=np.float64):
@@ -176,8 +197,11 @@ def lockstep(cfg, orc, states, eng, xsm, vp: VerifyParams, n_steps: int, first_b
                 tal.max_rel = max(tal.max_rel, e)
                 tal.rows += 1
                 assert e <= tol, f"{where}: head {k} logits rel err {e:.3e} > {tol}"
-                check_draw(tal, where, f"head {k}", r["diag"][k], int(g_blk[b, k]), r["next_block"][k],
-                           g_heads[b, k - 1], vp, n0 + a + 1 + k, k, st.seq_id)
+                if vp.sample != 2:
+                    check_draw(tal, where, f"head {k}", r["diag"][k], int(g_blk[b, k]), r["next_block"][k],
+                               g_heads[b, k - 1], vp, n0 + a + 1 + k, k, st.seq_id)
+            if vp.sample == 2 and K > 0:
+                check_pts(tal, where, g_blk[b, 1:], g_heads[b], vp, n0 + a + 1, st.seq_id)
             blocks[b] = r["next_block"]
     return tal
 
