@@ -282,31 +282,52 @@ __device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, floa
       __syncthreads();
     }
   }
+  // leaves in lexicographic order, a contiguous run per thread; running sums in double, thread
+  // partials combined in thread order
+  __shared__ double pt_part[256];
+  __shared__ double pt_total;
+  __shared__ int pt_last;
+  int n_paths = 1;
+  for (int k = 0; k < K; ++k) n_paths *= ks;
+  auto weight = [&](int leaf) {                    // digits of `leaf` base ks, first head most significant
+    double w = 1.0;
+    int rem = leaf, div = n_paths;
+    for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
+    return (w >= (double)prune && w > 0.0) ? w : 0.0;   // cut paths carry no weight
+  };
+  const int chunk = (n_paths + 255) / 256;
+  const int l0 = min(n_paths, (int)threadIdx.x * chunk), l1 = min(n_paths, l0 + chunk);
+  double loc = 0.0;
+  int lastpos = -1;
+  for (int leaf = l0; leaf < l1; ++leaf) {
+    const double w = weight(leaf);
+    loc += w;
+    if (w > 0.0) lastpos = leaf;
+  }
+  pt_part[threadIdx.x] = loc;
+  lastpos = block_max_i(lastpos, sm.redi);
+  __syncthreads();
   if (threadIdx.x == 0) {
-    int n_paths = 1;
-    for (int k = 0; k < K; ++k) n_paths *= ks;
-    auto weight = [&](int leaf) {                  // digits of `leaf` base ks, first head most significant
-      double w = 1.0;
-      int rem = leaf, div = n_paths;
-      for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
-      return w;
-    };
-    double S = 0.0;
-    int last = -1;
-    for (int leaf = 0; leaf < n_paths; ++leaf) {
+    double run = 0.0;
+    for (int t = 0; t < 256; ++t) { const double p = pt_part[t]; pt_part[t] = run; run += p; }
+    pt_total = run;
+    pt_last = lastpos;
+  }
+  __syncthreads();
+  int hit = 0x7FFFFFFF;
+  if (pt_last >= 0) {
+    const double target = (double)u * pt_total;
+    double run = pt_part[threadIdx.x];
+    for (int leaf = l0; leaf < l1; ++leaf) {
       const double w = weight(leaf);
-      if (w >= (double)prune && w > 0.0) { S += w; last = leaf; }
+      run += w;
+      if (w > 0.0 && run > target) { hit = leaf; break; }
     }
-    int pick = 0;                                   // no survivor: the most probable token of every head
-    if (last >= 0) {
-      const double target = (double)u * S;
-      double run = 0.0;
-      pick = last;
-      for (int leaf = 0; leaf <= last; ++leaf) {
-        const double w = weight(leaf);
-        if (w >= (double)prune && w > 0.0) { run += w; if (run > target) { pick = leaf; break; } }
-      }
-    }
+  }
+  hit = block_min_i(hit, sm.redi);
+  if (threadIdx.x == 0) {
+    // no survivor: the most probable token of every head; rounding left nothing above the target: the last survivor
+    const int pick = pt_last < 0 ? 0 : (hit == 0x7FFFFFFF ? pt_last : hit);
     int rem = pick, div = n_paths;
     for (int k = 0; k < K; ++k) { div /= ks; cand[k + 1] = top_i[k][rem / div]; rem %= div; }
   }
