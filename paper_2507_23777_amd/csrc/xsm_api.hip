@@ -469,7 +469,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
       if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     }
   }
-  launch_emit(Zh, *vp, eff, slot, acc, y0, wfl, bt->block, bt->kv_len, bt->out_tokens,
+  launch_emit(Zh, *vp, eff, slot, acc, y0, wfl, (int32_t*)(ws + ctx->ws.toks), bt->block, bt->kv_len, bt->out_tokens,
               bt->n_accepted, bt->flags, n_seq, R, K, V, s);
   hipError_t e2 = hipGetLastError();
   if (e2 != hipSuccess) return fail(ctx, XSM_EHIP, std::string("launch: ") + hipGetErrorString(e2));

@@ -219,8 +219,8 @@ void launch_head_act(int dtype, const float* G, const float* Hh, const void* con
                      float* Rk, int n_seq, int K, int d, hipStream_t s);
 void launch_emit(const float* Zh, const xsm_verify_params& vp, const int32_t* eff_len,
                  const int32_t* slot, const int32_t* acc, const int32_t* y0,
-                 const uint32_t* wflags, int32_t* block, int32_t* kv_len, int32_t* out_tokens,
-                 int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
+                 uint32_t* wflags, int32_t* drawn /*[n_seq][16] scratch*/, int32_t* block, int32_t* kv_len,
+                 int32_t* out_tokens, int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
                  hipStream_t s);
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
 // cache <-> float staging [H][n_pos][hd]; element (h, p, i) of the slot lives at

@@ -334,8 +334,26 @@ __device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, floa
   __syncthreads();
 }
 
-// draws from the K head rows, then emit: accepted tokens, count, next block, new length
-__global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params vp,
+// independent draws from the K head rows, one workgroup per (head, sequence): cand[b][k], and
+// near-tie flags OR-ed into dflags[b]
+__global__ __launch_bounds__(256) void k_draw_heads(const float* Zh, xsm_verify_params vp, const int32_t* eff_len,
+                                                    const int32_t* slot, const int32_t* acc, int32_t* cand,
+                                                    uint32_t* dflags, int K, int V) {
+  __shared__ RowScratch sm;
+  const int k = blockIdx.x + 1, b = blockIdx.y;
+  const int n = eff_len[b];
+  if (n < 0) return;
+  uint32_t flag = 0;
+  const int t = row_sample(Zh + (size_t)(b * K + k - 1) * V, V, vp, (uint32_t)(n + acc[b] + 1 + k), (uint32_t)k,
+                           (uint32_t)slot[b], sm, &flag);
+  if (threadIdx.x == 0) {
+    cand[b * 16 + k] = t;
+    if (flag) atomicOr(&dflags[b], flag);
+  }
+}
+
+// probability-tree draw if asked for, then emit: accepted tokens, count, next block, new length
+__global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params vp, const int32_t* drawn,
                                               const int32_t* eff_len, const int32_t* slot,
                                               const int32_t* acc, const int32_t* y0,
                                               const uint32_t* wflags, int32_t* block,
@@ -353,16 +371,12 @@ __global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params
   }
   const int a = acc[b];
   if (threadIdx.x < R) old_block[threadIdx.x] = block[b * R + threadIdx.x];
-  uint32_t flag = 0;
+  const uint32_t flag = 0;
   if (vp.sample == 2 && K > 0) {
     const float u = philox_uniform(vp.seed, (uint32_t)(n + a + 1), 254u, (uint32_t)slot[b]);
     pts_draw(Zh + (size_t)b * K * V, K, V, vp.top_ks, 1.0f / vp.temperature, vp.pts_prune, u, sm, cand);
-  } else {
-    for (int k = 1; k <= K; ++k) {
-      const int t = row_sample(Zh + (size_t)(b * K + k - 1) * V, V, vp, (uint32_t)(n + a + 1 + k),
-                               (uint32_t)k, (uint32_t)slot[b], sm, &flag);
-      if (threadIdx.x == 0) cand[k] = t;
-    }
+  } else if (threadIdx.x >= 1 && threadIdx.x <= K) {
+    cand[threadIdx.x] = drawn[b * 16 + threadIdx.x];          // k_draw_heads ran before this kernel
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -378,11 +392,13 @@ __global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params
 }
 void launch_emit(const float* Zh, const xsm_verify_params& vp, const int32_t* eff_len,
                  const int32_t* slot, const int32_t* acc, const int32_t* y0,
-                 const uint32_t* wflags, int32_t* block, int32_t* kv_len, int32_t* out_tokens,
+                 uint32_t* wflags, int32_t* drawn, int32_t* block, int32_t* kv_len, int32_t* out_tokens,
                  int32_t* n_accepted, uint32_t* flags, int n_seq, int R, int K, int V,
                  hipStream_t s) {
   TraceScope trace_("emit", s);
-  hipLaunchKernelGGL(k_emit, dim3(n_seq), dim3(256), 0, s, Zh, vp, eff_len, slot, acc, y0, wflags,
+  if (K > 0 && vp.sample != 2)
+    hipLaunchKernelGGL(k_draw_heads, dim3(K, n_seq), dim3(256), 0, s, Zh, vp, eff_len, slot, acc, drawn, wflags, K, V);
+  hipLaunchKernelGGL(k_emit, dim3(n_seq), dim3(256), 0, s, Zh, vp, drawn, eff_len, slot, acc, y0, wflags,
                      block, kv_len, out_tokens, n_accepted, flags, R, K, V);
 }
 
