@@ -171,9 +171,11 @@ XSM_API int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify
 XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
                    xsm_stream stream);
 
-/* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total,
- * greedy verification with argmax draws, and the model shape is supported, run it as one
- * persistent kernel instead of one kernel per stage; 0 forces the per-stage kernels. */
+/* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total and
+ * the model shape is supported, run backbone, heads and unembedding as one persistent kernel
+ * instead of one kernel per stage (greedy verification with argmax draws also finishes inside it;
+ * the other criteria and sampling rules follow in the verify / emit kernels); 0 forces the
+ * per-stage kernels. */
 enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2 };
 XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
 

@@ -199,6 +199,8 @@ struct SmallArgs {
   float* logits_dbg; float* head_logits_dbg; float* head_all_dbg; int32_t* acc_out;
   uint64_t* tlog;                        // optional stage timeline [256][L*16 + 8] clock stamps
   int n_seq, R, S, V, max_batch, max_ctx, bound, cap;
+  int defer_verify;                      // 1: stop after the unembedding (logits of all rows written); the
+                                         // caller runs verification and the draws as separate kernels
   float eps, scale_log2;
 };
 constexpr int kSmallMaxRows = 144;     // backbone rows + head rows (M + M K) of one single-launch step

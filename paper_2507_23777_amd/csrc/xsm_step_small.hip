@@ -869,8 +869,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
   XSM_STAMP(a.L * 16 + 3);
 
-  // ---- FINAL: workgroup b finishes sequence b ----
-  if (w < a.n_seq) {
+  // ---- FINAL: workgroup b finishes sequence b (greedy verification with argmax draws; the other
+  // criteria and sampling rules read the full logits rows in kernels of their own) ----
+  if (w < a.n_seq && !a.defer_verify) {
     const int b = w;
     const int n = sm.len[b];
     // global top-2 of rows: backbone rows b*R + j (j < R) and head rows ((b*R + j)*K + k)

@@ -324,6 +324,22 @@ def test_single_launch_eight_draft_heads(X):
     eng.xsm_check_device()
 
 
+@pytest.mark.parametrize("single_launch", [1, 0])
+def test_single_launch_with_sampling_rules(X, single_launch):
+    """Top-K_a acceptance with categorical draws, the probability threshold, and probability-tree
+    draws at a batch small enough for the persistent kernel: it then stops after the unembedding
+    and the verify / emit kernels take over."""
+    cfg = _c1_small(n_layers=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[70, 21], perturb=True)
+    eng.xsm_set_option(X.xsm.XSM_OPT_SINGLE_LAUNCH, single_launch)
+    for name, vp in (("top-8 categorical", VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=7)),
+                     ("threshold", VerifyParams(mode=2, delta=0.0004, temperature=1.0, sample=1, seed=8)),
+                     ("tree K_s=3", VerifyParams(mode=1, top_ka=8, temperature=0.04, sample=2, seed=9, top_ks=3))):
+        tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 4, si.first_block(cfg, 2))
+        _report(tal, f"c1-shape {name} single_launch={single_launch}")
+    eng.xsm_check_device()
+
+
 def test_single_launch_long_context_split_keys(X):
     cfg = _c1_small(n_layers=2, max_ctx=4608, prefix=0)
     n_pos = 4352
