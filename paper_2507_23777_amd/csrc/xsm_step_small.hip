@@ -241,13 +241,16 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
       if ((lane & 7) == 0) sm.rowsum[wave][(b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
       __syncthreads();
     }
+    // every thread forms the scales itself, all rows at once (hardware reciprocal square root, 1 ulp)
+    float scl[RB];
+#pragma unroll
+    for (int m = 0; m < RB; ++m)
+      scl[m] = NORM ? __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / (float)D) + eps)
+                    : 1.0f;
 #pragma unroll
     for (int m = 0; m < RB; ++m) {
       if (m0 + m < nrows) {
-        // every thread forms the scale itself (hardware reciprocal square root, 1 ulp): cheaper
-        // than a round through LDS and a barrier
-        const float sc = NORM ? __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / (float)D) + eps)
-                              : 1.0f;
+        const float sc = scl[m];
 #pragma unroll
         for (int j = 0; j < PP; ++j) {
           float x0 = __uint_as_float(pay[(m * PP + j) * 2]), x1 = __uint_as_float(pay[(m * PP + j) * 2 + 1]);
