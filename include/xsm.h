@@ -175,8 +175,9 @@ XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verif
  * the model shape is supported, run backbone, heads and unembedding as one persistent kernel
  * instead of one kernel per stage (greedy verification with argmax draws also finishes inside it;
  * the other criteria and sampling rules follow in the verify / emit kernels); 0 forces the
- * per-stage kernels. */
-enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2 };
+ * per-stage kernels.  XSM_OPT_ATTN_SPLITS (tuning aid, default 0 = automatic): key-range slices per
+ * (sequence, head) of the per-stage attention kernel. */
+enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2, XSM_OPT_ATTN_SPLITS = 3 };
 XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
 
 /* Tuning aid.  With XSM_OPT_TIMELINE = 1 every workgroup of the single-launch step stamps the

@@ -159,15 +159,28 @@ char* head_cache(const xsm_ctx* c, int k, int which) {
   return c->d_kv + (c->kv_self_elems + c->kv_cross_elems + ((size_t)which * g.n_draft + k) * per) * c->esz;
 }
 
-// split count of the key range per (sequence, head): enough workgroups to fill the chip, at
-// least ~4 chunks of 64 keys each, bounded by the partial slots in the workspace
+// Key-range slices per (sequence, head, query tile).  A workgroup streams chunks/S 64-key chunks
+// plus a fixed start-up and merge cost (about 8 chunks' worth), and the BH*S workgroups run in
+// ceil(BH*S / 256) rounds over the compute units: take the S that minimises rounds x per-workgroup
+// time (whole rounds matter: 384 workgroups on 256 compute units take as long as 512), at least
+// 4 chunks per workgroup, bounded by the partial slots in the workspace.
 int attn_splits(const xsm_ctx* c, int n_units, int len_bound) {
   const int BH = n_units * c->cfg.n_heads;           // n_units: sequences x query tiles
   const int chunks = (len_bound + 63) / 64;
-  int S = 512 / BH;
-  if (S > chunks / 4) S = chunks / 4;
-  if ((size_t)S * BH > c->part_entries) S = (int)(c->part_entries / BH);
-  return S < 1 ? 1 : S;
+  if (c->force_splits > 0) {
+    int S = c->force_splits;
+    if (S > chunks / 4) S = chunks / 4;
+    if ((size_t)S * BH > c->part_entries) S = (int)(c->part_entries / BH);
+    return S < 1 ? 1 : S;
+  }
+  int best = 1;
+  double best_cost = 0;
+  for (int S = 1; S <= 16; ++S) {
+    if (S > 1 && (S > chunks / 4 || (size_t)S * BH > c->part_entries)) break;
+    const double cost = (double)((BH * S + 255) / 256) * ((double)chunks / S + 8.0);
+    if (S == 1 || cost < best_cost * 0.999) { best = S; best_cost = cost; }
+  }
+  return best;
 }
 
 // MFMA path: all decoder blocks over M = n_seq*R rows held in ws.X (fp32 residual stream).
@@ -716,6 +729,7 @@ int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value) {
   if (!ctx) return XSM_EINVAL;
   if (option == XSM_OPT_SINGLE_LAUNCH) { ctx->use_small = value != 0; return XSM_OK; }
   if (option == XSM_OPT_TIMELINE) { ctx->timeline = value != 0; return XSM_OK; }
+  if (option == XSM_OPT_ATTN_SPLITS) { ctx->force_splits = value > 0 ? value : 0; return XSM_OK; }
   return fail(ctx, XSM_EINVAL, "unknown option");
 }
 

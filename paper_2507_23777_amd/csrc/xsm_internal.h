@@ -77,6 +77,7 @@ struct xsm_ctx {
   bool small_ok = false;   // single-launch step available for this model shape
   bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
   bool timeline = false;   // xsm_set_option(XSM_OPT_TIMELINE)
+  int force_splits = 0;    // xsm_set_option(XSM_OPT_ATTN_SPLITS): key-range slices per (sequence, head), 0 = automatic
   size_t layer_tab_off = 0;              // byte offset of the LayerTab array in the weights buffer
   std::vector<xsm::LayerTab> layer_tab;  // host copy (source of the upload)
   xsm::TiledOff toff;
