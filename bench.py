@@ -69,6 +69,52 @@ def cpu_baseline(cfg: dict, w: dict, prefix, first, budget_s: float = 15.0) -> d
                       f"(context {cfg['prefix']}..{st.n}), float64 numpy"}
 
 
+def fixed_point(args, torch, pkg, xsm, si) -> int:
+    """One workload of the sweep at a fixed context (not the default benchmark line): speculative
+    steps of config NAME at batch B with K heads, every sequence's cache length reset to CTX before
+    each step (rollback is length-only, so that is free); the cache holds zeros beyond what the
+    steps write, condition tokens are prefilled.  Prints one JSON line."""
+    name, B, K, ctx, *rest = args.fixed_point.split(",")
+    B, K, ctx = int(B), int(K), int(ctx)
+    cfg = si.get_config(name, batch=B, n_draft=K)
+    R = K + 1
+    eng = pkg.Engine(cfg, max_batch=B, max_ctx=int(rest[0]) if rest else ((ctx + R + 64) // 64) * 64)
+    eng.d_kv.zero_()
+    eng.xsm_load_weights(si.pack_canonical(cfg, si.make_weights(cfg)))
+    if cfg["n_cond"]:
+        eng.xsm_prefill(list(range(B)), None, eng.to_device(si.make_cond(cfg, B)))
+    buf = eng.buffers(B, spec=True)
+    buf.block.copy_(torch.tensor(si.first_block(cfg, B)))
+    # config 2 is defined with top-8 acceptance and categorical draws at T = 0.8, the others greedy
+    vp = pkg.xsm_verify_params(1, 8, 0.5, 0.8, 1, 1234) if name == "c2" else pkg.xsm_verify_params(0, 1, 0.5, 1.0, 0, 0)
+
+    def run(n):
+        for _ in range(n):
+            buf.kv_len.fill_(ctx)
+            eng.xsm_spec_step(buf, vp, ctx)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    xsm.xsm_debug_trace_enable(True)             # a second pass with per-launch event pairs for the breakdown
+    xsm.xsm_debug_trace_report()
+    run(args.steps)
+    torch.cuda.synchronize()
+    trace = xsm.xsm_debug_trace_report()
+    xsm.xsm_debug_trace_enable(False)
+    eng.xsm_check_device()
+    by = algorithmic_bytes(cfg, B, B * ctx)
+    print(json.dumps({"workload": f"{name} batch {B} K={K} context {ctx}", "steps": args.steps, "ms_per_step": round(ms, 4),
+                      "note": "ms_per_step from an untraced pass; the kernel breakdown from a second pass with per-launch event pairs",
+                      "verified_tok_per_s": round(B * R / ms * 1e3, 1), "hbm_frac": round(by / (ms * 1e6) / HBM_PEAK_GBS, 4),
+                      "kernels": {k: {"launches_per_step": v[0] / args.steps, "us_per_launch": round(1e3 * v[1] / v[0], 2)}
+                                  for k, v in sorted(trace.items(), key=lambda kv: -kv[1][1])}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +125,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the untimed extras (latency spread, fixed-context points): profiling runs then see "
                          "only the warm-up and timed steps")
+    ap.add_argument("--fixed-point", default=None, metavar="NAME,B,K,CTX[,MAX_CTX]",
+                    help="time another workload of the sweep at a fixed context instead of the benchmark line, "
+                         "e.g. c2,16,6,2048 or c4,128,8,10000")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy five times and exit (scale for the PMC byte counters)")
     args = ap.parse_args()
@@ -106,6 +155,8 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
         return 0
+    if args.fixed_point:
+        return fixed_point(args, torch, pkg, xsm, si)
     cfg = si.get_config(args.config)
     B, K, P = cfg["batch"], cfg["n_draft"], cfg["prefix"]
     R = K + 1

@@ -536,8 +536,22 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
                 g.n_layers <= 48;
   build_weight_offsets(c);
   build_work_offsets(c);
-  c->cap_self = (g.max_ctx + 63) / 64 * 64;
-  c->cap_cross = (g.n_cond + 63) / 64 * 64;
+  // cache capacities in positions: whole 64-key chunks.  Each (slot, head) owns one contiguous
+  // stretch of a cache plane and the attention kernel streams hundreds of those stretches side by
+  // side; measured on gfx950, stretches whose length lies within 8 KB of a multiple of 1 MiB
+  // (127, 129 or 257 chunks at head width 64) cost 11 % of a whole step against any length that
+  // is 24 KB or more away, so the capacity grows by a few chunks until it is.
+  auto spread_chunks = [&](int n) {
+    int ch = (n + 63) / 64;
+    const long chunk_bytes = 64L * g.head_dim * (long)c->esz, mib = 1L << 20, clear = 24L << 10;
+    for (;; ++ch) {
+      const long r = (ch * chunk_bytes) & (mib - 1);
+      if (ch * chunk_bytes < mib - clear || (r >= clear && mib - r >= clear)) break;
+    }
+    return ch * 64;
+  };
+  c->cap_self = spread_chunks(g.max_ctx);
+  c->cap_cross = g.n_cond > 0 ? spread_chunks(g.n_cond) : 0;
   c->w_canon_bytes = align_up(c->woff.total * c->esz);
   c->rope_off = c->w_canon_bytes;
   c->weights_bytes = c->rope_off + align_up((size_t)g.max_ctx * (g.head_dim / 2) * sizeof(float2));
