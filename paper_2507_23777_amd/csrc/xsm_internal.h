@@ -11,7 +11,7 @@
 namespace xsm {
 
 constexpr int kPrefillChunk = 16;   // prefix rows per sequence per backbone pass (general kernels)
-constexpr int kFastPassRows = 256;  // rows of one backbone pass the MFMA path's workspace always holds (prefill chunks)
+constexpr int kFastPassRows = 2048; // rows of one backbone pass the MFMA path's workspace always holds (prefill chunks)
 constexpr int kMaxRows = 16;        // rows per sequence per pass (K+1 <= 16)
 
 // Element offsets of the canonical weight tensors (same order as the weight file).

@@ -190,9 +190,10 @@ def test_cross_attention_decoding_heads(X):
 
 
 def test_prefill_in_large_chunks(X):
-    """Prefill on the MFMA path runs up to 256 prefix rows per pass (several 16-row query tiles per
-    sequence, causal inside the chunk): one sequence with a 300-token prefix (chunks 256 + 44) and
-    a ragged batch; the cache must match the oracle's and the steps after it too."""
+    """Prefill on the MFMA path runs up to 2048 rows per pass (many 16-row query tiles per sequence,
+    causal inside the chunk, the row-blocked GEMMs with a ragged last block): one sequence with a
+    300-token prefix in one pass, a ragged batch, and three sequences of 900 tokens, which take two
+    passes (672 + 228 rows each); the cache must match the oracle's and the steps after it too."""
     cfg = _mid_cfg(prefix=300, seed=41, n_layers=2, max_ctx=512)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1)
     for l in range(cfg["n_layers"]):
@@ -207,6 +208,16 @@ def test_prefill_in_large_chunks(X):
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, prefix_lens=[150, 97, 16])
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 3))
     _report(tal, "prefix 150/97/16 B3")
+    cfg = _mid_cfg(prefix=900, seed=43, n_layers=2, max_ctx=1024)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3)
+    for b in (0, 2):
+        for which, ref in ((0, states[b].k[1]), (1, states[b].v[1])):
+            got = eng.xsm_debug_kv_export(1, which, b, 0, 900)
+            want = np.transpose(np.asarray(ref[:900], np.float64), (1, 0, 2))
+            err = np.abs(got - want).max() / np.abs(want).max()
+            assert err < 1e-2, (b, which, err)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 3))
+    _report(tal, "prefix 900 B3 (two passes)")
 
 
 def test_cache_contents_and_rollback(X):
