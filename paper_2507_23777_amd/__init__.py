@@ -8,6 +8,8 @@ raises if the library has not been built (``python -m paper_2507_23777_amd.build
 from .xsm import (XSM_BF16, XSM_F32, Engine, StepBuffers, XsmError, lib, xsm_batch, xsm_config,
                   xsm_verify_params)
 from .metrics import step_compression_ratio, speedup
+from .batcher import Batcher, Request
 
 __all__ = ["Engine", "StepBuffers", "XsmError", "lib", "xsm_batch", "xsm_config",
-           "xsm_verify_params", "XSM_F32", "XSM_BF16", "step_compression_ratio", "speedup"]
+           "xsm_verify_params", "XSM_F32", "XSM_BF16", "step_compression_ratio", "speedup",
+           "Batcher", "Request"]

@@ -220,6 +220,79 @@ def test_prefill_in_large_chunks(X):
     _report(tal, "prefix 900 B3 (two passes)")
 
 
+def test_rows_name_their_cache_slot(X):
+    """A batch row carries the index of its cache slot: rows in an order that is not the slot
+    order, with one slot left out, against the oracle states of those sequences; on the per-stage
+    kernels and on the single-launch kernel.  The oracle's Philox counter carries the sequence id,
+    the library's the slot, so the states keep seq_id = slot."""
+    vp = VerifyParams(mode=1, top_ka=4, temperature=0.9, sample=1, seed=99)
+    cfg = _mid_cfg(seed=51, n_layers=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 4, prefix_lens=[37, 20, 9, 30])
+    order = [2, 0, 3]
+    first = si.first_block(cfg, 4)
+    tal = X.H.lockstep(cfg, orc, [states[b] for b in order], eng, X.xsm, vp, 5, [first[b] for b in order],
+                       slots=order)
+    _report(tal, "slots 2,0,3 of 4 (per-stage)")
+    cfg = _c1_small(n_layers=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, prefix_lens=[70, 33, 5])
+    order = [2, 0]
+    first = si.first_block(cfg, 3)
+    tal = X.H.lockstep(cfg, orc, [states[b] for b in order], eng, X.xsm, GREEDY, 5, [first[b] for b in order],
+                       slots=order)
+    _report(tal, "slots 2,0 of 3 (single launch)")
+    eng.xsm_check_device()
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_batcher_admission_and_compaction(X, dtype):
+    """Seven requests with different prefix lengths and token budgets through three cache slots:
+    sequences are admitted as slots free up and the batch rows are compacted when one finishes.
+    Greedy speculative decoding must give every request the tokens of plain greedy decoding of
+    that request alone (Sec. 4.2; the oracle's plain loop); at a decision the oracle marks as a
+    near-tie it continues from the GPU's token."""
+    from paper_2507_23777_amd.batcher import Batcher, Request
+    if dtype == "fp32":
+        cfg = si.tiny_config(n_layers=2, d_model=64, n_heads=2, head_dim=32, d_ffn=128, vocab=64, n_draft=3,
+                             dtype="fp32", max_ctx=160, seed=12)
+    else:
+        cfg = _mid_cfg(seed=52, n_layers=2, max_ctx=256)
+    K = cfg["n_draft"]
+    w = si.make_weights(cfg, perturb=True)
+    orc = Oracle(cfg, w)
+    eng = X.pkg.Engine(cfg, max_batch=3, max_ctx=cfg["max_ctx"])
+    eng.xsm_load_weights(si.pack_canonical(cfg, w))
+    P = [37, 20, 9, 37, 50, 0, 20]
+    budget = [30, 12, 45, 7, 25, 18, 33]
+    prefixes = si.make_prefix(cfg, len(P), P=max(P))
+    firsts = si.first_block(cfg, len(P))
+    bt = Batcher(eng, X.H.to_vp_gpu(X.xsm, GREEDY), spec=True)
+    for i in range(len(P)):
+        bt.submit(Request(first_block=list(map(int, firsts[i])), max_new_tokens=budget[i],
+                          prefix=None if P[i] == 0 else prefixes[i, :P[i]]))
+    got = bt.run()
+    assert sorted(got) == list(range(len(P)))
+    assert sorted(bt.free) == [0, 1, 2] and not bt.live
+    assert all(1 <= a <= K + 1 for a in bt.accepted_per_step)
+    compared = total = 0
+    tie = 1e-4 if dtype == "fp32" else X.H.TIE         # fp32 logits agree to 1e-5 of the row's largest
+    for i in range(len(P)):
+        assert len(got[i]) == budget[i]
+        st = orc.new_state(cap=cfg["max_ctx"], seq_id=0)
+        orc.prefill(st, None if P[i] == 0 else prefixes[i, :P[i]], None)
+        tok = int(firsts[i][0])
+        for j in range(budget[i]):
+            r = orc.plain_step(st, tok, GREEDY)
+            if r["diag"][0]["margin"] <= tie:          # flagged, not counted: the oracle follows the GPU's choice
+                tok = got[i][j]
+                continue
+            tok = int(r["out_tokens"][0])
+            assert got[i][j] == tok, f"request {i} token {j}: gpu {got[i][j]} oracle {tok}"
+            compared += 1
+        total += budget[i]
+    print(f"[batcher {dtype}] {bt.steps} steps for {total} tokens, {compared} compared token for token", flush=True)
+    assert compared >= total // 2
+
+
 def test_cache_contents_and_rollback(X):
     cfg = _mid_cfg(seed=26, n_layers=2)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)

@@ -128,15 +128,18 @@ def setup_pair(cfg, engine_cls, n_seq, prefix_lens=None, perturb=True, max_ctx=N
 
 
 def lockstep(cfg, orc, states, eng, xsm, vp: VerifyParams, n_steps: int, first_blocks, plain=False,
-             forced=None, tally: Tally | None = None) -> Tally:
+             forced=None, tally: Tally | None = None, slots=None) -> Tally:
     """Run n_steps with the oracle driving.  forced(step, b, state, block) may replace the block
-    (e.g. with the true continuation) before both sides run it."""
+    (e.g. with the true continuation) before both sides run it.  slots[i] is the cache slot of
+    batch row i (default: row i uses slot i)."""
     torch = eng.torch
     tal = tally or Tally()
     n_seq = len(states)
     K = 0 if plain else cfg["n_draft"]
     R = K + 1
     buf = eng.buffers(n_seq, spec=not plain, debug=True)
+    if slots is not None:
+        buf.slot.copy_(torch.tensor(list(slots), dtype=torch.int32))
     blocks = [list(map(int, bl[:R])) for bl in first_blocks]
     vpg = to_vp_gpu(xsm, vp)
     tol = logit_tol(cfg)
