@@ -64,7 +64,8 @@ void build_work_offsets(xsm_ctx* c) {
   WorkOff& w = c->ws;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p = align_up(p + bytes); return r; };
-  w.X = take(Mmax * d * 4); w.Xn = take(Mmax * d * 4); w.QKV = take(Mmax * 3 * d * 4);
+  w.X = take(Mmax * d * 4); w.QKV = take(Mmax * 3 * d * 4);
+  w.Xn = take(((Mmax + 15) & ~(size_t)15) * d * 4);       // (as bf16 hi / lo planes it covers whole 16-row tiles)
   w.Qr = take(Mmax * d * 4); w.AO = take(Mmax * d * 4); w.U = take(Mmax * F * 4);
   w.Z0 = take(Mb * V * 4);
   w.G = take((size_t)g.max_batch * d * 4);

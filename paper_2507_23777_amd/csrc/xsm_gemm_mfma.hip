@@ -256,16 +256,27 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
 // memory (HBM once, then the XCD's L2: all row blocks of one weight tile pair are placed on the
 // same XCD).  RMSNorm is done once per row by k_norm_rows instead of once per workgroup.
 // ---------------------------------------------------------------------------
-// normalised row piece -> fp32 row of out, or (split) bf16 hi / lo planes [M][K] laid over the same buffer
+// Normalised rows as MFMA operands: bf16 hi and lo planes in fragment order.  A tile of 16 rows x
+// 32 contraction indices is one contiguous KB in which lane (row & 15) + 16 * ((k >> 3) & 3) holds 8
+// consecutive k, tiles ordered [row tile][k tile]: a wavefront fetches a whole "B" fragment as one
+// contiguous KB.  (With row-major planes a fragment is 16 rows x 64 B, and the GEMMs that read
+// them straight from L2 took 30 % longer.)  A plane covers whole 16-row tiles; rows past M are
+// never written and feed only MFMA columns that are never stored.
+__host__ __device__ __forceinline__ size_t plane_elems(int M, int K) { return (size_t)((M + 15) & ~15) * K; }
+__device__ __forceinline__ size_t plane_index(int K, int m, int k) {
+  return ((size_t)((m >> 4) * (K >> 5) + (k >> 5)) * 64 + (m & 15) + 16 * ((k >> 3) & 3)) * 8 + (k & 7);
+}
+
+// normalised row piece (4 consecutive columns from c, c % 4 == 0) -> fp32 row of out, or (split) the planes
 __device__ __forceinline__ void norm_out(float* out, bool split, int M, int m, int K, int c, float4 v) {
   if (!split) {
     *reinterpret_cast<float4*>(out + (size_t)m * K + c) = v;
   } else {
     uint2 hi, lo;
     split4(v, hi, lo);
-    uint16_t* hp = reinterpret_cast<uint16_t*>(out) + (size_t)m * K + c;
+    uint16_t* hp = reinterpret_cast<uint16_t*>(out) + plane_index(K, m, c);
     *reinterpret_cast<uint2*>(hp) = hi;
-    *reinterpret_cast<uint2*>(hp + (size_t)M * K) = lo;
+    *reinterpret_cast<uint2*>(hp + plane_elems(M, K)) = lo;
   }
 }
 
@@ -759,7 +770,7 @@ static bool ws_gemm_usable(const FastGemm& g) {
 // across workgroups and no LDS staging.  The norm pass writes the rows as bf16 hi / lo planes;
 // one workgroup owns one 16-row weight tile over the whole contraction length (its four
 // wavefronts take a quarter each, fragments in registers from one request) and reads the
-// MFMA "B" fragments of all row tiles straight from the planes, 16 bytes per lane, two
+// MFMA "B" fragments of all row tiles straight from the planes, one contiguous KB per request, two
 // k-tiles in flight.  The four partial tiles are summed through LDS in a fixed order.
 // ---------------------------------------------------------------------------
 constexpr int kWtMaxKW = 16;                           // k-tiles per wavefront: K <= 2048
@@ -783,8 +794,8 @@ __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, gq = lane >> 4;
   const int nt = blockIdx.x, KT = g.K / 32, KW = KT / 4;
-  const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);          // [M][K] bf16 hi, then lo
-  const size_t lo_off = (size_t)g.M * g.K;
+  const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);          // bf16 hi plane, then lo plane
+  const size_t lo_off = plane_elems(g.M, g.K);
   const __amdgpu_buffer_rsrc_t brs = stream_rsrc(Bh, lo_off * 4);
 
   uint4 wf[kWtMaxKW];
@@ -796,11 +807,8 @@ __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
   }
   for (int m0 = 0; m0 < g.M; m0 += 128) {
     const int rows = min(128, g.M - m0), ntile = (rows + 15) >> 4;
-    // lane's row in row tile mt (rows past M are clamped: their columns are never stored)
-    const unsigned bp = (unsigned)(wave * KW * 32 + gq * 8) * 2u;      // byte offsets into the hi plane
-    unsigned roff[8];
-#pragma unroll
-    for (int mt = 0; mt < 8; ++mt) roff[mt] = (unsigned)min(m0 + mt * 16 + r, g.M - 1) * (unsigned)g.K * 2u;
+    // byte offset of this lane's piece of row tile 0, k-tile 0 of this wavefront's quarter
+    const unsigned bp = (unsigned)((((m0 >> 4) * KT + wave * KW) * 64 + lane) * 16);
     f32x4 acc[8];
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -809,7 +817,7 @@ __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
 #pragma unroll
       for (int mt = 0; mt < 8; ++mt)
         if (mt < ntile) {
-          const unsigned o = bp + roff[mt] + (unsigned)i * 64u;
+          const unsigned o = bp + (unsigned)(mt * KT + i) * 1024u;
           b[mt][0] = stream_ld16(brs, o);
           b[mt][1] = stream_ld16(brs, o + (unsigned)lo_off * 2u);
         }
@@ -874,7 +882,8 @@ __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
             for (int e = 0; e < 4; ++e) {
               const int n = n0 + e, c = n % g.K;
               const float pre = v[e] + bf2f(g.bias[n]);
-              const float gn = bf2f(Bh[(size_t)m * g.K + c]) + bf2f(Bh[lo_off + (size_t)m * g.K + c]);
+              const size_t pi = plane_index(g.K, m, c);
+              const float gn = bf2f(Bh[pi]) + bf2f(Bh[lo_off + pi]);
               o[e] = gn + pre / (1.0f + __expf(-pre));
             }
             *y = o;
@@ -924,11 +933,11 @@ static void wt_gemm(int epi, FastGemm g, hipStream_t s) {
 // ---------------------------------------------------------------------------
 // Large M (more than 256 rows): register-blocked.  A workgroup computes 32 WN weight rows x
 // 32 WM activation rows, its four wavefronts 2 x 2 with WN x WM MFMA tiles each (16 accumulator
-// tiles at 4 x 4), so every operand fragment feeds four MFMA pairs and the kernel is bound by the
-// matrix cores rather than by LDS reads.  Weight fragments go from global memory / L2 straight to
-// registers (they are stored in fragment order), one stage of 64 k ahead; activations are staged
-// through double-buffered LDS as bf16 hi / lo planes (copied from the norm pass's planes, or split
-// from fp32 rows on the way in), one barrier per stage.  No split of the contraction index; row
+// tiles at 4 x 4), so every operand fragment feeds four MFMA pairs and LDS reads do not bound the
+// kernel.  Weight fragments go from global memory / L2 straight to registers (they are stored in
+// fragment order), one stage of 64 k ahead; the normalised rows are staged through double-buffered
+// LDS as bf16 hi / lo planes (copied from the norm pass's fragment-ordered planes, one contiguous
+// KB per wavefront request), one barrier per stage.  No split of the contraction index; row
 // blocks of one weight block run next to each other on one XCD.
 // ---------------------------------------------------------------------------
 struct QkvRow { int m, pos; size_t head0; bool ok; };
@@ -968,11 +977,11 @@ __device__ __forceinline__ void qkv_quad_store(const FastGemm& g, const QkvCols&
 constexpr int kBlkKC = 64, kBlkST = kBlkKC + 8;        // contraction slice per stage, LDS row stride (bf16)
 constexpr int kBlkKT = kBlkKC / 32;
 
-template <int EPI, bool PLANES, int WN, int WM>
+template <int EPI, int WN, int WM>
 __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
   constexpr int BN = 32 * WN, BM = 32 * WM;
   constexpr int PLANE = BM * kBlkST, BUF = 2 * PLANE;   // hi plane, lo plane; two buffers
-  constexpr int NPC = PLANES ? BM * (kBlkKC / 8) / 256 : BM * (kBlkKC / 4) / 256;   // 16-byte pieces per thread, plane and stage
+  constexpr int NPC = BM * (kBlkKC / 8) / 256;          // 16-byte pieces per thread, plane and stage
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -984,6 +993,8 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
   const int wn = wave & 1, wm = wave >> 1;
   const int nt0 = nb * (BN / 16) + wn * WN, m0 = mb * BM, m_base = m0 + wm * WM * 16;
   const uint4* wbase = g.Wt + (size_t)nt0 * KT * 64 + lane;
+  const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);          // bf16 hi plane, then lo plane
+  const size_t lo_off = plane_elems(g.M, g.K);
 
   f32x4 acc[WN][WM];
 #pragma unroll
@@ -991,30 +1002,23 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
 #pragma unroll
     for (int q = 0; q < WM; ++q) acc[t][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // staging pieces: PLANES piece p = (row p/8, 8 columns), fp32 piece p = (row p/16, 4 columns)
+  // staging piece p of a stage: row tile p / 128, k-tile (p / 64) % 2, lane p % 64 of that fragment
+  // (one wavefront request = one contiguous KB of a plane); it lands at row, column of the LDS tile
   uint4 wreg[WN][kBlkKT];
-  uint4 breg[PLANES ? 2 * NPC : NPC];
+  uint4 breg[2 * NPC];
   auto request = [&](int st) {
-    const int k0 = st * kBlkKC;
 #pragma unroll
     for (int t = 0; t < WN; ++t)
 #pragma unroll
       for (int i = 0; i < kBlkKT; ++i) wreg[t][i] = wbase[((size_t)t * KT + st * kBlkKT + i) * 64];
 #pragma unroll
     for (int j = 0; j < NPC; ++j) {
-      const int p = tid + 256 * j;
-      if (PLANES) {
-        const int row = p / (kBlkKC / 8), c8 = p % (kBlkKC / 8);
-        breg[2 * j] = uint4{0, 0, 0, 0}; breg[2 * j + 1] = uint4{0, 0, 0, 0};
-        if (m0 + row < g.M) {
-          const uint16_t* src = reinterpret_cast<const uint16_t*>(g.X) + (size_t)(m0 + row) * g.K + k0 + c8 * 8;
-          breg[2 * j] = *reinterpret_cast<const uint4*>(src);
-          breg[2 * j + 1] = *reinterpret_cast<const uint4*>(src + (size_t)g.M * g.K);
-        }
-      } else {
-        const int row = p / (kBlkKC / 4), c4 = p % (kBlkKC / 4);
-        breg[j] = uint4{0, 0, 0, 0};
-        if (m0 + row < g.M) breg[j] = *reinterpret_cast<const uint4*>(g.X + (size_t)(m0 + row) * g.ldx + k0 + c4 * 4);
+      const int p = tid + 256 * j, mtl = p >> 7, ktl = (p >> 6) & 1;
+      breg[2 * j] = uint4{0, 0, 0, 0}; breg[2 * j + 1] = uint4{0, 0, 0, 0};
+      if (m0 + mtl * 16 < g.M) {
+        const uint16_t* src = Bh + ((size_t)(((m0 >> 4) + mtl) * KT + st * kBlkKT + ktl) * 64 + (p & 63)) * 8;
+        breg[2 * j] = *reinterpret_cast<const uint4*>(src);
+        breg[2 * j + 1] = *reinterpret_cast<const uint4*>(src + lo_off);
       }
     }
   };
@@ -1022,18 +1026,10 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
     uint16_t* dst = As + buf * BUF;
 #pragma unroll
     for (int j = 0; j < NPC; ++j) {
-      const int p = tid + 256 * j;
-      if (PLANES) {
-        const int row = p / (kBlkKC / 8), c8 = p % (kBlkKC / 8);
-        *reinterpret_cast<uint4*>(dst + row * kBlkST + c8 * 8) = breg[2 * j];
-        *reinterpret_cast<uint4*>(dst + PLANE + row * kBlkST + c8 * 8) = breg[2 * j + 1];
-      } else {
-        const int row = p / (kBlkKC / 4), c4 = p % (kBlkKC / 4);
-        uint2 hi, lo;
-        split4(__builtin_bit_cast(float4, breg[j]), hi, lo);
-        *reinterpret_cast<uint2*>(dst + row * kBlkST + c4 * 4) = hi;
-        *reinterpret_cast<uint2*>(dst + PLANE + row * kBlkST + c4 * 4) = lo;
-      }
+      const int p = tid + 256 * j, ln = p & 63;
+      const int row = (p >> 7) * 16 + (ln & 15), c8 = ((p >> 6) & 1) * 4 + (ln >> 4);
+      *reinterpret_cast<uint4*>(dst + row * kBlkST + c8 * 8) = breg[2 * j];
+      *reinterpret_cast<uint4*>(dst + PLANE + row * kBlkST + c8 * 8) = breg[2 * j + 1];
     }
   };
   request(0);
@@ -1106,13 +1102,13 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
       } else if (EPI == FEPI_GELU) {
         *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
       } else if (EPI == FEPI_HEAD) {
-        const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);      // PLANES only: the normalised rows
         f32x4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int n = n0 + e, c = n % g.K;
           const float pre = v[e] + bf2f(g.bias[n]);
-          const float gn = bf2f(Bh[(size_t)m * g.K + c]) + bf2f(Bh[(size_t)g.M * g.K + (size_t)m * g.K + c]);
+          const size_t pi = plane_index(g.K, m, c);
+          const float gn = bf2f(Bh[pi]) + bf2f(Bh[lo_off + pi]);
           o[e] = gn + pre / (1.0f + __expf(-pre));
         }
         *y = o;
@@ -1121,18 +1117,16 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
   }
 }
 
-static bool blk_gemm_usable(int pro, int epi, const FastGemm& g) {
-  if (g.M <= kWsMaxM || g.N % 64 != 0 || g.K % kBlkKC != 0 || !g.nscratch) return false;
-  if (epi == FEPI_HEAD && pro != PRO_NORM) return false;
-  if ((size_t)g.M * (pro == PRO_NORM ? g.K : g.ldx) * 4 >= (1ull << 31)) return false;   // 32-bit buffer offsets
-  return true;
+static bool blk_gemm_usable(int pro, const FastGemm& g) {
+  if (pro != PRO_NORM || g.M <= kWsMaxM || g.N % 64 != 0 || g.K % kBlkKC != 0 || !g.nscratch) return false;
+  return plane_elems(g.M, g.K) * 4 < (1ull << 31);
 }
 
-template <int EPI, bool PLANES, int WN, int WM>
+template <int EPI, int WN, int WM>
 static void blk_launch_t(const FastGemm& g, hipStream_t s) {
   constexpr int BN = 32 * WN, BM = 32 * WM;
   const size_t lds = (size_t)2 * 2 * BM * kBlkST * 2;
-  auto kfn = k_gemm_blk<EPI, PLANES, WN, WM>;
+  auto kfn = k_gemm_blk<EPI, WN, WM>;
   static bool configured = false;
   if (!configured && lds > 64 * 1024) {
     (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1140,33 +1134,23 @@ static void blk_launch_t(const FastGemm& g, hipStream_t s) {
   }
   hipLaunchKernelGGL(kfn, dim3((g.N / BN) * ((g.M + BM - 1) / BM)), dim3(256), lds, s, g);
 }
-template <int EPI, bool PLANES>
+template <int EPI>
 static void blk_launch(const FastGemm& g, hipStream_t s) {
   // 128 x 128 blocks when they fill the chip, else 64 weight rows x 128 activation rows
   const long blocks128 = (long)(g.N / 128) * ((g.M + 127) / 128);
-  if (g.N % 128 == 0 && blocks128 >= 200) blk_launch_t<EPI, PLANES, 4, 4>(g, s);
-  else blk_launch_t<EPI, PLANES, 2, 4>(g, s);
+  if (g.N % 128 == 0 && blocks128 >= 200) blk_launch_t<EPI, 4, 4>(g, s);
+  else blk_launch_t<EPI, 2, 4>(g, s);
 }
 
-static void blk_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
-  if (pro == PRO_NORM) {
-    norm_pass(g, 1, s);
-    switch (epi) {
-      case FEPI_STORE: blk_launch<FEPI_STORE, true>(g, s); break;
-      case FEPI_GELU: blk_launch<FEPI_GELU, true>(g, s); break;
-      case FEPI_QKV: blk_launch<FEPI_QKV, true>(g, s); break;
-      case FEPI_HEAD: blk_launch<FEPI_HEAD, true>(g, s); break;
-      case FEPI_ADD: blk_launch<FEPI_ADD, true>(g, s); break;
-      default: break;
-    }
-  } else {
-    flush_pending_add(g.pend, s);
-    switch (epi) {
-      case FEPI_STORE: blk_launch<FEPI_STORE, false>(g, s); break;
-      case FEPI_GELU: blk_launch<FEPI_GELU, false>(g, s); break;
-      case FEPI_ADD: blk_launch<FEPI_ADD, false>(g, s); break;
-      default: break;
-    }
+static void blk_gemm(int epi, FastGemm g, hipStream_t s) {
+  norm_pass(g, 1, s);
+  switch (epi) {
+    case FEPI_STORE: blk_launch<FEPI_STORE>(g, s); break;
+    case FEPI_GELU: blk_launch<FEPI_GELU>(g, s); break;
+    case FEPI_QKV: blk_launch<FEPI_QKV>(g, s); break;
+    case FEPI_HEAD: blk_launch<FEPI_HEAD>(g, s); break;
+    case FEPI_ADD: blk_launch<FEPI_ADD>(g, s); break;
+    default: break;
   }
 }
 
@@ -1224,9 +1208,9 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   if (g.M <= 0) return;
   // (the residual-add projections read fp32 rows and have few column blocks: k_gemm_big is faster there)
-  if (blk_gemm_usable(pro, epi, g) && pro == PRO_NORM) {
+  if (blk_gemm_usable(pro, g)) {
     TraceScope trace_("gemm_blk", s);
-    blk_gemm(pro, epi, g, s);
+    blk_gemm(epi, g, s);
     return;
   }
   if (wt_gemm_usable(pro, g) && epi != FEPI_ADD) {
