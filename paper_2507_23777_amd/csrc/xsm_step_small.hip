@@ -430,9 +430,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       uint16_t* const qs = As;                            // q: hi plane, lo plane 16 rows further
       uint16_t* const kns = As + 32 * kQS;                // new k / v: as the cache will hold them
       uint16_t* const vns = As + 48 * kQS;
-      // the first chunk of cached keys/values does not depend on this step: request it before waiting
+      // the first chunk of cached keys/values does not depend on this step: request it before waiting;
+      // after that a wavefront requests the next chunk's keys as soon as the scores of the current
+      // one are formed, and its values after the second product (same registers, no second set)
       uint4 kf[4][2], vf[4][2];
-      auto load_kv = [&](int c) {
+      auto load_k = [&](int c) {
         const int key0 = c << 6;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -440,6 +442,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           kf[t][0] = *reinterpret_cast<const uint4*>(kr);
           kf[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
         }
+      };
+      auto load_v = [&](int c) {
+        const int key0 = c << 6;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
           const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
@@ -447,7 +452,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           vf[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
         }
       };
-      if (c_lo + wave < c_hi) load_kv(c_lo + wave);
+      if (c_lo + wave < c_hi) { load_k(c_lo + wave); load_v(c_lo + wave); }
       watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, tag, ok && n >= 0, tid);
       if (n >= 0) {
         const int j0 = tid >> 6, c = tid & 63;            // rows j0, j0+4, j0+8, j0+12
@@ -492,7 +497,6 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       // cached keys 0..n-1: every live query sees all of them
       for (int c = c_lo + wave; c < c_hi; c += 4) {
         const int key0 = c << 6;
-        if (c != c_lo + wave) load_kv(c);                  // (the first chunk was requested before the q wait)
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -504,6 +508,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[hf], sc[t], 0, 0, 0);
           }
         }
+        if (c + 4 < c_hi) load_k(c + 4);
         const int kbase = key0 + g * 16;
         const bool edge = key0 + 64 > nn || !qlive;
         const int lim = qlive ? nn : 0;
@@ -564,6 +569,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, pl[jj]), o[dt], 0, 0, 0);
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, ph[jj]), o[dt], 0, 0, 0);
           }
+        if (c + 4 < c_hi) load_v(c + 4);
       }
 
       // the R new keys of this step (positions n..n+R-1): one 16-key tile, taken by wavefront 3
