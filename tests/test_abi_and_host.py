@@ -60,3 +60,88 @@ def test_speedup_formula_reproduces_printed_tables(golden_dir):
     assert metrics.step_compression_ratio([1, 2, 5, 1, 1]) == 2.0
     with pytest.raises(ValueError):
         metrics.step_compression_ratio([])
+
+
+class _StubEngine:
+    """Stands in for Engine in the batcher's host logic: the 'model' is a fixed integer rule of
+    (cache length, last token), so every request's token stream is known without a GPU."""
+
+    def __init__(self, torch, K, max_batch, max_ctx):
+        self.torch, self.device = torch, torch.device("cpu")
+        self.c_cfg = type("C", (), {"n_draft": K, "vocab": 1001})()
+        self.max_batch, self.max_ctx = max_batch, max_ctx
+        self.prefills, self.batch_sizes = [], []
+
+    def to_device(self, x):
+        return self.torch.from_numpy(x)
+
+    def xsm_prefill(self, slots, prefix=None, cond=None):
+        assert len(set(slots)) == len(slots) and all(0 <= s < self.max_batch for s in slots)
+        self.prefills.append((list(slots), 0 if prefix is None else int(prefix.shape[1])))
+
+    def buffers(self, n_seq, spec=True, debug=False):
+        K = self.c_cfg.n_draft
+        return xsm.StepBuffers(self.torch, self.device, n_seq, K + 1 if spec else 1, 1001, K, False)
+
+    @staticmethod
+    def rule(n, last, R):
+        a = 1 + (last + n) % R
+        return a, [(last * 31 + n + 7 * j) % 1000 + 1 for j in range(a)]
+
+    def xsm_spec_step(self, buf, vp, bound):
+        slots = buf.slot.tolist()
+        assert len(set(slots)) == len(slots)
+        self.batch_sizes.append(buf.n_seq)
+        for i in range(buf.n_seq):
+            n, last = int(buf.kv_len[i]), int(buf.block[i, 0])
+            assert n <= bound and n + buf.R <= self.max_ctx
+            a, toks = self.rule(n, last, buf.R)
+            buf.n_accepted[i] = a
+            buf.out_tokens[i, :a] = self.torch.tensor(toks, dtype=self.torch.int32)
+            buf.block[i, 0] = toks[-1]
+            buf.kv_len[i] = n + a
+            buf.flags[i] = 0
+
+    xsm_plain_step = xsm_spec_step
+
+
+@pytest.mark.parametrize("spec", [True, False])
+def test_batcher_admission_compaction_budget_and_eos(spec):
+    import numpy as np
+    import torch
+    from paper_2507_23777_amd.batcher import Batcher, Request
+    K = 4
+    R = K + 1 if spec else 1
+    eng = _StubEngine(torch, K, max_batch=3, max_ctx=200)
+    P = [10, 0, 10, 33, 5, 10, 0, 21]
+    budget = [17, 5, 40, 1, 23, 9, 30, 12]
+    eos = [-1, -1, -1, -1, -1, -1, 500, -1]
+    expect = {}
+    for i in range(len(P)):
+        n, last, toks = P[i], 3 + i, []
+        while len(toks) < budget[i]:
+            a, t = _StubEngine.rule(n, last, R)
+            toks += t
+            n, last = n + a, t[-1]
+        toks = toks[:budget[i]]
+        if i == 6:                       # an EOS that the stream is known to reach
+            eos[i] = toks[11]
+            toks = toks[:toks.index(eos[i]) + 1]
+        expect[i] = toks
+    bt = Batcher(eng, None, spec=spec)
+    for i in range(len(P)):
+        rid = bt.submit(Request(first_block=[3 + i] + [0] * K, max_new_tokens=budget[i], eos=eos[i],
+                                prefix=None if P[i] == 0 else np.zeros((P[i], 8), np.float32)))
+        assert rid == i
+    got = bt.run()
+    assert got == expect
+    assert sorted(bt.free) == [0, 1, 2] and not bt.live and not bt.pending
+    assert max(eng.batch_sizes) == 3 and min(eng.batch_sizes) >= 1
+    # every request was prefilled exactly once (empty prefixes need none), into a slot that was free
+    assert sorted(s for slots, _ in eng.prefills for s in slots).count(0) >= 1
+    assert sum(len(slots) for slots, _ in eng.prefills) == sum(1 for p in P if p > 0)
+    assert all(p in P for _, p in eng.prefills)
+    with pytest.raises(ValueError):
+        bt.submit(Request(first_block=[1] * R, max_new_tokens=500))          # does not fit max_ctx
+    with pytest.raises(ValueError):
+        bt.submit(Request(first_block=[1], max_new_tokens=5) if spec else Request(first_block=[], max_new_tokens=5))
