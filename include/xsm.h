@@ -162,7 +162,12 @@ XSM_API int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, cons
 
 /* One speculative step (one iteration of Alg. 1's outer loop) for every sequence
  * of the batch: accepted tokens, their count, the next draft block and the new
- * cache length are written to the batch's device arrays. */
+ * cache length are written to the batch's device arrays.  A step only enqueues
+ * kernels on `stream` (no allocation, copy, memset or synchronisation), and its
+ * state between calls (lengths, blocks, the step epoch) lives on the device, so
+ * a caller may capture it in a HIP graph after one eager call; the graph then
+ * repeats the call with the n_seq, kv_len_bound, parameters and options of the
+ * capture. */
 XSM_API int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
                   xsm_stream stream);
 

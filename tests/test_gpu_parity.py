@@ -471,6 +471,61 @@ def test_single_launch_free_running_equals_per_stage(X):
     print(f"[single vs per-stage] {n} tokens compared, ties {outs[0][1]} {outs[1][1]}", flush=True)
 
 
+@pytest.mark.parametrize("path", ["single_launch", "per_stage_sampling"])
+def test_step_replayed_from_a_captured_graph(X, path):
+    """A step enqueues kernels only (no allocation, copy, memset or synchronisation) and keeps its
+    epoch and lengths on the device, so a caller may capture it in a HIP graph: six replays, with
+    eager work and synchronisation between them, must reproduce six eager steps from the same start."""
+    torch = X.torch
+    if path == "single_launch":
+        cfg, vp, n_seq, lens = _c1_small(n_layers=2), GREEDY, 2, [70, 21]
+    else:
+        cfg, vp, n_seq, lens = _mid_cfg(seed=61, n_layers=2), VerifyParams(mode=1, top_ka=4, temperature=0.9, sample=1, seed=5), 3, [37, 20, 9]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, n_seq, prefix_lens=lens)
+    vpg = X.H.to_vp_gpu(X.xsm, vp)
+    buf = eng.buffers(n_seq, spec=True)
+    first = torch.tensor(si.first_block(cfg, n_seq))
+    start_len = torch.tensor(lens, dtype=torch.int32)
+    bound = max(lens) + 6 * (cfg["n_draft"] + 1)
+
+    def reset():
+        buf.kv_len.copy_(start_len); buf.block.copy_(first)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.cpu().clone() for t in (buf.n_accepted, buf.out_tokens, buf.block, buf.kv_len, buf.flags)]
+
+    reset()
+    eager = []
+    for _ in range(6):
+        eng.xsm_spec_step(buf, vpg, bound)
+        eager.append(snapshot())
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            eng.xsm_spec_step(buf, vpg, bound)
+    torch.cuda.current_stream().wait_stream(side)
+    reset()                                   # (capture enqueues nothing, the state is still the start state)
+    scratch = torch.zeros(1 << 16, device=eng.device)
+    for i in range(6):
+        graph.replay()
+        got = snapshot()
+        for a, b, name in zip(got, eager[i], ("n_accepted", "out_tokens", "block", "kv_len", "flags")):
+            if name == "out_tokens":          # only the first n_accepted entries are defined
+                for r in range(n_seq):
+                    k = int(got[0][r])
+                    assert torch.equal(a[r, :k], b[r, :k]), (i, name, r)
+            else:
+                assert torch.equal(a, b), (i, name)
+        scratch.add_(1.0)                     # the program's own eager work between replays
+        torch.cuda.synchronize()
+    eng.xsm_check_device()
+
+
 def test_argument_and_device_side_errors(X):
     cfg = _mid_cfg(seed=28, n_layers=1)
     torch = X.torch
