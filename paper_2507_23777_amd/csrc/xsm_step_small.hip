@@ -53,6 +53,12 @@ namespace {
 
 constexpr int kSpinBudget = 150000;         // polls before a wait gives up (a fraction of a second)
 constexpr float kTieMarginS = 1e-2f;
+// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds + 16 l
+__device__ __forceinline__ void lds_direct16(const void* gptr, void* lds) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
+}
+
 constexpr int kQS = 72;                     // LDS row stride (bf16) of the attention q / new-k / new-v tiles
 
 __device__ __forceinline__ uint64_t ll_ld(const uint64_t* p) {
@@ -430,9 +436,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       uint16_t* const qs = As;                            // q: hi plane, lo plane 16 rows further
       uint16_t* const kns = As + 32 * kQS;                // new k / v: as the cache will hold them
       uint16_t* const vns = As + 48 * kQS;
-      // the first chunk of cached keys/values does not depend on this step: request it before waiting;
-      // after that a wavefront requests the next chunk's keys as soon as the scores of the current
-      // one are formed, and its values after the second product (same registers, no second set)
+      // the first chunk of cached keys/values does not depend on this step: request it before waiting.
+      // While a wavefront works on one chunk, the next one is on its way from HBM straight into LDS
+      // (LDS-direct loads: no registers - a second register set for it spills - and lane l's 16
+      // bytes of a request land at base + 16 l, i.e. already in fragment order), 16 KB per wavefront
+      unsigned char* const ring = dyn + 16384 + wave * 16384;
       uint4 kf[4][2], vf[4][2];
       auto load_k = [&](int c) {
         const int key0 = c << 6;
@@ -451,6 +459,30 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           vf[dt][0] = *reinterpret_cast<const uint4*>(vr);
           vf[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
         }
+      };
+      auto request_next = [&](int c) {
+        const int key0 = c << 6;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint16_t* kr = kb + (size_t)(key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 64 + g * 8;
+          lds_direct16(kr, ring + (t * 2) * 1024);
+          lds_direct16(kr + 32, ring + (t * 2 + 1) * 1024);
+        }
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
+          lds_direct16(vr, ring + 8192 + (dt * 2) * 1024);
+          lds_direct16(vr + 8, ring + 8192 + (dt * 2 + 1) * 1024);
+        }
+      };
+      auto take_next = [&]() {                              // (waits for the requests above)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            kf[t][j] = *reinterpret_cast<const uint4*>(ring + (t * 2 + j) * 1024 + lane * 16);
+            vf[t][j] = *reinterpret_cast<const uint4*>(ring + 8192 + (t * 2 + j) * 1024 + lane * 16);
+          }
       };
       if (c_lo + wave < c_hi) { load_k(c_lo + wave); load_v(c_lo + wave); }
       watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, tag, ok && n >= 0, tid);
@@ -497,6 +529,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       // cached keys 0..n-1: every live query sees all of them
       for (int c = c_lo + wave; c < c_hi; c += 4) {
         const int key0 = c << 6;
+        const bool more = c + 4 < c_hi;
+        if (more) request_next(c + 4);
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -508,7 +542,6 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[hf], sc[t], 0, 0, 0);
           }
         }
-        if (c + 4 < c_hi) load_k(c + 4);
         const int kbase = key0 + g * 16;
         const bool edge = key0 + 64 > nn || !qlive;
         const int lim = qlive ? nn : 0;
@@ -569,7 +602,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, pl[jj]), o[dt], 0, 0, 0);
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, __builtin_bit_cast(bf16x8, ph[jj]), o[dt], 0, 0, 0);
           }
-        if (c + 4 < c_hi) load_v(c + 4);
+        if (more) take_next();
       }
 
       // the R new keys of this step (positions n..n+R-1): one 16-key tile, taken by wavefront 3
