@@ -375,15 +375,12 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     a.n_seq = n_seq; a.R = R; a.V = V; a.max_batch = g.max_batch; a.max_ctx = g.max_ctx;
     a.bound = bt->kv_len_bound; a.cap = ctx->cap_self;
     a.eps = g.rms_eps; a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
-    // key-range slices per (sequence, head), S * n_seq * H <= 256 workgroups: the cached keys and
-    // values come from HBM at full memory latency and one workgroup has 64 KB of them in flight,
-    // so the stage is as fast as the number of workgroups that share the range - measured at
-    // contexts 100..4353, more slices won from three chunks on, even with most slices empty and
-    // the merge stage added (context 200: S = 8 beats S = 1; 4353: S = 16 beats 8 by 4 %)
-    const int chunks = (bt->kv_len_bound + 63) / 64;
+    // upper limit of the key slices per (sequence, head): S * n_seq * H <= 256 workgroups; the kernel
+    // picks the count from the cache lengths it reads (a forced count is taken as it is)
     int S = 1;
-    const int want = ctx->force_splits > 0 ? ctx->force_splits : chunks <= 2 ? 1 : chunks <= 8 ? 8 : 16;
+    const int want = ctx->force_splits > 0 ? ctx->force_splits : 16;
     while (S * 2 <= want && S < 16 && 2 * S * n_seq * g.n_heads <= 256) S *= 2;
+    a.s_auto = ctx->force_splits > 0 ? 0 : 1;
     a.S = S;
     launch_step_small(a, d, g.d_ffn, s);
     if (defer) {

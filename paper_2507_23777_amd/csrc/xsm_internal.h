@@ -199,7 +199,8 @@ struct SmallArgs {
   uint32_t* flags;
   float* logits_dbg; float* head_logits_dbg; float* head_all_dbg; int32_t* acc_out;
   uint64_t* tlog;                        // optional stage timeline [256][L*16 + 8] clock stamps
-  int n_seq, R, S, V, max_batch, max_ctx, bound, cap;
+  int n_seq, R, S, V, max_batch, max_ctx, bound, cap;   // S: key slices per (sequence, head), or their upper limit
+  int s_auto;                            // 1: the kernel picks the slice count <= S from the cache lengths it reads
   int defer_verify;                      // 1: stop after the unembedding (logits of all rows written); the
                                          // caller runs verification and the draws as separate kernels
   float eps, scale_log2;

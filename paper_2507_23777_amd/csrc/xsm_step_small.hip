@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 
   const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int R = a.R, K = R - 1, M = a.n_seq * R, S = a.S, V = a.V;
+  const int R = a.R, K = R - 1, M = a.n_seq * R, V = a.V;
 
   // ---- set-up: epoch, layer table, per-sequence validation (every workgroup, redundantly) ----
   if (tid == 0) {
@@ -332,6 +332,20 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   __syncthreads();
   if (sm.fail != 0) return;                 // an earlier step timed out: stay down until reset
   const uint32_t tag = sm.tag;
+  // Key slices per (sequence, head), from the longest live cache (every workgroup reads the same
+  // lengths, so all agree).  The cached keys and values come from HBM at full memory latency and a
+  // workgroup has at most 128 KB of them in flight, so the attention stage is as fast as the
+  // number of workgroups sharing a key range: measured at contexts 100..4353, 8 slices win from
+  // three 64-key chunks on (even with most slices empty and the merge stage added), 16 from about
+  // twenty chunks on.
+  int S = a.S;
+  if (a.s_auto) {
+    int longest = 0;
+    for (int b = 0; b < a.n_seq; ++b) longest = max(longest, sm.len[b]);
+    const int chunks = (longest + 63) >> 6;
+    const int want = chunks <= 2 ? 1 : chunks <= 20 ? 8 : 16;
+    while (S > want) S >>= 1;
+  }
   // this lane's activation row (MFMA column) m = r
   // the output element this thread finishes after tile_reduce: tile column nrow of row om
   const int om = tid >> 4, nrow = tid & 15;
