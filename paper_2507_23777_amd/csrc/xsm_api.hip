@@ -66,7 +66,8 @@ void build_work_offsets(xsm_ctx* c) {
   auto take = [&](size_t bytes) { size_t r = p; p = align_up(p + bytes); return r; };
   w.X = take(Mmax * d * 4); w.QKV = take(Mmax * 3 * d * 4);
   w.Xn = take(((Mmax + 15) & ~(size_t)15) * d * 4);       // (as bf16 hi / lo planes it covers whole 16-row tiles)
-  w.Qr = take(Mmax * d * 4); w.AO = take(Mmax * d * 4); w.U = take(Mmax * F * 4);
+  const size_t Mpad = (Mmax + 15) & ~(size_t)15;          // (AO and U may hold operand planes: whole 16-row tiles)
+  w.Qr = take(Mmax * d * 4); w.AO = take(Mpad * d * 4); w.U = take(Mpad * F * 4);
   w.Z0 = take(Mb * V * 4);
   w.G = take((size_t)g.max_batch * d * 4);
   w.Hh = take((size_t)g.max_batch * (K ? K : 1) * d * 4);
@@ -202,6 +203,14 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
   const int32_t* slot = (const int32_t*)(ws + c->ws.slot);
   const float2* rope = (const float2*)(c->d_w + c->rope_off);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)hd);
+  // The row-blocked kernel reads its input as bf16 hi/lo operand planes.  When the residual-add
+  // projections (d output columns) have enough 64 x 128 blocks to fill the chip, attention and the
+  // FFN-up epilogue write such planes directly and those projections run on it too (no fp32 round
+  // trip, no conversion in the GEMM): 8 % on a 2048-row prefill pass; with fewer blocks (1152 rows
+  // at d = 1024: 144) the kernel with smaller blocks that converts fp32 rows on the way in is faster.
+  const bool planes = fgemm_planes_ok(M, d, d) && fgemm_planes_ok(M, d, F) && fgemm_planes_ok(M, F, d) &&
+                      (d / 64) * ((M + 127) / 128) >= 256;
+  const int pro_in = planes ? PRO_PLANES : PRO_F32;
   for (int l = 0; l < g.n_layers; ++l) {
     const LayerPtrs P = layer_ptrs(c, l);
     const TiledLayer& T = c->toff.layer[l];
@@ -218,13 +227,13 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     a.eff_len = eff; a.slot = slot; a.O = AO; a.ldo = d;
     a.part = (float*)(ws + c->ws.part); a.tickets = (uint32_t*)(ws + c->ws.tickets);
     a.R = R; a.H = H; a.cap = c->cap_self; a.S = attn_splits(c, n_seq * ((R + 15) / 16), len_bound + R); a.fixed_limit = 0;
-    a.scale_log2 = scale_log2;
+    a.scale_log2 = scale_log2; a.o_planes = planes ? 1 : 0; a.o_rows = M;
     launch_fattn(a, n_seq, s);
 
     FastGemm o{};
     o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
     o.X = AO; o.ldx = d; o.Y = X; o.ldy = d; o.nscratch = Xn; o.ws_part = gpart; o.ws_tickets = gtick; o.pend = PEND;
-    launch_fgemm(PRO_F32, FEPI_ADD, o, s);
+    launch_fgemm(pro_in, FEPI_ADD, o, s);
 
     if (g.n_cond > 0) {
       FastGemm cq{};
@@ -238,19 +247,20 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
       launch_fattn(ca, n_seq, s);
       FastGemm co = o;
       co.Wt = (const uint4*)(c->d_w + T.Wco);
-      launch_fgemm(PRO_F32, FEPI_ADD, co, s);
+      launch_fgemm(pro_in, FEPI_ADD, co, s);
     }
 
     FastGemm u{};
     u.Wt = (const uint4*)(c->d_w + T.W1); u.N = F; u.K = d; u.M = M;
     u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
     u.Y = U; u.ldy = F; u.nscratch = Xn; u.ws_part = gpart; u.ws_tickets = gtick; u.pend = PEND;
+    u.y_planes = planes ? 1 : 0;
     launch_fgemm(PRO_NORM, FEPI_GELU, u, s);
 
     FastGemm dn{};
     dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
     dn.X = U; dn.ldx = F; dn.Y = X; dn.ldy = d; dn.nscratch = Xn; dn.ws_part = gpart; dn.ws_tickets = gtick; dn.pend = PEND;
-    launch_fgemm(PRO_F32, FEPI_ADD, dn, s);
+    launch_fgemm(pro_in, FEPI_ADD, dn, s);
   }
   flush_pending_add(PEND, s);                     // the residual rows are read by the caller next
 }

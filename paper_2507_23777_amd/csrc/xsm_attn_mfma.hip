@@ -40,6 +40,12 @@ __device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t&
   lo = pack2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 
+// four consecutive dims (col % 4 == 0) of output row `row`: fp32, or operand planes for the projection that follows
+__device__ __forceinline__ void store_out4(const FastAttn& a, int row, int col, float4 v) {
+  if (a.o_planes) plane_store4(a.O, a.o_rows, a.ldo, row, col, v);
+  else *reinterpret_cast<float4*>(a.O + (size_t)row * a.ldo + col) = v;
+}
+
 __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   __shared__ float sm_ml[4][2][16];
   __shared__ __align__(16) float sm_o[4][4][64][4];
@@ -53,8 +59,8 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   const int nseq = a.eff_len[b];
   if (nseq < 0) {                                  // skipped sequence: defined (zero) output
     if (s == 0)
-      for (int i = tid; i < R * 64; i += 256)
-        a.O[(size_t)(row0 + i / 64) * a.ldo + h * 64 + (i & 63)] = 0;
+      for (int i = tid; i < R * 16; i += 256)
+        store_out4(a, row0 + i / 16, h * 64 + (i & 15) * 4, float4{0.f, 0.f, 0.f, 0.f});
     return;
   }
   const int n = nseq + qt * 16;                    // keys every query of this tile sees
@@ -201,8 +207,7 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   if (S == 1) {
     if (r < R) {
       const float inv = 1.0f / L;
-      float* dst = a.O + (size_t)(row0 + r) * a.ldo + h * 64 + dt * 16 + g * 4;
-      *reinterpret_cast<float4*>(dst) = float4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+      store_out4(a, row0 + r, h * 64 + dt * 16 + g * 4, float4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv});
     }
     return;
   }
@@ -237,8 +242,7 @@ __global__ __launch_bounds__(256) void k_fattn(const FastAttn a) {
   }
   if (r < R) {
     const float inv = 1.0f / Lg;
-    float* dst = a.O + (size_t)(row0 + r) * a.ldo + h * 64 + dt * 16 + g * 4;
-    *reinterpret_cast<float4*>(dst) = float4{og[0] * inv, og[1] * inv, og[2] * inv, og[3] * inv};
+    store_out4(a, row0 + r, h * 64 + dt * 16 + g * 4, float4{og[0] * inv, og[1] * inv, og[2] * inv, og[3] * inv});
   }
 }
 

@@ -18,6 +18,31 @@ __device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(ui
 __device__ __forceinline__ uint32_t f2bf_pair(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
+// four floats -> packed bf16 pairs of the rounded values (hi) and of what the rounding dropped (lo)
+__device__ __forceinline__ void split4(const float4 v, uint2& hi, uint2& lo) {
+  hi = uint2{f2bf_pair(v.x, v.y), f2bf_pair(v.z, v.w)};
+  lo = uint2{f2bf_pair(v.x - __uint_as_float(hi.x << 16), v.y - __uint_as_float(hi.x & 0xFFFF0000u)),
+             f2bf_pair(v.z - __uint_as_float(hi.y << 16), v.w - __uint_as_float(hi.y & 0xFFFF0000u))};
+}
+
+// Activation rows as MFMA operands: bf16 hi and lo planes in fragment order.  A tile of 16 rows x
+// 32 contraction indices is one contiguous KB in which lane (row & 15) + 16 * ((k >> 3) & 3) holds 8
+// consecutive k, tiles ordered [row tile][k tile]: a wavefront fetches a whole "B" fragment as one
+// contiguous KB.  (With row-major planes a fragment is 16 rows x 64 B, and the GEMMs that read
+// them straight from L2 took 30 % longer.)  A plane covers whole 16-row tiles; rows past M are
+// never written and feed only MFMA columns that are never stored.
+__host__ __device__ __forceinline__ size_t plane_elems(int M, int K) { return (size_t)((M + 15) & ~15) * K; }
+__device__ __forceinline__ size_t plane_index(int K, int m, int k) {
+  return ((size_t)((m >> 4) * (K >> 5) + (k >> 5)) * 64 + (m & 15) + 16 * ((k >> 3) & 3)) * 8 + (k & 7);
+}
+// v = columns k..k+3 (k % 4 == 0) of row m of an [M][K] activation block -> both planes at `planes`
+__device__ __forceinline__ void plane_store4(void* planes, int M, int K, int m, int k, float4 v) {
+  uint2 hi, lo;
+  split4(v, hi, lo);
+  uint16_t* hp = reinterpret_cast<uint16_t*>(planes) + plane_index(K, m, k);
+  *reinterpret_cast<uint2*>(hp) = hi;
+  *reinterpret_cast<uint2*>(hp + plane_elems(M, K)) = lo;
+}
 __device__ __forceinline__ float ldf(const float* p) { return *p; }
 __device__ __forceinline__ float ldf(const bf16_t* p) { return bf2f(p->x); }
 __device__ __forceinline__ void stf(float* p, float v) { *p = v; }

@@ -83,12 +83,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return f2bf_pa
 // multiplied against the same weight fragment: the activation keeps ~16 mantissa bits, so what
 // is left of the bf16 format in a projection is the weights' own rounding (which the model
 // definition shares).  At these M the second MFMA is free.
-__device__ __forceinline__ void split4(const float4 v, uint2& hi, uint2& lo) {
-  hi = uint2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
-  lo = uint2{pack_bf16(v.x - __uint_as_float(hi.x << 16), v.y - __uint_as_float(hi.x & 0xFFFF0000u)),
-             pack_bf16(v.z - __uint_as_float(hi.y << 16), v.w - __uint_as_float(hi.y & 0xFFFF0000u))};
-}
-
 // shared epilogue of the fused QKV projection for one element: rotary pair (v, partner), then
 // q to the fp32 query buffer, k / v to the bf16 cache
 __device__ __forceinline__ void qkv_store(const FastGemm& g, int nt, int nrow, int m, float v, float partner) {
@@ -256,27 +250,12 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
 // memory (HBM once, then the XCD's L2: all row blocks of one weight tile pair are placed on the
 // same XCD).  RMSNorm is done once per row by k_norm_rows instead of once per workgroup.
 // ---------------------------------------------------------------------------
-// Normalised rows as MFMA operands: bf16 hi and lo planes in fragment order.  A tile of 16 rows x
-// 32 contraction indices is one contiguous KB in which lane (row & 15) + 16 * ((k >> 3) & 3) holds 8
-// consecutive k, tiles ordered [row tile][k tile]: a wavefront fetches a whole "B" fragment as one
-// contiguous KB.  (With row-major planes a fragment is 16 rows x 64 B, and the GEMMs that read
-// them straight from L2 took 30 % longer.)  A plane covers whole 16-row tiles; rows past M are
-// never written and feed only MFMA columns that are never stored.
-__host__ __device__ __forceinline__ size_t plane_elems(int M, int K) { return (size_t)((M + 15) & ~15) * K; }
-__device__ __forceinline__ size_t plane_index(int K, int m, int k) {
-  return ((size_t)((m >> 4) * (K >> 5) + (k >> 5)) * 64 + (m & 15) + 16 * ((k >> 3) & 3)) * 8 + (k & 7);
-}
-
 // normalised row piece (4 consecutive columns from c, c % 4 == 0) -> fp32 row of out, or (split) the planes
 __device__ __forceinline__ void norm_out(float* out, bool split, int M, int m, int K, int c, float4 v) {
   if (!split) {
     *reinterpret_cast<float4*>(out + (size_t)m * K + c) = v;
   } else {
-    uint2 hi, lo;
-    split4(v, hi, lo);
-    uint16_t* hp = reinterpret_cast<uint16_t*>(out) + plane_index(K, m, c);
-    *reinterpret_cast<uint2*>(hp) = hi;
-    *reinterpret_cast<uint2*>(hp + plane_elems(M, K)) = lo;
+    plane_store4(out, M, K, m, c, v);
   }
 }
 
@@ -1100,7 +1079,9 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
       } else if (EPI == FEPI_ADD) {
         *y = *y + v;
       } else if (EPI == FEPI_GELU) {
-        *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
+        const float4 u = float4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
+        if (g.y_planes) plane_store4(g.Y, g.M, g.N, m, n0, u);      // operand planes of the next projection
+        else *y = f32x4{u.x, u.y, u.z, u.w};
       } else if (EPI == FEPI_HEAD) {
         f32x4 o;
 #pragma unroll
@@ -1117,9 +1098,12 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
   }
 }
 
+bool fgemm_planes_ok(int M, int N, int K) {
+  return M > kWsMaxM && N % 64 == 0 && K % kBlkKC == 0 && plane_elems(M, K) * 4 < (1ull << 31);
+}
 static bool blk_gemm_usable(int pro, const FastGemm& g) {
-  if (pro != PRO_NORM || g.M <= kWsMaxM || g.N % 64 != 0 || g.K % kBlkKC != 0 || !g.nscratch) return false;
-  return plane_elems(g.M, g.K) * 4 < (1ull << 31);
+  if (pro == PRO_PLANES) return fgemm_planes_ok(g.M, g.N, g.K);
+  return pro == PRO_NORM && g.nscratch && fgemm_planes_ok(g.M, g.N, g.K);
 }
 
 template <int EPI, int WN, int WM>
@@ -1142,8 +1126,9 @@ static void blk_launch(const FastGemm& g, hipStream_t s) {
   else blk_launch_t<EPI, 2, 4>(g, s);
 }
 
-static void blk_gemm(int epi, FastGemm g, hipStream_t s) {
-  norm_pass(g, 1, s);
+static void blk_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
+  if (pro == PRO_NORM) norm_pass(g, 1, s);
+  else flush_pending_add(g.pend, s);                   // (input planes come from the producing kernel)
   switch (epi) {
     case FEPI_STORE: blk_launch<FEPI_STORE>(g, s); break;
     case FEPI_GELU: blk_launch<FEPI_GELU>(g, s); break;
@@ -1210,7 +1195,7 @@ void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   // (the residual-add projections read fp32 rows and have few column blocks: k_gemm_big is faster there)
   if (blk_gemm_usable(pro, g)) {
     TraceScope trace_("gemm_blk", s);
-    blk_gemm(epi, g, s);
+    blk_gemm(pro, epi, g, s);
     return;
   }
   if (wt_gemm_usable(pro, g) && epi != FEPI_ADD) {

@@ -140,16 +140,17 @@ void launch_attention(int dtype, const float* Q, const void* Kc, const void* Vc,
                       int H, int hd, int cap, int fixed_limit, hipStream_t s);
 
 // ---- MFMA path (xsm_gemm_mfma.hip, xsm_attn_mfma.hip) ----------------------------
-enum { PRO_NORM = 0, PRO_F32 = 1 };
+enum { PRO_NORM = 0, PRO_F32 = 1, PRO_PLANES = 2 };   // PRO_PLANES: X holds fragment-ordered bf16 hi/lo planes (M > 256 only)
 enum { FEPI_STORE = 0, FEPI_ADD = 1, FEPI_GELU = 2, FEPI_QKV = 3, FEPI_HEAD = 4 };
 struct FastGemm {
   const uint4* Wt;             // fragment-ordered weights [N/16][K/32][64 lanes][8]
   int N, K, M, KC;
-  const float* X; int ldx;     // fp32 input rows
+  const float* X; int ldx;     // fp32 input rows (PRO_PLANES: the planes, ldx unused)
   const uint16_t* gain;        // bf16 RMSNorm gain [K] (PRO_NORM)
   float eps;
   const int32_t* row_index;    // optional gather: input row of output row m
   float* Y; int ldy;           // fp32 output (for FEPI_QKV: the rotated queries [M][d])
+  int y_planes;                // FEPI_GELU in the row-blocked kernel: write Y as operand planes [M][N] instead
   const uint16_t* bias;        // FEPI_HEAD: stacked biases [N]
   float* nscratch;             // [M][K] fp32: normalised rows for the kernels that do not fuse the norm
   float* ws_part; uint32_t* ws_tickets;   // split-contraction partial products and arrival counters
@@ -160,6 +161,8 @@ struct FastGemm {
   uint16_t* Kc; uint16_t* Vc;
 };
 bool fgemm_supported(int N, int K);
+// true when a projection of these sizes can take its input as operand planes (PRO_PLANES)
+bool fgemm_planes_ok(int M, int N, int K);
 constexpr size_t kWsTickets = 4096;      // arrival counters of the split-contraction GEMM
 bool ws_gemm_shape_ok(int M, int N, int K);
 size_t ws_gemm_part_floats(int M, int N, int K);
@@ -173,6 +176,7 @@ struct FastAttn {
   const uint16_t* Vt;                 // layer's values, transposed [slot][H][64][cap]
   const int32_t* eff_len; const int32_t* slot;
   float* O; int ldo;                  // fp32 output [M][d]
+  int o_planes, o_rows;               // o_planes: write O as operand planes [o_rows][ldo] instead (o_rows = M)
   float* part; uint32_t* tickets;     // split-key partials and arrival counters
   int R, H, cap, S, fixed_limit;
   float scale_log2;                   // log2(e) / sqrt(head_dim)

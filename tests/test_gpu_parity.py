@@ -220,6 +220,21 @@ def test_prefill_in_large_chunks(X):
     _report(tal, "prefix 900 B3 (two passes)")
 
 
+def test_prefill_pass_with_operand_planes_end_to_end(X):
+    """A 2048-row pass at d = 1024: the residual-add projections have enough blocks for the
+    row-blocked kernel, so attention and the FFN-up epilogue hand them bf16 hi/lo operand planes
+    instead of fp32 rows.  Second-layer cache and the steps after it against the oracle."""
+    cfg = _c1_small(n_layers=2, prefix=2048, max_ctx=2112)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1)
+    for which, ref in ((0, states[0].k[1]), (1, states[0].v[1])):
+        got = eng.xsm_debug_kv_export(1, which, 0, 0, 2048)
+        want = np.transpose(np.asarray(ref[:2048], np.float64), (1, 0, 2))
+        err = np.abs(got - want).max() / np.abs(want).max()
+        assert err < 1e-2, (which, err)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 2, si.first_block(cfg, 1))
+    _report(tal, "prefix 2048 B1 d1024 (operand planes)")
+
+
 def test_rows_name_their_cache_slot(X):
     """A batch row carries the index of its cache slot: rows in an order that is not the slot
     order, with one slot left out, against the oracle states of those sequences; on the per-stage
