@@ -153,6 +153,12 @@ def test_cross_attention_backbone(X):
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 6, si.first_block(cfg, 1))
     _report(tal, "cross-attn f32")
     assert tal.max_rel < 1e-5
+    # a prefix as well: the prefill pass runs the 64-row attention kernel over the cached prefix rows
+    # (causal) and over the condition tokens (all visible), here with a ragged last tile
+    cfg = _mid_cfg(n_cond=70, prefix=85, seed=29, n_layers=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[85, 40])
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 2))
+    _report(tal, "cross-attn with prefixes 85 / 40")
 
 
 def test_cross_attention_decoding_heads(X):
