@@ -702,13 +702,15 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
     float* Xn = (float*)(ws + ctx->ws.Xn);
     float* gpart = (float*)(ws + ctx->ws.gpart);
     uint32_t* gtick = (uint32_t*)(ws + ctx->ws.gtickets);
+    bool cond_plane = false;
     auto project = [&](const void* Wcanon, size_t Wtiled, int M, char* kc, char* vc, int C, int r0) {
       if (ctx->fast) {
         FastGemm p{};
         p.Wt = (const uint4*)(ctx->d_w + Wtiled); p.N = 2 * d; p.K = d; p.M = M;
         p.X = X; p.ldx = d; p.Y = QKV; p.ldy = 2 * d;
         p.nscratch = Xn; p.ws_part = gpart; p.ws_tickets = gtick; p.pend = &ctx->pend;
-        launch_fgemm(PRO_F32, FEPI_STORE, p, s);
+        p.x_single = cond_plane ? 1 : 0;             // (X then holds the condition rows as one bf16 operand plane)
+        launch_fgemm(cond_plane ? PRO_PLANES : PRO_F32, FEPI_STORE, p, s);
       } else {
         launch_gemm(dt, EPI_STORE, X, d, Wcanon, QKV, 2 * d, M, 2 * d, d, s);
       }
@@ -717,7 +719,11 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
     };
     for (int r0 = 0; r0 < g.n_cond; r0 += chunk) {
       const int C = g.n_cond - r0 < chunk ? g.n_cond - r0 : chunk;
-      launch_load_rows(dt, d_cond, X, n_seq, C, r0, g.n_cond, d, s);
+      // the condition tokens are bf16: in a pass large enough for the row-blocked kernel they go in
+      // as they are (one operand plane, no low part, half the products of an fp32 activation)
+      cond_plane = ctx->fast && fgemm_planes_ok(n_seq * C, 2 * d, d);
+      if (cond_plane) launch_load_rows_plane(d_cond, X, n_seq, C, r0, g.n_cond, d, s);
+      else launch_load_rows(dt, d_cond, X, n_seq, C, r0, g.n_cond, d, s);
       for (int l = 0; l < g.n_layers; ++l) {
         const LayerPtrs L = layer_ptrs(ctx, l);
         project(L.Wckv, ctx->fast ? ctx->toff.layer[l].Wckv : 0, n_seq * C, cross_cache(ctx, l, 0), cross_cache(ctx, l, 1), C, r0);

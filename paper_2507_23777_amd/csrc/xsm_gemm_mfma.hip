@@ -956,10 +956,11 @@ __device__ __forceinline__ void qkv_quad_store(const FastGemm& g, const QkvCols&
 constexpr int kBlkKC = 64, kBlkST = kBlkKC + 8;        // contraction slice per stage, LDS row stride (bf16)
 constexpr int kBlkKT = kBlkKC / 32;
 
-template <int EPI, int WN, int WM>
+// SINGLE: the input is exact in bf16 (one plane, one MFMA per fragment pair)
+template <int EPI, int WN, int WM, bool SINGLE>
 __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
   constexpr int BN = 32 * WN, BM = 32 * WM;
-  constexpr int PLANE = BM * kBlkST, BUF = 2 * PLANE;   // hi plane, lo plane; two buffers
+  constexpr int PLANE = BM * kBlkST, BUF = (SINGLE ? 1 : 2) * PLANE;   // hi plane, lo plane; two buffers
   constexpr int NPC = BM * (kBlkKC / 8) / 256;          // 16-byte pieces per thread, plane and stage
   extern __shared__ __align__(16) unsigned char smem[];
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);
@@ -997,7 +998,7 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
       if (m0 + mtl * 16 < g.M) {
         const uint16_t* src = Bh + ((size_t)(((m0 >> 4) + mtl) * KT + st * kBlkKT + ktl) * 64 + (p & 63)) * 8;
         breg[2 * j] = *reinterpret_cast<const uint4*>(src);
-        breg[2 * j + 1] = *reinterpret_cast<const uint4*>(src + lo_off);
+        if (!SINGLE) breg[2 * j + 1] = *reinterpret_cast<const uint4*>(src + lo_off);
       }
     }
   };
@@ -1008,7 +1009,7 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
       const int p = tid + 256 * j, ln = p & 63;
       const int row = (p >> 7) * 16 + (ln & 15), c8 = ((p >> 6) & 1) * 4 + (ln >> 4);
       *reinterpret_cast<uint4*>(dst + row * kBlkST + c8 * 8) = breg[2 * j];
-      *reinterpret_cast<uint4*>(dst + PLANE + row * kBlkST + c8 * 8) = breg[2 * j + 1];
+      if (!SINGLE) *reinterpret_cast<uint4*>(dst + PLANE + row * kBlkST + c8 * 8) = breg[2 * j + 1];
     }
   };
   request(0);
@@ -1027,12 +1028,14 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
 #pragma unroll
       for (int q = 0; q < WM; ++q) {
         const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + q * 16 * kBlkST + i * 32));
-        const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + PLANE + q * 16 * kBlkST + i * 32));
         // the two products into one accumulator are kept WN MFMAs apart (a dependent MFMA issued
         // back to back waits out the first one's latency)
+        if (!SINGLE) {
+          const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bp + PLANE + q * 16 * kBlkST + i * 32));
 #pragma unroll
-        for (int t = 0; t < WN; ++t)
-          acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[t][i]), bl, acc[t][q], 0, 0, 0);
+          for (int t = 0; t < WN; ++t)
+            acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[t][i]), bl, acc[t][q], 0, 0, 0);
+        }
 #pragma unroll
         for (int t = 0; t < WN; ++t)
           acc[t][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[t][i]), bh, acc[t][q], 0, 0, 0);
@@ -1102,15 +1105,16 @@ bool fgemm_planes_ok(int M, int N, int K) {
   return M > kWsMaxM && N % 64 == 0 && K % kBlkKC == 0 && plane_elems(M, K) * 4 < (1ull << 31);
 }
 static bool blk_gemm_usable(int pro, const FastGemm& g) {
+  if (g.x_single && pro != PRO_PLANES) return false;
   if (pro == PRO_PLANES) return fgemm_planes_ok(g.M, g.N, g.K);
   return pro == PRO_NORM && g.nscratch && fgemm_planes_ok(g.M, g.N, g.K);
 }
 
-template <int EPI, int WN, int WM>
+template <int EPI, int WN, int WM, bool SINGLE = false>
 static void blk_launch_t(const FastGemm& g, hipStream_t s) {
   constexpr int BN = 32 * WN, BM = 32 * WM;
-  const size_t lds = (size_t)2 * 2 * BM * kBlkST * 2;
-  auto kfn = k_gemm_blk<EPI, WN, WM>;
+  const size_t lds = (size_t)2 * (SINGLE ? 1 : 2) * BM * kBlkST * 2;
+  auto kfn = k_gemm_blk<EPI, WN, WM, SINGLE>;
   static bool configured = false;
   if (!configured && lds > 64 * 1024) {
     (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1122,8 +1126,15 @@ template <int EPI>
 static void blk_launch(const FastGemm& g, hipStream_t s) {
   // 128 x 128 blocks when they fill the chip, else 64 weight rows x 128 activation rows
   const long blocks128 = (long)(g.N / 128) * ((g.M + 127) / 128);
-  if (g.N % 128 == 0 && blocks128 >= 200) blk_launch_t<EPI, 4, 4>(g, s);
-  else blk_launch_t<EPI, 2, 4>(g, s);
+  const bool big = g.N % 128 == 0 && blocks128 >= 200;
+  if (EPI == FEPI_STORE && g.x_single) {
+    if (big) blk_launch_t<FEPI_STORE, 4, 4, true>(g, s);
+    else blk_launch_t<FEPI_STORE, 2, 4, true>(g, s);
+  } else if (big) {
+    blk_launch_t<EPI, 4, 4>(g, s);
+  } else {
+    blk_launch_t<EPI, 2, 4>(g, s);
+  }
 }
 
 static void blk_gemm(int pro, int epi, FastGemm g, hipStream_t s) {

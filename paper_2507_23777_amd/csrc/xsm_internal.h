@@ -117,6 +117,9 @@ void launch_fill_i32(int32_t* p, int n, int32_t v, hipStream_t s);
 void launch_embed(int dtype, const void* E, const int32_t* block, const int32_t* eff_len, float* X,
                   int n_seq, int R, int d, hipStream_t s);
 // X[b*C + j] = emb[b][row0 + j] for j < C
+// bf16 rows -> one fragment-ordered operand plane [n_seq*C][d] (d % 32 == 0)
+void launch_load_rows_plane(const void* emb, void* plane, int n_seq, int C, int row0, int rows_per_seq, int d,
+                            hipStream_t s);
 void launch_load_rows(int dtype, const void* emb, float* X, int n_seq, int C, int row0,
                       int rows_per_seq, int d, hipStream_t s);
 void launch_rmsnorm(int dtype, const float* X, const void* gain, float* Y, int M, int d, float eps,
@@ -146,6 +149,7 @@ struct FastGemm {
   const uint4* Wt;             // fragment-ordered weights [N/16][K/32][64 lanes][8]
   int N, K, M, KC;
   const float* X; int ldx;     // fp32 input rows (PRO_PLANES: the planes, ldx unused)
+  int x_single;                // PRO_PLANES: the input is exact in bf16, only the hi plane exists (FEPI_STORE only)
   const uint16_t* gain;        // bf16 RMSNorm gain [K] (PRO_NORM)
   float eps;
   const int32_t* row_index;    // optional gather: input row of output row m

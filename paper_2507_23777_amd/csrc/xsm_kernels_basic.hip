@@ -111,6 +111,23 @@ void launch_load_rows(int dtype, const void* emb, float* X, int n_seq, int C, in
                        C, row0, rows_per_seq, d);
 }
 
+// bf16 input rows as one MFMA operand plane in fragment order (the values are bf16 already, so
+// there is no low part): thread = 8 consecutive columns of one row, 16 bytes in and out
+__global__ void k_load_rows_plane(const uint16_t* emb, uint16_t* plane, int M, int C, int row0, int rows_per_seq, int d) {
+  const int idx = blockIdx.x * 256 + threadIdx.x, per_row = d / 8;
+  if (idx >= M * per_row) return;
+  const int m = idx / per_row, k = (idx % per_row) * 8, b = m / C, j = m % C;
+  const uint4 v = *reinterpret_cast<const uint4*>(emb + ((size_t)b * rows_per_seq + row0 + j) * d + k);
+  *reinterpret_cast<uint4*>(plane + plane_index(d, m, k)) = v;
+}
+void launch_load_rows_plane(const void* emb, void* plane, int n_seq, int C, int row0, int rows_per_seq, int d,
+                            hipStream_t s) {
+  TraceScope trace_("load_rows", s);
+  const int M = n_seq * C, n = M * (d / 8);
+  hipLaunchKernelGGL(k_load_rows_plane, dim3((n + 255) / 256), dim3(256), 0, s, (const uint16_t*)emb, (uint16_t*)plane,
+                     M, C, row0, rows_per_seq, d);
+}
+
 // ---------------------------------------------------------------------------
 // RMSNorm: Y = X * g / sqrt(mean(X^2) + eps), one workgroup per row
 // ---------------------------------------------------------------------------
