@@ -691,7 +691,7 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
   int32_t* slot = (int32_t*)(ws + ctx->ws.slot);
   XSM_HIP(hipMemcpyAsync(slot, h_slot, (size_t)n_seq * 4, hipMemcpyHostToDevice, s));
   // rows per sequence per pass: 16 on the general kernels; on the MFMA path as many as the
-  // workspace holds (whole query tiles), so that a pass streams the weights for up to 256 rows
+  // workspace holds (whole query tiles), so that a pass streams the weights for up to 2048 rows
   int chunk = kPrefillChunk;
   if (ctx->fast) {
     chunk = (int)(ctx->rows_max / n_seq) / 16 * 16;

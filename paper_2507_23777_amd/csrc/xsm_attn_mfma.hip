@@ -1,7 +1,8 @@
 // Block-causal KV-cache attention for R query rows per sequence on bf16 MFMA (gfx950),
 // head_dim 64.  Query row j of sequence b sits at position n_b + j and sees cache positions
-// 0..n_b + j (Sec. 4.2: causal mask inside the draft block x_{s:s+D}).  A workgroup takes one
-// tile of 16 query rows (a speculative step has one tile; prefill chunks have several).
+// 0..n_b + j (Sec. 4.2: causal mask inside the draft block x_{s:s+D}).  k_fattn: a workgroup takes
+// one tile of 16 query rows (a speculative step has one tile); k_pattn, further down, serves the
+// prefill passes with many tiles per sequence.
 //
 // HBM-bound: every cached key and value is read once per step, so the layout is chosen for
 // the loads.  Keys are [position][64] (128 B rows); values are stored transposed,
