@@ -749,8 +749,10 @@ static bool ws_gemm_usable(const FastGemm& g) {
 // across workgroups and no LDS staging.  The norm pass writes the rows as bf16 hi / lo planes;
 // one workgroup owns one 16-row weight tile over the whole contraction length (its four
 // wavefronts take a quarter each, fragments in registers from one request) and reads the
-// MFMA "B" fragments of all row tiles straight from the planes, one contiguous KB per request, two
-// k-tiles in flight.  The four partial tiles are summed through LDS in a fixed order.
+// MFMA "B" fragments straight from the planes, one contiguous KB per request, 64 rows (four row
+// tiles) per pass with the fragments of four k-tiles in flight: the contraction loop is a chain of L2
+// round trips, and four tiles x four k-tiles beat eight tiles x two.  The four partial tiles are
+// summed through LDS in a fixed order.
 // ---------------------------------------------------------------------------
 constexpr int kWtMaxKW = 16;                           // k-tiles per wavefront: K <= 2048
 
@@ -767,11 +769,46 @@ __device__ __forceinline__ uint4 stream_ld16(__amdgpu_buffer_rsrc_t rs, unsigned
   return uint4{v.x, v.y, v.z, v.w};
 }
 
+// k_gemm_wt: finish the 4 columns lg*4.. of weight tile nt for row m (every lane of the wavefront
+// calls it: the rotary partner, tile rows +- 8 = fragment lane ^ 32, is held by the thread PX further)
+template <int EPI, int PX>
+__device__ __forceinline__ void wt_finish(const FastGemm& g, const uint16_t* Bh, size_t lo_off, int nt, int m, int lg, f32x4 v) {
+  const int n0 = nt * 16 + lg * 4;
+  if (EPI == FEPI_QKV) {
+    float pr[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(v[e], PX, WAVE);
+    if (m < g.M) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qkv_store(g, nt, lg * 4 + e, m, v[e], pr[e]);
+    }
+  } else if (m < g.M) {
+    f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
+    if (EPI == FEPI_STORE) {
+      *y = v;
+    } else if (EPI == FEPI_ADD) {
+      *y = *y + v;
+    } else if (EPI == FEPI_GELU) {
+      *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
+    } else if (EPI == FEPI_HEAD) {
+      f32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int n = n0 + e, c = n % g.K;
+        const float pre = v[e] + bf2f(g.bias[n]);
+        const size_t pi = plane_index(g.K, m, c);
+        const float gn = bf2f(Bh[pi]) + bf2f(Bh[lo_off + pi]);
+        o[e] = gn + pre / (1.0f + __expf(-pre));
+      }
+      *y = o;
+    }
+  }
+}
+
 template <int EPI>
 __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
-  __shared__ __align__(16) float red[4][8][64][4];      // [wavefront][row tile][lane][4]
+  __shared__ __align__(16) float red[4][4][64][4];      // [wavefront][row tile][lane][4]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int r = lane & 15, gq = lane >> 4;
   const int nt = blockIdx.x, KT = g.K / 32, KW = KT / 4;
   const uint16_t* Bh = reinterpret_cast<const uint16_t*>(g.X);          // bf16 hi plane, then lo plane
   const size_t lo_off = plane_elems(g.M, g.K);
@@ -784,91 +821,68 @@ __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
     for (int i = 0; i < kWtMaxKW; ++i)
       if (i < KW) wf[i] = wb[(size_t)i * 64];
   }
-  for (int m0 = 0; m0 < g.M; m0 += 128) {
-    const int rows = min(128, g.M - m0), ntile = (rows + 15) >> 4;
-    // byte offset of this lane's piece of row tile 0, k-tile 0 of this wavefront's quarter
+  for (int m0 = 0; m0 < g.M; m0 += 64) {
+    const int ntile = (min(64, g.M - m0) + 15) >> 4;
     const unsigned bp = (unsigned)((((m0 >> 4) * KT + wave * KW) * 64 + lane) * 16);
-    f32x4 acc[8];
+    f32x4 acc[4];
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    uint4 b0[8][2], b1[8][2];
-    auto fetch = [&](uint4 (&b)[8][2], int i) {
+    for (int mt = 0; mt < 4; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 b0[4][2], b1[4][2], b2[4][2], b3[4][2];
+    auto fetch = [&](uint4 (&b)[4][2], int i) {
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt)
+      for (int mt = 0; mt < 4; ++mt)
         if (mt < ntile) {
           const unsigned o = bp + (unsigned)(mt * KT + i) * 1024u;
           b[mt][0] = stream_ld16(brs, o);
           b[mt][1] = stream_ld16(brs, o + (unsigned)lo_off * 2u);
         }
     };
-    auto mac = [&](const uint4 (&b)[8][2], const uint4& w) {
+    auto mac = [&](const uint4 (&b)[4][2], const uint4& w) {
       const bf16x8 a = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-      for (int mt = 0; mt < 8; ++mt)
+      for (int mt = 0; mt < 4; ++mt)
         if (mt < ntile) {
           acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[mt][1]), acc[mt], 0, 0, 0);
           acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, b[mt][0]), acc[mt], 0, 0, 0);
         }
     };
     fetch(b0, 0);
+    if (1 < KW) fetch(b1, 1);
+    if (2 < KW) fetch(b2, 2);
 #pragma unroll
-    for (int i = 0; i < kWtMaxKW; i += 2) {
+    for (int i = 0; i < kWtMaxKW; i += 4) {
       if (i < KW) {
-        if (i + 1 < KW) fetch(b1, i + 1);
+        if (i + 3 < KW) fetch(b3, i + 3);
         mac(b0, wf[i]);
         if (i + 1 < KW) {
-          if (i + 2 < KW) fetch(b0, i + 2);
+          if (i + 4 < KW) fetch(b0, i + 4);
           mac(b1, wf[i + 1]);
+        }
+        if (i + 2 < KW) {
+          if (i + 5 < KW) fetch(b1, i + 5);
+          mac(b2, wf[i + 2]);
+        }
+        if (i + 3 < KW) {
+          if (i + 6 < KW) fetch(b2, i + 6);
+          mac(b3, wf[i + 3]);
         }
       }
     }
-    __syncthreads();                                   // red is free (previous row block finished)
+    __syncthreads();                                   // red is free (previous pass finished)
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt)
+    for (int mt = 0; mt < 4; ++mt)
       if (mt < ntile) *reinterpret_cast<f32x4*>(&red[wave][mt][lane][0]) = acc[mt];
     __syncthreads();
-    // thread: row tile tid/32, lanes 2(tid%32), +1 of it
-    const int mt = tid >> 5;
+    // thread: row tile tid / 64, lane tid % 64 of it
+    const int mt = tid >> 6;
     if (mt < ntile) {
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int ll = (tid & 31) * 2 + q, lr = ll & 15, lg = ll >> 4;
-        f32x4 v = *reinterpret_cast<const f32x4*>(&red[0][mt][ll][0]);
-        v += *reinterpret_cast<const f32x4*>(&red[1][mt][ll][0]);
-        f32x4 v2 = *reinterpret_cast<const f32x4*>(&red[2][mt][ll][0]);
-        v2 += *reinterpret_cast<const f32x4*>(&red[3][mt][ll][0]);
-        v += v2;
-        const int m = m0 + mt * 16 + lr, n0 = nt * 16 + lg * 4;
-        if (EPI == FEPI_QKV) {
-          float pr[4];                                  // rows +- 8 of the tile: lane ll ^ 32, thread ^ 16
-#pragma unroll
-          for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(v[e], 16, WAVE);
-          if (m < g.M) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) qkv_store(g, nt, lg * 4 + e, m, v[e], pr[e]);
-          }
-        } else if (m < g.M) {
-          f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
-          if (EPI == FEPI_STORE) {
-            *y = v;
-          } else if (EPI == FEPI_ADD) {
-            *y = *y + v;
-          } else if (EPI == FEPI_GELU) {
-            *y = f32x4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
-          } else if (EPI == FEPI_HEAD) {
-            f32x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int n = n0 + e, c = n % g.K;
-              const float pre = v[e] + bf2f(g.bias[n]);
-              const size_t pi = plane_index(g.K, m, c);
-              const float gn = bf2f(Bh[pi]) + bf2f(Bh[lo_off + pi]);
-              o[e] = gn + pre / (1.0f + __expf(-pre));
-            }
-            *y = o;
-          }
-        }
-      }
+      const int ll = tid & 63, lr = ll & 15, lg = ll >> 4;
+      f32x4 v = *reinterpret_cast<const f32x4*>(&red[0][mt][ll][0]);
+      v += *reinterpret_cast<const f32x4*>(&red[1][mt][ll][0]);
+      f32x4 v2 = *reinterpret_cast<const f32x4*>(&red[2][mt][ll][0]);
+      v2 += *reinterpret_cast<const f32x4*>(&red[3][mt][ll][0]);
+      v += v2;
+      wt_finish<EPI, 32>(g, Bh, lo_off, nt, m0 + mt * 16 + lr, lg, v);
     }
   }
 }

@@ -383,6 +383,23 @@ def _c1_small(**kw):
     return cfg
 
 
+def test_mid_batch_few_rows_on_the_wide_model(X):
+    """M = 35 block rows (7 sequences, K = 4) and 28 head rows at d = 1024: the mid-batch kernels'
+    variant for up to 64 rows (QKV, GELU, unembedding and head epilogues), ragged lengths, and a
+    46-row batch with top-8 acceptance and categorical draws."""
+    cfg = _c1_small(n_layers=2)
+    lens = [70, 33, 5, 64, 17, 48, 21]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 7, prefix_lens=lens)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 7))
+    _report(tal, "B7 d1024")
+    cfg = _c1_small(n_layers=2, n_draft=1)
+    lens = [5 + 3 * b for b in range(23)]
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 23, prefix_lens=lens)
+    vp = VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=78)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 2, si.first_block(cfg, 23))
+    _report(tal, "B23 K1 d1024 top-8")
+
+
 @pytest.mark.parametrize("single_launch", [1, 0])
 def test_single_launch_step_matches_oracle_and_per_stage_kernels(X, single_launch):
     cfg = _c1_small()
