@@ -744,7 +744,7 @@ static bool ws_gemm_usable(const FastGemm& g) {
 }
 
 // ---------------------------------------------------------------------------
-// Same M range, projections whose input is a normalised row block and that have at least 128
+// Same M range, projections whose input is a normalised row block and that have at least 64
 // column tiles (QKV, FFN up, unembedding, stacked heads): no split of the contraction index
 // across workgroups and no LDS staging.  The norm pass writes the rows as bf16 hi / lo planes;
 // one workgroup owns one 16-row weight tile over the whole contraction length (its four
@@ -888,7 +888,7 @@ __global__ __launch_bounds__(256) void k_gemm_wt(const FastGemm g) {
 }
 
 static bool wt_gemm_usable(int pro, const FastGemm& g) {
-  return pro == PRO_NORM && g.M > 16 && g.M <= kWsMaxM && g.N % 16 == 0 && g.N / 16 >= 128 && g.K % 128 == 0 &&
+  return pro == PRO_NORM && g.M > 16 && g.M <= kWsMaxM && g.N % 16 == 0 && g.N / 16 >= 64 && g.K % 128 == 0 &&
          g.K / 128 <= kWtMaxKW && g.nscratch;
 }
 
