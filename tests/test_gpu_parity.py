@@ -564,6 +564,19 @@ def test_step_replayed_from_a_captured_graph(X, path):
     eng.xsm_check_device()
 
 
+def test_model_without_draft_heads(X):
+    """Degenerate case K = 0: no decoding heads, only next-token decoding exists (both dtypes'
+    kernels); a speculative step is refused."""
+    for cfg in (si.tiny_config(n_layers=2, d_model=64, n_heads=2, head_dim=32, d_ffn=128, vocab=64, n_draft=0,
+                               dtype="fp32", max_ctx=96, seed=13),
+                _mid_cfg(seed=53, n_layers=2, n_draft=0)):
+        w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[9, 4])
+        tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 5, [[1], [2]], plain=True)
+        _report(tal, f"K=0 plain {cfg['dtype']}")
+        with pytest.raises(X.xsm.XsmError, match="n_draft"):
+            eng.xsm_spec_step(eng.buffers(2, spec=False), X.H.to_vp_gpu(X.xsm, GREEDY), 32)
+
+
 def test_argument_and_device_side_errors(X):
     cfg = _mid_cfg(seed=28, n_layers=1)
     torch = X.torch
@@ -579,6 +592,10 @@ def test_argument_and_device_side_errors(X):
     bad = X.xsm.xsm_verify_params(1, 0, 0.5, 1.0, 0, 0)
     with pytest.raises(X.xsm.XsmError, match="top_ka"):
         eng.xsm_spec_step(buf, bad, 100)
+    empty = eng.buffers(2, spec=True)
+    empty.n_seq = 0                                   # an empty batch is an argument error, nothing is enqueued
+    with pytest.raises(X.xsm.XsmError):
+        eng.xsm_spec_step(empty, vpg, 100)
     # device-side: sequence 0 has a token outside the vocabulary, sequence 1 is fine
     buf.block[0, 2] = cfg["vocab"] + 5
     eng.xsm_spec_step(buf, vpg, cfg["prefix"])
