@@ -7,8 +7,9 @@
  *     block (Sec. 4.1 first paragraph, Sec. 4.2, Alg. 1 "forward with causal mask"),
  *   - the backbone distribution p^(0) = softmax(W^(0) h) (Eq. 3),
  *   - K decoding heads on the same final hidden state, head d predicting the
- *     token d+1 positions ahead (Eq. 4; here the MLP head of Table 3 rows B/C:
- *     r = h + SiLU(W_d h + b_d), logits through the shared unembedding),
+ *     token d+1 positions ahead (Eq. 4): the MLP head of Table 3 rows B/C,
+ *     r = h + SiLU(W_d h + b_d) with logits through the shared unembedding, or
+ *     the cross-attention head of rows D/E with its own unembedding W^(d),
  *   - verification: accept candidates until the first one that fails the
  *     criterion, resample K+1 tokens at the first rejected position
  *     (Sec. 4.2, Fig. 3, Alg. 1 inner loop and resample line),
@@ -181,7 +182,8 @@ XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verif
  * instead of one kernel per stage (greedy verification with argmax draws also finishes inside it;
  * the other criteria and sampling rules follow in the verify / emit kernels); 0 forces the
  * per-stage kernels.  XSM_OPT_ATTN_SPLITS (tuning aid, default 0 = automatic): key-range slices per
- * (sequence, head) of the per-stage attention kernel. */
+ * (sequence, head) of the attention kernel / stage (the single-launch step takes the largest power
+ * of two not above it). */
 enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2, XSM_OPT_ATTN_SPLITS = 3 };
 XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
 
