@@ -930,20 +930,29 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   if (w < a.n_seq && !a.defer_verify) {
     const int b = w;
     const int n = sm.len[b];
-    // global top-2 of rows: backbone rows b*R + j (j < R) and head rows ((b*R + j)*K + k)
-    const int nrows_b = R + R * K;
-    for (int q = wave; q < nrows_b; q += 4) {
-      const int grow = q < R ? b * R + q : M + (b * R + (q - R) / K) * K + (q - R) % K;
+    // global top-2 of a logits row from the per-tile statistics (one wavefront per row, four tiles
+    // per lane and request, all twelve words of a request in flight together) -> slot q of sm.st_*
+    auto row_top2 = [&](int q, int grow) {
       float bv = -INFINITY, sv = -INFINITY;
       int bi = 0x7FFFFFFF;
-      for (int t = lane; t < NTV; t += 64) {
-        const int off[3] = {0, 1, 2};
-        uint32_t pw[3];
-        ll_wait_list<3>(tb + OFF_ST + ((size_t)t * kSmallMaxRows + grow) * 4, off, tag, pw, ok);
-        const float tv = __uint_as_float(pw[0]), ts = __uint_as_float(pw[2]);
-        const int ti = (int)pw[1];
-        if (tv > bv || (tv == bv && ti < bi)) { sv = fmaxf(bv, fmaxf(sv, ts)); bv = tv; bi = ti; }
-        else sv = fmaxf(sv, fmaxf(tv, ts));
+      for (int t0 = 0; t0 < NTV; t0 += 256) {
+        int off[12];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int t = t0 + lane + 64 * i;
+#pragma unroll
+          for (int j = 0; j < 3; ++j) off[3 * i + j] = t < NTV ? (t * kSmallMaxRows + grow) * 4 + j : -1;
+        }
+        uint32_t pw[12];
+        ll_wait_list<12>(tb + OFF_ST, off, tag, pw, ok);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (off[3 * i] < 0) continue;
+          const float tv = __uint_as_float(pw[3 * i]), ts = __uint_as_float(pw[3 * i + 2]);
+          const int ti = (int)pw[3 * i + 1];
+          if (tv > bv || (tv == bv && ti < bi)) { sv = fmaxf(bv, fmaxf(sv, ts)); bv = tv; bi = ti; }
+          else sv = fmaxf(sv, fmaxf(tv, ts));
+        }
       }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) {
@@ -954,7 +963,18 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         if (take) { bv = bv2; bi = bi2; }
       }
       if (lane == 0) { sm.st_max[q] = bv; sm.st_sec[q] = sv; sm.st_idx[q] = bi; }
-    }
+    };
+    // the R backbone rows first; they fix the accepted length, and only the K head rows of that
+    // position are needed after it (slots R .. R + K - 1)
+    for (int q = wave; q < R; q += 4) row_top2(q, b * R + q);
+    __syncthreads();
+    int acc_all = 0;                                      // (every thread: same values, same result)
+    if (n >= 0)
+      for (int j = 1; j <= K; ++j) {
+        if (a.block[b * R + j] != sm.st_idx[j - 1]) break;
+        ++acc_all;
+      }
+    for (int k = wave; k < K; k += 4) row_top2(R + k, M + (b * R + acc_all) * K + k);
     __syncthreads();
     if (tid == 0) {
       uint32_t fl = sm.flag[b];
@@ -978,7 +998,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         for (int j = acc_n + 1; j < R; ++j) a.out_tokens[b * R + j] = -1;
         a.block[b * R] = y0;
         for (int k = 0; k < K; ++k) {
-          const int q = R + acc_n * K + k;
+          const int q = R + k;
           a.block[b * R + 1 + k] = sm.st_idx[q];
           if (sm.st_max[q] - sm.st_sec[q] <= kTieMarginS) fl |= XSM_FLAG_NEAR_TIE;
         }
