@@ -183,8 +183,9 @@ XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verif
  * the other criteria and sampling rules follow in the verify / emit kernels); 0 forces the
  * per-stage kernels.  XSM_OPT_ATTN_SPLITS (tuning aid, default 0 = automatic): key-range slices per
  * (sequence, head) of the attention kernel / stage (the single-launch step takes the largest power
- * of two not above it). */
-enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2, XSM_OPT_ATTN_SPLITS = 3 };
+ * of two not above it).  XSM_OPT_PREFILL_ROWS (tuning aid, default 0 = as many as the workspace
+ * holds, 8192): upper limit of the rows (sequences x positions) one prefill pass takes. */
+enum { XSM_OPT_SINGLE_LAUNCH = 1, XSM_OPT_TIMELINE = 2, XSM_OPT_ATTN_SPLITS = 3, XSM_OPT_PREFILL_ROWS = 4 };
 XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
 
 /* Tuning aid.  With XSM_OPT_TIMELINE = 1 every workgroup of the single-launch step stamps the

@@ -691,10 +691,12 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
   int32_t* slot = (int32_t*)(ws + ctx->ws.slot);
   XSM_HIP(hipMemcpyAsync(slot, h_slot, (size_t)n_seq * 4, hipMemcpyHostToDevice, s));
   // rows per sequence per pass: 16 on the general kernels; on the MFMA path as many as the
-  // workspace holds (whole query tiles), so that a pass streams the weights for up to 2048 rows
+  // workspace holds (whole query tiles), so that a pass streams the weights for up to 8192 rows
   int chunk = kPrefillChunk;
   if (ctx->fast) {
-    chunk = (int)(ctx->rows_max / n_seq) / 16 * 16;
+    size_t pass_rows = ctx->rows_max;
+    if (ctx->prefill_rows > 0 && (size_t)ctx->prefill_rows < pass_rows) pass_rows = ctx->prefill_rows;
+    chunk = (int)(pass_rows / n_seq) / 16 * 16;
     if (chunk > kFastPassRows) chunk = kFastPassRows;
     if (chunk < 16) chunk = 16;
   }
@@ -762,6 +764,7 @@ int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value) {
   if (option == XSM_OPT_SINGLE_LAUNCH) { ctx->use_small = value != 0; return XSM_OK; }
   if (option == XSM_OPT_TIMELINE) { ctx->timeline = value != 0; return XSM_OK; }
   if (option == XSM_OPT_ATTN_SPLITS) { ctx->force_splits = value > 0 ? value : 0; return XSM_OK; }
+  if (option == XSM_OPT_PREFILL_ROWS) { ctx->prefill_rows = value > 0 ? value : 0; return XSM_OK; }
   return fail(ctx, XSM_EINVAL, "unknown option");
 }
 

@@ -11,7 +11,7 @@
 namespace xsm {
 
 constexpr int kPrefillChunk = 16;   // prefix rows per sequence per backbone pass (general kernels)
-constexpr int kFastPassRows = 2048; // rows of one backbone pass the MFMA path's workspace always holds (prefill chunks)
+constexpr int kFastPassRows = 8192; // rows of one backbone pass the MFMA path's workspace always holds (prefill chunks)
 constexpr int kMaxRows = 16;        // rows per sequence per pass (K+1 <= 16)
 
 // Element offsets of the canonical weight tensors (same order as the weight file).
@@ -78,6 +78,7 @@ struct xsm_ctx {
   bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
   bool timeline = false;   // xsm_set_option(XSM_OPT_TIMELINE)
   int force_splits = 0;    // xsm_set_option(XSM_OPT_ATTN_SPLITS): key-range slices per (sequence, head), 0 = automatic
+  int prefill_rows = 0;              // XSM_OPT_PREFILL_ROWS: rows per prefill pass, 0 = what the workspace holds
   size_t layer_tab_off = 0;              // byte offset of the LayerTab array in the weights buffer
   std::vector<xsm::LayerTab> layer_tab;  // host copy (source of the upload)
   xsm::TiledOff toff;

@@ -13,6 +13,7 @@ XSM_HEAD_MLP, XSM_HEAD_CA = 0, 1
 XSM_OPT_SINGLE_LAUNCH = 1
 XSM_OPT_TIMELINE = 2
 XSM_OPT_ATTN_SPLITS = 3
+XSM_OPT_PREFILL_ROWS = 4
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libxsm.so")
 API = ["xsm_create", "xsm_destroy", "xsm_last_error", "xsm_weights_bytes", "xsm_kv_bytes",

@@ -196,10 +196,11 @@ def test_cross_attention_decoding_heads(X):
 
 
 def test_prefill_in_large_chunks(X):
-    """Prefill on the MFMA path runs up to 2048 rows per pass (many 16-row query tiles per sequence,
+    """Prefill on the MFMA path runs up to 8192 rows per pass (many 16-row query tiles per sequence,
     causal inside the chunk, the row-blocked GEMMs with a ragged last block): one sequence with a
-    300-token prefix in one pass, a ragged batch, and three sequences of 900 tokens, which take two
-    passes (672 + 228 rows each); the cache must match the oracle's and the steps after it too."""
+    300-token prefix in one pass, a ragged batch, and three sequences of 900 tokens, in one pass of
+    2700 rows and, with the pass size limited to 2048 rows, in two passes (672 + 228 rows each); the
+    cache must match the oracle's and the steps after it too."""
     cfg = _mid_cfg(prefix=300, seed=41, n_layers=2, max_ctx=512)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1)
     for l in range(cfg["n_layers"]):
@@ -215,19 +216,20 @@ def test_prefill_in_large_chunks(X):
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 3))
     _report(tal, "prefix 150/97/16 B3")
     cfg = _mid_cfg(prefix=900, seed=43, n_layers=2, max_ctx=1024)
-    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3)
-    for b in (0, 2):
-        for which, ref in ((0, states[b].k[1]), (1, states[b].v[1])):
-            got = eng.xsm_debug_kv_export(1, which, b, 0, 900)
-            want = np.transpose(np.asarray(ref[:900], np.float64), (1, 0, 2))
-            err = np.abs(got - want).max() / np.abs(want).max()
-            assert err < 1e-2, (b, which, err)
-    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 3))
-    _report(tal, "prefix 900 B3 (two passes)")
+    for pass_rows in (0, 2048):
+        w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3, options=[(X.xsm.XSM_OPT_PREFILL_ROWS, pass_rows)])
+        for b in (0, 2):
+            for which, ref in ((0, states[b].k[1]), (1, states[b].v[1])):
+                got = eng.xsm_debug_kv_export(1, which, b, 0, 900)
+                want = np.transpose(np.asarray(ref[:900], np.float64), (1, 0, 2))
+                err = np.abs(got - want).max() / np.abs(want).max()
+                assert err < 1e-2, (pass_rows, b, which, err)
+        tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 3, si.first_block(cfg, 3))
+        _report(tal, f"prefix 900 B3 (pass limit {pass_rows})")
 
 
 def test_prefill_pass_with_operand_planes_end_to_end(X):
-    """A 2048-row pass at d = 1024: the residual-add projections have enough blocks for the
+    """A 2048-row pass at d = 1024 (the same chain serves passes of up to 8192 rows): the residual-add projections have enough blocks for the
     row-blocked kernel, so attention and the FFN-up epilogue hand them bf16 hi/lo operand planes
     instead of fp32 rows.  Second-layer cache and the steps after it against the oracle."""
     cfg = _c1_small(n_layers=2, prefix=2048, max_ctx=2112)

@@ -100,13 +100,17 @@ def to_vp_gpu(xsm, vp: VerifyParams):
                                  vp.top_ks, vp.pts_prune)
 
 
-def setup_pair(cfg, engine_cls, n_seq, prefix_lens=None, perturb=True, max_ctx=None, kv_dtype=np.float64):
+def setup_pair(cfg, engine_cls, n_seq, prefix_lens=None, perturb=True, max_ctx=None, kv_dtype=np.float64,
+               options=()):
     """Weights, oracle states and a GPU engine prefilled with the same condition prefixes.
-    prefix_lens: per-sequence prefix lengths (ragged batches); default cfg['prefix']."""
+    prefix_lens: per-sequence prefix lengths (ragged batches); default cfg['prefix'].
+    options: (option, value) pairs set on the engine before the prefill."""
     w = si.make_weights(cfg, perturb=perturb)
     orc = Oracle(cfg, w, kv_dtype=kv_dtype)
     eng = engine_cls(cfg, max_batch=n_seq, max_ctx=max_ctx or cfg["max_ctx"])
     eng.xsm_load_weights(si.pack_canonical(cfg, w))
+    for opt, val in options:
+        eng.xsm_set_option(opt, val)
     prefix_lens = prefix_lens or [cfg["prefix"]] * n_seq
     pmax = max(prefix_lens)
     prefix = si.make_prefix(cfg, n_seq, P=pmax) if pmax > 0 else None
