@@ -145,3 +145,18 @@ def test_batcher_admission_compaction_budget_and_eos(spec):
         bt.submit(Request(first_block=[1] * R, max_new_tokens=500))          # does not fit max_ctx
     with pytest.raises(ValueError):
         bt.submit(Request(first_block=[1], max_new_tokens=5) if spec else Request(first_block=[], max_new_tokens=5))
+
+
+def test_algorithmic_bytes_of_the_workloads():
+    """The roofline's numerator: weights once + cached keys/values once + new keys/values + logits.
+    Hand-computed figures of three workloads: config 1 at context 257 (620.8 MB of weights, 25.3 MB
+    of cache), config 4 at batch 128, K = 8, context 10000 (327.2 MB, 62.9 GB), config 3 at batch 8,
+    context 16384 (1.63 GB, 19.3 GB of self-attention cache and 2.4 GB of condition keys/values)."""
+    import bench
+    import synth_inputs as si
+    c1 = si.get_config("c1")
+    assert abs(bench.algorithmic_bytes(c1, 1, 257) - (620.8e6 + 25.3e6 + 0.5e6 + 0.15e6)) < 0.5e6
+    c4 = si.get_config("c4", batch=128, n_draft=8)
+    assert abs(bench.algorithmic_bytes(c4, 128, 128 * 10000) - (0.3272e9 + 62.91e9 + 0.057e9 + 0.036e9)) < 0.02e9
+    c3 = si.get_config("c3")
+    assert abs(bench.algorithmic_bytes(c3, 8, 8 * 16384) - (1.63e9 + 19.33e9 + 2.42e9)) < 0.02e9
