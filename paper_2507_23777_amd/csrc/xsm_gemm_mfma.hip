@@ -743,6 +743,41 @@ static bool ws_gemm_usable(const FastGemm& g) {
          (size_t)(g.N / 64) * ((g.M + kWsBM - 1) / kWsBM) <= kWsTickets;
 }
 
+// the same epilogue for four consecutive tile rows of one activation row (vector stores)
+struct QkvRow { int m, pos; size_t head0; bool ok; };
+__device__ __forceinline__ QkvRow qkv_row(const FastGemm& g, int m) {
+  QkvRow q{m, 0, 0, false};
+  if (m < g.M) {
+    const int b = m / g.R, j = m - b * g.R;
+    const int len = g.eff_len[b];
+    if (len >= 0) { q.pos = len + j; q.head0 = (size_t)g.slot[b] * g.H; q.ok = true; }
+  }
+  return q;
+}
+// four consecutive tile rows (n..n+3, n a multiple of 4) of row q.m: v and the values 8 tile rows away
+__device__ __forceinline__ void qkv_quad_store(const FastGemm& g, const QkvCols& c, const QkvRow& q, f32x4 v, f32x4 partner) {
+  if (!q.ok) return;
+  f32x4 o = v;
+  if (c.sec < 2) {
+    const float4* rp = reinterpret_cast<const float4*>(&g.rope[(size_t)q.pos * (g.hd / 2) + c.pi0]);
+    const float4 cs0 = rp[0], cs1 = rp[1];             // (cos, sin) of pi0, pi0+1 | pi0+2, pi0+3
+    const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = c.low ? v[e] * co[e] - partner[e] * si[e] : partner[e] * si[e] + v[e] * co[e];
+  }
+  const size_t head = q.head0 + c.h;
+  if (c.sec == 0) {
+    *reinterpret_cast<f32x4*>(g.Y + (size_t)q.m * g.ldy + c.h * g.hd + c.dim0) = o;
+  } else if (c.sec == 1) {
+    *reinterpret_cast<uint2*>(g.Kc + (head * g.cap + q.pos) * g.hd + c.dim0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+  } else if (g.v_transposed) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) g.Vc[(head * g.hd + c.dim0 + e) * g.cap + q.pos] = f2bf(o[e]);
+  } else {
+    *reinterpret_cast<uint2*>(g.Vc + (head * g.cap + q.pos) * g.hd + c.dim0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Same M range, projections whose input is a normalised row block and that have at least 64
 // column tiles (QKV, FFN up, unembedding, stacked heads): no split of the contraction index
@@ -775,13 +810,10 @@ template <int EPI, int PX>
 __device__ __forceinline__ void wt_finish(const FastGemm& g, const uint16_t* Bh, size_t lo_off, int nt, int m, int lg, f32x4 v) {
   const int n0 = nt * 16 + lg * 4;
   if (EPI == FEPI_QKV) {
-    float pr[4];
+    f32x4 pr;
 #pragma unroll
     for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(v[e], PX, WAVE);
-    if (m < g.M) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) qkv_store(g, nt, lg * 4 + e, m, v[e], pr[e]);
-    }
+    qkv_quad_store(g, qkv_cols(g, n0), qkv_row(g, m), v, pr);
   } else if (m < g.M) {
     f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
     if (EPI == FEPI_STORE) {
@@ -933,40 +965,6 @@ static void wt_gemm(int epi, FastGemm g, hipStream_t s) {
 // KB per wavefront request), one barrier per stage.  No split of the contraction index; row
 // blocks of one weight block run next to each other on one XCD.
 // ---------------------------------------------------------------------------
-struct QkvRow { int m, pos; size_t head0; bool ok; };
-__device__ __forceinline__ QkvRow qkv_row(const FastGemm& g, int m) {
-  QkvRow q{m, 0, 0, false};
-  if (m < g.M) {
-    const int b = m / g.R, j = m - b * g.R;
-    const int len = g.eff_len[b];
-    if (len >= 0) { q.pos = len + j; q.head0 = (size_t)g.slot[b] * g.H; q.ok = true; }
-  }
-  return q;
-}
-// four consecutive tile rows (n..n+3, n a multiple of 4) of row q.m: v and the values 8 tile rows away
-__device__ __forceinline__ void qkv_quad_store(const FastGemm& g, const QkvCols& c, const QkvRow& q, f32x4 v, f32x4 partner) {
-  if (!q.ok) return;
-  f32x4 o = v;
-  if (c.sec < 2) {
-    const float4* rp = reinterpret_cast<const float4*>(&g.rope[(size_t)q.pos * (g.hd / 2) + c.pi0]);
-    const float4 cs0 = rp[0], cs1 = rp[1];             // (cos, sin) of pi0, pi0+1 | pi0+2, pi0+3
-    const float co[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, si[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = c.low ? v[e] * co[e] - partner[e] * si[e] : partner[e] * si[e] + v[e] * co[e];
-  }
-  const size_t head = q.head0 + c.h;
-  if (c.sec == 0) {
-    *reinterpret_cast<f32x4*>(g.Y + (size_t)q.m * g.ldy + c.h * g.hd + c.dim0) = o;
-  } else if (c.sec == 1) {
-    *reinterpret_cast<uint2*>(g.Kc + (head * g.cap + q.pos) * g.hd + c.dim0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-  } else if (g.v_transposed) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) g.Vc[(head * g.hd + c.dim0 + e) * g.cap + q.pos] = f2bf(o[e]);
-  } else {
-    *reinterpret_cast<uint2*>(g.Vc + (head * g.cap + q.pos) * g.hd + c.dim0) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-  }
-}
-
 constexpr int kBlkKC = 64, kBlkST = kBlkKC + 8;        // contraction slice per stage, LDS row stride (bf16)
 constexpr int kBlkKT = kBlkKC / 32;
 
