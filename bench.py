@@ -107,7 +107,32 @@ def fixed_point(args, torch, pkg, xsm, si) -> int:
     xsm.xsm_debug_trace_enable(False)
     eng.xsm_check_device()
     by = algorithmic_bytes(cfg, B, B * ctx)
+    cpu = None
+    if args.cpu_baseline_at_point:
+        # the oracle on one sequence at the same context (cache of zeros, like the GPU's), a few
+        # steps; sequences are independent, so the whole batch costs B times that
+        import numpy as np
+        from threadpoolctl import threadpool_info
+        from oracle import Oracle, VerifyParams
+        del eng
+        orc = Oracle(cfg, si.make_weights(cfg), kv_dtype=np.float32)
+        st = orc.new_state(cap=ctx + 4 * R + 8)
+        if cfg["n_cond"]:
+            orc.prefill(st, None, si.make_cond(cfg, 1)[0])
+        for l in range(cfg["n_layers"]):
+            st.k[l][:ctx] = 0.0; st.v[l][:ctx] = 0.0
+        st.n = ctx
+        block, n, t1 = list(map(int, si.first_block(cfg, 1)[0])), 0, time.perf_counter()
+        while n < 3 or (time.perf_counter() - t1 < 10.0 and n < 20):
+            block = orc.spec_step(st, block, VerifyParams())["next_block"]; st.n = ctx; n += 1
+        el = (time.perf_counter() - t1) / n
+        cpu = {"kind": "oracle", "ms_per_step_one_sequence": round(1e3 * el, 1), "steps": n,
+               "verified_tok_per_s_batch": round(R / el, 2),
+               "cores": int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1])),
+               "sample": f"{n} speculative steps of one sequence at context {ctx}, float64 numpy with a float32 cache; "
+                         f"a batch of {B} independent sequences takes {B} times as long per step, so the rate is the same"}
     print(json.dumps({"workload": f"{name} batch {B} K={K} context {ctx}", "steps": args.steps, "ms_per_step": round(ms, 4),
+                      "cpu_baseline": cpu,
                       "note": "ms_per_step from an untraced pass; the kernel breakdown from a second pass with per-launch event pairs",
                       "verified_tok_per_s": round(B * R / ms * 1e3, 1), "hbm_frac": round(by / (ms * 1e6) / HBM_PEAK_GBS, 4),
                       "kernels": {k: {"launches_per_step": v[0] / args.steps, "us_per_launch": round(1e3 * v[1] / v[0], 2)}
@@ -122,6 +147,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-at-point", action="store_true",
+                    help="with --fixed-point: also time the oracle on one sequence at that context")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the untimed extras (latency spread, fixed-context points): profiling runs then see "
                          "only the warm-up and timed steps")
