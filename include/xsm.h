@@ -139,6 +139,10 @@ XSM_API size_t xsm_weights_bytes(const xsm_ctx* ctx);        /* weights in libra
 XSM_API size_t xsm_kv_bytes(const xsm_ctx* ctx);             /* self- and cross-attention caches */
 XSM_API size_t xsm_workspace_bytes(const xsm_ctx* ctx);      /* per-step activations and partials */
 XSM_API size_t xsm_canonical_weight_elems(const xsm_ctx* ctx); /* elements in the canonical weight file */
+/* Bind the three buffers (device pointers, owned by the caller, alive until xsm_destroy).  Call
+ * with the buffers' device current: the device's compute-unit count is read here (the
+ * single-launch step needs 256 units, one per workgroup; smaller devices and partitions take the
+ * per-stage kernels).  XSM_EINVAL on a null or misaligned pointer. */
 XSM_API int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspace);
 
 /* Upload weights.  h_canonical: host array of n_elems elements of cfg.dtype
@@ -177,8 +181,8 @@ XSM_API int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify
 XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
                    xsm_stream stream);
 
-/* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total and
- * the model shape is supported, run backbone, heads and unembedding as one persistent kernel
+/* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total,
+ * the model shape is supported and the device has 256 compute units, run backbone, heads and unembedding as one persistent kernel
  * instead of one kernel per stage (greedy verification with argmax draws also finishes inside it;
  * the other criteria and sampling rules follow in the verify / emit kernels); 0 forces the
  * per-stage kernels.  XSM_OPT_ATTN_SPLITS (tuning aid, default 0 = automatic): key-range slices per

@@ -360,7 +360,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   const char* wb = ctx->d_w;
   const size_t e = ctx->esz;
 
-  if (ctx->small_ok && ctx->use_small && M <= 16 && M + M * K <= kSmallMaxRows && n_seq * g.n_heads <= 256) {
+  if (ctx->small_ok && ctx->small_dev && ctx->use_small && M <= 16 && M + M * K <= kSmallMaxRows && n_seq * g.n_heads <= 256) {
     // the whole step as one persistent kernel; greedy verification with argmax draws finishes inside
     // it, the other criteria and sampling rules run on its logits in the verify / emit kernels
     const bool defer = !(vp->mode == XSM_VERIFY_GREEDY && vp->sample == 0);
@@ -597,6 +597,16 @@ int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspace) {
     return fail(ctx, XSM_EINVAL, "buffers must be 256-byte aligned");
   ctx->d_w = (char*)d_weights; ctx->d_kv = (char*)d_kv; ctx->d_ws = (char*)d_workspace;
   ctx->loaded = false;
+  // The single-launch step hands data between its 256 workgroups, one per compute unit (each
+  // takes most of a unit's LDS), so all of them must be resident together: a device, or a
+  // partition of one, with fewer units takes the per-stage path.
+  ctx->small_dev = false;
+  if (ctx->small_ok) {
+    int dev = 0, units = 0;
+    XSM_HIP(hipGetDevice(&dev));
+    XSM_HIP(hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, dev));
+    ctx->small_dev = units >= 256;
+  }
   return XSM_OK;
 }
 

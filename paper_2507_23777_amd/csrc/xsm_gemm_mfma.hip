@@ -397,11 +397,7 @@ static void big_launch_t(const FastGemm& g, hipStream_t s) {
   const int MB = (g.M + BM - 1) / BM;
   const size_t lds = (size_t)2 * BM * (kBigKC + 8) * 2;
   auto kfn = k_gemm_big<EPI, MTW>;
-  static bool configured = false;
-  if (!configured && lds > 64 * 1024) {
-    (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = true;
-  }
+  allow_dynamic_lds((const void*)kfn, lds);
   hipLaunchKernelGGL(kfn, dim3((g.N / 32) * MB), dim3(256), lds, s, g);
 }
 template <int EPI>
@@ -730,11 +726,7 @@ template <int EPI, bool RED>
 static void ws_launch(const FastGemm& g, hipStream_t s) {
   const size_t lds = (size_t)2 * kWsPlane * 2;
   auto kfn = k_gemm_ws<EPI, RED>;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = true;
-  }
+  allow_dynamic_lds((const void*)kfn, lds);
   hipLaunchKernelGGL(kfn, dim3((g.N / 64) * (g.K / kWsKS)), dim3(256), lds, s, g);
 }
 
@@ -1127,11 +1119,7 @@ static void blk_launch_t(const FastGemm& g, hipStream_t s) {
   constexpr int BN = 32 * WN, BM = 32 * WM;
   const size_t lds = (size_t)2 * (SINGLE ? 1 : 2) * BM * kBlkST * 2;
   auto kfn = k_gemm_blk<EPI, WN, WM, SINGLE>;
-  static bool configured = false;
-  if (!configured && lds > 64 * 1024) {
-    (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = true;
-  }
+  allow_dynamic_lds((const void*)kfn, lds);
   hipLaunchKernelGGL(kfn, dim3((g.N / BN) * ((g.M + BM - 1) / BM)), dim3(256), lds, s, g);
 }
 template <int EPI>
@@ -1202,11 +1190,7 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 #define XSM_FG(MTV)                                                                             \
   {                                                                                             \
     auto kfn = k_fgemm<PRO, EPI, MTV>;                                                          \
-    static size_t configured = 0;                                                               \
-    if (lds > 64 * 1024 && lds > configured) {                                                  \
-      (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)budget); \
-      configured = budget;                                                                      \
-    }                                                                                           \
+    allow_dynamic_lds((const void*)kfn, lds > 64 * 1024 ? budget : lds);                         \
     hipLaunchKernelGGL(kfn, grid, blk, lds, s, g);                                              \
   }
   if (MT == 1) XSM_FG(1) else if (MT == 2) XSM_FG(2) else XSM_FG(4)

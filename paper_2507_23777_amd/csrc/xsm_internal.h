@@ -3,7 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <map>
+#include <mutex>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/xsm.h"
@@ -76,6 +79,7 @@ struct xsm_ctx {
   bool fast = false;       // bf16 MFMA path (head_dim 64, values cached transposed)
   bool small_ok = false;   // single-launch step available for this model shape
   bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
+  bool small_dev = false;  // the bound device can hold the single launch's 256 workgroups at once
   bool timeline = false;   // xsm_set_option(XSM_OPT_TIMELINE)
   int force_splits = 0;    // xsm_set_option(XSM_OPT_ATTN_SPLITS): key-range slices per (sequence, head), 0 = automatic
   int prefill_rows = 0;              // XSM_OPT_PREFILL_ROWS: rows per prefill pass, 0 = what the workspace holds
@@ -97,6 +101,22 @@ namespace xsm {
 
 // Optional per-kernel timing with HIP events on the launch stream (off by default; used by
 // the benchmark to attribute step time to kernels).  A scope brackets one launch.
+// A kernel's dynamic-LDS limit above 64 KB is a property of (kernel, device): raised once for
+// each pair, and again if a later launch of the kernel needs more.
+inline void allow_dynamic_lds(const void* kfn, size_t bytes) {
+  if (bytes <= 64 * 1024) return;
+  static std::mutex mu;
+  static std::map<std::pair<const void*, int>, size_t> granted;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  std::lock_guard<std::mutex> lock(mu);
+  size_t& have = granted[{kfn, dev}];
+  if (bytes > have) {
+    (void)hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    have = bytes;
+  }
+}
+
 struct TraceScope {
   TraceScope(const char* name, hipStream_t s);
   ~TraceScope();

@@ -1039,11 +1039,7 @@ void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
     auto kfn = k_step_small<1024, 4096>;
     // activation tiles as bf16 hi + lo planes: two 16-row model-width tiles in the tail
     const size_t lds = (size_t)4 * 16 * (1024 + 8) * 2;
-    static bool configured = false;
-    if (!configured) {
-      (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      configured = true;
-    }
+    allow_dynamic_lds((const void*)kfn, lds);
     hipLaunchKernelGGL(kfn, dim3(256), dim3(256), lds, s, a);
   }
 }
