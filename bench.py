@@ -250,8 +250,17 @@ def main() -> int:
 
     # ---- extras (outside the timed region): per-step latency spread, fixed-context points and
     # accepted tokens/s under given acceptance lengths (step latency depends on shapes only)
-    spread, fixed = None, []
+    spread, fixed, accept_hist = None, [], None
     if not args.no_extras:
+        # accept-length histogram: the free-running generation goes on for up to 200 more steps,
+        # each step's per-sequence count kept in a device array (no host round trip per step)
+        n_hist = max(0, min(200, (max_ctx - R - int(len1.max())) // R))
+        log = torch.zeros((max(n_hist, 1), B), dtype=torch.int32, device=buf.n_accepted.device)
+        for i in range(n_hist):
+            eng.xsm_spec_step(buf, vp, int(len1.max()) + i * R)
+            log[i].copy_(buf.n_accepted)
+        counts = torch.bincount(log[:n_hist].flatten().long(), minlength=R + 1).cpu().tolist()
+        accept_hist = {"steps": n_hist, "counts": {str(a): counts[a] for a in range(1, R + 1)}}
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(201)]
         ctx_mid = int(len0[0])
         evs[0].record()
@@ -288,7 +297,7 @@ def main() -> int:
                                   f"free-running generation",
                       "batch": B, "n_draft": K, "ctx_start": int(len0.max()), "ctx_end": int(len1.max())},
            "accepted_tok_per_s": round(accepted / sec, 1), "scr": round(accepted / (B * args.steps), 4),
-           "roofline": roofline, "kernels": kernels,
+           "accept_length_histogram": accept_hist, "roofline": roofline, "kernels": kernels,
            "kernel_ms_per_step": round(tot_ms / args.steps, 4),
            "step_ms_spread": spread, "fixed_context": fixed,
            "accepted_tok_per_s_at_accept_length": dict(
