@@ -65,7 +65,7 @@ def cpu_baseline(cfg: dict, w: dict, prefix, first, budget_s: float = 15.0) -> d
     return {"value": round((cfg["n_draft"] + 1) * steps / el, 2), "unit": "tok/s", "cores": int(threads),
             "kind": "oracle", "accepted_tok_per_s": round(acc / el, 2),
             "ms_per_step": round(1e3 * el / steps, 2),
-            "sample": f"{steps} speculative steps of the same model after the same 257-token prefix "
+            "sample": f"{steps} speculative steps of the same model after the same {cfg['prefix']}-token prefix "
                       f"(context {cfg['prefix']}..{st.n}), float64 numpy"}
 
 
