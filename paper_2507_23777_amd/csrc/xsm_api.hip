@@ -94,6 +94,8 @@ void build_work_offsets(xsm_ctx* c) {
       const size_t need = ws_gemm_part_floats((int)(Mmax > Mb ? Mmax : Mb), sh[0], sh[1]);
       if (need > fl) fl = need;
     }
+    const size_t need_dn = blk_add_part_floats((int)Mmax, (int)d, (int)F);   // FFN-down in slices at a few hundred rows
+    if (need_dn > fl) fl = need_dn;
     w.gpart = take(fl * 4);
     w.gtickets = take(kWsTickets * 4);
   }
@@ -211,6 +213,9 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
   const bool planes = fgemm_planes_ok(M, d, d) && fgemm_planes_ok(M, d, F) && fgemm_planes_ok(M, F, d) &&
                       (d / 64) * ((M + 127) / 128) >= 256;
   const int pro_in = planes ? PRO_PLANES : PRO_F32;
+  // FFN-down alone also runs there with fewer rows, its contraction cut into slices (the sum is
+  // left to the next RMSNorm pass): 4 x the O-projection's contraction length to split
+  const bool dn_planes = planes || (fgemm_planes_ok(M, F, d) && blk_add_split(M, d, F) > 1);
   for (int l = 0; l < g.n_layers; ++l) {
     const LayerPtrs P = layer_ptrs(c, l);
     const TiledLayer& T = c->toff.layer[l];
@@ -254,13 +259,13 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     u.Wt = (const uint4*)(c->d_w + T.W1); u.N = F; u.K = d; u.M = M;
     u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
     u.Y = U; u.ldy = F; u.nscratch = Xn; u.ws_part = gpart; u.ws_tickets = gtick; u.pend = PEND;
-    u.y_planes = planes ? 1 : 0;
+    u.y_planes = dn_planes ? 1 : 0;
     launch_fgemm(PRO_NORM, FEPI_GELU, u, s);
 
     FastGemm dn{};
     dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
     dn.X = U; dn.ldx = F; dn.Y = X; dn.ldy = d; dn.nscratch = Xn; dn.ws_part = gpart; dn.ws_tickets = gtick; dn.pend = PEND;
-    launch_fgemm(pro_in, FEPI_ADD, dn, s);
+    launch_fgemm(dn_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, dn, s);
   }
   flush_pending_add(PEND, s);                     // the residual rows are read by the caller next
 }

@@ -970,10 +970,13 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
   uint16_t* As = reinterpret_cast<uint16_t*>(smem);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, gq = lane >> 4;
-  const int KT = g.K / 32, NS = g.K / kBlkKC, MBk = (g.M + BM - 1) / BM, total = (g.N / BN) * MBk;
+  // FEPI_ADD with g.ksplit > 1: a workgroup contracts one slice of K and stores its partial tile
+  const int KS = EPI == FEPI_ADD && g.ksplit > 1 ? g.ksplit : 1;
+  const int KT = g.K / 32, NS = g.K / kBlkKC / KS, MBk = (g.M + BM - 1) / BM, total = (g.N / BN) * KS * MBk;
   int id = blockIdx.x;
   if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
-  const int nb = id / MBk, mb = id % MBk;
+  // (consecutive blocks, i.e. one XCD, stay inside one slice: they share its activation columns)
+  const int wb = id / MBk, mb = id % MBk, nb = wb % (g.N / BN), ks = wb / (g.N / BN), st0 = ks * NS;
   const int wn = wave & 1, wm = wave >> 1;
   const int nt0 = nb * (BN / 16) + wn * WN, m0 = mb * BM, m_base = m0 + wm * WM * 16;
   const uint4* wbase = g.Wt + (size_t)nt0 * KT * 64 + lane;
@@ -994,13 +997,13 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
 #pragma unroll
     for (int t = 0; t < WN; ++t)
 #pragma unroll
-      for (int i = 0; i < kBlkKT; ++i) wreg[t][i] = wbase[((size_t)t * KT + st * kBlkKT + i) * 64];
+      for (int i = 0; i < kBlkKT; ++i) wreg[t][i] = wbase[((size_t)t * KT + (st0 + st) * kBlkKT + i) * 64];
 #pragma unroll
     for (int j = 0; j < NPC; ++j) {
       const int p = tid + 256 * j, mtl = p >> 7, ktl = (p >> 6) & 1;
       breg[2 * j] = uint4{0, 0, 0, 0}; breg[2 * j + 1] = uint4{0, 0, 0, 0};
       if (m0 + mtl * 16 < g.M) {
-        const uint16_t* src = Bh + ((size_t)(((m0 >> 4) + mtl) * KT + st * kBlkKT + ktl) * 64 + (p & 63)) * 8;
+        const uint16_t* src = Bh + ((size_t)(((m0 >> 4) + mtl) * KT + (st0 + st) * kBlkKT + ktl) * 64 + (p & 63)) * 8;
         breg[2 * j] = *reinterpret_cast<const uint4*>(src);
         if (!SINGLE) breg[2 * j + 1] = *reinterpret_cast<const uint4*>(src + lo_off);
       }
@@ -1084,7 +1087,10 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
       if (EPI == FEPI_STORE) {
         *y = v;
       } else if (EPI == FEPI_ADD) {
-        *y = *y + v;
+        // slices: partial tile [n / 64][slice][m][64], summed onto the rows in slice order by the
+        // RMSNorm pass that follows
+        if (KS > 1) *reinterpret_cast<f32x4*>(g.ws_part + (((size_t)(n0 >> 6) * KS + ks) * g.M + m) * 64 + (n0 & 63)) = v;
+        else *y = *y + v;
       } else if (EPI == FEPI_GELU) {
         const float4 u = float4{gelu_erf_f(v[0]), gelu_erf_f(v[1]), gelu_erf_f(v[2]), gelu_erf_f(v[3])};
         if (g.y_planes) plane_store4(g.Y, g.M, g.N, m, n0, u);      // operand planes of the next projection
@@ -1114,18 +1120,37 @@ static bool blk_gemm_usable(int pro, const FastGemm& g) {
   return pro == PRO_NORM && g.nscratch && fgemm_planes_ok(g.M, g.N, g.K);
 }
 
+// A residual-add projection from operand planes has few output blocks (N = model width): its
+// contraction is cut into 2, 4 or 8 slices of at least 512 until 128 x 128 blocks fill the chip.
+int blk_add_split(int M, int N, int K) {
+  if (!fgemm_planes_ok(M, N, K) || N % 128 != 0) return 1;
+  const long blocks128 = (long)(N / 128) * ((M + 127) / 128);
+  int ks = 1;
+  while (blocks128 * ks < 200 && ks < 8 && K % (ks * 2 * kBlkKC) == 0 && K / (ks * 2) >= 512) ks *= 2;
+  return ks;
+}
+size_t blk_add_part_floats(int Mmax, int N, int K) {
+  size_t need = 0;
+  for (int M = kWsMaxM + 1; M <= Mmax; ++M) {
+    const int ks = blk_add_split(M, N, K);
+    if (ks > 1 && (size_t)ks * M * N > need) need = (size_t)ks * M * N;
+  }
+  return need;
+}
+
 template <int EPI, int WN, int WM, bool SINGLE = false>
 static void blk_launch_t(const FastGemm& g, hipStream_t s) {
   constexpr int BN = 32 * WN, BM = 32 * WM;
   const size_t lds = (size_t)2 * (SINGLE ? 1 : 2) * BM * kBlkST * 2;
   auto kfn = k_gemm_blk<EPI, WN, WM, SINGLE>;
   allow_dynamic_lds((const void*)kfn, lds);
-  hipLaunchKernelGGL(kfn, dim3((g.N / BN) * ((g.M + BM - 1) / BM)), dim3(256), lds, s, g);
+  const int KS = EPI == FEPI_ADD && g.ksplit > 1 ? g.ksplit : 1;
+  hipLaunchKernelGGL(kfn, dim3((g.N / BN) * KS * ((g.M + BM - 1) / BM)), dim3(256), lds, s, g);
 }
 template <int EPI>
 static void blk_launch(const FastGemm& g, hipStream_t s) {
   // 128 x 128 blocks when they fill the chip, else 64 weight rows x 128 activation rows
-  const long blocks128 = (long)(g.N / 128) * ((g.M + 127) / 128);
+  const long blocks128 = (long)(g.N / 128) * ((g.M + 127) / 128) * (EPI == FEPI_ADD && g.ksplit > 1 ? g.ksplit : 1);
   const bool big = g.N % 128 == 0 && blocks128 >= 200;
   if (EPI == FEPI_STORE && g.x_single) {
     if (big) blk_launch_t<FEPI_STORE, 4, 4, true>(g, s);
@@ -1145,7 +1170,11 @@ static void blk_gemm(int pro, int epi, FastGemm g, hipStream_t s) {
     case FEPI_GELU: blk_launch<FEPI_GELU>(g, s); break;
     case FEPI_QKV: blk_launch<FEPI_QKV>(g, s); break;
     case FEPI_HEAD: blk_launch<FEPI_HEAD>(g, s); break;
-    case FEPI_ADD: blk_launch<FEPI_ADD>(g, s); break;
+    case FEPI_ADD:
+      g.ksplit = pro == PRO_PLANES && g.pend && g.ws_part ? blk_add_split(g.M, g.N, g.K) : 1;
+      blk_launch<FEPI_ADD>(g, s);
+      if (g.ksplit > 1) *g.pend = PendingAdd{true, g.ws_part, g.ksplit, g.M, g.N, g.Y, g.ldy};
+      break;
     default: break;
   }
 }

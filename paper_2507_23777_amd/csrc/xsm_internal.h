@@ -178,6 +178,7 @@ struct FastGemm {
   int y_planes;                // FEPI_GELU in the row-blocked kernel: write Y as operand planes [M][N] instead
   const uint16_t* bias;        // FEPI_HEAD: stacked biases [N]
   float* nscratch;             // [M][K] fp32: normalised rows for the kernels that do not fuse the norm
+  int ksplit;                  // row-blocked kernel, FEPI_ADD: slices of the contraction index (set by the launcher)
   float* ws_part; uint32_t* ws_tickets;   // split-contraction partial products and arrival counters
   PendingAdd* pend;            // host-side: where a residual-add projection may leave its sum pending
   // FEPI_QKV
@@ -188,6 +189,11 @@ struct FastGemm {
 bool fgemm_supported(int N, int K);
 // true when a projection of these sizes can take its input as operand planes (PRO_PLANES)
 bool fgemm_planes_ok(int M, int N, int K);
+// slices of the contraction index the row-blocked kernel takes for a residual-add projection
+// from operand planes (1 = whole contraction per workgroup), and the partial-product floats
+// such projections need for up to Mmax rows
+int blk_add_split(int M, int N, int K);
+size_t blk_add_part_floats(int Mmax, int N, int K);
 constexpr size_t kWsTickets = 4096;      // arrival counters of the split-contraction GEMM
 bool ws_gemm_shape_ok(int M, int N, int K);
 size_t ws_gemm_part_floats(int M, int N, int K);
