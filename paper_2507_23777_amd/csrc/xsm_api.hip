@@ -94,8 +94,10 @@ void build_work_offsets(xsm_ctx* c) {
       const size_t need = ws_gemm_part_floats((int)(Mmax > Mb ? Mmax : Mb), sh[0], sh[1]);
       if (need > fl) fl = need;
     }
-    const size_t need_dn = blk_add_part_floats((int)Mmax, (int)d, (int)F);   // FFN-down in slices at a few hundred rows
+    // the residual-add projections in slices on the row-blocked kernel (a few hundred rows)
+    const size_t need_dn = blk_add_part_floats((int)Mmax, (int)d, (int)F), need_o = blk_add_part_floats((int)Mmax, (int)d, (int)d);
     if (need_dn > fl) fl = need_dn;
+    if (need_o > fl) fl = need_o;
     w.gpart = take(fl * 4);
     w.gtickets = take(kWsTickets * 4);
   }
@@ -212,9 +214,10 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
   // at d = 1024: 144) the kernel with smaller blocks that converts fp32 rows on the way in is faster.
   const bool planes = fgemm_planes_ok(M, d, d) && fgemm_planes_ok(M, d, F) && fgemm_planes_ok(M, F, d) &&
                       (d / 64) * ((M + 127) / 128) >= 256;
-  const int pro_in = planes ? PRO_PLANES : PRO_F32;
-  // FFN-down alone also runs there with fewer rows, its contraction cut into slices (the sum is
-  // left to the next RMSNorm pass): 4 x the O-projection's contraction length to split
+  // With fewer rows they still run there when their contraction can be cut into slices that give
+  // the chip enough blocks (the sum is left to the next RMSNorm pass): FFN-down into up to 8
+  // slices (75 -> 37 us at 1152 rows), the O-projections into 2 (22 -> 19 us).
+  const bool o_planes = planes || blk_add_split(M, d, d) > 1;
   const bool dn_planes = planes || (fgemm_planes_ok(M, F, d) && blk_add_split(M, d, F) > 1);
   for (int l = 0; l < g.n_layers; ++l) {
     const LayerPtrs P = layer_ptrs(c, l);
@@ -232,13 +235,13 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     a.eff_len = eff; a.slot = slot; a.O = AO; a.ldo = d;
     a.part = (float*)(ws + c->ws.part); a.tickets = (uint32_t*)(ws + c->ws.tickets);
     a.R = R; a.H = H; a.cap = c->cap_self; a.S = attn_splits(c, n_seq * ((R + 15) / 16), len_bound + R); a.fixed_limit = 0;
-    a.scale_log2 = scale_log2; a.o_planes = planes ? 1 : 0; a.o_rows = M;
+    a.scale_log2 = scale_log2; a.o_planes = o_planes ? 1 : 0; a.o_rows = M;
     launch_fattn(a, n_seq, s);
 
     FastGemm o{};
     o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
     o.X = AO; o.ldx = d; o.Y = X; o.ldy = d; o.nscratch = Xn; o.ws_part = gpart; o.ws_tickets = gtick; o.pend = PEND;
-    launch_fgemm(pro_in, FEPI_ADD, o, s);
+    launch_fgemm(o_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, o, s);
 
     if (g.n_cond > 0) {
       FastGemm cq{};
@@ -252,7 +255,7 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
       launch_fattn(ca, n_seq, s);
       FastGemm co = o;
       co.Wt = (const uint4*)(c->d_w + T.Wco);
-      launch_fgemm(pro_in, FEPI_ADD, co, s);
+      launch_fgemm(o_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, co, s);
     }
 
     FastGemm u{};

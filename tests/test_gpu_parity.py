@@ -159,6 +159,16 @@ def test_cross_attention_backbone(X):
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[85, 40])
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 2))
     _report(tal, "cross-attn with prefixes 85 / 40")
+    # prefill passes of a few hundred and of several thousand rows: the self- and cross-attention
+    # outputs reach their O-projections as operand planes (contraction in slices / whole)
+    cfg = _c1_small(n_layers=2, n_cond=40, prefix=300, seed=30, max_ctx=384)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 2, si.first_block(cfg, 1))
+    _report(tal, "cross-attn d1024, prefix 300")
+    cfg = _mid_cfg(n_cond=70, prefix=2700, seed=31, n_layers=2, max_ctx=2752)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 3)
+    tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 2, si.first_block(cfg, 3))
+    _report(tal, "cross-attn, one 8100-row prefill pass")
 
 
 def test_cross_attention_decoding_heads(X):
