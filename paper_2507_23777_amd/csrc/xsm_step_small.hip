@@ -499,6 +499,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           }
       };
       if (c_lo + wave < c_hi) { load_k(c_lo + wave); load_v(c_lo + wave); }
+      if (c_lo + wave + 4 < c_hi) request_next(c_lo + wave + 4);   // the wavefront's second chunk too
       watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, tag, ok && n >= 0, tid);
       if (n >= 0) {
         const int j0 = tid >> 6, c = tid & 63;            // rows j0, j0+4, j0+8, j0+12
@@ -544,7 +545,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       for (int c = c_lo + wave; c < c_hi; c += 4) {
         const int key0 = c << 6;
         const bool more = c + 4 < c_hi;
-        if (more) request_next(c + 4);
+        if (more && c != c_lo + wave) request_next(c + 4);
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
