@@ -132,7 +132,9 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
   constexpr int PP = W / 512, N = ROWS * PP * 2;
   const int rows = min(ROWS, nrows - m0);
   const uint64_t* base = buf + (size_t)m0 * RS + 2 * tid;
-  watch_then_sync(base + (size_t)(rows > 0 ? rows - 1 : 0) * RS + (PP - 1) * 512 + 1, tag, ok && rows > 0, tid);
+  // (later rounds of a block come from the same producers as its first rows: no watch, its poll
+  // would be one more round trip in front of the read)
+  if (m0 == 0) watch_then_sync(base + (size_t)(rows > 0 ? rows - 1 : 0) * RS + (PP - 1) * 512 + 1, tag, ok && rows > 0, tid);
   if (stamp && tid == 0) stamp[0] = wall_clock64();
   if (ok && rows > 0) {
     int spin = 0;
