@@ -209,8 +209,11 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_
 
 // Stage nrows rows, D columns each, of an fp32-payload block with row stride RS words into LDS
 // rows dst_row.. as two bf16 planes of row stride D + 8: hi at As, lo at As + 16 * (D + 8).
-// NORM: RMSNorm over the D columns with the gain pairs gpair[j] (columns 2(tid + 256 j), +1).
-template <int D, int RS, bool NORM>
+// NORM 1: RMSNorm over the D columns with the gain pairs gpair[j] (columns 2(tid + 256 j), +1).
+// NORM 2: only the gains are applied and the rows' sums of squares are left in sm.rowsum[.][row];
+// the caller multiplies its products by row_scale(row) - the rows reach LDS without waiting for
+// the sums to be exchanged.
+template <int D, int RS, int NORM>
 __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst_row, const uint64_t* buf,
                                                int nrows, const uint32_t (&gpair)[D / 512], float eps, int tid,
                                                uint32_t tag, bool& ok, uint64_t* stamp = nullptr) {
@@ -221,7 +224,7 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
     uint32_t pay[RB * PP * 2];
     coop_wait<D, RS, RB>(buf, m0, nrows, tid, tag, pay, ok, stamp);
     if (NORM) {
-      if (m0 > 0) __syncthreads();                       // this call's earlier readers of rowsum are done
+      if (NORM == 1 && m0 > 0) __syncthreads();          // this call's earlier readers of rowsum are done
       // eight row sums per wavefront in ten lane exchanges instead of forty-eight: each exchange
       // step halves the rows a lane carries (lane bits 5, 4, 3 pick the row), then three steps
       // finish the one row left.  Cross-lane moves cost LDS-like latency at one wavefront per SIMD.
@@ -246,14 +249,14 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
       s1 += __shfl_xor(s1, 4, WAVE);
       s1 += __shfl_xor(s1, 2, WAVE);
       s1 += __shfl_xor(s1, 1, WAVE);
-      if ((lane & 7) == 0) sm.rowsum[wave][(b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
-      __syncthreads();
+      if ((lane & 7) == 0) sm.rowsum[wave][(NORM == 2 ? m0 : 0) + (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
+      if (NORM == 1) __syncthreads();
     }
     // every thread forms the scales itself, all rows at once (hardware reciprocal square root, 1 ulp)
     float scl[RB];
 #pragma unroll
     for (int m = 0; m < RB; ++m)
-      scl[m] = NORM ? __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / (float)D) + eps)
+      scl[m] = NORM == 1 ? __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / (float)D) + eps)
                     : 1.0f;
 #pragma unroll
     for (int m = 0; m < RB; ++m) {
@@ -262,7 +265,8 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
 #pragma unroll
         for (int j = 0; j < PP; ++j) {
           float x0 = __uint_as_float(pay[(m * PP + j) * 2]), x1 = __uint_as_float(pay[(m * PP + j) * 2 + 1]);
-          if (NORM) { x0 *= sc * lo_bf(gpair[j]); x1 *= sc * hi_bf(gpair[j]); }
+          if (NORM == 1) { x0 *= sc * lo_bf(gpair[j]); x1 *= sc * hi_bf(gpair[j]); }
+          if (NORM == 2) { x0 *= lo_bf(gpair[j]); x1 *= hi_bf(gpair[j]); }
           uint32_t hi, lo;
           split2(x0, x1, hi, lo);
           uint16_t* dst = As + (size_t)(dst_row + m0 + m) * ST + 2 * (tid + 256 * j);
@@ -273,6 +277,12 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
     }
   }
   __syncthreads();
+}
+
+// 1 / rms of a row staged with NORM 2 (hardware reciprocal square root, 1 ulp)
+template <int D>
+__device__ __forceinline__ float row_scale(const Shared& sm, int row, float eps) {
+  return __builtin_amdgcn_rsqf(((sm.rowsum[0][row] + sm.rowsum[1][row]) + (sm.rowsum[2][row] + sm.rowsum[3][row])) * (1.0f / (float)D) + eps);
 }
 
 // acc += Wfrag . (hi + lo) for activation row `row`, k-tile kt of an LDS tile staged by
@@ -404,12 +414,12 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const int q_sec = w / (D / 16), q_ts = w % (D / 16), q_h = q_ts >> 2, q_tt = q_ts & 3;
       float2 cs = float2{1.f, 0.f};
       if (live && q_sec < 2) cs = a.rope[(size_t)(len_m + mj) * 32 + q_tt * 8 + (nrow & 7)];
-      stage_rows_f32<D, D, true>(sm, As, 0, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
+      stage_rows_f32<D, D, 2>(sm, As, 0, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
       XSM_STAMP(l * 16 + 8);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
-      const float v = tile_reduce(sm, acc, wave, lane, tid);
+      const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
       const float partner = __shfl_xor(v, 8, WAVE);        // tile column nrow +- 8
       if (live) {
         const int pos = len_m + mj;
@@ -774,7 +784,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const uint32_t px = row_in ? ll_wait1(lb + OFF_X + (size_t)om * D + nt * 16 + nrow, tag, ok) : 0u;
       const uint32_t nogain[D / 512] = {};
       __syncthreads();
-      stage_rows_f32<D, D, false>(sm, As, 0, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
+      stage_rows_f32<D, D, 0>(sm, As, 0, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
       XSM_STAMP(l * 16 + 14);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -791,12 +801,12 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
       for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g2 + 2 * (tid + 256 * j));
       __syncthreads();
-      stage_rows_f32<D, D, true>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok, tl ? tl + l * 16 + 13 : nullptr);
+      stage_rows_f32<D, D, 2>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok, tl ? tl + l * 16 + 13 : nullptr);
       XSM_STAMP(l * 16 + 7);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < KD; ++i) acc = mac2(acc, wu[i], As, STD, r, wave * KD + i, g);
-      const float v = tile_reduce(sm, acc, wave, lane, tid);
+      const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
       if (row_in)
         ll_st(lb + OFF_U + (size_t)om * F + w * 16 + nrow,
               __float_as_uint(0.5f * v * (1.0f + erff(v * 0.70710678118654752f))), tag);
@@ -807,7 +817,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     {
       const uint32_t nogain[FS / 512] = {};
       __syncthreads();
-      stage_rows_f32<FS, F, false>(sm, As, 0, lb + OFF_U + d_ks * FS, M, nogain, a.eps, tid, tag, ok);
+      stage_rows_f32<FS, F, 0>(sm, As, 0, lb + OFF_U + d_ks * FS, M, nogain, a.eps, tid, tag, ok);
       XSM_STAMP(l * 16 + 12);
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -859,7 +869,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
     for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(a.gf + 2 * (tid + 256 * j));
     __syncthreads();
-    stage_rows_f32<D, D, true>(sm, T0, 0, tb + OFF_X, M, gp, a.eps, tid, tag, ok);
+    stage_rows_f32<D, D, 1>(sm, T0, 0, tb + OFF_X, M, gp, a.eps, tid, tag, ok);
   }
   XSM_STAMP(a.L * 16 + 1);
 
@@ -889,7 +899,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
       if (q_hi > q_lo) {
         const uint32_t nogain[D / 512] = {};
-        stage_rows_f32<D, D, false>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, q_hi - q_lo, nogain,
+        stage_rows_f32<D, D, 0>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, q_hi - q_lo, nogain,
                                     a.eps, tid, tag, ok);
       }
     }
