@@ -59,6 +59,11 @@ __device__ __forceinline__ void lds_direct16(const void* gptr, void* lds) {
                                    (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// raw buffer descriptor word 3 (32-bit data format, no swizzle) and the cache-policy bits of a
+// load that is coherent across the device (sc1)
+constexpr int kRawBufferFlags = 0x00020000, kCoherentLoad = 16;
+
 constexpr int kQS = 72;                     // LDS row stride (bf16) of the attention q / new-k / new-v tiles
 
 __device__ __forceinline__ uint64_t ll_ld(const uint64_t* p) {
@@ -137,26 +142,31 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
   if (m0 == 0) watch_then_sync(base + (size_t)(rows > 0 ? rows - 1 : 0) * RS + (PP - 1) * 512 + 1, tag, ok && rows > 0, tid);
   if (stamp && tid == 0) stamp[0] = wall_clock64();
   if (ok && rows > 0) {
+    // a thread's two adjacent words travel as one 16-byte device-coherent load (each word is
+    // validated by its own tag, so the pair needs no atomicity of its own)
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint64_t*>(buf + (size_t)m0 * RS), 0, rows * RS * 8, kRawBufferFlags);
     int spin = 0;
     for (; spin < kSpinBudget; ++spin) {
-      uint64_t w[N];
+      u32x4 q[N / 2];                                     // {payload, tag, payload, tag}
 #pragma unroll
       for (int m = 0; m < ROWS; ++m)
 #pragma unroll
         for (int j = 0; j < PP; ++j)
-          if (m < rows) {
-            w[(m * PP + j) * 2] = ll_ld(base + (size_t)m * RS + j * 512);
-            w[(m * PP + j) * 2 + 1] = ll_ld(base + (size_t)m * RS + j * 512 + 1);
-          }
+          if (m < rows)
+            q[m * PP + j] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((m * RS + j * 512 + 2 * tid) * 8), 0, kCoherentLoad);
       bool good = true;
 #pragma unroll
       for (int m = 0; m < ROWS; ++m)
 #pragma unroll
-        for (int j = 0; j < PP * 2; ++j)
-          if (m < rows) good &= (uint32_t)(w[m * PP * 2 + j] >> 32) == tag;
+        for (int j = 0; j < PP; ++j)
+          if (m < rows) good &= q[m * PP + j].y == tag && q[m * PP + j].w == tag;
       if (good) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) pay[i] = (i / (PP * 2)) < rows ? (uint32_t)w[i] : 0u;
+        for (int i = 0; i < N / 2; ++i) {
+          pay[2 * i] = (i / PP) < rows ? q[i].x : 0u;
+          pay[2 * i + 1] = (i / PP) < rows ? q[i].z : 0u;
+        }
         if (stamp && tid == 0) stamp[1] = wall_clock64();
         return;
       }
