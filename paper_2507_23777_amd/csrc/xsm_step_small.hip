@@ -115,6 +115,41 @@ __device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bo
   return out[0];
 }
 
+// The same for pairs of adjacent words (even word offsets off[i], < 0: skipped) of a block of
+// nbytes bytes at p: each pair is one 16-byte device-coherent load, payloads to out[2i], out[2i+1].
+template <int N>
+__device__ __forceinline__ void ll_wait_pairs(const uint64_t* p, int nbytes, const int (&off)[N], uint32_t tag,
+                                              uint32_t (&out)[2 * N], bool& ok) {
+  bool any = false;
+#pragma unroll
+  for (int i = 0; i < N; ++i) any |= off[i] >= 0;
+  if (ok && any) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint64_t*>(p), 0, nbytes, kRawBufferFlags);
+    for (int spin = 0; spin < kSpinBudget; ++spin) {
+      u32x4 q[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i)
+        if (off[i] >= 0) q[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[i] * 8, 0, kCoherentLoad);
+      bool good = true;
+#pragma unroll
+      for (int i = 0; i < N; ++i)
+        if (off[i] >= 0) good &= q[i].y == tag && q[i].w == tag;
+      if (good) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          out[2 * i] = off[i] >= 0 ? q[i].x : 0u;
+          out[2 * i + 1] = off[i] >= 0 ? q[i].z : 0u;
+        }
+        return;
+      }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    ok = false;
+  }
+#pragma unroll
+  for (int i = 0; i < 2 * N; ++i) out[i] = 0u;
+}
+
 // Every poll of a word that another XCD is about to write costs fabric traffic that slows the
 // writes everybody is waiting for, so a workgroup polls with one lane: it watches one word of the
 // block until it carries the tag while the rest sit at the barrier; the block is read afterwards
@@ -524,28 +559,28 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       if (c_lo + wave + 4 < c_hi) request_next(c_lo + wave + 4);   // the wavefront's second chunk too
       watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, tag, ok && n >= 0, tid);
       if (n >= 0) {
-        const int j0 = tid >> 6, c = tid & 63;            // rows j0, j0+4, j0+8, j0+12
-        int off[12];
+        const int j0 = tid >> 5, c = 2 * (tid & 31);      // rows j0, j0+8; columns c, c+1 as one word pair
+        int off[6];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int j = j0 + 4 * q;
+        for (int q = 0; q < 2; ++q) {
+          const int j = j0 + 8 * q;
           const int base = (b * R + j) * D + h * 64 + c;
           off[3 * q] = j < R ? (int)OFF_Q + base : -1;
           off[3 * q + 1] = j < R ? (int)OFF_KN + base : -1;
           off[3 * q + 2] = j < R ? (int)OFF_VN + base : -1;
         }
         uint32_t pw[12];
-        ll_wait_list<12>(lb, off, tag, pw, ok);
+        ll_wait_pairs<6>(lb, (int)OFF_U * 8, off, tag, pw, ok);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int j = j0 + 4 * q;
+        for (int q = 0; q < 2; ++q) {
+          const int j = j0 + 8 * q;
           if (j < R) {
-            const float qv = __uint_as_float(pw[3 * q]);
-            const uint16_t qh = f2bf(qv);
-            qs[j * kQS + c] = qh;
-            qs[(16 + j) * kQS + c] = f2bf(qv - bf2f(qh));
-            kns[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q + 1]));
-            vns[j * kQS + c] = f2bf(__uint_as_float(pw[3 * q + 2]));
+            uint32_t qh, ql;
+            split2(__uint_as_float(pw[6 * q]), __uint_as_float(pw[6 * q + 1]), qh, ql);
+            *reinterpret_cast<uint32_t*>(qs + j * kQS + c) = qh;
+            *reinterpret_cast<uint32_t*>(qs + (16 + j) * kQS + c) = ql;
+            *reinterpret_cast<uint32_t*>(kns + j * kQS + c) = pk2(__uint_as_float(pw[6 * q + 2]), __uint_as_float(pw[6 * q + 3]));
+            *reinterpret_cast<uint32_t*>(vns + j * kQS + c) = pk2(__uint_as_float(pw[6 * q + 4]), __uint_as_float(pw[6 * q + 5]));
           }
         }
       }
@@ -749,18 +784,22 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       float* const cb = reinterpret_cast<float*>(As);       // [S][P]
       watch_then_sync(p0 + (size_t)(S - 1) * 1056 + 32 + (s * dps + dps - 1) * 16, tag, ok, tid);
       {
-        int off[6];
+        // word pairs 2 tid + 512 q of the S x P words (P is even: a pair stays inside one slice)
+        int off[3];
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
-          const int i = tid + 256 * q;
+        for (int q = 0; q < 3; ++q) {
+          const int i = 2 * tid + 512 * q;
           const int k = i / P, j = i % P;
           off[q] = i < S * P ? k * 1056 + (j < 32 ? j : 32 + s * dps * 16 + (j - 32)) : -1;
         }
         uint32_t pw[6];
-        ll_wait_list<6>(p0, off, tag, pw, ok);
+        ll_wait_pairs<3>(p0, S * 1056 * 8, off, tag, pw, ok);
 #pragma unroll
-        for (int q = 0; q < 6; ++q)
-          if (off[q] >= 0) cb[tid + 256 * q] = __uint_as_float(pw[q]);
+        for (int q = 0; q < 3; ++q)
+          if (off[q] >= 0) {
+            cb[2 * tid + 512 * q] = __uint_as_float(pw[2 * q]);
+            cb[2 * tid + 512 * q + 1] = __uint_as_float(pw[2 * q + 1]);
+          }
       }
       __syncthreads();
       for (int qd = tid >> 4; qd < dps; qd += 16) {
