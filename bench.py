@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, scaled by a plain copy of known size (see profiles/ and the design doc);
 # measured for k_step_small on the default workload with --steps 60 (context 282..370), where the
-# algorithmic figure is 653 MB: 779.1 MB read + 41.0 MB written.
-TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 820.1e6}
+# algorithmic figure is 653 MB: 779.6 MB read + 41.0 MB written.
+TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 820.6e6}
 
 
 def algorithmic_bytes(cfg: dict, n_seq: int, sum_ctx: float) -> float:
