@@ -158,7 +158,7 @@ __device__ __forceinline__ void ll_wait_pairs(const uint64_t* p, int nbytes, con
 __device__ __forceinline__ void watch_then_sync(const uint64_t* word, uint32_t tag, bool active, int tid) {
   if (tid == 0 && active) {
     int spin = 0;
-    while ((uint32_t)(ll_ld(word) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(4);
+    while ((uint32_t)(ll_ld(word) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
   }
   __syncthreads();
 }
