@@ -66,6 +66,35 @@ template <> struct VecOf<bf16_t> { static constexpr int n = 8; };
 
 constexpr int WAVE = 64;
 
+// Value held by lane (l ^ MASK), MASK a power of two, without the LDS crossbar that __shfl_xor
+// goes through (ds_bpermute: an address computation plus LDS latency per exchange): the lane-swap
+// instructions of gfx950 for 32 and 16, DPP row operations for 8 and below.  All 64 lanes must
+// be active and blockDim.x a multiple of 64.  (Lane layouts checked on gfx950 against __shfl_xor.)
+template <int MASK>
+__device__ __forceinline__ uint32_t lane_xor_u32(uint32_t x) {
+  static_assert(MASK == 1 || MASK == 2 || MASK == 4 || MASK == 8 || MASK == 16 || MASK == 32, "one lane bit");
+  if constexpr (MASK == 32) {
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return (threadIdx.x & 32) ? r[0] : r[1];
+  } else if constexpr (MASK == 16) {
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    return (threadIdx.x & 16) ? r[0] : r[1];
+  } else if constexpr (MASK == 8) {
+    return __builtin_amdgcn_update_dpp(0u, x, 0x128, 0xf, 0xf, false);          // row_ror:8
+  } else if constexpr (MASK == 4) {
+    const uint32_t y = __builtin_amdgcn_update_dpp(0u, x, 0x141, 0xf, 0xf, false);   // row_half_mirror: lane 7 - i of the eight
+    return __builtin_amdgcn_update_dpp(0u, y, 0x1B, 0xf, 0xf, false);           // quad_perm [3,2,1,0]
+  } else if constexpr (MASK == 2) {
+    return __builtin_amdgcn_update_dpp(0u, x, 0x4E, 0xf, 0xf, false);           // quad_perm [2,3,0,1]
+  } else {
+    return __builtin_amdgcn_update_dpp(0u, x, 0xB1, 0xf, 0xf, false);           // quad_perm [1,0,3,2]
+  }
+}
+template <int MASK> __device__ __forceinline__ float lane_xor(float x) {
+  return __uint_as_float(lane_xor_u32<MASK>(__float_as_uint(x)));
+}
+template <int MASK> __device__ __forceinline__ int lane_xor(int x) { return (int)lane_xor_u32<MASK>((uint32_t)x); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);

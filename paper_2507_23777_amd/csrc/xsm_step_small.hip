@@ -287,13 +287,13 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
       const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
       float s4[4], s2[2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s4[i] = (b5 ? ss[4 + i] : ss[i]) + __shfl_xor(b5 ? ss[i] : ss[4 + i], 32, WAVE);
+      for (int i = 0; i < 4; ++i) s4[i] = (b5 ? ss[4 + i] : ss[i]) + lane_xor<32>(b5 ? ss[i] : ss[4 + i]);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) s2[i] = (b4 ? s4[2 + i] : s4[i]) + __shfl_xor(b4 ? s4[i] : s4[2 + i], 16, WAVE);
-      float s1 = (b3 ? s2[1] : s2[0]) + __shfl_xor(b3 ? s2[0] : s2[1], 8, WAVE);
-      s1 += __shfl_xor(s1, 4, WAVE);
-      s1 += __shfl_xor(s1, 2, WAVE);
-      s1 += __shfl_xor(s1, 1, WAVE);
+      for (int i = 0; i < 2; ++i) s2[i] = (b4 ? s4[2 + i] : s4[i]) + lane_xor<16>(b4 ? s4[i] : s4[2 + i]);
+      float s1 = (b3 ? s2[1] : s2[0]) + lane_xor<8>(b3 ? s2[0] : s2[1]);
+      s1 += lane_xor<4>(s1);
+      s1 += lane_xor<2>(s1);
+      s1 += lane_xor<1>(s1);
       if ((lane & 7) == 0) sm.rowsum[wave][(NORM == 2 ? m0 : 0) + (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
       if (NORM == 1) __syncthreads();
     }
@@ -465,7 +465,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
       for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
-      const float partner = __shfl_xor(v, 8, WAVE);        // tile column nrow +- 8
+      const float partner = lane_xor<8>(v);        // tile column nrow +- 8
       if (live) {
         const int pos = len_m + mj;
         float o = v;
@@ -627,8 +627,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             sc[t][i] = v;
             cmax = fmaxf(cmax, v);
           }
-        cmax = fmaxf(cmax, __shfl_xor(cmax, 16, WAVE));
-        cmax = fmaxf(cmax, __shfl_xor(cmax, 32, WAVE));
+        cmax = fmaxf(cmax, lane_xor<16>(cmax));
+        cmax = fmaxf(cmax, lane_xor<32>(cmax));
         const float m_new = fmaxf(m_run, cmax);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = exp2f(m_run - m_use);
@@ -641,8 +641,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             sc[t][i] = p;
             psum += p;
           }
-        psum += __shfl_xor(psum, 16, WAVE);
-        psum += __shfl_xor(psum, 32, WAVE);
+        psum += lane_xor<16>(psum);
+        psum += lane_xor<32>(psum);
         l_run = l_run * alpha + psum;
         m_run = m_new;
 #pragma unroll
@@ -697,8 +697,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           sc[i] = v;
           cmax = fmaxf(cmax, v);
         }
-        cmax = fmaxf(cmax, __shfl_xor(cmax, 16, WAVE));
-        cmax = fmaxf(cmax, __shfl_xor(cmax, 32, WAVE));
+        cmax = fmaxf(cmax, lane_xor<16>(cmax));
+        cmax = fmaxf(cmax, lane_xor<32>(cmax));
         const float m_new = fmaxf(m_run, cmax);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = exp2f(m_run - m_use);
@@ -709,8 +709,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           sc[i] = p;
           psum += p;
         }
-        psum += __shfl_xor(psum, 16, WAVE);
-        psum += __shfl_xor(psum, 32, WAVE);
+        psum += lane_xor<16>(psum);
+        psum += lane_xor<32>(psum);
         l_run = l_run * alpha + psum;
         m_run = m_new;
         // contraction index of the second product: k = g*8 + e  <->  new key g*4 + e (e < 4)
@@ -1016,14 +1016,16 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           else sv = fmaxf(sv, fmaxf(tv, ts));
         }
       }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const float bv2 = __shfl_xor(bv, o, WAVE), sv2 = __shfl_xor(sv, o, WAVE);
-        const int bi2 = __shfl_xor(bi, o, WAVE);
-        const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);
-        sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));
-        if (take) { bv = bv2; bi = bi2; }
+#define XSM_FOLD(O)                                                          \
+      {                                                                        \
+        const float bv2 = lane_xor<O>(bv), sv2 = lane_xor<O>(sv);              \
+        const int bi2 = lane_xor<O>(bi);                                       \
+        const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);               \
+        sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));                            \
+        if (take) { bv = bv2; bi = bi2; }                                      \
       }
+      XSM_FOLD(32) XSM_FOLD(16) XSM_FOLD(8) XSM_FOLD(4) XSM_FOLD(2) XSM_FOLD(1)
+#undef XSM_FOLD
       if (lane == 0) { sm.st_max[q] = bv; sm.st_sec[q] = sv; sm.st_idx[q] = bi; }
     };
     // the R backbone rows first; they fix the accepted length, and only the K head rows of that
