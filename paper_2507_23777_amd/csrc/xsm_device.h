@@ -95,14 +95,30 @@ template <int MASK> __device__ __forceinline__ float lane_xor(float x) {
 }
 template <int MASK> __device__ __forceinline__ int lane_xor(int x) { return (int)lane_xor_u32<MASK>((uint32_t)x); }
 
+// every lane receives the result; fixed combination order (lane distance 32, 16, ..., 1)
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  v += lane_xor<32>(v); v += lane_xor<16>(v); v += lane_xor<8>(v);
+  v += lane_xor<4>(v); v += lane_xor<2>(v); v += lane_xor<1>(v);
   return v;
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  v = fmaxf(v, lane_xor<32>(v)); v = fmaxf(v, lane_xor<16>(v)); v = fmaxf(v, lane_xor<8>(v));
+  v = fmaxf(v, lane_xor<4>(v)); v = fmaxf(v, lane_xor<2>(v)); v = fmaxf(v, lane_xor<1>(v));
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+  v += lane_xor<32>(v); v += lane_xor<16>(v); v += lane_xor<8>(v);
+  v += lane_xor<4>(v); v += lane_xor<2>(v); v += lane_xor<1>(v);
+  return v;
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+  v = min(v, lane_xor<32>(v)); v = min(v, lane_xor<16>(v)); v = min(v, lane_xor<8>(v));
+  v = min(v, lane_xor<4>(v)); v = min(v, lane_xor<2>(v)); v = min(v, lane_xor<1>(v));
+  return v;
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+  v = max(v, lane_xor<32>(v)); v = max(v, lane_xor<16>(v)); v = max(v, lane_xor<8>(v));
+  v = max(v, lane_xor<4>(v)); v = max(v, lane_xor<2>(v)); v = max(v, lane_xor<1>(v));
   return v;
 }
 
@@ -123,24 +139,21 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 __device__ __forceinline__ int block_sum_i(int v, int* red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  v = wave_sum_i(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
   return red[0] + red[1] + red[2] + red[3];
 }
 __device__ __forceinline__ int block_min_i(int v, int* red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, WAVE));
+  v = wave_min_i(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
   return min(min(red[0], red[1]), min(red[2], red[3]));
 }
 __device__ __forceinline__ int block_max_i(int v, int* red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, WAVE));
+  v = wave_max_i(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();

@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void k_fgemm(const FastGemm g) {
       for (int w = 0; w < 4; ++w) v += red[((size_t)(w * MT + mt) * 64 + li) * 4 + ii];
       const int m = m0 + mt * 16 + mcol;
       if (EPI == FEPI_QKV) {
-        const float partner = __shfl_xor(v, 32, WAVE);    // row nrow +- 8 of the same tile
+        const float partner = lane_xor<32>(v);    // row nrow +- 8 of the same tile
         if (m < g.M) qkv_store(g, nt, nrow, m, v, partner);
       } else if (m < g.M) {
         if (EPI == FEPI_STORE) g.Y[(size_t)m * g.ldy + n] = v;
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(256) void k_gemm_big(const FastGemm g) {
     if (EPI == FEPI_QKV) {
       float pr[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) pr[i] = __shfl_xor(acc[mt][i], 32, WAVE);
+      for (int i = 0; i < 4; ++i) pr[i] = lane_xor<32>(acc[mt][i]);
       if (m < g.M) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) qkv_store(g, nt, (lane >> 4) * 4 + i, m, acc[mt][i], pr[i]);
@@ -804,7 +804,7 @@ __device__ __forceinline__ void wt_finish(const FastGemm& g, const uint16_t* Bh,
   if (EPI == FEPI_QKV) {
     f32x4 pr;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(v[e], PX, WAVE);
+    for (int e = 0; e < 4; ++e) pr[e] = lane_xor<PX>(v[e]);
     qkv_quad_store(g, qkv_cols(g, n0), qkv_row(g, m), v, pr);
   } else if (m < g.M) {
     f32x4* y = reinterpret_cast<f32x4*>(g.Y + (size_t)m * g.ldy + n0);
@@ -1069,7 +1069,7 @@ __global__ __launch_bounds__(256) void k_gemm_blk(const FastGemm g) {
       for (int q = 0; q < WM; ++q) {
         f32x4 pr;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pr[e] = __shfl_xor(acc[t][q][e], 32, WAVE);   // tile row +- 8
+        for (int e = 0; e < 4; ++e) pr[e] = lane_xor<32>(acc[t][q][e]);   // tile row +- 8
         qkv_quad_store(g, c, rows[q], acc[t][q], pr);
       }
     }
