@@ -140,6 +140,46 @@ def fixed_point(args, torch, pkg, xsm, si) -> int:
     return 0
 
 
+def stage_timeline(args, torch, pkg, xsm, si) -> int:
+    """Tuning aid: the single-launch step's own stage clock (XSM_OPT_TIMELINE) for one step of the
+    benchmark model at a fixed context; median over workgroups of each stage's duration."""
+    import numpy as np
+    cfg = si.get_config(args.config)
+    B, K, ctx = cfg["batch"], cfg["n_draft"], args.timeline
+    R, L = K + 1, cfg["n_layers"]
+    eng = pkg.Engine(cfg, max_batch=B, max_ctx=((ctx + 8 * R + 64) // 64) * 64)
+    eng.d_kv.zero_()
+    eng.xsm_load_weights(si.pack_canonical(cfg, si.make_weights(cfg)))
+    buf = eng.buffers(B, spec=True)
+    buf.block.copy_(torch.tensor(si.first_block(cfg, B)))
+    vp = pkg.xsm_verify_params(0, 1, 0.5, 1.0, 0, 0)
+    for _ in range(5):
+        buf.kv_len.fill_(ctx); eng.xsm_spec_step(buf, vp, ctx)
+    torch.cuda.synchronize()
+    eng.xsm_set_option(xsm.XSM_OPT_TIMELINE, 1)
+    buf.kv_len.fill_(ctx); eng.xsm_spec_step(buf, vp, ctx)
+    t = eng.xsm_debug_timeline().astype(np.int64)          # [256 workgroups][L*16 + 8] ticks of 10 ns
+    eng.xsm_check_device()
+    us = (t - t[:, 0].min()) / 100.0
+    names = ["qkv", "att", "merge", "oproj", "up", "down+sum"]
+    mid = L // 2
+    row = us[:, mid * 16:mid * 16 + 7]
+    starts = us[:, [l * 16 for l in range(L)]].mean(0)
+    tail = us[:, L * 16:L * 16 + 5]
+    out = {"workload": f"{args.config} batch {B} K={K} context {ctx}, one speculative step",
+           "kernel_us": round(float(us[:, L * 16 + 4].max()), 1),
+           "layer_period_us": round(float(np.diff(starts).mean()), 2),
+           f"layer_{mid}_stage_us_median_over_workgroups":
+               {n: round(float(np.median(row[:, i + 1] - row[:, i])), 2) for i, n in enumerate(names)},
+           f"layer_{mid}_stage_us_workgroup_0":
+               {n: round(float(row[0, i + 1] - row[0, i]), 2) for i, n in enumerate(names)},
+           "tail_stage_us_median": [round(float(np.median(tail[:, i + 1] - tail[:, i])), 2) for i in range(4)],
+           "note": "a workgroup's stage time includes waiting for the stage's inputs; workgroups that sit a "
+                   "stage out pass through it in ~0.1 us, so the median understates stages few workgroups run"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,6 +195,8 @@ def main() -> int:
     ap.add_argument("--fixed-point", default=None, metavar="NAME,B,K,CTX[,MAX_CTX]",
                     help="time another workload of the sweep at a fixed context instead of the benchmark line, "
                          "e.g. c2,16,6,2048 or c4,128,8,10000")
+    ap.add_argument("--timeline", type=int, default=None, metavar="CTX",
+                    help="print the single-launch step's per-stage clock for one step at context CTX and exit")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy five times and exit (scale for the PMC byte counters)")
     args = ap.parse_args()
@@ -182,6 +224,8 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 5}))
         return 0
+    if args.timeline is not None:
+        return stage_timeline(args, torch, pkg, xsm, si)
     if args.fixed_point:
         return fixed_point(args, torch, pkg, xsm, si)
     cfg = si.get_config(args.config)
