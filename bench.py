@@ -49,7 +49,8 @@ def cpu_baseline(cfg: dict, w: dict, prefix, first, budget_s: float = 15.0) -> d
     from threadpoolctl import threadpool_info
     from oracle import Oracle, VerifyParams
     orc = Oracle(cfg, w)
-    st = orc.new_state(cap=cfg["prefix"] + 64 * (cfg["n_draft"] + 1) + 16)
+    max_steps = 200                                   # ~12 s of host time at config 1; budget_s bounds slower hosts
+    st = orc.new_state(cap=cfg["prefix"] + (max_steps + 4) * (cfg["n_draft"] + 1) + 16)
     orc.prefill(st, prefix[0])
     block, steps, acc = list(first[0]), 0, 0
     t0 = time.perf_counter()
@@ -59,7 +60,7 @@ def cpu_baseline(cfg: dict, w: dict, prefix, first, budget_s: float = 15.0) -> d
         steps += 1
         acc += r["n_accepted"]
         el = time.perf_counter() - t0
-        if el > budget_s or steps >= 60:
+        if el > budget_s or steps >= max_steps:
             break
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": round((cfg["n_draft"] + 1) * steps / el, 2), "unit": "tok/s", "cores": int(threads),
