@@ -106,11 +106,19 @@ typedef struct {
 
 /* flags[b] bits */
 enum {
-  XSM_FLAG_NEAR_TIE = 1u,     /* some decision of this step had a top-1/top-2 (or rank
-                                 boundary) logit margin <= 1e-2 */
+  XSM_FLAG_NEAR_TIE = 1u,     /* some decision of this step was close to flipping: an argmax or
+                                 rank-boundary logit margin <= 1e-2, T |ln(p / delta)| <= 1e-2 under
+                                 the threshold criterion (the logit change that would flip it),
+                                 a draw's uniform within 2e-5 (of the total
+                                 weight) of an inverse-CDF edge, or a probability-tree path within
+                                 1e-4 (relative) of the cut-off */
   XSM_FLAG_BAD_LEN = 2u,      /* kv_len[b] < 0 or kv_len[b] + rows > max_ctx or > kv_len_bound */
   XSM_FLAG_BAD_TOKEN = 4u,    /* a block token outside [0, vocab) */
-  XSM_FLAG_BAD_SLOT = 8u      /* slot[b] outside [0, max_batch) */
+  XSM_FLAG_BAD_SLOT = 8u,     /* slot[b] outside [0, max_batch) */
+  XSM_FLAG_DEVICE_TIMEOUT = 16u /* a bounded device-side wait of the single-launch step gave up, in
+                                 this step or an earlier one: the sequence produced nothing
+                                 (n_accepted[b] = 0, block / kv_len / out_tokens untouched); see
+                                 xsm_check_device */
 };
 
 /* One call's worth of sequences.  R = n_draft + 1 for xsm_spec_step, 1 for
@@ -145,7 +153,8 @@ XSM_API size_t xsm_canonical_weight_elems(const xsm_ctx* ctx); /* elements in th
  * per-stage kernels).  XSM_EINVAL on a null or misaligned pointer. */
 XSM_API int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspace);
 
-/* Upload weights.  h_canonical: host array of n_elems elements of cfg.dtype
+/* Upload the model (Sec. 4.1: the backbone's decoder blocks and W^(0) of Eq. 3; Sec. 4.2, Eq. 4: the D
+ * decoding heads).  h_canonical: host array of n_elems elements of cfg.dtype
  * (bf16 bit patterns or float), all matrices [out][in] row-major, in this order:
  * E[V][d]; per layer g1[d], Wqkv[3d][d] (q rows, k rows, v rows), Wo[d][d],
  * (if n_cond: gc[d], Wcq[d][d], Wckv[2d][d], Wco[d][d]), g2[d], W1[F][d], W2[d][F];
@@ -155,13 +164,17 @@ XSM_API int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspac
  * array may be reused once the stream has been synchronised. */
 XSM_API int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_stream stream);
 
-/* Condition prefill: run the backbone over P prefix embeddings per sequence
- * (used directly as layer-0 hidden states at positions 0..P-1, full causal mask)
- * filling the cache of slot h_slot[i]; with n_cond > 0 also project the condition
- * tokens to every layer's cross-attention keys/values.  d_prefix_emb:
- * [n_seq][P][d] of cfg.dtype (may be NULL when P == 0); d_cond:
- * [n_seq][n_cond][d] of cfg.dtype (NULL when n_cond == 0).  The caller then sets
- * kv_len = P.  Enqueues on `stream`, does not synchronise. */
+/* Condition prefill (Sec. 4.1: generation is conditioned on c, and the decoder attends to the
+ * cached x_0..x_{s-1}; Alg. 1 starts from that state): run the backbone over P prefix embeddings
+ * per sequence (used directly as layer-0 hidden states at positions 0..P-1, full causal mask)
+ * filling the cache of slot h_slot[i]; with n_cond > 0 also project the condition tokens to every
+ * layer's cross-attention keys/values (and to the cross-attention heads' own, Eq. 4).
+ * d_prefix_emb: [n_seq][P][d] of cfg.dtype (may be NULL when P == 0); d_cond:
+ * [n_seq][n_cond][d] of cfg.dtype (NULL when n_cond == 0).  Cache lengths belong to the caller
+ * (xsm_batch.kv_len is a caller-owned device array the library only reads and advances in a
+ * step): the prefill writes cache positions 0..P-1 and no length, and the caller sets
+ * kv_len[b] = P for these sequences before their first step.  h_slot is a host array, read
+ * before the call returns.  Enqueues on `stream`, does not synchronise. */
 XSM_API int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* d_prefix_emb,
                 int32_t P, const void* d_cond, xsm_stream stream);
 
@@ -198,9 +211,17 @@ XSM_API int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value);
 XSM_API int xsm_debug_timeline(xsm_ctx* ctx, uint64_t* h_out, size_t n_words);
 
 /* Synchronises the device and reports whether a bounded device-side wait of the
- * single-launch step ever gave up (XSM_EDEVICE; results of that step are invalid and later
- * single-launch steps return immediately until weights are loaded again).  XSM_OK otherwise. */
+ * single-launch step gave up since the last call (XSM_EDEVICE, reported once).  The step in
+ * which that happened, and every single-launch step enqueued after it, wrote n_accepted[b] = 0
+ * and XSM_FLAG_DEVICE_TIMEOUT for the sequences it could not finish and left their block,
+ * kv_len and out_tokens untouched, so a caller that reads a step's outputs sees the failure
+ * without this call.  After the report this context's steps run on the per-stage kernels
+ * (until weights are loaded again): repeat the lost step.  XSM_OK otherwise. */
 XSM_API int xsm_check_device(xsm_ctx* ctx);
+
+/* Test only, synchronous: set the single-launch step's device-side error word as a timed-out
+ * wait would (no wait is made to spin), so that the failure path above can be exercised. */
+XSM_API int xsm_debug_inject_device_error(xsm_ctx* ctx, uint32_t code);
 
 /* Test/bench only, synchronous (they synchronise the device): copy cache rows of
  * one layer/slot to or from a host float array [n_heads][n_pos][head_dim].

@@ -117,7 +117,10 @@ class Batcher:
             flags = self.buf.flags.cpu().numpy()
             keep = []
             for i, lv in enumerate(self.live):
-                if flags[i] & ~1:
+                if flags[i] & 16:           # XSM_FLAG_DEVICE_TIMEOUT: nothing was produced; say why
+                    self.eng.xsm_check_device()
+                    raise RuntimeError(f"request {lv.rid}: the step timed out on the device")
+                if flags[i] & ~1 or n_acc[i] < 1:
                     raise RuntimeError(f"request {lv.rid}: device flagged input error {int(flags[i])}")
                 req = self.requests[lv.rid]
                 a = int(n_acc[i])

@@ -189,6 +189,17 @@ int attn_splits(const xsm_ctx* c, int n_units, int len_bound) {
   return best;
 }
 
+// A projection on the MFMA path; a (prologue, epilogue) pair no kernel takes is remembered and
+// reported by the entry point (nothing is enqueued for it, so its output would be stale).
+void fgemm(xsm_ctx* c, int pro, int epi, const FastGemm& g, hipStream_t s) {
+  if (!launch_fgemm(pro, epi, g, s)) c->gemm_unmatched = true;
+}
+int unmatched_gemm(xsm_ctx* c) {
+  if (!c->gemm_unmatched) return XSM_OK;
+  c->gemm_unmatched = false;
+  return fail(c, XSM_EINVAL, "internal: a projection found no kernel for its prologue / epilogue at this shape");
+}
+
 // MFMA path: all decoder blocks over M = n_seq*R rows held in ws.X (fp32 residual stream).
 void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_t s) {
   const xsm_config& g = c->cfg;
@@ -228,7 +239,7 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     q.Y = Qr; q.ldy = d; q.nscratch = Xn; q.ws_part = gpart; q.ws_tickets = gtick; q.pend = PEND;
     q.rope = rope; q.eff_len = eff; q.slot = slot; q.R = R; q.H = H; q.hd = hd; q.cap = c->cap_self;
     q.v_transposed = 1; q.Kc = (uint16_t*)self_cache(c, l, 0); q.Vc = (uint16_t*)self_cache(c, l, 1);
-    launch_fgemm(PRO_NORM, FEPI_QKV, q, s);
+    fgemm(c, PRO_NORM, FEPI_QKV, q, s);
 
     FastAttn a{};
     a.Q = Qr; a.ldq = d; a.Kc = (const uint16_t*)self_cache(c, l, 0); a.Vt = (const uint16_t*)self_cache(c, l, 1);
@@ -241,21 +252,21 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     FastGemm o{};
     o.Wt = (const uint4*)(c->d_w + T.Wo); o.N = d; o.K = d; o.M = M;
     o.X = AO; o.ldx = d; o.Y = X; o.ldy = d; o.nscratch = Xn; o.ws_part = gpart; o.ws_tickets = gtick; o.pend = PEND;
-    launch_fgemm(o_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, o, s);
+    fgemm(c, o_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, o, s);
 
     if (g.n_cond > 0) {
       FastGemm cq{};
       cq.Wt = (const uint4*)(c->d_w + T.Wcq); cq.N = d; cq.K = d; cq.M = M;
       cq.X = X; cq.ldx = d; cq.gain = (const uint16_t*)P.gc; cq.eps = g.rms_eps;
       cq.Y = Qr; cq.ldy = d; cq.nscratch = Xn; cq.ws_part = gpart; cq.ws_tickets = gtick; cq.pend = PEND;
-      launch_fgemm(PRO_NORM, FEPI_STORE, cq, s);
+      fgemm(c, PRO_NORM, FEPI_STORE, cq, s);
       FastAttn ca = a;
       ca.Kc = (const uint16_t*)cross_cache(c, l, 0); ca.Vt = (const uint16_t*)cross_cache(c, l, 1);
       ca.cap = c->cap_cross; ca.fixed_limit = g.n_cond; ca.S = attn_splits(c, n_seq * ((R + 15) / 16), g.n_cond);
       launch_fattn(ca, n_seq, s);
       FastGemm co = o;
       co.Wt = (const uint4*)(c->d_w + T.Wco);
-      launch_fgemm(o_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, co, s);
+      fgemm(c, o_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, co, s);
     }
 
     FastGemm u{};
@@ -263,12 +274,12 @@ void forward_blocks_fast(xsm_ctx* c, int n_seq, int R, int len_bound, hipStream_
     u.X = X; u.ldx = d; u.gain = (const uint16_t*)P.g2; u.eps = g.rms_eps;
     u.Y = U; u.ldy = F; u.nscratch = Xn; u.ws_part = gpart; u.ws_tickets = gtick; u.pend = PEND;
     u.y_planes = dn_planes ? 1 : 0;
-    launch_fgemm(PRO_NORM, FEPI_GELU, u, s);
+    fgemm(c, PRO_NORM, FEPI_GELU, u, s);
 
     FastGemm dn{};
     dn.Wt = (const uint4*)(c->d_w + T.W2); dn.N = d; dn.K = F; dn.M = M;
     dn.X = U; dn.ldx = F; dn.Y = X; dn.ldy = d; dn.nscratch = Xn; dn.ws_part = gpart; dn.ws_tickets = gtick; dn.pend = PEND;
-    launch_fgemm(dn_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, dn, s);
+    fgemm(c, dn_planes ? PRO_PLANES : PRO_F32, FEPI_ADD, dn, s);
   }
   flush_pending_add(PEND, s);                     // the residual rows are read by the caller next
 }
@@ -368,7 +379,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   const char* wb = ctx->d_w;
   const size_t e = ctx->esz;
 
-  if (ctx->small_ok && ctx->small_dev && ctx->use_small && M <= 16 && M + M * K <= kSmallMaxRows && n_seq * g.n_heads <= 256) {
+  if (ctx->small_ok && ctx->small_dev && ctx->use_small && !ctx->small_failed && M <= 16 && M + M * K <= kSmallMaxRows && n_seq * g.n_heads <= 256) {
     // the whole step as one persistent kernel; greedy verification with argmax draws finishes inside
     // it, the other criteria and sampling rules run on its logits in the verify / emit kernels
     const bool defer = !(vp->mode == XSM_VERIFY_GREEDY && vp->sample == 0);
@@ -377,6 +388,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
                      bt->kv_len_bound, eff, slot, wfl, s);
     SmallArgs a{};
     a.defer_verify = defer ? 1 : 0;
+    a.eff_out = defer ? eff : nullptr; a.wflags_out = defer ? wfl : nullptr;
     a.layers = (const LayerTab*)(wb + ctx->layer_tab_off); a.L = g.n_layers;
     a.E = (const uint16_t*)(wb + ctx->woff.E * e); a.gf = (const uint16_t*)(wb + ctx->woff.gf * e);
     a.hb = (const uint16_t*)(wb + ctx->toff.hb);
@@ -427,7 +439,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     z.Wt = (const uint4*)(wb + ctx->toff.WU); z.N = V; z.K = d; z.M = M;
     z.X = X; z.ldx = d; z.gain = (const uint16_t*)(wb + ctx->woff.gf * e); z.eps = g.rms_eps;
     z.Y = Z0; z.ldy = V; z.nscratch = Xn; z.ws_part = gpart; z.ws_tickets = gtick; z.pend = PEND;
-    launch_fgemm(PRO_NORM, FEPI_STORE, z, s);
+    fgemm(ctx, PRO_NORM, FEPI_STORE, z, s);
     if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
     launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
     if (K > 0 && g.head_kind == XSM_HEAD_CA) {
@@ -447,7 +459,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
       hq.Wt = (const uint4*)(wb + ctx->toff.Wh); hq.N = K * d; hq.K = d; hq.M = n_seq;
       hq.X = G; hq.ldx = d; hq.Y = Qh; hq.ldy = K * d;
       hq.nscratch = Xn; hq.ws_part = gpart; hq.ws_tickets = gtick; hq.pend = PEND;
-      launch_fgemm(PRO_F32, FEPI_STORE, hq, s);
+      fgemm(ctx, PRO_F32, FEPI_STORE, hq, s);
       FastAttn ha{};
       ha.Q = Qh; ha.ldq = d; ha.Kc = (const uint16_t*)head_cache(ctx, 0, 0); ha.Vt = (const uint16_t*)head_cache(ctx, 0, 1);
       ha.eff_len = eff2; ha.slot = slot2; ha.O = Oh; ha.ldo = d;
@@ -460,12 +472,12 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
         ho.Wt = (const uint4*)(wb + ctx->toff.Who[k]); ho.N = d; ho.K = d; ho.M = n_seq;
         ho.X = Oh + (size_t)k * d; ho.ldx = K * d; ho.Y = Rk + (size_t)k * d; ho.ldy = K * d;
         ho.nscratch = Xn; ho.ws_part = gpart; ho.ws_tickets = gtick; ho.pend = nullptr;
-        launch_fgemm(PRO_F32, FEPI_ADD, ho, s);
+        fgemm(ctx, PRO_F32, FEPI_ADD, ho, s);
         FastGemm zu{};
         zu.Wt = (const uint4*)(wb + ctx->toff.WhU[k]); zu.N = V; zu.K = d; zu.M = n_seq;
         zu.X = Rk + (size_t)k * d; zu.ldx = K * d; zu.Y = Zh + (size_t)k * V; zu.ldy = K * V;
         zu.nscratch = Xn; zu.ws_part = gpart; zu.ws_tickets = gtick; zu.pend = PEND;
-        launch_fgemm(PRO_F32, FEPI_STORE, zu, s);
+        fgemm(ctx, PRO_F32, FEPI_STORE, zu, s);
       }
       if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     } else if (K > 0) {
@@ -476,11 +488,11 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
       hg.X = X; hg.ldx = d; hg.gain = z.gain; hg.eps = g.rms_eps; hg.row_index = rowidx;
       hg.Y = Rk; hg.ldy = K * d; hg.bias = (const uint16_t*)(wb + ctx->toff.hb);
       hg.nscratch = Xn; hg.ws_part = gpart; hg.ws_tickets = gtick; hg.pend = PEND;
-      launch_fgemm(PRO_NORM, FEPI_HEAD, hg, s);
+      fgemm(ctx, PRO_NORM, FEPI_HEAD, hg, s);
       FastGemm zh{};
       zh.Wt = z.Wt; zh.N = V; zh.K = d; zh.M = n_seq * K;
       zh.X = Rk; zh.ldx = d; zh.Y = Zh; zh.ldy = V; zh.nscratch = Xn; zh.ws_part = gpart; zh.ws_tickets = gtick; zh.pend = PEND;
-      launch_fgemm(PRO_F32, FEPI_STORE, zh, s);
+      fgemm(ctx, PRO_F32, FEPI_STORE, zh, s);
       if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
     }
   } else {
@@ -522,7 +534,7 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
               bt->n_accepted, bt->flags, n_seq, R, K, V, s);
   hipError_t e2 = hipGetLastError();
   if (e2 != hipSuccess) return fail(ctx, XSM_EHIP, std::string("launch: ") + hipGetErrorString(e2));
-  return XSM_OK;
+  return unmatched_gemm(ctx);
 }
 
 }  // namespace
@@ -682,6 +694,7 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
   }
   XSM_HIP(hipGetLastError());
   ctx->loaded = true;
+  ctx->small_failed = false;
   return XSM_OK;
 }
 
@@ -730,7 +743,7 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
         p.X = X; p.ldx = d; p.Y = QKV; p.ldy = 2 * d;
         p.nscratch = Xn; p.ws_part = gpart; p.ws_tickets = gtick; p.pend = &ctx->pend;
         p.x_single = cond_plane ? 1 : 0;             // (X then holds the condition rows as one bf16 operand plane)
-        launch_fgemm(cond_plane ? PRO_PLANES : PRO_F32, FEPI_STORE, p, s);
+        fgemm(ctx, cond_plane ? PRO_PLANES : PRO_F32, FEPI_STORE, p, s);
       } else {
         launch_gemm(dt, EPI_STORE, X, d, Wcanon, QKV, 2 * d, M, 2 * d, d, s);
       }
@@ -761,7 +774,7 @@ int xsm_prefill(xsm_ctx* ctx, int32_t n_seq, const int32_t* h_slot, const void* 
     forward_blocks(ctx, n_seq, C, r0, s);
   }
   XSM_HIP(hipGetLastError());
-  return XSM_OK;
+  return unmatched_gemm(ctx);
 }
 
 int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
@@ -802,9 +815,24 @@ int xsm_check_device(xsm_ctx* ctx) {
   if (!ctx->small_ok || !ctx->d_ws || !ctx->loaded) return XSM_OK;
   uint32_t c[2] = {0, 0};
   XSM_HIP(hipMemcpy(c, ctx->d_ws + ctx->ws.ctrl, 8, hipMemcpyDeviceToHost));
-  if (c[1] != 0)
+  if (c[1] != 0) {
+    // reported once: the error word is cleared and this context's later steps take the per-stage
+    // kernels (the exchange buffers may hold half a step; loading weights again resets them)
+    const uint32_t zero = 0;
+    XSM_HIP(hipMemcpy(ctx->d_ws + ctx->ws.ctrl + 4, &zero, 4, hipMemcpyHostToDevice));
+    ctx->small_failed = true;
     return fail(ctx, XSM_EDEVICE, "single-launch step: a wait for stage inputs timed out (stage code " +
-                                      std::to_string(c[1]) + ")");
+                                      std::to_string(c[1]) + "); the sequences of that step carry n_accepted = 0 and "
+                                      "XSM_FLAG_DEVICE_TIMEOUT, later steps run on the per-stage kernels");
+  }
+  return XSM_OK;
+}
+
+int xsm_debug_inject_device_error(xsm_ctx* ctx, uint32_t code) {
+  if (!ctx) return XSM_EINVAL;
+  if (!ctx->small_ok || !ctx->d_ws || !ctx->loaded) return fail(ctx, XSM_ESTATE, "no single-launch step for this model");
+  XSM_HIP(hipDeviceSynchronize());
+  XSM_HIP(hipMemcpy(ctx->d_ws + ctx->ws.ctrl + 4, &code, 4, hipMemcpyHostToDevice));
   return XSM_OK;
 }
 

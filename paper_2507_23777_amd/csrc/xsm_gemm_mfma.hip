@@ -14,12 +14,23 @@
 // Epilogues: store, residual add, erf-GELU, rotary + q / cache write (fused QKV),
 // decoding-head activation r = g + SiLU(y + b).
 //
-// Three kernels share the fragment layout and the epilogues:
-//   k_fgemm     M <= 32: one tile per workgroup, whole contraction length, norm fused
-//   k_gemm_ws   M <= 256: 64 weight rows x 256 of the contraction index per workgroup, all
-//               held in registers from one request; partial products merged by the last
-//               workgroup to finish (fixed order)
-//   k_gemm_big  larger M: row-blocked, weights re-read from the XCD's L2 per row block
+// Five kernels share the fragment layout and the epilogues; launch_fgemm picks by row count
+// and prologue (first match):
+//   k_gemm_blk  M > 256, input as bf16 hi/lo operand planes (written by the norm pass in front
+//               of it, or by the producing kernel): 128 x 128 (or 64 x 128) register blocks,
+//               activations through double-buffered LDS; residual-add projections with the
+//               contraction cut into slices whose sum the next norm pass takes in
+//   k_gemm_wt   17 <= M <= 256, normalised input, at least 64 column tiles (QKV, FFN-up,
+//               unembedding): one 16-row weight tile per workgroup over the whole contraction,
+//               operand fragments straight from the norm pass's planes
+//   k_gemm_ws   17 <= M <= 256, everything else (the residual-add projections): 64 weight rows
+//               x 256 of the contraction index per workgroup, all held in registers from one
+//               request; partial products merged by the last workgroup to finish, or left to
+//               the next norm pass (fixed order either way)
+//   k_gemm_big  M > 32 where none of the above applies (fp32 input, contraction that cannot
+//               be cut): row-blocked, weights re-read from the XCD's L2 per row block
+//   k_fgemm     M <= 16 on the per-stage path, and the fallback for any shape: one tile per
+//               workgroup, whole contraction length, norm fused, up to 64 rows per pass
 #include "xsm_device.h"
 #include "xsm_internal.h"
 
@@ -1226,28 +1237,30 @@ static void fgemm_launch(FastGemm g, hipStream_t s) {
 #undef XSM_FG
 }
 
-void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
-  if (g.M <= 0) return;
+bool launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
+  if (g.M <= 0) return true;
+  // operand planes in (PRO_PLANES) or out (y_planes) exist only on the row-blocked kernel
+  if ((pro == PRO_PLANES || g.y_planes) && !blk_gemm_usable(pro, g)) return false;
   // (the residual-add projections read fp32 rows and have few column blocks: k_gemm_big is faster there)
   if (blk_gemm_usable(pro, g)) {
     TraceScope trace_("gemm_blk", s);
     blk_gemm(pro, epi, g, s);
-    return;
+    return true;
   }
   if (wt_gemm_usable(pro, g) && epi != FEPI_ADD) {
     TraceScope trace_("gemm_wt", s);
     wt_gemm(epi, g, s);
-    return;
+    return true;
   }
   if (ws_gemm_usable(g)) {
     TraceScope trace_("gemm_ws", s);
     ws_gemm(pro, epi, g, s);
-    return;
+    return true;
   }
   flush_pending_add(g.pend, s);                        // the other kernels read finished rows
   if (g.M > kBigMinM) {
     TraceScope trace_("gemm_big", s);
-    if (big_gemm(pro, epi, g, s)) return;
+    if (big_gemm(pro, epi, g, s)) return true;
   }
   TraceScope trace_("fgemm", s);
   if (pro == PRO_NORM && epi == FEPI_QKV) fgemm_launch<PRO_NORM, FEPI_QKV>(g, s);
@@ -1256,6 +1269,8 @@ void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s) {
   else if (pro == PRO_NORM && epi == FEPI_HEAD) fgemm_launch<PRO_NORM, FEPI_HEAD>(g, s);
   else if (pro == PRO_F32 && epi == FEPI_ADD) fgemm_launch<PRO_F32, FEPI_ADD>(g, s);
   else if (pro == PRO_F32 && epi == FEPI_STORE) fgemm_launch<PRO_F32, FEPI_STORE>(g, s);
+  else return false;
+  return true;
 }
 
 }  // namespace xsm

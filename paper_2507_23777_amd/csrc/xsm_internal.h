@@ -80,6 +80,8 @@ struct xsm_ctx {
   bool small_ok = false;   // single-launch step available for this model shape
   bool use_small = true;   // xsm_set_option(XSM_OPT_SINGLE_LAUNCH)
   bool small_dev = false;  // the bound device can hold the single launch's 256 workgroups at once
+  bool small_failed = false;   // xsm_check_device found a timed-out wait: per-stage kernels until weights are loaded again
+  bool gemm_unmatched = false; // a projection found no kernel for its (prologue, epilogue) pair: the step reports it
   bool timeline = false;   // xsm_set_option(XSM_OPT_TIMELINE)
   int force_splits = 0;    // xsm_set_option(XSM_OPT_ATTN_SPLITS): key-range slices per (sequence, head), 0 = automatic
   int prefill_rows = 0;              // XSM_OPT_PREFILL_ROWS: rows per prefill pass, 0 = what the workspace holds
@@ -197,7 +199,8 @@ size_t blk_add_part_floats(int Mmax, int N, int K);
 constexpr size_t kWsTickets = 4096;      // arrival counters of the split-contraction GEMM
 bool ws_gemm_shape_ok(int M, int N, int K);
 size_t ws_gemm_part_floats(int M, int N, int K);
-void launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s);
+// false: no kernel takes this (prologue, epilogue) pair at this shape; nothing was enqueued
+bool launch_fgemm(int pro, int epi, const FastGemm& g, hipStream_t s);
 void launch_tile_weights(const void* W, void* out, int N, int K, int rope_d, int rope_hd, hipStream_t s);
 void launch_copy_u16(const void* src, void* dst, int n, hipStream_t s);
 
@@ -238,6 +241,8 @@ struct SmallArgs {
   int s_auto;                            // 1: the kernel picks the slice count <= S from the cache lengths it reads
   int defer_verify;                      // 1: stop after the unembedding (logits of all rows written); the
                                          // caller runs verification and the draws as separate kernels
+  int32_t* eff_out; uint32_t* wflags_out; // deferred steps: the effective lengths / flag words those kernels
+                                         // read; a sequence lost to a timed-out wait is marked skipped there
   float eps, scale_log2;
 };
 constexpr int kSmallMaxRows = 144;     // backbone rows + head rows (M + M K) of one single-launch step

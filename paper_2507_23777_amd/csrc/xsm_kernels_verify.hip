@@ -9,7 +9,9 @@
 
 namespace xsm {
 
-constexpr float kTieMargin = 1e-2f;
+constexpr float kTieMargin = 1e-2f;      // logit gap of an argmax or rank decision
+constexpr float kCdfMargin = 2e-5f;      // distance of a draw's uniform from a CDF edge, relative to the total weight
+constexpr float kCutMargin = 1e-4f;      // relative distance of a tree path's weight from the cut-off
 
 struct RowScratch {
   float redf[8];
@@ -123,8 +125,9 @@ __device__ float row_prob(const float* z, int V, int x, float invT, RowScratch& 
   return expf((z[x] - mx) * invT) / s;
 }
 
-// categorical draw by inverse CDF over ascending token index
-__device__ int row_categorical(const float* z, int V, float invT, float u, RowScratch& sm) {
+// categorical draw by inverse CDF over ascending token index; *near_edge: the uniform lies within
+// kCdfMargin (relative to the total weight) of a CDF edge
+__device__ int row_categorical(const float* z, int V, float invT, float u, RowScratch& sm, bool* near_edge) {
   float mx = -INFINITY;
   for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
   mx = block_max(mx, sm.redf);
@@ -141,15 +144,17 @@ __device__ int row_categorical(const float* z, int V, float invT, float u, RowSc
     sm.redf[4] = run;
   }
   __syncthreads();
-  const float target = u * sm.redf[4];
+  const float target = u * sm.redf[4], band = kCdfMargin * sm.redf[4];
   float run = sm.part[threadIdx.x];
-  int hit = 0x7FFFFFFF, lastpos = -1;
+  int hit = 0x7FFFFFFF, lastpos = -1, close = fabsf(run - target) <= band ? 1 : 0;
   for (int v = v0; v < v1; ++v) {
     const float w = expf((z[v] - mx) * invT);
     run += w;
     if (w > 0.f) lastpos = v;
     if (hit == 0x7FFFFFFF && run > target) hit = v;
+    close |= fabsf(run - target) <= band ? 1 : 0;
   }
+  *near_edge = block_max_i(close, sm.redi) != 0;
   hit = block_min_i(hit, sm.redi);
   if (hit != 0x7FFFFFFF) return hit;
   return block_max_i(lastpos, sm.redi);
@@ -164,7 +169,10 @@ __device__ int row_sample(const float* z, int V, const xsm_verify_params& vp, ui
     return t;
   }
   const float u = philox_uniform(vp.seed, pos, head, seq);
-  return row_categorical(z, V, 1.0f / vp.temperature, u, sm);
+  bool near_edge;
+  const int t = row_categorical(z, V, 1.0f / vp.temperature, u, sm, &near_edge);
+  if (near_edge) *flag |= XSM_FLAG_NEAR_TIE;
+  return t;
 }
 
 // accept scan + backbone draw + hidden-state gather
@@ -188,7 +196,11 @@ __global__ __launch_bounds__(256) void k_verify(const float* Z0, const float* Hf
     const int x = block[b * R + j];
     bool ok;
     if (vp.mode == XSM_VERIFY_THRESHOLD) {
-      ok = row_prob(z, V, x, 1.0f / vp.temperature, sm) > vp.delta;
+      const float p = row_prob(z, V, x, 1.0f / vp.temperature, sm);
+      ok = p > vp.delta;
+      // p crosses delta when the candidate's logit moves by about T |ln(p / delta)|
+      if (p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin)
+        flag |= XSM_FLAG_NEAR_TIE;
     } else {
       const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
       const int rank = row_rank(z, V, x, sm);
@@ -242,8 +254,10 @@ void launch_head_act(int dtype, const float* G, const float* Hh, const void* con
 // holds the ks most probable tokens of softmax(z_d / T) with their probabilities as edge weights;
 // a complete path survives if its weight (a product of numbers <= 1, so the smallest of its
 // prefixes' weights) is at least `prune`; one survivor is drawn in proportion to its weight by
-// inverse CDF in depth-first (= lexicographic) order.  cand[1..K] receives the tokens.
-__device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
+// inverse CDF in depth-first (= lexicographic) order.  cand[1..K] receives the tokens.  Returns
+// true (to every thread) when the draw is a near-tie: the uniform within kCdfMargin of a path
+// boundary, or a path's weight within kCutMargin (relative) of the cut-off.
+__device__ bool pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
                          RowScratch& sm, int* cand) {
   __shared__ int top_i[16][4];
   __shared__ float top_p[16][4];
@@ -295,14 +309,21 @@ __device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, floa
     for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
     return (w >= (double)prune && w > 0.0) ? w : 0.0;   // cut paths carry no weight
   };
+  auto raw_weight = [&](int leaf) {
+    double w = 1.0;
+    int rem = leaf, div = n_paths;
+    for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
+    return w;
+  };
   const int chunk = (n_paths + 255) / 256;
   const int l0 = min(n_paths, (int)threadIdx.x * chunk), l1 = min(n_paths, l0 + chunk);
   double loc = 0.0;
-  int lastpos = -1;
+  int lastpos = -1, close = 0;
   for (int leaf = l0; leaf < l1; ++leaf) {
     const double w = weight(leaf);
     loc += w;
     if (w > 0.0) lastpos = leaf;
+    if (fabs(raw_weight(leaf) - (double)prune) <= (double)kCutMargin * (double)prune) close = 1;
   }
   pt_part[threadIdx.x] = loc;
   lastpos = block_max_i(lastpos, sm.redi);
@@ -316,14 +337,17 @@ __device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, floa
   __syncthreads();
   int hit = 0x7FFFFFFF;
   if (pt_last >= 0) {
-    const double target = (double)u * pt_total;
+    const double target = (double)u * pt_total, band = (double)kCdfMargin * pt_total;
     double run = pt_part[threadIdx.x];
+    if (fabs(run - target) <= band) close = 1;
     for (int leaf = l0; leaf < l1; ++leaf) {
       const double w = weight(leaf);
       run += w;
-      if (w > 0.0 && run > target) { hit = leaf; break; }
+      if (fabs(run - target) <= band) close = 1;
+      if (hit == 0x7FFFFFFF && w > 0.0 && run > target) hit = leaf;
     }
   }
+  close = block_max_i(close, sm.redi);
   hit = block_min_i(hit, sm.redi);
   if (threadIdx.x == 0) {
     // no survivor: the most probable token of every head; rounding left nothing above the target: the last survivor
@@ -332,6 +356,7 @@ __device__ void pts_draw(const float* Zh, int K, int V, int ks, float invT, floa
     for (int k = 0; k < K; ++k) { div /= ks; cand[k + 1] = top_i[k][rem / div]; rem %= div; }
   }
   __syncthreads();
+  return close != 0;
 }
 
 // independent draws from the K head rows, one workgroup per (head, sequence): cand[b][k], and
@@ -371,10 +396,11 @@ __global__ __launch_bounds__(256) void k_emit(const float* Zh, xsm_verify_params
   }
   const int a = acc[b];
   if (threadIdx.x < R) old_block[threadIdx.x] = block[b * R + threadIdx.x];
-  const uint32_t flag = 0;
+  uint32_t flag = 0;
   if (vp.sample == 2 && K > 0) {
     const float u = philox_uniform(vp.seed, (uint32_t)(n + a + 1), 254u, (uint32_t)slot[b]);
-    pts_draw(Zh + (size_t)b * K * V, K, V, vp.top_ks, 1.0f / vp.temperature, vp.pts_prune, u, sm, cand);
+    if (pts_draw(Zh + (size_t)b * K * V, K, V, vp.top_ks, 1.0f / vp.temperature, vp.pts_prune, u, sm, cand))
+      flag = XSM_FLAG_NEAR_TIE;
   } else if (threadIdx.x >= 1 && threadIdx.x <= K) {
     cand[threadIdx.x] = drawn[b * 16 + threadIdx.x];          // k_draw_heads ran before this kernel
   }

@@ -387,7 +387,19 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     sm.len[tid] = len; sm.slot[tid] = sl; sm.flag[tid] = f;
   }
   __syncthreads();
-  if (sm.fail != 0) return;                 // an earlier step timed out: stay down until reset
+  // A bounded wait gave up, in this step or an earlier one: sequence b produced nothing.  The
+  // caller sees it in the step's own outputs (n_accepted 0, the timeout flag), and the verify /
+  // emit kernels that follow a deferred step skip the sequence.
+  auto report_timeout = [&](int b) {
+    const uint32_t f = sm.flag[b] | XSM_FLAG_DEVICE_TIMEOUT;
+    a.n_accepted[b] = 0;
+    a.flags[b] = f;
+    if (a.eff_out) { a.eff_out[b] = -1; a.wflags_out[b] = f; }
+  };
+  if (sm.fail != 0) {                       // an earlier step timed out: stay down until reset
+    if (w < a.n_seq && tid == 0) report_timeout(w);
+    return;
+  }
   const uint32_t tag = sm.tag;
   // Key slices per (sequence, head), from the longest live cache (every workgroup reads the same
   // lengths, so all agree).  The cached keys and values come from HBM at full memory latency and a
@@ -893,7 +905,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     }
     // a workgroup that timed out anywhere leaves (its consumers will time out in turn)
     if (__syncthreads_or(!ok)) {
-      if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u + (uint32_t)l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) {
+        __hip_atomic_store(a.ctrl + 1, 1u + (uint32_t)l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (w < a.n_seq) report_timeout(w);
+      }
       return;
     }
   }
@@ -1039,10 +1054,12 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         ++acc_all;
       }
     for (int k = wave; k < K; k += 4) row_top2(R + k, M + (b * R + acc_all) * K + k);
-    __syncthreads();
+    const bool late = __syncthreads_or(!ok);              // some statistics never arrived: nothing to emit
     if (tid == 0) {
       uint32_t fl = sm.flag[b];
-      if (n < 0) {
+      if (late) {
+        report_timeout(b);
+      } else if (n < 0) {
         a.n_accepted[b] = 0;
         a.flags[b] = fl;
       } else {
@@ -1075,7 +1092,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
   XSM_STAMP(a.L * 16 + 4);
   if (__syncthreads_or(!ok)) {
-    if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+      __hip_atomic_store(a.ctrl + 1, 1000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (w < a.n_seq) report_timeout(w);
+    }
     return;
   }
   // workgroup 0 closes the step: its FINAL needed every workgroup's statistics, so every

@@ -20,7 +20,8 @@ API = ["xsm_create", "xsm_destroy", "xsm_last_error", "xsm_weights_bytes", "xsm_
        "xsm_workspace_bytes", "xsm_canonical_weight_elems", "xsm_bind", "xsm_load_weights",
        "xsm_prefill", "xsm_spec_step", "xsm_plain_step", "xsm_debug_kv_export",
        "xsm_debug_kv_import", "xsm_debug_trace_enable", "xsm_debug_trace_report", "xsm_set_option",
-       "xsm_check_device", "xsm_debug_timeline", "xsm_debug_kv_clone"]
+       "xsm_check_device", "xsm_debug_timeline", "xsm_debug_kv_clone", "xsm_debug_inject_device_error"]
+XSM_FLAG_NEAR_TIE, XSM_FLAG_BAD_LEN, XSM_FLAG_BAD_TOKEN, XSM_FLAG_BAD_SLOT, XSM_FLAG_DEVICE_TIMEOUT = 1, 2, 4, 8, 16
 
 
 class XsmError(RuntimeError):
@@ -79,6 +80,7 @@ def lib() -> C.CDLL:
     L.xsm_debug_kv_clone.argtypes, L.xsm_debug_kv_clone.restype = [vp, i32, i32], C.c_int
     L.xsm_debug_timeline.argtypes, L.xsm_debug_timeline.restype = [vp, vp, sz], C.c_int
     L.xsm_check_device.argtypes, L.xsm_check_device.restype = [vp], C.c_int
+    L.xsm_debug_inject_device_error.argtypes, L.xsm_debug_inject_device_error.restype = [vp, C.c_uint32], C.c_int
     L.xsm_debug_trace_enable.argtypes, L.xsm_debug_trace_enable.restype = [C.c_int], None
     L.xsm_debug_trace_report.argtypes, L.xsm_debug_trace_report.restype = [C.c_char_p, sz], C.c_int
     _lib = L
@@ -224,6 +226,9 @@ class Engine:
 
     def xsm_check_device(self):
         self._check(self.L.xsm_check_device(self.h), "xsm_check_device")
+
+    def xsm_debug_inject_device_error(self, code: int):
+        self._check(self.L.xsm_debug_inject_device_error(self.h, code), "xsm_debug_inject_device_error")
 
     def xsm_debug_kv_export(self, layer: int, which: int, slot: int, pos0: int, n_pos: int) -> np.ndarray:
         out = np.empty((self.c_cfg.n_heads, n_pos, self.c_cfg.head_dim), np.float32)

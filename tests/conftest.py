@@ -15,3 +15,12 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_terminal_summary(terminalreporter):
+    """What the GPU parity cases compared (rows, decisions, near-ties), also under -q."""
+    import xsm_harness
+    if xsm_harness.SUMMARY:
+        terminalreporter.write_sep("-", "parity tallies (flagged = near-ties, not compared)")
+        for line in xsm_harness.SUMMARY:
+            terminalreporter.write_line(line)

@@ -24,9 +24,12 @@ def X():
     return type("X", (), {"pkg": pkg, "xsm": xsm, "H": H, "torch": torch})
 
 
-def _run_sampled(X, cfg, B, n_pos, lens, sample_ids, vp, steps=2, single_launch=None):
-    """GPU: B sequences with lengths lens; oracle: only sample_ids.  Returns the tally."""
-    K = cfg["n_draft"]
+def _run_sampled(X, cfg, B, n_pos, lens, sample_ids, vp, steps=2, single_launch=None, plain=False,
+                 expect_kernel=None):
+    """GPU: B sequences with lengths lens; oracle: only sample_ids.  plain: next-token steps
+    (one row per sequence) instead of speculative ones.  expect_kernel: a kernel class that the
+    steps must have launched (checked with the library's per-launch trace).  Returns the tally."""
+    K = 0 if plain else cfg["n_draft"]
     max_ctx = ((n_pos + (K + 1) * (steps + 1) + 63) // 64) * 64
     w = si.make_weights(cfg)
     eng = X.pkg.Engine(cfg, max_batch=B, max_ctx=max_ctx)
@@ -45,9 +48,9 @@ def _run_sampled(X, cfg, B, n_pos, lens, sample_ids, vp, steps=2, single_launch=
         eng.xsm_debug_kv_import(l, 1, 0, 0, fill[l, 1, 0])
     for b in range(1, B):
         eng.xsm_debug_kv_clone(0, b)
-    first = si.first_block(cfg, B)
+    first = si.first_block(cfg, B)[:, :K + 1]
     torch = X.torch
-    buf = eng.buffers(B, spec=True, debug=True)
+    buf = eng.buffers(B, spec=not plain, debug=True)
     cur_len = list(lens)
     blocks = first.copy()
     states = {}
@@ -64,10 +67,14 @@ def _run_sampled(X, cfg, B, n_pos, lens, sample_ids, vp, steps=2, single_launch=
     tal = X.H.Tally()
     tol = X.H.logit_tol(cfg)
     vpg = X.H.to_vp_gpu(X.xsm, vp)
+    own = X.H.own_draws(cfg)
+    if expect_kernel:
+        X.xsm.xsm_debug_trace_enable(True)
+        X.xsm.xsm_debug_trace_report()
     for step in range(steps):
         buf.kv_len.copy_(torch.tensor(cur_len, dtype=torch.int32))
         buf.block.copy_(torch.tensor(blocks, dtype=torch.int32))
-        eng.xsm_spec_step(buf, vpg, max(cur_len))
+        (eng.xsm_plain_step if plain else eng.xsm_spec_step)(buf, vpg, max(cur_len))
         torch.cuda.synchronize()
         eng.xsm_check_device()
         g_acc = buf.n_accepted.cpu().numpy()
@@ -79,13 +86,13 @@ def _run_sampled(X, cfg, B, n_pos, lens, sample_ids, vp, steps=2, single_launch=
         for b in sample_ids:
             st = states[b]
             n0 = st.n
-            r = orc.spec_step(st, blocks[b], vp)
+            r = orc.plain_step(st, int(blocks[b][0]), vp) if plain else orc.spec_step(st, blocks[b], vp)
             zg = buf.logits[b].cpu().numpy()
             for j in range(K + 1):
                 e = X.H.rel_err(zg[j], r["Z0"][j])
                 tal.max_rel = max(tal.max_rel, e); tal.rows += 1
                 assert e <= tol, f"step {step} seq {b} row {j}: rel err {e:.3e}"
-            a = r["a"]
+            a = r["n_accepted"] - 1
             safe = all(X.H.accept_margin(r["Z0"][j - 1], int(blocks[b][j]), vp) > X.H.TIE
                        for j in range(1, min(a + 1, K) + 1))
             tal.decisions += 1
@@ -94,24 +101,27 @@ def _run_sampled(X, cfg, B, n_pos, lens, sample_ids, vp, steps=2, single_launch=
             elif int(g_acc[b]) != a + 1:
                 tal.mismatches.append(f"step {step} seq {b}: n_accepted {g_acc[b]} vs {a + 1}")
             else:
-                zh = buf.head_logits[b].cpu().numpy()
+                zh = buf.head_logits[b].cpu().numpy() if K > 0 else None
                 X.H.check_draw(tal, f"step {step} seq {b}", "y0", r["diag"][0], int(g_out[b, a]),
-                               r["out_tokens"][a], zg[a], vp, n0 + a + 1, 0, st.seq_id)
+                               r["out_tokens"][a], zg[a], vp, n0 + a + 1, 0, st.seq_id, own=own)
                 for k in range(1, K + 1):
                     e = X.H.rel_err(zh[k - 1], r["Zh"][k - 1])
                     tal.max_rel = max(tal.max_rel, e); tal.rows += 1
                     assert e <= tol, f"step {step} seq {b} head {k}: rel err {e:.3e}"
                     X.H.check_draw(tal, f"step {step} seq {b}", f"head {k}", r["diag"][k], int(g_blk[b, k]),
-                                   r["next_block"][k], zh[k - 1], vp, n0 + a + 1 + k, k, st.seq_id)
+                                   r["next_block"][k], zh[k - 1], vp, n0 + a + 1 + k, k, st.seq_id, own=own)
             # teacher forcing for the sampled sequences; the others free-run
             g_blk[b] = r["next_block"]
             g_acc[b] = r["n_accepted"]
         blocks = g_blk.copy()
         cur_len = [int(cur_len[b] + g_acc[b]) for b in range(B)]
+    if expect_kernel:
+        ran = X.xsm.xsm_debug_trace_report()
+        X.xsm.xsm_debug_trace_enable(False)
+        assert expect_kernel in ran and ran[expect_kernel][0] >= steps, (expect_kernel, sorted(ran))
     eng.close()
-    print(f"[{cfg['name']} B{B} ctx {n_pos}] rows {tal.rows} max_rel {tal.max_rel:.3e} decisions {tal.decisions} "
-          f"flagged {tal.flagged} mismatches {len(tal.mismatches)}", flush=True)
-    assert not tal.mismatches, tal.mismatches[:5]
+    X.H.report(tal, f"{cfg['name']} B{B} K{K}{' plain' if plain else ''} ctx {n_pos}"
+                    f"{'' if single_launch is None else f' single_launch={single_launch}'}")
     return tal
 
 
@@ -151,3 +161,25 @@ def test_config4_large_batch(X):
     cfg = si.get_config("c4", batch=128, n_draft=8)
     lens = [10000 - 7 * b for b in range(128)]
     _run_sampled(X, cfg, 128, 10000, lens, [0, 127], GREEDY, steps=2)
+
+
+@pytest.mark.parametrize("B,K", [(1, 8), (8, 4), (32, 4), (64, 4), (64, 8)])
+def test_config4_grid_points(X, B, K):
+    """More points of the throughput sweep at context 10000, two sampled sequences each:
+    batch 1 with K = 8 runs on the single-launch kernel (9 block rows: two read rounds per stage,
+    16 key slices per head); M = 40 / 160 on the mid-batch kernels, M = 320 / 576 on the
+    row-blocked ones."""
+    cfg = si.get_config("c4", batch=B, n_draft=K)
+    lens = [10000 - 7 * b for b in range(B)]
+    _run_sampled(X, cfg, B, 10000, lens, sorted({0, B - 1}), GREEDY, steps=2,
+                 expect_kernel="step_small" if B == 1 else "fattn")
+
+
+@pytest.mark.parametrize("B", [8, 128])
+def test_config4_plain_step(X, B):
+    """The sweep's non-speculative comparison: next-token steps at the same shapes (batch 8 runs
+    on the single-launch kernel, batch 128 on the mid-batch kernels)."""
+    cfg = si.get_config("c4", batch=B)
+    lens = [10000 - 7 * b for b in range(B)]
+    _run_sampled(X, cfg, B, 10000, lens, [0, B - 1], GREEDY, steps=2, plain=True,
+                 expect_kernel="step_small" if B == 8 else "fattn")
