@@ -194,6 +194,23 @@ XSM_API int xsm_spec_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify
 XSM_API int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
                    xsm_stream stream);
 
+/* xsm_spec_step for callers that cannot allocate device memory or be handed a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same outputs (the per-stage kernels of xsm_spec_step, same arithmetic in the same
+ * order), but the step's activations, partial products and arrival counters live in a scratch
+ * array that is part of the library image (64 MiB of device memory per GPU, held from the time
+ * the library is loaded until the process ends) instead of the bound workspace, which this
+ * call neither reads nor writes.  Weights and cache are the bound buffers (xsm_bind looks the
+ * array's address up for its device; call with that device current).  The call allocates
+ * nothing, copies nothing and does not synchronise; it enqueues kernels only.
+ * XSM_ECAPACITY when the configuration's steps need more than the 64 MiB (the need grows with
+ * max_batch: 6 MB for a 24-layer d = 1024 model at max_batch 1, 45 MB at max_batch 16 with K = 6,
+ * 72 MB at max_batch 32 with K = 8, which is refused; then use xsm_spec_step).  Every call on a GPU, from any context, shares that GPU's one array, which
+ * keeps the last call's contents (the call clears what must start at zero): calls that overlap
+ * in time on one GPU race, so order them on one stream or with events. */
+XSM_API int xsm_spec_step_static(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
+                                 xsm_stream stream);
+
 /* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total,
  * the model shape is supported and the device has 256 compute units, run backbone, heads and unembedding as one persistent kernel
  * instead of one kernel per stage (greedy verification with argmax draws also finishes inside it;

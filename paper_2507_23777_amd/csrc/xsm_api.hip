@@ -54,14 +54,17 @@ void build_weight_offsets(xsm_ctx* c) {
   o.total = p;
 }
 
-void build_work_offsets(xsm_ctx* c) {
+// Layout of a workspace.  step_only: sized for decoding steps alone (max_batch x 16 rows, no
+// prefill passes, no exchange buffers of the single-launch step) - the layout of the static
+// scratch array.
+void build_work_offsets(const xsm_ctx* c, bool step_only, WorkOff& w, size_t& rows_max, size_t& part_entries,
+                        size_t& n_tickets) {
   const xsm_config& g = c->cfg;
   const size_t d = g.d_model, F = g.d_ffn, V = g.vocab, K = g.n_draft;
   size_t Mmax = (size_t)g.max_batch * kMaxRows;           // rows of one backbone pass
-  if (c->fast && Mmax < (size_t)kFastPassRows) Mmax = kFastPassRows;   // prefill chunks of few sequences
-  c->rows_max = Mmax;
+  if (c->fast && !step_only && Mmax < (size_t)kFastPassRows) Mmax = kFastPassRows;   // prefill chunks of few sequences
+  rows_max = Mmax;
   const size_t Mb = (size_t)g.max_batch * (K + 1);        // rows of one step
-  WorkOff& w = c->ws;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t r = p; p = align_up(p + bytes); return r; };
   w.X = take(Mmax * d * 4); w.QKV = take(Mmax * 3 * d * 4);
@@ -81,8 +84,9 @@ void build_work_offsets(xsm_ctx* c) {
   // (sequence, head) pairs of one attention call: the backbone's, or all cross-attention decoding heads at once
   size_t attn_pairs = (size_t)g.max_batch * g.n_heads * (g.head_kind == XSM_HEAD_CA && K ? K : 1);
   if (attn_pairs < Mmax / 16 * g.n_heads) attn_pairs = Mmax / 16 * g.n_heads;   // (sequence, head, query tile) units
-  c->part_entries = attn_pairs < 1024 ? 1024 : attn_pairs;
-  w.part = take(fattn_part_bytes(c->part_entries));
+  part_entries = attn_pairs < 1024 ? 1024 : attn_pairs;
+  n_tickets = attn_pairs;
+  w.part = take(fattn_part_bytes(part_entries));
   w.tickets = take(attn_pairs * 4);
   w.gpart = w.gtickets = 0;
   if (c->fast) {
@@ -102,13 +106,41 @@ void build_work_offsets(xsm_ctx* c) {
     w.gtickets = take(kWsTickets * 4);
   }
   w.ll = w.ctrl = w.head_all = w.tlog = 0;
-  if (c->small_ok) {
+  if (c->small_ok && !step_only) {
     w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
     w.ctrl = take(256);
     w.head_all = take((size_t)kSmallMaxRows * V * 4);
     w.tlog = take((size_t)256 * (g.n_layers * 16 + 8) * 8);
   }
   w.total = p;
+}
+
+// ---- the scratch of the step entry point that allocates nothing ------------------------------
+// One array per GPU, held from the time the library is loaded until the process ends; every
+// xsm_spec_step_static call on that GPU works in it, whatever its context.  In host code the
+// array's name is only a handle: its device address is looked up once per device (xsm_bind, with
+// that device current) and kernels, fills and copies are given the looked-up pointer.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on first use, then kept)
+int static_scratch_lookup(xsm_ctx* ctx, int* dev_out, char** ptr_out) {
+  int dev = 0;
+  XSM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(ctx, XSM_EINVAL, "device index beyond the static scratch table");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    XSM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(ctx, XSM_EHIP, "hipGetSymbolAddress returned a null address for the static scratch");
+    g_scratch_ptr[dev] = (char*)p;
+  }
+  *dev_out = dev;
+  *ptr_out = g_scratch_ptr[dev];
+  return XSM_OK;
 }
 
 // Fragment-ordered copies of the bf16 matrices, placed after the rotary table.
@@ -567,7 +599,11 @@ int xsm_create(const xsm_config* cfg, xsm_ctx** out) {
   c->small_ok = c->fast && g.n_cond == 0 && small_supported(g.d_model, g.d_ffn) && g.vocab <= 65536 &&
                 g.n_layers <= 48;
   build_weight_offsets(c);
-  build_work_offsets(c);
+  {
+    size_t n_tickets = 0;
+    build_work_offsets(c, false, c->ws, c->rows_max, c->part_entries, n_tickets);
+    build_work_offsets(c, true, c->ws_static, c->rows_max_static, c->part_entries_static, c->n_tickets_static);
+  }
   // cache capacities in positions: whole 64-key chunks.  Each (slot, head) owns one contiguous
   // stretch of a cache plane and the attention kernel streams hundreds of those stretches side by
   // side; measured on gfx950, stretches whose length lies within 8 KB of a multiple of 1 MiB
@@ -617,6 +653,10 @@ int xsm_bind(xsm_ctx* ctx, void* d_weights, void* d_kv, void* d_workspace) {
     return fail(ctx, XSM_EINVAL, "buffers must be 256-byte aligned");
   ctx->d_w = (char*)d_weights; ctx->d_kv = (char*)d_kv; ctx->d_ws = (char*)d_workspace;
   ctx->loaded = false;
+  {
+    const int rc = static_scratch_lookup(ctx, &ctx->dev, &ctx->d_static);
+    if (rc) return rc;
+  }
   // The single-launch step hands data between its 256 workgroups, one per compute unit (each
   // takes most of a unit's LDS), so all of them must be resident together: a device, or a
   // partition of one, with fewer units takes the per-stage path.
@@ -788,6 +828,41 @@ int xsm_plain_step(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params
                    xsm_stream stream) {
   if (!ctx) return XSM_EINVAL;
   return step_common(ctx, batch, vp, stream, 1);
+}
+
+int xsm_spec_step_static(xsm_ctx* ctx, const xsm_batch* batch, const xsm_verify_params* vp,
+                         xsm_stream stream) {
+  if (!ctx) return XSM_EINVAL;
+  if (ctx->cfg.n_draft < 1) return fail(ctx, XSM_EINVAL, "speculative step needs n_draft >= 1");
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if (ctx->ws_static.total > kStaticScratchBytes)
+    return fail(ctx, XSM_ECAPACITY, "this configuration's steps need " + std::to_string(ctx->ws_static.total) +
+                                        " bytes of scratch, the static array holds " +
+                                        std::to_string(kStaticScratchBytes) + ": use xsm_spec_step with a bound workspace");
+  int dev = -1;
+  XSM_HIP(hipGetDevice(&dev));
+  if (dev != ctx->dev || !ctx->d_static)
+    return fail(ctx, XSM_ESTATE, "the current device is not the one the buffers were bound on");
+  // The step's kernels find their activations, partial products and arrival counters through
+  // the context's workspace pointer and layout: for this call those name the static array.
+  struct Swap {
+    xsm_ctx* c; char* d_ws; WorkOff ws; size_t part_entries, rows_max; bool use_small;
+    explicit Swap(xsm_ctx* x) : c(x), d_ws(x->d_ws), ws(x->ws), part_entries(x->part_entries),
+                                rows_max(x->rows_max), use_small(x->use_small) {
+      c->d_ws = c->d_static; c->ws = c->ws_static; c->part_entries = c->part_entries_static;
+      c->rows_max = c->rows_max_static;
+      c->use_small = false;          // (the single-launch step's exchange buffers are not part of this layout)
+    }
+    ~Swap() { c->d_ws = d_ws; c->ws = ws; c->part_entries = part_entries; c->rows_max = rows_max; c->use_small = use_small; }
+  } swap(ctx);
+  // The array keeps what the last call on this GPU left (of any context, any layout): the
+  // arrival counters must start at zero.  Fill kernels, not memset nodes, so that a caller may
+  // capture the call in a graph.
+  hipStream_t s = (hipStream_t)stream;
+  launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.tickets), (int)ctx->n_tickets_static, 0, s);
+  if (ctx->fast) launch_fill_i32((int32_t*)(ctx->d_ws + ctx->ws.gtickets), (int)kWsTickets, 0, s);
+  return step_common(ctx, batch, vp, stream, ctx->cfg.n_draft + 1);
 }
 
 int xsm_set_option(xsm_ctx* ctx, int32_t option, int32_t value) {

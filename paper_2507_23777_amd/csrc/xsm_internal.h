@@ -92,6 +92,11 @@ struct xsm_ctx {
   xsm::PendingAdd pend;              // see PendingAdd
   size_t part_entries = 0;           // (sequence, head, query tile, split) partial slots in the workspace
   size_t rows_max = 0;               // rows of one backbone pass the workspace holds
+  // layout of the static scratch array (decoding steps only) for xsm_spec_step_static
+  xsm::WorkOff ws_static;
+  size_t part_entries_static = 0, rows_max_static = 0, n_tickets_static = 0;
+  int dev = -1;                      // device the buffers were bound on
+  char* d_static = nullptr;          // that device's address of the static scratch array
   char* d_w = nullptr;
   char* d_kv = nullptr;
   char* d_ws = nullptr;

@@ -20,7 +20,8 @@ API = ["xsm_create", "xsm_destroy", "xsm_last_error", "xsm_weights_bytes", "xsm_
        "xsm_workspace_bytes", "xsm_canonical_weight_elems", "xsm_bind", "xsm_load_weights",
        "xsm_prefill", "xsm_spec_step", "xsm_plain_step", "xsm_debug_kv_export",
        "xsm_debug_kv_import", "xsm_debug_trace_enable", "xsm_debug_trace_report", "xsm_set_option",
-       "xsm_check_device", "xsm_debug_timeline", "xsm_debug_kv_clone", "xsm_debug_inject_device_error"]
+       "xsm_check_device", "xsm_debug_timeline", "xsm_debug_kv_clone", "xsm_debug_inject_device_error",
+       "xsm_spec_step_static"]
 XSM_FLAG_NEAR_TIE, XSM_FLAG_BAD_LEN, XSM_FLAG_BAD_TOKEN, XSM_FLAG_BAD_SLOT, XSM_FLAG_DEVICE_TIMEOUT = 1, 2, 4, 8, 16
 
 
@@ -71,7 +72,7 @@ def lib() -> C.CDLL:
     L.xsm_bind.argtypes, L.xsm_bind.restype = [vp, vp, vp, vp], C.c_int
     L.xsm_load_weights.argtypes, L.xsm_load_weights.restype = [vp, vp, sz, vp], C.c_int
     L.xsm_prefill.argtypes, L.xsm_prefill.restype = [vp, i32, C.POINTER(i32), vp, i32, vp, vp], C.c_int
-    for f in ("xsm_spec_step", "xsm_plain_step"):
+    for f in ("xsm_spec_step", "xsm_plain_step", "xsm_spec_step_static"):
         getattr(L, f).argtypes = [vp, C.POINTER(xsm_batch), C.POINTER(xsm_verify_params), vp]
         getattr(L, f).restype = C.c_int
     for f in ("xsm_debug_kv_export", "xsm_debug_kv_import"):
@@ -208,6 +209,11 @@ class Engine:
     def xsm_spec_step(self, buf: StepBuffers, vp: xsm_verify_params, kv_len_bound: int):
         bt = buf.struct(kv_len_bound)
         self._check(self.L.xsm_spec_step(self.h, C.byref(bt), C.byref(vp), self.stream()), "xsm_spec_step")
+
+    def xsm_spec_step_static(self, buf: StepBuffers, vp: xsm_verify_params, kv_len_bound: int):
+        bt = buf.struct(kv_len_bound)
+        self._check(self.L.xsm_spec_step_static(self.h, C.byref(bt), C.byref(vp), self.stream()),
+                    "xsm_spec_step_static")
 
     def xsm_plain_step(self, buf: StepBuffers, vp: xsm_verify_params, kv_len_bound: int):
         bt = buf.struct(kv_len_bound)
