@@ -24,11 +24,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# of this same command, scaled by a plain copy of known size (see profiles/ and the design doc);
-# measured for k_step_small on the default workload with --steps 60 (context 282..370), where the
-# algorithmic figure is 653 MB: 779.6 MB read + 41.0 MB written.
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by a plain copy of known size (profiles/c1_step_small_hbm_traffic.md has the command and
+# the counter values).  A counter run cannot happen inside this process, so the figure is the
+# profiling run's, and `traffic_source` in the output says which run that was.
 TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 820.6e6}
+TRAFFIC_SOURCE = {"step_small": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `python3 bench.py --steps 60 --warmup 20 "
+                                "--no-extras --no-cpu-baseline` (context 282..370, algorithmic 653 MB per launch): "
+                                "779.6 MB read + 41.0 MB written; profiles/c1_step_small_hbm_traffic.md"}
 
 
 def algorithmic_bytes(cfg: dict, n_seq: int, sum_ctx: float) -> float:
@@ -70,44 +74,81 @@ def cpu_baseline(cfg: dict, w: dict, prefix, first, budget_s: float = 15.0) -> d
                       f"(context {cfg['prefix']}..{st.n}), float64 numpy"}
 
 
-def fixed_point(args, torch, pkg, xsm, si) -> int:
-    """One workload of the sweep at a fixed context (not the default benchmark line): speculative
-    steps of config NAME at batch B with K heads, every sequence's cache length reset to CTX before
-    each step (rollback is length-only, so that is free); the cache holds zeros beyond what the
-    steps write, condition tokens are prefilled.  Prints one JSON line."""
-    name, B, K, ctx, *rest = args.fixed_point.split(",")
-    B, K, ctx = int(B), int(K), int(ctx)
+def projection_flops(cfg: dict, M: int, n_seq: int) -> float:
+    """Useful multiply-adds x 2 of one speculative step's projections over M block rows (every
+    weight matrix once per row; the decoding heads and their unembedding run on n_seq x K rows)."""
+    L, d, F, V, K = cfg["n_layers"], cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_draft"]
+    cross = 2 * d * d if cfg["n_cond"] else 0
+    return 2.0 * (M * (L * (4 * d * d + 2 * d * F + cross) + V * d) + n_seq * K * (d * d + V * d))
+
+
+def measure_point(name, B, K, ctx, steps, warmup, torch, pkg, xsm, si, max_ctx=None, plain=False):
+    """One workload at a fixed context: speculative (or plain) steps of config NAME at batch B with
+    K heads, every sequence's cache length reset to CTX before each step (rollback is length-only,
+    so that is free); the cache holds zeros beyond what the steps write, condition tokens are
+    prefilled.  Returns the measurements as a dict."""
     cfg = si.get_config(name, batch=B, n_draft=K)
-    R = K + 1
-    eng = pkg.Engine(cfg, max_batch=B, max_ctx=int(rest[0]) if rest else ((ctx + R + 64) // 64) * 64)
+    R = 1 if plain else K + 1
+    eng = pkg.Engine(cfg, max_batch=B, max_ctx=max_ctx or ((ctx + R + 64) // 64) * 64)
     eng.d_kv.zero_()
     eng.xsm_load_weights(si.pack_canonical(cfg, si.make_weights(cfg)))
     if cfg["n_cond"]:
         eng.xsm_prefill(list(range(B)), None, eng.to_device(si.make_cond(cfg, B)))
-    buf = eng.buffers(B, spec=True)
-    buf.block.copy_(torch.tensor(si.first_block(cfg, B)))
+    buf = eng.buffers(B, spec=not plain)
+    buf.block.copy_(torch.tensor(si.first_block(cfg, B)[:, :R]))
     # config 2 is defined with top-8 acceptance and categorical draws at T = 0.8, the others greedy
     vp = pkg.xsm_verify_params(1, 8, 0.5, 0.8, 1, 1234) if name == "c2" else pkg.xsm_verify_params(0, 1, 0.5, 1.0, 0, 0)
+    step = eng.xsm_plain_step if plain else eng.xsm_spec_step
 
     def run(n):
         for _ in range(n):
             buf.kv_len.fill_(ctx)
-            eng.xsm_spec_step(buf, vp, ctx)
+            step(buf, vp, ctx)
 
-    run(args.warmup)
+    run(warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(args.steps)
+    run(steps)
     torch.cuda.synchronize()
-    ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    ms = 1e3 * (time.perf_counter() - t0) / steps
     xsm.xsm_debug_trace_enable(True)             # a second pass with per-launch event pairs for the breakdown
     xsm.xsm_debug_trace_report()
-    run(args.steps)
+    run(steps)
     torch.cuda.synchronize()
     trace = xsm.xsm_debug_trace_report()
     xsm.xsm_debug_trace_enable(False)
     eng.xsm_check_device()
-    by = algorithmic_bytes(cfg, B, B * ctx)
+    cfgb = dict(cfg, n_draft=R - 1)
+    by = algorithmic_bytes(cfgb, B, B * ctx)
+    gemm_ms = sum(v[1] for k, v in trace.items() if k.startswith("gemm") or k == "fgemm") / steps
+    fl = projection_flops(cfgb, B * R, B)
+    dom = max(trace.items(), key=lambda kv: kv[1][1])[0]
+    out = {"workload": f"{name} batch {B} K={R - 1}{' plain step' if plain else ''} context {ctx}", "steps": steps,
+           "ms_per_step": round(ms, 4), "verified_tok_per_s": round(B * R / ms * 1e3, 1),
+           "hbm_frac": round(by / (ms * 1e6) / HBM_PEAK_GBS, 4), "dominant_kernel": dom,
+           "kernels": {k: {"launches_per_step": v[0] / steps, "us_per_launch": round(1e3 * v[1] / v[0], 2)}
+                       for k, v in sorted(trace.items(), key=lambda kv: -kv[1][1])}}
+    if gemm_ms > 0:
+        tf = fl / (gemm_ms * 1e-3) / 1e12
+        out["projections"] = {"ms_per_step": round(gemm_ms, 4), "useful_tflops": round(tf, 1),
+                              "frac_of_mfma_bf16_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                              "note": "useful flops of all projection GEMMs / their summed launch time (event pairs); every "
+                                      "product is issued twice (hi and lo operand halves of an fp32 activation), so the "
+                                      "matrix cores issue twice this"}
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    return out, cfg
+
+
+def fixed_point(args, torch, pkg, xsm, si) -> int:
+    """One workload of the sweep at a fixed context (not the default benchmark line).  Prints one
+    JSON line."""
+    name, B, K, ctx, *rest = args.fixed_point.split(",")
+    B, K, ctx = int(B), int(K), int(ctx)
+    out, cfg = measure_point(name, B, K, ctx, args.steps, args.warmup, torch, pkg, xsm, si,
+                             max_ctx=int(rest[0]) if rest else None)
+    R = K + 1
     cpu = None
     if args.cpu_baseline_at_point:
         # the oracle on one sequence at the same context (cache of zeros, like the GPU's), a few
@@ -115,7 +156,6 @@ def fixed_point(args, torch, pkg, xsm, si) -> int:
         import numpy as np
         from threadpoolctl import threadpool_info
         from oracle import Oracle, VerifyParams
-        del eng
         orc = Oracle(cfg, si.make_weights(cfg), kv_dtype=np.float32)
         st = orc.new_state(cap=ctx + 4 * R + 8)
         if cfg["n_cond"]:
@@ -132,12 +172,9 @@ def fixed_point(args, torch, pkg, xsm, si) -> int:
                "cores": int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1])),
                "sample": f"{n} speculative steps of one sequence at context {ctx}, float64 numpy with a float32 cache; "
                          f"a batch of {B} independent sequences takes {B} times as long per step, so the rate is the same"}
-    print(json.dumps({"workload": f"{name} batch {B} K={K} context {ctx}", "steps": args.steps, "ms_per_step": round(ms, 4),
-                      "cpu_baseline": cpu,
-                      "note": "ms_per_step from an untraced pass; the kernel breakdown from a second pass with per-launch event pairs",
-                      "verified_tok_per_s": round(B * R / ms * 1e3, 1), "hbm_frac": round(by / (ms * 1e6) / HBM_PEAK_GBS, 4),
-                      "kernels": {k: {"launches_per_step": v[0] / args.steps, "us_per_launch": round(1e3 * v[1] / v[0], 2)}
-                                  for k, v in sorted(trace.items(), key=lambda kv: -kv[1][1])}}))
+    out["cpu_baseline"] = cpu
+    out["note"] = "ms_per_step from an untraced pass; the kernel breakdown from a second pass with per-launch event pairs"
+    print(json.dumps(out))
     return 0
 
 
@@ -190,6 +227,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-at-point", action="store_true",
                     help="with --fixed-point: also time the oracle on one sequence at that context")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the three fixed points of the other configurations (config 2 batch 16, config 4 batch 32 "
+                         "and 128) that the default run measures after the benchmark line's own workload")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the untimed extras (latency spread, fixed-context points): profiling runs then see "
                          "only the warm-up and timed steps")
@@ -233,7 +273,9 @@ def main() -> int:
     B, K, P = cfg["batch"], cfg["n_draft"], cfg["prefix"]
     R = K + 1
     total_steps = args.steps + args.warmup
-    max_ctx = P + total_steps * R + 16
+    # room for the free-running generation and for the fixed-context points up to the end of
+    # the configuration's 4096-token generation (257 + 4096), whatever --steps is
+    max_ctx = max(P + (total_steps + 200) * R + 16, 4353 + R + 64)
     w = si.make_weights(cfg)
     eng = pkg.Engine(cfg, max_batch=B, max_ctx=max_ctx)
     eng.xsm_load_weights(si.pack_canonical(cfg, w))
@@ -290,6 +332,7 @@ def main() -> int:
     achieved = dom_bytes_per_launch / (1e3 * avg_us)           # GB/s
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(dom_name),
+                "traffic_source": TRAFFIC_SOURCE.get(dom_name),
                 "avg_launch_us": round(avg_us, 3), "algorithmic_bytes_per_launch": int(dom_bytes_per_launch),
                 "launches_per_step": dom_cnt / args.steps}
 
@@ -330,8 +373,36 @@ def main() -> int:
         by = algorithmic_bytes(cfg, B, B * ctx)
         fixed.append({"context": ctx, "ms_per_step": round(ms, 4), "verified_tok_per_s": round(B * R / ms * 1e3, 1),
                       "hbm_frac": round(by / (ms * 1e6) / HBM_PEAK_GBS, 4)})
+    # the non-speculative comparison (Table 3 row A): next-token steps of the same model at the
+    # benchmark's starting context
+    plain = None
+    if not args.no_extras:
+        pb = eng.buffers(B, spec=False)
+        pb.block.copy_(torch.tensor(first[:, :1]))
+        ctx_p = int(len0[0])
+        for _ in range(5):
+            pb.kv_len.fill_(ctx_p); eng.xsm_plain_step(pb, vp, ctx_p)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(100):
+            pb.kv_len.fill_(ctx_p); eng.xsm_plain_step(pb, vp, ctx_p)
+        torch.cuda.synchronize()
+        pms = 1e3 * (time.perf_counter() - t2) / 100
+        plain = {"context": ctx_p, "ms_per_step": round(pms, 4), "tok_per_s": round(B / pms * 1e3, 1),
+                 "spec_step_cost_ratio": round(ms_per_step / pms, 3),
+                 "note": "one token per step; a speculative step yields between 1 and K+1 tokens for spec_step_cost_ratio "
+                         "times the latency (the paper's Table 3 reports 1.23x for its step and 2.02 tokens per step)"}
     eng.xsm_check_device()
     forced = {f"{a:g}": round(B * a / ms_per_step * 1e3, 1) for a in (1.0, 2.02, float(R))}
+    sweep = None
+    if not (args.no_extras or args.no_sweep):
+        eng.close()
+        del eng
+        torch.cuda.empty_cache()
+        sweep = []
+        for name2, B2, K2, ctx2 in (("c2", 16, 6, 8100), ("c4", 32, 4, 10000), ("c4", 128, 8, 10000)):
+            pt, _ = measure_point(name2, B2, K2, ctx2, 10, 3, torch, pkg, xsm, si)
+            sweep.append(pt)
 
     out = {"metric": "verified tok/s/GPU per spec step", "value": round(verified_tps, 1), "unit": "tok/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -344,7 +415,7 @@ def main() -> int:
            "accepted_tok_per_s": round(accepted / sec, 1), "scr": round(accepted / (B * args.steps), 4),
            "accept_length_histogram": accept_hist, "roofline": roofline, "kernels": kernels,
            "kernel_ms_per_step": round(tot_ms / args.steps, 4),
-           "step_ms_spread": spread, "fixed_context": fixed,
+           "step_ms_spread": spread, "fixed_context": fixed, "plain_step": plain, "sweep": sweep,
            "accepted_tok_per_s_at_accept_length": dict(
                forced, note="synthetic acceptance profiles: measured step latency x a given mean number of accepted "
                             "tokens per step (1 = no draft accepted, 2.02 = the paper's Table 3 row E, K+1 = all)")}

@@ -330,14 +330,29 @@ __device__ __forceinline__ float row_scale(const Shared& sm, int row, float eps)
   return __builtin_amdgcn_rsqf(((sm.rowsum[0][row] + sm.rowsum[1][row]) + (sm.rowsum[2][row] + sm.rowsum[3][row])) * (1.0f / (float)D) + eps);
 }
 
-// acc += Wfrag . (hi + lo) for activation row `row`, k-tile kt of an LDS tile staged by
-// stage_rows_f32 (row stride ST, lo plane 16 rows further)
-__device__ __forceinline__ f32x4 mac2(f32x4 acc, const uint4& wfrag, const uint16_t* As, int ST, int row,
-                                      int kt, int g) {
-  const uint16_t* p = As + (size_t)row * ST + kt * 32 + g * 8;
-  const bf16x8 wa = __builtin_bit_cast(bf16x8, wfrag);
-  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + 16 * ST)), acc, 0, 0, 0);
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p)), acc, 0, 0, 0);
+// acc = sum_i Wfrag[i] . (hi + lo) over k-tiles kt0 .. kt0 + N - 1 of activation row `row` of an
+// LDS tile staged by stage_rows_f32 (row stride ST, lo plane 16 rows further).  All operand
+// fragments are requested from LDS before the first product (the scheduler otherwise sinks every
+// read next to its use, and each product then waits out a full LDS round trip), and the hi and lo
+// products run as two independent accumulation chains.
+template <int N>
+__device__ __forceinline__ f32x4 mac_tiles(const uint4 (&wf)[N], const uint16_t* As, int ST, int row, int kt0, int g) {
+  const uint16_t* p = As + (size_t)row * ST + kt0 * 32 + g * 8;
+  uint4 bh[N], bl[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    bh[i] = *reinterpret_cast<const uint4*>(p + i * 32);
+    bl[i] = *reinterpret_cast<const uint4*>(p + i * 32 + 16 * ST);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  f32x4 a0 = f32x4{0.f, 0.f, 0.f, 0.f}, a1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const bf16x8 wa = __builtin_bit_cast(bf16x8, wf[i]);
+    a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bl[i]), a0, 0, 0, 0);
+    a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bh[i]), a1, 0, 0, 0);
+  }
+  return a0 + a1;
 }
 
 }  // namespace
@@ -473,9 +488,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       if (live && q_sec < 2) cs = a.rope[(size_t)(len_m + mj) * 32 + q_tt * 8 + (nrow & 7)];
       stage_rows_f32<D, D, 2>(sm, As, 0, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
       XSM_STAMP(l * 16 + 8);
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
+      const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
       const float partner = lane_xor<8>(v);        // tile column nrow +- 8
       if (live) {
@@ -847,9 +860,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
       stage_rows_f32<D, D, 0>(sm, As, 0, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
       XSM_STAMP(l * 16 + 14);
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KD; ++i) acc = mac2(acc, wq[i], As, STD, r, wave * KD + i, g);
+      const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
       xm = __uint_as_float(px) + v;
       if (row_in) ll_st(lb + OFF_XM + (size_t)om * D + nt * 16 + nrow, __float_as_uint(xm), tag);
@@ -864,9 +875,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
       stage_rows_f32<D, D, 2>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok, tl ? tl + l * 16 + 13 : nullptr);
       XSM_STAMP(l * 16 + 7);
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KD; ++i) acc = mac2(acc, wu[i], As, STD, r, wave * KD + i, g);
+      const f32x4 acc = mac_tiles<KD>(wu, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
       if (row_in)
         ll_st(lb + OFF_U + (size_t)om * F + w * 16 + nrow,
@@ -880,9 +889,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
       stage_rows_f32<FS, F, 0>(sm, As, 0, lb + OFF_U + d_ks * FS, M, nogain, a.eps, tid, tag, ok);
       XSM_STAMP(l * 16 + 12);
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KFS; ++i) acc = mac2(acc, wd[i], As, STS, r, wave * KFS + i, g);
+      const f32x4 acc = mac_tiles<KFS>(wd, As, STS, r, wave * KFS, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
       const size_t col = (size_t)om * D + d_nt * 16 + nrow;
       if (d_ks < 3) {
@@ -940,9 +947,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   // ---- HEADS on every row: r_k = g + SiLU(W_k g + b_k)  (Eq. 4, MLP variant) ----
   for (int t = w; t < K * (D / 16); t += 256) {
     if (t != w) load_frags<KD>(wh, a.Wh, t, KTD, wave * KD, lane);
-    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < KD; ++i) acc = mac2(acc, wh[i], T0, STD, r, wave * KD + i, g);
+    const f32x4 acc = mac_tiles<KD>(wh, T0, STD, r, wave * KD, g);
     const float y = tile_reduce(sm, acc, wave, lane, tid);
     const int kh = t / (D / 16), c = (t % (D / 16)) * 16 + nrow;   // head index, column
     if (row_in) {
@@ -969,9 +974,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     }
     for (int t = w; t < NTV; t += 256) {
       if (t != w) load_frags<KD>(wv, a.WU, t, KTD, wave * KD, lane);
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KD; ++i) acc = mac2(acc, wv[i], T, STD, r, wave * KD + i, g);
+      const f32x4 acc = mac_tiles<KD>(wv, T, STD, r, wave * KD, g);
       __syncthreads();
       *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
       __syncthreads();

@@ -48,3 +48,13 @@ def test_json_line_has_the_agreed_fields():
     assert "steps" in cb["sample"]
     hist = d["accept_length_histogram"]
     assert sum(hist["counts"].values()) == hist["steps"]
+    # the fixed-context points do not depend on --steps; the plain step and the other
+    # configurations' fixed points ride on the same line
+    assert [f["context"] for f in d["fixed_context"]] == [257, 2048, 4353]
+    assert d["plain_step"]["ms_per_step"] > 0 and d["plain_step"]["spec_step_cost_ratio"] > 0.5
+    assert rf["traffic_source"]
+    sw = d["sweep"]
+    assert [p["workload"].split(" context")[0] for p in sw] == ["c2 batch 16 K=6", "c4 batch 32 K=4", "c4 batch 128 K=8"]
+    for p in sw:
+        assert p["ms_per_step"] > 0 and 0 < p["hbm_frac"] < 1 and p["dominant_kernel"] in p["kernels"]
+        assert 0 < p["projections"]["frac_of_mfma_bf16_peak"] < 1
