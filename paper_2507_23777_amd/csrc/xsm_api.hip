@@ -107,8 +107,8 @@ void build_work_offsets(const xsm_ctx* c, bool step_only, WorkOff& w, size_t& ro
   }
   w.ll = w.ctrl = w.head_all = w.tlog = 0;
   if (c->small_ok && !step_only) {
-    w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 8);
-    w.ctrl = take(256);
+    w.ll = take(small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) * 4);
+    w.ctrl = take(kSmallCtrlBytes);
     w.head_all = take((size_t)kSmallMaxRows * V * 4);
     w.tlog = take((size_t)256 * (g.n_layers * 16 + 8) * 8);
   }
@@ -426,7 +426,8 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     a.hb = (const uint16_t*)(wb + ctx->toff.hb);
     a.WU = (const uint4*)(wb + ctx->toff.WU); a.Wh = (const uint4*)(wb + ctx->toff.Wh);
     a.rope = (const float2*)(wb + ctx->rope_off);
-    a.ll = (uint64_t*)(ws + ctx->ws.ll); a.ll_layer_stride = small_ll_layer_stride(d, g.d_ffn);
+    a.ll = (uint32_t*)(ws + ctx->ws.ll); a.ll_layer_stride = small_ll_layer_stride(d, g.d_ffn);
+    a.ll_words = small_ll_words(g.n_layers, d, g.d_ffn, K);
     a.ctrl = (uint32_t*)(ws + ctx->ws.ctrl);
     a.slot = bt->slot; a.kv_len = bt->kv_len; a.block = bt->block; a.out_tokens = bt->out_tokens;
     a.n_accepted = bt->n_accepted; a.flags = bt->flags;
@@ -726,9 +727,10 @@ int xsm_load_weights(xsm_ctx* ctx, const void* h_canonical, size_t n_elems, xsm_
       }
       XSM_HIP(hipMemcpyAsync(wb + ctx->layer_tab_off, ctx->layer_tab.data(),
                              sizeof(LayerTab) * g.n_layers, hipMemcpyHostToDevice, s));
-      // exchange words start with tag 0; the step epoch starts at 1, error word clear
+      // exchange words start with tag 0; the step epoch starts at 1, error word and barrier words clear
       launch_fill_u64((uint64_t*)(ctx->d_ws + ctx->ws.ll),
-                      small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft), 0ull, s);
+                      small_ll_words(g.n_layers, g.d_model, g.d_ffn, g.n_draft) / 2, 0ull, s);
+      launch_fill_u64((uint64_t*)(ctx->d_ws + ctx->ws.ctrl), kSmallCtrlBytes / 8, 0ull, s);
       launch_fill_u64((uint64_t*)(ctx->d_ws + ctx->ws.ctrl), 1, 1ull, s);
     }
   }

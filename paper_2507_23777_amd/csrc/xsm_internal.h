@@ -236,8 +236,9 @@ struct SmallArgs {
   const uint16_t* E; const uint16_t* gf; const uint16_t* hb;
   const uint4* WU; const uint4* Wh;
   const float2* rope;
-  uint64_t* ll; size_t ll_layer_stride;  // tagged-word exchange buffers
-  uint32_t* ctrl;                        // [0] step epoch, [1] error word
+  uint32_t* ll; size_t ll_layer_stride;  // tagged-word exchange buffers (4-byte words), words per layer
+  size_t ll_words;                       // words of the whole exchange region
+  uint32_t* ctrl;                        // [0] step epoch, [1] error word, [64..319] the workgroups' barrier words
   const int32_t* slot; int32_t* kv_len; int32_t* block; int32_t* out_tokens; int32_t* n_accepted;
   uint32_t* flags;
   float* logits_dbg; float* head_logits_dbg; float* head_all_dbg; int32_t* acc_out;
@@ -252,8 +253,9 @@ struct SmallArgs {
 };
 constexpr int kSmallMaxRows = 144;     // backbone rows + head rows (M + M K) of one single-launch step
 bool small_supported(int D, int F);
-size_t small_ll_words(int n_layers, int D, int F, int K);
+size_t small_ll_words(int n_layers, int D, int F, int K);     // 4-byte words
 size_t small_ll_layer_stride(int D, int F);
+constexpr size_t kSmallCtrlBytes = 2048;
 void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s);
 void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s);
 // head_logits_dbg[b][k][:] = head_all[(b*R + acc[b])*K + k][:]

@@ -2,41 +2,56 @@
 // latency regime: at most 16 block rows in total (batch x (K+1) <= 16), bf16,
 // d_model 1024 / FFN 4096 / head_dim 64 models, greedy verification.
 //
-// At batch 1 a step streams every weight once (hundreds of MB) through ~150 dependent
+// At batch 1 a step streams every weight once (hundreds of MB) through ~120 dependent
 // stages of a few MB each, so what bounds it is not bandwidth inside a stage but the
 // latency of handing a few KB of activations from one stage's producers to the next
 // stage's consumers.  Kernel boundaries cost several microseconds each; here all 256
 // workgroups (one per compute unit) stay resident for the whole step and exchange
-// activations through memory with a flag in every 8-byte word:
-//     word = { 32-bit payload (one fp32 value), 32-bit tag }, tag = step epoch.
+// activations through memory with a flag in every 4-byte word:
+//     word = { 24-bit payload: an fp32 value rounded to 16 significant bits, 8-bit tag },
+//     tag  = 1 + (step epoch - 1) mod 255.
 // A producer writes words with device-coherent stores; a consumer loads the words it
 // needs with device-coherent loads and retries until every tag equals the current
-// epoch, so arrival of the data IS the synchronisation (no barrier, no second round
+// one, so arrival of the data IS the synchronisation (no barrier, no second round
 // trip).  Each (layer, stage) owns its own buffer, so there is no reuse hazard inside a
-// step; the epoch makes last step's contents invalid.  Every wait is bounded: a
-// workgroup that does not see its inputs within the spin budget raises the error word
-// and leaves, and so does every workgroup waiting on it.
+// step.  A word written 255 steps ago would carry the current tag again: in every step
+// whose tag is 1 the workgroups first clear the whole exchange region and meet at a
+// barrier of their own (one word per workgroup carrying the full epoch).  Every wait is
+// bounded: a workgroup that does not see its inputs within the spin budget raises the
+// error word and leaves, and so does every workgroup waiting on it.
+//
+// 16 significant bits are what the consumer can use: an activation enters the bf16 MFMAs as
+// two operands, hi = bf16(x) and lo = bf16(x - hi), against the same weight fragment, so the
+// result carries the weights' bf16 rounding (part of the model) but none of the activations'
+// beyond the 2^-17 of the exchange word.  Values that must arrive exactly are made exact
+// before they are sent: new keys / values are rounded to bf16 by their producer (what the
+// cache holds), attention's running maxima are rounded up to integers.
 //
 // Coherent loads bypass the caches, so they are issued fully coalesced (a wavefront reads
-// 1 KB of consecutive words) and the activation block is re-laid through LDS into MFMA
-// operand order; a lane-scattered read of the same words costs an order of magnitude more.
-//
-// Activations travel as fp32 and enter the bf16 MFMAs as two operands, hi = bf16(x) and
-// lo = bf16(x - hi), against the same weight fragment, so the result carries the weights'
-// bf16 rounding (part of the model) but not a second one from the activations.
+// 1 KB of consecutive words, a thread 16 bytes = four words of one row) and the activation
+// block is re-laid through LDS into MFMA operand order.  What such a read costs is one
+// round trip of about a microsecond almost regardless of its size (up to ~100 KB per
+// workgroup when all loads are in flight together), so a consumer may as well read
+// several partial blocks and add them itself; two dependent hand-offs per layer are
+// saved that way:
+//   - the FFN-down products of the four slices of the FFN width are not summed by anybody:
+//     the next layer's QKV stage (and its O-projection, for the residual) reads the four
+//     partial blocks; the last slice's workgroup has added the mid-layer residual to its own;
+//   - with up to 4 key slices per (sequence, head) attention's partial outputs are merged by
+//     the O-projection workgroups while they stage them; only longer contexts (8 or 16
+//     slices) keep a merge stage of their own.
 //
 // Weights never depend on activations, so each workgroup requests the fragments of the
 // tile it will need one layer ahead and holds them in registers; HBM stays busy while
 // the dependency chain is waiting.  Stages per layer (Sec. 4.1 block = self-attention +
 // feed-forward; Alg. 1 "forward with causal mask"):
-//   QKV   192 tiles  RMSNorm + projection + rotary, new k/v also written to the cache
+//   QKV   192 tiles  residual = sum of 4 partial blocks, RMSNorm + projection + rotary,
+//                    new k/v also written to the cache
 //   ATT   B*H*S units  MFMA attention over a slice of the cached keys (+ the new block)
-//   COMB  merge of the S slices (skipped when S == 1)
-//   OPROJ 64 tiles   output projection + residual
+//   COMB  merge of the S slices (S = 8 or 16 only)
+//   OPROJ 64 tiles   merge of up to 4 slices, output projection + residual
 //   UP    256 tiles  RMSNorm + W1 + erf-GELU
-//   DOWN  64 tiles x 4 slices of the FFN width: W2 partial products on all 256 workgroups;
-//         the workgroup of the last slice (which also made the tile's OPROJ output) adds the
-//         other three and the residual
+//   DOWN  64 tiles x 4 slices of the FFN width: W2 partial products on all 256 workgroups
 // then the decoding heads on every block row (Alg. 1 runs each head on h_{s:s+D}), the
 // shared unembedding over backbone and head rows with a per-tile top-2 reduction, and one
 // workgroup per sequence that does the accept scan, picks the tokens at the first rejected
@@ -53,6 +68,7 @@ namespace {
 
 constexpr int kSpinBudget = 150000;         // polls before a wait gives up (a fraction of a second)
 constexpr float kTieMarginS = 1e-2f;
+constexpr float kEmptySliceMax = -30000.f;  // running maximum published by a key slice that saw no key
 // 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds + 16 l
 __device__ __forceinline__ void lds_direct16(const void* gptr, void* lds) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
@@ -60,22 +76,25 @@ __device__ __forceinline__ void lds_direct16(const void* gptr, void* lds) {
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-// raw buffer descriptor word 3 (32-bit data format, no swizzle) and the cache-policy bits of a
-// load that is coherent across the device (sc1)
-constexpr int kRawBufferFlags = 0x00020000, kCoherentLoad = 16;
+// Pointers that went through LDS (the layer table) have lost their address space, and a load
+// through one is a FLAT load: the compiler cannot count those against younger loads and waits for
+// every outstanding access instead.  Weights and cache are global memory: say so.
+typedef const __attribute__((address_space(1))) u32x4* gptr16;
+__device__ __forceinline__ gptr16 as_global(const void* p) { return (gptr16)(p); }
+__device__ __forceinline__ uint4 ldg16(gptr16 p, int piece) { return __builtin_bit_cast(uint4, p[piece]); }
+// raw buffer descriptor word 3 (32-bit data format, no swizzle) and the cache-policy bits of an
+// access that is coherent across the device (sc1)
+constexpr int kRawBufferFlags = 0x00020000, kCoherent = 16;
 
 constexpr int kQS = 72;                     // LDS row stride (bf16) of the attention q / new-k / new-v tiles
 
+// ---- 8-byte tagged words {32-bit payload, full epoch}: the tail's per-tile logits statistics ----
 __device__ __forceinline__ uint64_t ll_ld(const uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void ll_st(uint64_t* p, uint32_t payload, uint32_t tag) {
   __hip_atomic_store(p, ((uint64_t)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint32_t pk2(float a, float b) { return f2bf_pair(a, b); }
-__device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
 // Wait for the tagged words at p + off[i] (entries with off[i] < 0 are skipped); payloads to
 // out.  Meant for small blocks: the words are simply re-read together until every tag
 // matches, one round trip from arrival to use.  On timeout, or when an earlier wait of this
@@ -108,38 +127,50 @@ __device__ __forceinline__ void ll_wait_list(const uint64_t* p, const int (&off)
 #pragma unroll
   for (int i = 0; i < N; ++i) out[i] = 0u;
 }
-__device__ __forceinline__ uint32_t ll_wait1(const uint64_t* p, uint32_t tag, bool& ok) {
-  const int off[1] = {0};
-  uint32_t out[1];
-  ll_wait_list<1>(p, off, tag, out, ok);
-  return out[0];
-}
 
-// The same for pairs of adjacent words (even word offsets off[i], < 0: skipped) of a block of
-// nbytes bytes at p: each pair is one 16-byte device-coherent load, payloads to out[2i], out[2i+1].
+// ---- 4-byte tagged words {24-bit payload, 8-bit tag}: everything else ----
+// fp32 -> 16 significant bits (round to nearest even on bit 8) with the tag in the low byte
+__device__ __forceinline__ uint32_t enc24(float x, uint32_t t8) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7Fu + ((u >> 8) & 1u);
+  return (u & 0xFFFFFF00u) | t8;
+}
+__device__ __forceinline__ float dec24(uint32_t w) { return __uint_as_float(w & 0xFFFFFF00u); }
+__device__ __forceinline__ f32x4 dec24(u32x4 q) { return f32x4{dec24(q.x), dec24(q.y), dec24(q.z), dec24(q.w)}; }
+// all-zero low byte iff all four tags match
+__device__ __forceinline__ uint32_t tagdiff(u32x4 q, uint32_t t8) { return (q.x ^ t8) | (q.y ^ t8) | (q.z ^ t8) | (q.w ^ t8); }
+__device__ __forceinline__ void st32(uint32_t* p, float x, uint32_t t8) {
+  __hip_atomic_store(p, enc24(x, t8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// four consecutive words (16-byte aligned, `word` counted from the start of the buffer rs describes)
+// as one device-coherent store; every word carries its own tag.  The descriptor must be the same
+// in all lanes (it lives in scalar registers); the offset is the lane's own.
+__device__ __forceinline__ void st32x4(__amdgpu_buffer_rsrc_t rs, int word, f32x4 v, uint32_t t8) {
+  __builtin_amdgcn_raw_buffer_store_b128(u32x4{enc24(v[0], t8), enc24(v[1], t8), enc24(v[2], t8), enc24(v[3], t8)}, rs,
+                                         word * 4, 0, kCoherent);
+}
+__device__ __forceinline__ uint32_t ld32(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// the same small-block wait for 4-byte words; payloads decoded to floats
 template <int N>
-__device__ __forceinline__ void ll_wait_pairs(const uint64_t* p, int nbytes, const int (&off)[N], uint32_t tag,
-                                              uint32_t (&out)[2 * N], bool& ok) {
+__device__ __forceinline__ void wait_words(const uint32_t* p, const int (&off)[N], uint32_t t8, float (&out)[N], bool& ok) {
   bool any = false;
 #pragma unroll
   for (int i = 0; i < N; ++i) any |= off[i] >= 0;
   if (ok && any) {
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint64_t*>(p), 0, nbytes, kRawBufferFlags);
     for (int spin = 0; spin < kSpinBudget; ++spin) {
-      u32x4 q[N];
+      uint32_t w[N];
 #pragma unroll
       for (int i = 0; i < N; ++i)
-        if (off[i] >= 0) q[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[i] * 8, 0, kCoherentLoad);
-      bool good = true;
+        if (off[i] >= 0) w[i] = ld32(p + off[i]);
+      uint32_t bad = 0;
 #pragma unroll
       for (int i = 0; i < N; ++i)
-        if (off[i] >= 0) good &= q[i].y == tag && q[i].w == tag;
-      if (good) {
+        if (off[i] >= 0) bad |= w[i] ^ t8;
+      if ((bad & 0xFFu) == 0) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-          out[2 * i] = off[i] >= 0 ? q[i].x : 0u;
-          out[2 * i + 1] = off[i] >= 0 ? q[i].z : 0u;
-        }
+        for (int i = 0; i < N; ++i) out[i] = off[i] >= 0 ? dec24(w[i]) : 0.f;
         return;
       }
       __builtin_amdgcn_s_sleep(4);
@@ -147,60 +178,145 @@ __device__ __forceinline__ void ll_wait_pairs(const uint64_t* p, int nbytes, con
     ok = false;
   }
 #pragma unroll
-  for (int i = 0; i < 2 * N; ++i) out[i] = 0u;
+  for (int i = 0; i < N; ++i) out[i] = 0.f;
 }
 
 // Every poll of a word that another XCD is about to write costs fabric traffic that slows the
 // writes everybody is waiting for, so a workgroup polls with one lane: it watches one word of the
 // block until it carries the tag while the rest sit at the barrier; the block is read afterwards
 // (and re-read in the rare case that other producers' words lag).  Must be reached by every
-// thread of the workgroup.
-__device__ __forceinline__ void watch_then_sync(const uint64_t* word, uint32_t tag, bool active, int tid) {
+// thread of the workgroup.  (Measured: several polls in flight, or a different watch word per
+// workgroup, both cost more than they gain.)
+__device__ __forceinline__ void watch_then_sync(const uint32_t* word, uint32_t t8, bool active, int tid) {
   if (tid == 0 && active) {
     int spin = 0;
-    while ((uint32_t)(ll_ld(word) >> 32) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
+    while ((ld32(word) & 0xFFu) != t8 && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(1);
   }
   __syncthreads();
 }
 
-// Cooperative, coalesced wait for rows [m0, m0 + ROWS) (clipped to nrows), W words of each, of a
-// block of tagged words with row stride RS: thread t takes the word pairs 2(t + 256 j), +1, j < W/512, of
-// every row, so a wavefront instruction covers 1 KB of consecutive words.
-template <int W, int RS, int ROWS>
-__device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows, int tid, uint32_t tag,
-                                          uint32_t (&pay)[ROWS * (W / 512) * 2], bool& ok, uint64_t* stamp = nullptr) {
-  constexpr int PP = W / 512, N = ROWS * PP * 2;
-  const int rows = min(ROWS, nrows - m0);
-  const uint64_t* base = buf + (size_t)m0 * RS + 2 * tid;
+// Cooperative, coalesced wait for rows [m0, m0 + RB) (clipped to nrows) of NB blocks of tagged
+// words (1024 words per row, row stride RS, block stride BS; buf = block 0, row 0): thread t
+// takes words 4t .. 4t+3 of every row, so a wavefront instruction covers 1 KB of consecutive
+// words; v[m] = the blocks' values added in the fixed order ((b0 + b1) + (b2 + b3)), zero for
+// m >= RB.  All loads of a round are in flight together (NB x RB x 4 registers): a round costs one
+// round trip whatever NB is.
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+
+// One row (this thread's four words of each of NB blocks) that the wide read found incomplete:
+// re-read until every tag matches.  The slow path of read_rows; one row at a time keeps it small.
+template <int NB>
+__device__ __forceinline__ f32x4 retry_row(__amdgpu_buffer_rsrc_t rs, int word0, int BS, uint32_t t8, bool& ok) {
+  if (ok) {
+    for (int spin = 0; spin < kSpinBudget; ++spin) {
+      __builtin_amdgcn_s_sleep(4);
+      u32x4 q[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) q[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, (b * BS + word0) * 4, 0, kCoherent);
+      uint32_t bad = 0;
+#pragma unroll
+      for (int b = 0; b < NB; ++b) bad |= tagdiff(q[b], t8);
+      if ((bad & 0xFFu) == 0) {
+        if constexpr (NB == 4) return (dec24(q[0]) + dec24(q[1])) + (dec24(q[2]) + dec24(q[3]));
+        else return dec24(q[0]);
+      }
+    }
+    ok = false;
+  }
+  return f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+// Cooperative, coalesced wait for rows [m0, m0 + RB) (clipped to nrows) of NB blocks of tagged
+// words (1024 words per row, row stride RS, block stride BS; buf = block 0, row 0): thread t
+// takes words 4t .. 4t+3 of every row, so a wavefront instruction covers 1 KB of consecutive
+// words; v[m] = the blocks' values added in the fixed order ((b0 + b1) + (b2 + b3)), zero for
+// m >= RB.  All loads of a round are in flight together (NB x RB x 4 registers): a round costs one
+// round trip whatever NB is; a row that turns out incomplete (rare after the watch) is re-read on
+// its own.  after_issue runs once, between the issue of the loads and the wait for them:
+// requests placed there (weights, cached keys) travel behind the block instead of in front of
+// the next stage's poll - a wavefront's loads return in order.
+template <int NB, int RB, class Hook>
+__device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, int m0, int nrows, int tid, uint32_t t8,
+                                          bool watch, f32x4 (&v)[8], bool& ok, uint64_t* stamp, Hook&& after_issue) {
+  static_assert((NB == 1 || NB == 4) && RB <= 8, "one block, or four partial blocks; at most 8 rows a round");
+  const int rows = min(RB, nrows - m0);
   // (later rounds of a block come from the same producers as its first rows: no watch, its poll
   // would be one more round trip in front of the read)
-  if (m0 == 0) watch_then_sync(base + (size_t)(rows > 0 ? rows - 1 : 0) * RS + (PP - 1) * 512 + 1, tag, ok && rows > 0, tid);
+  if (watch)
+    watch_then_sync(buf + (size_t)(NB - 1) * BS + (size_t)(m0 + (rows > 0 ? rows - 1 : 0)) * RS + 513, t8, ok && rows > 0, tid);
+  if (stamp && tid == 0) stamp[0] = wall_clock64();
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(buf + (size_t)m0 * RS), 0, ((NB - 1) * BS + (rows > 0 ? rows : 0) * RS) * 4, kRawBufferFlags);
+  u32x4 q[NB][RB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int m = 0; m < RB; ++m)
+      if (m < rows) q[b][m] = __builtin_amdgcn_raw_buffer_load_b128(rs, (b * BS + m * RS + 4 * tid) * 4, 0, kCoherent);
+  // (the hook's requests stay between the block's loads and their first use: without the fences
+  // the compiler sinks them to where their data is used, stages later)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  after_issue();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int m = RB; m < 8; ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int m = 0; m < RB; ++m) {
+    if (m < rows) {
+      uint32_t bad = 0;
+#pragma unroll
+      for (int b = 0; b < NB; ++b) bad |= tagdiff(q[b][m], t8);
+      if ((bad & 0xFFu) == 0 && ok) {
+        if constexpr (NB == 4) v[m] = (dec24(q[0][m]) + dec24(q[1][m])) + (dec24(q[2][m]) + dec24(q[3][m]));
+        else v[m] = dec24(q[0][m]);
+      } else {
+        v[m] = retry_row<NB>(rs, m * RS + 4 * tid, BS, t8, ok);
+      }
+    } else {
+      v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
+  if (stamp && tid == 0) stamp[1] = wall_clock64();
+}
+
+// The same without a hook: everything is re-read until every tag matches (when the watched word is
+// in but another producer's words are not yet, one more round trip brings all of them).
+template <int NB, int RB>
+__device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, int m0, int nrows, int tid, uint32_t t8,
+                                          bool watch, f32x4 (&v)[8], bool& ok, uint64_t* stamp, NoHook) {
+  const int rows = min(RB, nrows - m0);
+  if (watch)
+    watch_then_sync(buf + (size_t)(NB - 1) * BS + (size_t)(m0 + (rows > 0 ? rows - 1 : 0)) * RS + 513, t8, ok && rows > 0, tid);
   if (stamp && tid == 0) stamp[0] = wall_clock64();
   if (ok && rows > 0) {
-    // a thread's two adjacent words travel as one 16-byte device-coherent load (each word is
-    // validated by its own tag, so the pair needs no atomicity of its own)
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint64_t*>(buf + (size_t)m0 * RS), 0, rows * RS * 8, kRawBufferFlags);
-    int spin = 0;
-    for (; spin < kSpinBudget; ++spin) {
-      u32x4 q[N / 2];                                     // {payload, tag, payload, tag}
+        const_cast<uint32_t*>(buf + (size_t)m0 * RS), 0, ((NB - 1) * BS + rows * RS) * 4, kRawBufferFlags);
+    for (int spin = 0; spin < kSpinBudget; ++spin) {
+      u32x4 q[NB][RB];
 #pragma unroll
-      for (int m = 0; m < ROWS; ++m)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int j = 0; j < PP; ++j)
-          if (m < rows)
-            q[m * PP + j] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((m * RS + j * 512 + 2 * tid) * 8), 0, kCoherentLoad);
-      bool good = true;
+        for (int m = 0; m < RB; ++m)
+          if (m < rows) q[b][m] = __builtin_amdgcn_raw_buffer_load_b128(rs, (b * BS + m * RS + 4 * tid) * 4, 0, kCoherent);
+      uint32_t bad = 0;
 #pragma unroll
-      for (int m = 0; m < ROWS; ++m)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int j = 0; j < PP; ++j)
-          if (m < rows) good &= q[m * PP + j].y == tag && q[m * PP + j].w == tag;
-      if (good) {
+        for (int m = 0; m < RB; ++m)
+          if (m < rows) bad |= tagdiff(q[b][m], t8);
+      if ((bad & 0xFFu) == 0) {
 #pragma unroll
-        for (int i = 0; i < N / 2; ++i) {
-          pay[2 * i] = (i / PP) < rows ? q[i].x : 0u;
-          pay[2 * i + 1] = (i / PP) < rows ? q[i].z : 0u;
+        for (int m = RB; m < 8; ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int m = 0; m < RB; ++m) {
+          if (m < rows) {
+            if constexpr (NB == 4) v[m] = (dec24(q[0][m]) + dec24(q[1][m])) + (dec24(q[2][m]) + dec24(q[3][m]));
+            else v[m] = dec24(q[0][m]);
+          } else {
+            v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+          }
         }
         if (stamp && tid == 0) stamp[1] = wall_clock64();
         return;
@@ -210,22 +326,32 @@ __device__ __forceinline__ void coop_wait(const uint64_t* buf, int m0, int nrows
     ok = false;
   }
 #pragma unroll
-  for (int i = 0; i < N; ++i) pay[i] = 0u;
+  for (int m = 0; m < 8; ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
 template <int N>
 __device__ __forceinline__ void load_frags(uint4 (&w)[N], const uint4* Wt, int nt, int KT, int kt0,
                                            int lane) {
-  const uint4* p = Wt + ((size_t)nt * KT + kt0) * 64 + lane;
+  const gptr16 p = as_global(Wt + ((size_t)nt * KT + kt0) * 64 + lane);
 #pragma unroll
-  for (int i = 0; i < N; ++i) w[i] = p[(size_t)i * 64];
+  for (int i = 0; i < N; ++i) w[i] = ldg16(p, i * 64);
+}
+
+// all ones or zero, hidden from the optimiser.  Requests placed between a block read's loads and
+// their first use must be unconditional: behind a branch the compiler cannot count what is in
+// flight on which path and waits for everything; and arithmetic on a visible condition it turns
+// back into a branch.
+__device__ __forceinline__ int opaque_mask(bool use) {
+  int m = use ? -1 : 0;
+  asm volatile("" : "+v"(m));
+  return m;
 }
 
 struct Shared {
   float red[4][64][4];          // cross-wavefront tile reduction
   float rowsum[4][16];          // RMSNorm partial sums
   float att_ml[4][2][16];
-  float att_o[4][4][64][4];
+  float att_o[4][4][64][4];     // attention: the wavefronts' partial outputs; O-projection: the slices' (m, l)
   int len[16], slot[16];
   uint32_t flag[16];
   uint32_t tag;
@@ -236,7 +362,7 @@ struct Shared {
 };
 
 // Sum the four wavefronts' partial 16x16 tiles; thread t gets element D[column t % 16][row t / 16],
-// so that the 16 words of one row's tile leave in one 128-byte store.
+// so that the 16 words of one row's tile leave in one 64-byte store.
 __device__ __forceinline__ float tile_reduce(Shared& sm, f32x4 acc, int wave, int lane, int tid) {
   __syncthreads();
   *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
@@ -246,44 +372,40 @@ __device__ __forceinline__ float tile_reduce(Shared& sm, f32x4 acc, int wave, in
   return (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
 }
 
-// bf16 pair of (a, b) and of what that rounding dropped
-__device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo) {
-  hi = pk2(x0, x1);
-  lo = pk2(x0 - lo_bf(hi), x1 - hi_bf(hi));
+// four floats -> LDS rows of the hi and lo planes (row stride ST bf16, lo plane 16 rows further)
+__device__ __forceinline__ void put4(uint16_t* As, int ST, int row, int col, f32x4 x) {
+  uint2 hi, lo;
+  split4(float4{x[0], x[1], x[2], x[3]}, hi, lo);
+  uint16_t* dst = As + (size_t)row * ST + col;
+  *reinterpret_cast<uint2*>(dst) = hi;
+  *reinterpret_cast<uint2*>(dst + 16 * ST) = lo;
 }
 
-// Stage nrows rows, D columns each, of an fp32-payload block with row stride RS words into LDS
-// rows dst_row.. as two bf16 planes of row stride D + 8: hi at As, lo at As + 16 * (D + 8).
-// NORM 1: RMSNorm over the D columns with the gain pairs gpair[j] (columns 2(tid + 256 j), +1).
+constexpr int kST = 1024 + 8;               // LDS row stride (bf16) of a staged 1024-column tile
+
+// Stage nrows rows, 1024 columns each, of NB tagged-word blocks (added up, see read_rows8) into LDS
+// rows dst_row.. as two bf16 planes of row stride kST: hi at As, lo at As + 16 * kST.
+// NORM 1: RMSNorm over the columns with the gains g4 (this thread's columns 4 tid .. 4 tid + 3).
 // NORM 2: only the gains are applied and the rows' sums of squares are left in sm.rowsum[.][row];
 // the caller multiplies its products by row_scale(row) - the rows reach LDS without waiting for
 // the sums to be exchanged.
-template <int D, int RS, int NORM>
-__device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst_row, const uint64_t* buf,
-                                               int nrows, const uint32_t (&gpair)[D / 512], float eps, int tid,
-                                               uint32_t tag, bool& ok, uint64_t* stamp = nullptr) {
-  constexpr int PP = D / 512, ST = D + 8, LO = 16 * ST;
-  constexpr int RB = PP >= 4 ? 4 : 8;                    // rows per round: at most 32 words in flight per thread
+template <int NB, int NORM, int RB, class Hook = NoHook>
+__device__ __forceinline__ void stage_rows(Shared& sm, uint16_t* As, int dst_row, const uint32_t* buf, int BS, int RS,
+                                           int nrows, f32x4 g4, float eps, int tid, uint32_t t8, bool& ok,
+                                           uint64_t* stamp = nullptr, Hook&& after_issue = NoHook{}) {
   const int wave = tid >> 6, lane = tid & 63;
   for (int m0 = 0; m0 < nrows; m0 += RB) {
-    uint32_t pay[RB * PP * 2];
-    coop_wait<D, RS, RB>(buf, m0, nrows, tid, tag, pay, ok, stamp);
+    f32x4 v[8];
+    if (m0 == 0) read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, true, v, ok, stamp, after_issue);
+    else read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, false, v, ok, stamp, NoHook{});
     if (NORM) {
       if (NORM == 1 && m0 > 0) __syncthreads();          // this call's earlier readers of rowsum are done
       // eight row sums per wavefront in ten lane exchanges instead of forty-eight: each exchange
       // step halves the rows a lane carries (lane bits 5, 4, 3 pick the row), then three steps
       // finish the one row left.  Cross-lane moves cost LDS-like latency at one wavefront per SIMD.
-      static_assert(RB == 8, "row-sum exchange is written for eight rows");
       float ss[8];
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        ss[m] = 0.f;
-#pragma unroll
-        for (int j = 0; j < PP * 2; ++j) {
-          const float x = __uint_as_float(pay[m * PP * 2 + j]);
-          ss[m] += x * x;
-        }
-      }
+      for (int m = 0; m < 8; ++m) ss[m] = (v[m][0] * v[m][0] + v[m][1] * v[m][1]) + (v[m][2] * v[m][2] + v[m][3] * v[m][3]);
       const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8;
       float s4[4], s2[2];
 #pragma unroll
@@ -294,30 +416,20 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
       s1 += lane_xor<4>(s1);
       s1 += lane_xor<2>(s1);
       s1 += lane_xor<1>(s1);
-      if ((lane & 7) == 0) sm.rowsum[wave][(NORM == 2 ? m0 : 0) + (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0)] = s1;
+      const int ri = (b5 ? 4 : 0) + (b4 ? 2 : 0) + (b3 ? 1 : 0);     // the row whose sum this lane ended up with
+      if ((lane & 7) == 0 && ri < RB) sm.rowsum[wave][(NORM == 2 ? m0 : 0) + ri] = s1;
       if (NORM == 1) __syncthreads();
     }
-    // every thread forms the scales itself, all rows at once (hardware reciprocal square root, 1 ulp)
-    float scl[RB];
-#pragma unroll
-    for (int m = 0; m < RB; ++m)
-      scl[m] = NORM == 1 ? __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / (float)D) + eps)
-                    : 1.0f;
 #pragma unroll
     for (int m = 0; m < RB; ++m) {
       if (m0 + m < nrows) {
-        const float sc = scl[m];
-#pragma unroll
-        for (int j = 0; j < PP; ++j) {
-          float x0 = __uint_as_float(pay[(m * PP + j) * 2]), x1 = __uint_as_float(pay[(m * PP + j) * 2 + 1]);
-          if (NORM == 1) { x0 *= sc * lo_bf(gpair[j]); x1 *= sc * hi_bf(gpair[j]); }
-          if (NORM == 2) { x0 *= lo_bf(gpair[j]); x1 *= hi_bf(gpair[j]); }
-          uint32_t hi, lo;
-          split2(x0, x1, hi, lo);
-          uint16_t* dst = As + (size_t)(dst_row + m0 + m) * ST + 2 * (tid + 256 * j);
-          *reinterpret_cast<uint32_t*>(dst) = hi;
-          *reinterpret_cast<uint32_t*>(dst + LO) = lo;
+        f32x4 x = v[m];
+        if (NORM == 1) {      // (hardware reciprocal square root, 1 ulp)
+          const float sc = __builtin_amdgcn_rsqf(((sm.rowsum[0][m] + sm.rowsum[1][m]) + (sm.rowsum[2][m] + sm.rowsum[3][m])) * (1.0f / 1024.0f) + eps);
+          x = x * sc * g4;
         }
+        if (NORM == 2) x = x * g4;
+        put4(As, kST, dst_row + m0 + m, 4 * tid, x);
       }
     }
   }
@@ -325,13 +437,19 @@ __device__ __forceinline__ void stage_rows_f32(Shared& sm, uint16_t* As, int dst
 }
 
 // 1 / rms of a row staged with NORM 2 (hardware reciprocal square root, 1 ulp)
-template <int D>
 __device__ __forceinline__ float row_scale(const Shared& sm, int row, float eps) {
-  return __builtin_amdgcn_rsqf(((sm.rowsum[0][row] + sm.rowsum[1][row]) + (sm.rowsum[2][row] + sm.rowsum[3][row])) * (1.0f / (float)D) + eps);
+  return __builtin_amdgcn_rsqf(((sm.rowsum[0][row] + sm.rowsum[1][row]) + (sm.rowsum[2][row] + sm.rowsum[3][row])) * (1.0f / 1024.0f) + eps);
+}
+
+// bf16 gains of this thread's four columns
+__device__ __forceinline__ f32x4 gains4(const uint16_t* g, int tid) {
+  const uint2 w = *reinterpret_cast<const uint2*>(g + 4 * tid);
+  return f32x4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u), __uint_as_float(w.y << 16),
+               __uint_as_float(w.y & 0xFFFF0000u)};
 }
 
 // acc = sum_i Wfrag[i] . (hi + lo) over k-tiles kt0 .. kt0 + N - 1 of activation row `row` of an
-// LDS tile staged by stage_rows_f32 (row stride ST, lo plane 16 rows further).  All operand
+// LDS tile staged by stage_rows (row stride ST, lo plane 16 rows further).  All operand
 // fragments are requested from LDS before the first product (the scheduler otherwise sinks every
 // read next to its use, and each product then waits out a full LDS round trip), and the hi and lo
 // products run as two independent accumulation chains.
@@ -355,6 +473,98 @@ __device__ __forceinline__ f32x4 mac_tiles(const uint4 (&wf)[N], const uint16_t*
   return a0 + a1;
 }
 
+// bf16 pair of (a, b) and of what that rounding dropped
+__device__ __forceinline__ uint32_t pk2(float a, float b) { return f2bf_pair(a, b); }
+__device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  hi = pk2(x0, x1);
+  lo = pk2(x0 - lo_bf(hi), x1 - hi_bf(hi));
+}
+
+// Attention's output rows as the O-projection's operand: the partial rows of the S_eff key slices
+// (blocks of 16 x 1024 words at word off_op + slice * blk of the layer buffer rs describes) are
+// merged while they are staged into LDS, O = sum_s f_s O_s / sum_s f_s l_s with f_s = 2^(m_s - max m).
+// The slices' (maximum, sum) pairs of all rows and heads ([16 rows][H][4 slices][2] words at off_ml,
+// 8 KB) go through LDS.  RB rows a round, all loads of a round in flight together.
+template <int H, int RB>
+__device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgpu_buffer_rsrc_t rs, const uint32_t* watch_word,
+                                               int off_op, int blk, int off_ml, int M, int S_eff, int tid, uint32_t t8, bool& ok) {
+  float* const mls = &sm.att_o[0][0][0][0];
+  watch_then_sync(watch_word, t8, ok, tid);
+  for (int m0 = 0; m0 < M; m0 += RB) {
+    const int rows = min(RB, M - m0);
+    u32x4 q[4][RB], mlq[2];
+    // (maximum, sum) pieces tid and tid + 256: row = piece / (2 H), slices 2 (piece & 1) and the one after it
+    bool need_ml[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int p = tid + 256 * j;
+      need_ml[j] = m0 == 0 && (p / (2 * H)) < M && (p & 1) * 2 < S_eff;
+    }
+    bool got = false;
+    if (ok) {
+      for (int spin = 0; spin < kSpinBudget; ++spin) {
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+          for (int m = 0; m < RB; ++m)
+            if (sl < S_eff && m < rows)
+              q[sl][m] = __builtin_amdgcn_raw_buffer_load_b128(rs, (off_op + sl * blk + (m0 + m) * 1024 + 4 * tid) * 4, 0, kCoherent);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          if (need_ml[j]) mlq[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (off_ml + 4 * (tid + 256 * j)) * 4, 0, kCoherent);
+        uint32_t bad = 0;
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+          for (int m = 0; m < RB; ++m)
+            if (sl < S_eff && m < rows) bad |= tagdiff(q[sl][m], t8);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          if (need_ml[j]) {
+            bad |= (mlq[j].x ^ t8) | (mlq[j].y ^ t8);
+            if ((tid & 1) * 2 + 1 < S_eff) bad |= (mlq[j].z ^ t8) | (mlq[j].w ^ t8);
+          }
+        if ((bad & 0xFFu) == 0) { got = true; break; }
+        __builtin_amdgcn_s_sleep(4);
+      }
+      if (!got) ok = false;
+    }
+    if (m0 == 0) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (need_ml[j] && got) *reinterpret_cast<f32x4*>(mls + 4 * (tid + 256 * j)) = dec24(mlq[j]);
+      __syncthreads();
+    }
+    const int hd = tid >> 4;                              // head of this thread's four columns
+#pragma unroll
+    for (int m = 0; m < RB; ++m) {
+      if (m < rows) {
+        f32x4 x = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (got) {
+          const float* ml = mls + ((m0 + m) * H + hd) * 8;
+          float Mg = ml[0];
+#pragma unroll
+          for (int sl = 1; sl < 4; ++sl)
+            if (sl < S_eff) Mg = fmaxf(Mg, ml[2 * sl]);
+          float Lg = 0.f;
+#pragma unroll
+          for (int sl = 0; sl < 4; ++sl)
+            if (sl < S_eff) {
+              const float f = exp2f(ml[2 * sl] - Mg);
+              Lg += ml[2 * sl + 1] * f;
+              x += dec24(q[sl][m]) * f;
+            }
+          x = Lg > 0.f ? x * (1.0f / Lg) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        put4(As, kST, m0 + m, 4 * tid, x);
+      }
+    }
+  }
+  __syncthreads();
+}
+
 }  // namespace
 
 template <int D, int F>
@@ -366,10 +576,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   constexpr int O_BASE = NQ;
   constexpr int FS = F / 4;                          // DOWN: slice of the FFN width per workgroup
   constexpr int KFS = FS / 32 / 4;                   // its k-tiles per wavefront
-  constexpr int STD = D + 8, STS = FS + 8;           // LDS row strides (bf16 elements)
+  constexpr int STD = kST;
   static_assert(NQ + NO <= 256 && NU <= 256 && NO * 4 == 256, "tile roles must fit 256 workgroups");
-  static_assert(FS % 512 == 0 && FS <= D, "DOWN slice is staged like a model-width row block");
-  static_assert(D % 512 == 0 && F % 1024 == 0, "cooperative staging needs whole pair rounds");
+  static_assert(D == 1024 && FS == 1024, "a thread stages four words of a 1024-word row");
   __shared__ Shared sm;
   extern __shared__ __align__(16) unsigned char dyn[];
   uint16_t* const As = reinterpret_cast<uint16_t*>(dyn);     // activation tile(s), several layouts
@@ -415,21 +624,54 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (w < a.n_seq && tid == 0) report_timeout(w);
     return;
   }
-  const uint32_t tag = sm.tag;
+  const uint32_t tag = sm.tag;                          // full epoch: 8-byte words, barrier words
+  const uint32_t t8 = 1u + (tag - 1u) % 255u;           // tag of the 4-byte words
+  bool ok = true;
+
+  // ---- once per 255 steps: clear the exchange region (words of 255 steps ago would pass for
+  // this step's), then a barrier of all workgroups before anybody writes ----
+  if (t8 == 1u) {
+    const size_t n16 = a.ll_words / 4;
+    // (device-coherent stores: a plain store could sit in this XCD's L2 and be written back over
+    // newer words later; the region is smaller than 2 GB, the launcher checks)
+    const __amdgpu_buffer_rsrc_t zr = __builtin_amdgcn_make_buffer_rsrc(a.ll, 0, (int)(n16 * 16), kRawBufferFlags);
+    for (size_t i = (size_t)w * 256 + tid; i < n16; i += 65536)
+      __builtin_amdgcn_raw_buffer_store_b128(u32x4{0u, 0u, 0u, 0u}, zr, (int)(i * 16), 0, kCoherent);
+    __threadfence();                                    // this thread's clears have landed
+    __syncthreads();
+    uint32_t* const arrive = a.ctrl + 64;               // [256]: epoch of the last clear each workgroup finished
+    if (tid == 0) __hip_atomic_store(arrive + w, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int spin = 0;
+    while (ld32(arrive + tid) != tag && ++spin < kSpinBudget) __builtin_amdgcn_s_sleep(8);
+    if (spin >= kSpinBudget) ok = false;
+    if (__syncthreads_or(!ok)) {
+      if (tid == 0) {
+        __hip_atomic_store(a.ctrl + 1, 2000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (w < a.n_seq) report_timeout(w);
+      }
+      return;
+    }
+  }
+
   // Key slices per (sequence, head), from the longest live cache (every workgroup reads the same
   // lengths, so all agree).  The cached keys and values come from HBM at full memory latency and a
   // workgroup has at most 128 KB of them in flight, so the attention stage is as fast as the
-  // number of workgroups sharing a key range: measured at contexts 100..4353, 8 slices win from
-  // three 64-key chunks on (even with most slices empty and the merge stage added), 16 from about
-  // twenty chunks on.
+  // number of workgroups sharing a key range.  Up to 4 slices are merged by the O-projection's
+  // workgroups as they read them; 8 and 16 slices need a merge stage of their own, which pays
+  // from about two thousand keys on.
   int S = a.S;
   if (a.s_auto) {
     int longest = 0;
     for (int b = 0; b < a.n_seq; ++b) longest = max(longest, sm.len[b]);
     const int chunks = (longest + 63) >> 6;
-    const int want = chunks <= 2 ? 1 : chunks <= 20 ? 8 : 16;
+    const int want = chunks <= 2 ? 1 : chunks <= 6 ? 2 : chunks <= 28 ? 4 : 16;
     while (S > want) S >>= 1;
   }
+  const int S_eff = S <= 4 ? S : 1;                    // slices the O-projection merges itself
+  // Rows a read round of four partial blocks takes: all of them when there are at most 5 (20
+  // loads in flight per thread), else 4 (16 loads) - what the register file holds next to the
+  // weight tiles.
+  const bool few = M <= 5;
   // this lane's activation row (MFMA column) m = r
   // the output element this thread finishes after tile_reduce: tile column nrow of row om
   const int om = tid >> 4, nrow = tid & 15;
@@ -439,17 +681,26 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   const bool live = row_in && len_m >= 0;              // rows of skipped sequences carry zeros
 
   const size_t LS = a.ll_layer_stride;                 // words per layer
-  uint64_t* const llb = a.ll;
-  const size_t OFF_X = 0, OFF_Q = 16 * D, OFF_KN = 2 * 16 * D, OFF_VN = 3 * 16 * D, OFF_O = 4 * 16 * D,
-               OFF_XM = 5 * 16 * D, OFF_U = 6 * 16 * D, OFF_PD = OFF_U + 16 * F, OFF_P = OFF_PD + 3 * 16 * D;
+  uint32_t* const llb = a.ll;
+  constexpr int BLK = 16 * D;                          // one [16 rows][D] block
+  constexpr int OFF_XP = 0,                            // [4][16][D]  the layer's input residual as four partial blocks
+                OFF_Q = 4 * BLK, OFF_KN = 5 * BLK, OFF_VN = 6 * BLK,
+                OFF_OP = 7 * BLK,                      // [4][16][D]  attention outputs of up to 4 key slices (unnormalised)
+                OFF_ML = 11 * BLK,                     // [16 rows][H][4 slices][2]  their (maximum, sum)
+                OFF_XM = OFF_ML + 16 * H * 8, OFF_U = OFF_XM + BLK,
+                OFF_P = OFF_U + 16 * F;                // [256 units][1056]  partials of the merge stage (8 / 16 slices)
 
   const bool has_q = w < NQ, has_o = w >= O_BASE && w < O_BASE + NO, has_u = w < NU;
   const int d_nt = w % NO, d_ks = w / NO;              // DOWN: output tile and slice of the FFN width
   // Weight fragments live in registers and are requested ahead of use.  A wavefront's loads
-  // return in order, so a bulk request delays whatever wait is issued right behind it; each
-  // request is therefore placed where its workgroup is about to sit out a stage:
+  // return in order, so a request delays whatever wait is issued right behind it: a poll that
+  // follows a request to HBM comes back a memory latency later.  Requests are therefore placed
+  // where their workgroup is about to sit out a stage, or right behind a block read's loads (they
+  // then travel behind data that is waited for anyway):
   //   workgroups with a QKV tile: this layer's UP and DOWN tiles and next layer's QKV tile after
-  //     COMB - they have no OPROJ tile;
+  //     attention (the O-projection runs elsewhere meanwhile); the attention unit's first chunk of
+  //     cached keys / values behind the QKV stage's block read, two hand-offs before it is used
+  //     (measured: 8 % of a step; the next QKV tile behind the UP stage's block read instead: a loss);
   //   the OPROJ workgroups: next layer's OPROJ, UP and DOWN tiles after DOWN - they sit out QKV
   //     and attention.
   uint4 wq[KD], wu[KD], wd[KFS];           // wq doubles as the OPROJ tile (disjoint workgroups)
@@ -462,34 +713,84 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
   float xm = 0.f;                          // OPROJ workgroups: their element of the mid-layer residual
 
-  // ---- EMBED: layer-0 residual rows as tagged words ----
+  // ---- EMBED: layer-0 residual rows as tagged words (partial block 3; the others are zero) ----
   for (int idx = w * 256 + tid; idx < M * D; idx += 256 * 256) {
     const int m = idx / D, c = idx % D, b = m / R;
     const float x = sm.len[b] >= 0 ? bf2f(a.E[(size_t)a.block[m] * D + c]) : 0.f;
-    ll_st(llb + OFF_X + (size_t)m * D + c, __float_as_uint(x), tag);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) st32(llb + OFF_XP + p * BLK + (size_t)m * D + c, p == 3 ? x : 0.f, t8);
   }
 
   // optional timeline: thread 0 of every workgroup stamps the 100 MHz clock at stage boundaries
   uint64_t* const tl = a.tlog ? a.tlog + (size_t)w * (a.L * 16 + 8) : nullptr;
 #define XSM_STAMP(idx) do { if (tl && tid == 0) tl[idx] = wall_clock64(); } while (0)
-  bool ok = true;
   for (int l = 0; l < a.L; ++l) {
-    uint64_t* const lb = llb + (size_t)l * LS;
+    uint32_t* const lb = llb + (size_t)l * LS;
     const LayerTab& lt = sm.tab[l];
+    const __amdgpu_buffer_rsrc_t lrs = __builtin_amdgcn_make_buffer_rsrc(lb, 0, (int)(LS * 4), kRawBufferFlags);
     XSM_STAMP(l * 16 + 0);
+
+    // the attention unit of this workgroup: slice s of the keys of (sequence b, head h)
+    const int n_units = a.n_seq * H * S;
+    const bool att = w < n_units;
+    const int b = att ? w / (H * S) : 0, h = (w / S) % H, s = w % S;
+    const int n = att ? sm.len[b] : -1;
+    const int nn = n < 0 ? 0 : n;                         // skipped sequence: no cached keys read
+    const int NC = (nn + 63) >> 6, CPS = (NC + S - 1) / S;
+    const int c_lo = s * CPS, c_hi = att ? min(NC, c_lo + CPS) : 0;
+    const size_t uhead = (size_t)sm.slot[b] * H + h;
+    const uint16_t* const kb = lt.Kc + uhead * (size_t)a.cap * 64;
+    const uint16_t* const vb = lt.Vt + uhead * 64 * (size_t)a.cap;
+    // A wavefront holds one 64-key chunk of cached keys / values in registers.  The first one does
+    // not depend on this step; it is requested behind the QKV stage's block read, two hand-offs
+    // before attention needs it.
+    uint4 kf[4][2], vf[4][2];
+    // the wavefront's first chunk, without a branch (see opaque_mask): a wavefront that has none
+    // re-reads one piece of the head's first key
+    auto first_chunk = [&]() {
+      const bool use = c_lo + wave < c_hi;
+      const int m = opaque_mask(use);
+      const int key0 = (c_lo + wave) << 6;
+      const gptr16 kq = as_global(kb), vq = as_global(vb);             // 16-byte pieces
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int piece = ((key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 8 + g) & m;    // 8 pieces per key row
+        kf[t][0] = ldg16(kq, piece);
+        kf[t][1] = ldg16(kq, piece + (4 & m));
+      }
+      const int capp = a.cap >> 3;                                      // pieces per value row
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const int piece = ((dt * 16 + r) * capp + (key0 >> 3) + g * 2) & m;
+        vf[dt][0] = ldg16(vq, piece);
+        vf[dt][1] = ldg16(vq, piece + (1 & m));
+      }
+    };
+
+    // OPROJ workgroups: their element of the residual entering the layer (four partial words),
+    // read while the others run QKV and attention
+    float px = 0.f;
+    auto read_px = [&]() {
+      const int col = om * D + (w - O_BASE) * 16 + nrow;
+      const int off[4] = {row_in ? OFF_XP + col : -1, row_in ? OFF_XP + BLK + col : -1, row_in ? OFF_XP + 2 * BLK + col : -1,
+                          row_in ? OFF_XP + 3 * BLK + col : -1};
+      float pv[4];
+      wait_words<4>(lb, off, t8, pv, ok);
+      px = (pv[0] + pv[1]) + (pv[2] + pv[3]);
+    };
+    if (has_o) read_px();
 
     // ================= QKV =================
     if (has_q) {
-      uint32_t gp[D / 512];                            // gain pairs and rotary entry: requested before waiting
-#pragma unroll
-      for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g1 + 2 * (tid + 256 * j));
+      const f32x4 g4 = gains4(lt.g1, tid);             // gains and rotary entry: requested before waiting
       const int q_sec = w / (D / 16), q_ts = w % (D / 16), q_h = q_ts >> 2, q_tt = q_ts & 3;
       float2 cs = float2{1.f, 0.f};
       if (live && q_sec < 2) cs = a.rope[(size_t)(len_m + mj) * 32 + q_tt * 8 + (nrow & 7)];
-      stage_rows_f32<D, D, 2>(sm, As, 0, lb + OFF_X, M, gp, a.eps, tid, tag, ok);
+      if (few) stage_rows<4, 2, 5>(sm, As, 0, lb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, first_chunk);
+      else stage_rows<4, 2, 4>(sm, As, 0, lb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, first_chunk);
       XSM_STAMP(l * 16 + 8);
       const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
-      const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
+      const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale(sm, om, a.eps);
       const float partner = lane_xor<8>(v);        // tile column nrow +- 8
       if (live) {
         const int pos = len_m + mj;
@@ -505,57 +806,33 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         const size_t col = (size_t)om * D + q_h * 64 + dim;
         const size_t head = (size_t)sm.slot[mb] * H + q_h;
         if (q_sec == 0) {
-          ll_st(lb + OFF_Q + col, __float_as_uint(o), tag);
-        } else if (q_sec == 1) {
-          ll_st(lb + OFF_KN + col, __float_as_uint(o), tag);
-          lt.Kc[(head * a.cap + pos) * 64 + dim] = f2bf(o);
+          st32(lb + OFF_Q + col, o, t8);
         } else {
-          ll_st(lb + OFF_VN + col, __float_as_uint(o), tag);
-          lt.Vt[(head * 64 + dim) * a.cap + pos] = f2bf(o);
+          // new keys / values travel as the bf16 values the cache holds (exact in an exchange word)
+          const uint16_t ob = f2bf(o);
+          if (q_sec == 1) {
+            st32(lb + OFF_KN + col, bf2f(ob), t8);
+            lt.Kc[(head * a.cap + pos) * 64 + dim] = ob;
+          } else {
+            st32(lb + OFF_VN + col, bf2f(ob), t8);
+            lt.Vt[(head * 64 + dim) * a.cap + pos] = ob;
+          }
         }
       }
     }
+    else first_chunk();                                   // (an attention unit without a QKV tile)
     XSM_STAMP(l * 16 + 1);
 
     // ================= ATT =================
-    const int n_units = a.n_seq * H * S;
-    if (w < n_units) {
-      const int b = w / (H * S), h = (w / S) % H, s = w % S;
-      const int n = sm.len[b];
-      const int nn = n < 0 ? 0 : n;                       // skipped sequence: no cached keys read
-      const int NC = (nn + 63) >> 6, CPS = (NC + S - 1) / S;
-      const int c_lo = s * CPS, c_hi = min(NC, c_lo + CPS);
-      const size_t head = (size_t)sm.slot[b] * H + h;
-      const uint16_t* kb = lt.Kc + head * (size_t)a.cap * 64;
-      const uint16_t* vb = lt.Vt + head * 64 * (size_t)a.cap;
+    if (att) {
       // this step's q, k, v rows of (sequence b, head h): [R][64] each, staged as bf16 tiles
       uint16_t* const qs = As;                            // q: hi plane, lo plane 16 rows further
       uint16_t* const kns = As + 32 * kQS;                // new k / v: as the cache will hold them
       uint16_t* const vns = As + 48 * kQS;
-      // the first chunk of cached keys/values does not depend on this step: request it before waiting.
       // While a wavefront works on one chunk, the next one is on its way from HBM straight into LDS
       // (LDS-direct loads: no registers - a second register set for it spills - and lane l's 16
       // bytes of a request land at base + 16 l, i.e. already in fragment order), 16 KB per wavefront
       unsigned char* const ring = dyn + 16384 + wave * 16384;
-      uint4 kf[4][2], vf[4][2];
-      auto load_k = [&](int c) {
-        const int key0 = c << 6;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const uint16_t* kr = kb + (size_t)(key0 + (r >> 2) * 16 + t * 4 + (r & 3)) * 64 + g * 8;
-          kf[t][0] = *reinterpret_cast<const uint4*>(kr);
-          kf[t][1] = *reinterpret_cast<const uint4*>(kr + 32);
-        }
-      };
-      auto load_v = [&](int c) {
-        const int key0 = c << 6;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          const uint16_t* vr = vb + (size_t)(dt * 16 + r) * a.cap + key0 + g * 16;
-          vf[dt][0] = *reinterpret_cast<const uint4*>(vr);
-          vf[dt][1] = *reinterpret_cast<const uint4*>(vr + 8);
-        }
-      };
       auto request_next = [&](int c) {
         const int key0 = c << 6;
 #pragma unroll
@@ -580,33 +857,32 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
             vf[t][j] = *reinterpret_cast<const uint4*>(ring + 8192 + (t * 2 + j) * 1024 + lane * 16);
           }
       };
-      if (c_lo + wave < c_hi) { load_k(c_lo + wave); load_v(c_lo + wave); }
-      if (c_lo + wave + 4 < c_hi) request_next(c_lo + wave + 4);   // the wavefront's second chunk too
-      watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, tag, ok && n >= 0, tid);
+      if (c_lo + wave + 4 < c_hi) request_next(c_lo + wave + 4);   // the wavefront's second chunk
+      watch_then_sync(lb + OFF_VN + (size_t)(b * R + R - 1) * D + h * 64 + 63, t8, ok && n >= 0, tid);
       if (n >= 0) {
-        const int j0 = tid >> 5, c = 2 * (tid & 31);      // rows j0, j0+8; columns c, c+1 as one word pair
-        int off[6];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int j = j0 + 8 * q;
-          const int base = (b * R + j) * D + h * 64 + c;
-          off[3 * q] = j < R ? (int)OFF_Q + base : -1;
-          off[3 * q + 1] = j < R ? (int)OFF_KN + base : -1;
-          off[3 * q + 2] = j < R ? (int)OFF_VN + base : -1;
-        }
-        uint32_t pw[12];
-        ll_wait_pairs<6>(lb, (int)OFF_U * 8, off, tag, pw, ok);
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int j = j0 + 8 * q;
-          if (j < R) {
-            uint32_t qh, ql;
-            split2(__uint_as_float(pw[6 * q]), __uint_as_float(pw[6 * q + 1]), qh, ql);
-            *reinterpret_cast<uint32_t*>(qs + j * kQS + c) = qh;
-            *reinterpret_cast<uint32_t*>(qs + (16 + j) * kQS + c) = ql;
-            *reinterpret_cast<uint32_t*>(kns + j * kQS + c) = pk2(__uint_as_float(pw[6 * q + 2]), __uint_as_float(pw[6 * q + 3]));
-            *reinterpret_cast<uint32_t*>(vns + j * kQS + c) = pk2(__uint_as_float(pw[6 * q + 4]), __uint_as_float(pw[6 * q + 5]));
+        // thread (row j, four columns c4..) of the 16 x 64 q / new-k / new-v blocks of this head
+        const int j = tid >> 4, c4 = 4 * (tid & 15);
+        if (j < R && ok) {
+          const int base = ((b * R + j) * D + h * 64 + c4) * 4;
+          bool got = false;
+          for (int spin = 0; spin < kSpinBudget; ++spin) {
+            const u32x4 wq4 = __builtin_amdgcn_raw_buffer_load_b128(lrs, OFF_Q * 4 + base, 0, kCoherent);
+            const u32x4 wk4 = __builtin_amdgcn_raw_buffer_load_b128(lrs, OFF_KN * 4 + base, 0, kCoherent);
+            const u32x4 wv4 = __builtin_amdgcn_raw_buffer_load_b128(lrs, OFF_VN * 4 + base, 0, kCoherent);
+            if (((tagdiff(wq4, t8) | tagdiff(wk4, t8) | tagdiff(wv4, t8)) & 0xFFu) == 0) {
+              const f32x4 q4 = dec24(wq4), k4 = dec24(wk4), v4 = dec24(wv4);
+              uint2 hi, lo;
+              split4(float4{q4[0], q4[1], q4[2], q4[3]}, hi, lo);
+              *reinterpret_cast<uint2*>(qs + j * kQS + c4) = hi;
+              *reinterpret_cast<uint2*>(qs + (16 + j) * kQS + c4) = lo;
+              *reinterpret_cast<uint2*>(kns + j * kQS + c4) = uint2{pk2(k4[0], k4[1]), pk2(k4[2], k4[3])};
+              *reinterpret_cast<uint2*>(vns + j * kQS + c4) = uint2{pk2(v4[0], v4[1]), pk2(v4[2], v4[3])};
+              got = true;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(4);
           }
+          if (!got) ok = false;
         }
       }
       __syncthreads();
@@ -779,52 +1055,73 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         Lx += sm.att_ml[q][1][r] * f;
         acc += *reinterpret_cast<const f32x4*>(&sm.att_o[q][wave][lane][0]) * f;
       }
-      if (S == 1) {
+      // What leaves the unit is relative to a maximum that an exchange word holds exactly: the
+      // next integer above it (a slice without keys says so with a very low maximum and sum 0;
+      // rows of a skipped sequence are zeros with sum 1).
+      const bool none = Mx == -INFINITY;
+      const float Mref = n < 0 ? 0.f : none ? kEmptySliceMax : ceilf(Mx);
+      const float resc = none ? 0.f : exp2f(Mx - Mref);
+      const float Lout = n < 0 ? 1.f : Lx * resc;
+      acc = n < 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc * resc;
+      if (S <= 4) {
         if (r < R) {
-          const float inv = n >= 0 ? 1.0f / Lx : 0.f;
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            ll_st(lb + OFF_O + (size_t)(b * R + r) * D + h * 64 + wave * 16 + g * 4 + i,
-                  __float_as_uint(n >= 0 ? acc[i] * inv : 0.f), tag);
+          st32x4(lrs, OFF_OP + s * BLK + (b * R + r) * D + h * 64 + wave * 16 + g * 4, acc, t8);
+          if (wave == 0 && g == 0) {
+            uint32_t* ml = lb + OFF_ML + (size_t)(((b * R + r) * H + h) * 4 + s) * 2;
+            st32(ml, Mref, t8);
+            st32(ml + 1, Lout, t8);
+          }
         }
       } else {
-        uint64_t* part = lb + OFF_P + (size_t)w * 1056;
+        uint32_t* part = lb + OFF_P + (size_t)w * 1056;
         if (wave == 0 && g == 0) {
-          ll_st(part + r, __float_as_uint(Mx), tag);
-          ll_st(part + 16 + r, __float_as_uint(Lx), tag);
+          st32(part + r, Mref, t8);
+          st32(part + 16 + r, Lout, t8);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          ll_st(part + 32 + (size_t)(wave * 16 + g * 4 + i) * 16 + r, __float_as_uint(acc[i]), tag);
+        for (int i = 0; i < 4; ++i) st32(part + 32 + (size_t)(wave * 16 + g * 4 + i) * 16 + r, acc[i], t8);
       }
     }
     XSM_STAMP(l * 16 + 2);
 
-    // ================= COMB =================
-    if (S > 1 && w < n_units) {
-      const int b = w / (H * S), h = (w / S) % H, s = w % S;
+    // ================= COMB (8 or 16 key slices) =================
+    if (S > 4 && att) {
       const int dps = 64 / S;                               // dims finished by this unit
       const int P = 32 + dps * 16;                          // words needed from each slice: m, l, O^T rows
-      const uint64_t* p0 = lb + OFF_P + (size_t)(w - s) * 1056;
+      const uint32_t* p0 = lb + OFF_P + (size_t)(w - s) * 1056;
       float* const cb = reinterpret_cast<float*>(As);       // [S][P]
-      watch_then_sync(p0 + (size_t)(S - 1) * 1056 + 32 + (s * dps + dps - 1) * 16, tag, ok, tid);
-      {
-        // word pairs 2 tid + 512 q of the S x P words (P is even: a pair stays inside one slice)
-        int off[3];
+      watch_then_sync(p0 + (size_t)(S - 1) * 1056 + 32 + (s * dps + dps - 1) * 16, t8, ok, tid);
+      if (ok) {
+        // 16-byte pieces tid + 256 q of the S x P words (P is a multiple of 4: a piece stays inside
+        // one slice and on one side of its (m, l) words)
+        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p0), 0, S * 1056 * 4, kRawBufferFlags);
+        int off[2];
 #pragma unroll
-        for (int q = 0; q < 3; ++q) {
-          const int i = 2 * tid + 512 * q;
+        for (int q = 0; q < 2; ++q) {
+          const int i = 4 * (tid + 256 * q);
           const int k = i / P, j = i % P;
           off[q] = i < S * P ? k * 1056 + (j < 32 ? j : 32 + s * dps * 16 + (j - 32)) : -1;
         }
-        uint32_t pw[6];
-        ll_wait_pairs<3>(p0, S * 1056 * 8, off, tag, pw, ok);
+        bool got = false;
+        for (int spin = 0; spin < kSpinBudget; ++spin) {
+          u32x4 pq[2];
+          uint32_t bad = 0;
 #pragma unroll
-        for (int q = 0; q < 3; ++q)
-          if (off[q] >= 0) {
-            cb[2 * tid + 512 * q] = __uint_as_float(pw[2 * q]);
-            cb[2 * tid + 512 * q + 1] = __uint_as_float(pw[2 * q + 1]);
+          for (int q = 0; q < 2; ++q)
+            if (off[q] >= 0) pq[q] = __builtin_amdgcn_raw_buffer_load_b128(prs, off[q] * 4, 0, kCoherent);
+#pragma unroll
+          for (int q = 0; q < 2; ++q)
+            if (off[q] >= 0) bad |= tagdiff(pq[q], t8);
+          if ((bad & 0xFFu) == 0) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+              if (off[q] >= 0) *reinterpret_cast<f32x4*>(cb + 4 * (tid + 256 * q)) = dec24(pq[q]);
+            got = true;
+            break;
           }
+          __builtin_amdgcn_s_sleep(4);
+        }
+        if (!got) ok = false;
       }
       __syncthreads();
       for (int qd = tid >> 4; qd < dps; qd += 16) {
@@ -834,14 +1131,19 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           for (int k = 0; k < S; ++k) Mg = fmaxf(Mg, cb[k * P + rq]);
           float Lg = 0.f, og = 0.f;
           for (int k = 0; k < S; ++k) {
-            const float mk = cb[k * P + rq];
-            const float f = mk == -INFINITY ? 0.f : exp2f(mk - Mg);
+            const float f = exp2f(cb[k * P + rq] - Mg);
             Lg += cb[k * P + 16 + rq] * f;
             og += cb[k * P + 32 + qd * 16 + rq] * f;
           }
-          const float outv = sm.len[b] >= 0 ? og / Lg : 0.f;
-          ll_st(lb + OFF_O + (size_t)(b * R + rq) * D + h * 64 + s * dps + qd, __float_as_uint(outv), tag);
+          const float outv = (sm.len[b] >= 0 && Lg > 0.f) ? og / Lg : 0.f;
+          st32(lb + OFF_OP + (size_t)(b * R + rq) * D + h * 64 + s * dps + qd, outv, t8);
         }
+      }
+      // the merged rows stand in partial block 0 with maximum 0 and sum 1
+      if (s == 0 && tid < R) {
+        uint32_t* ml = lb + OFF_ML + (size_t)(((b * R + tid) * H + h) * 4) * 2;
+        st32(ml, 0.f, t8);
+        st32(ml + 1, 1.f, t8);
       }
     }
     XSM_STAMP(l * 16 + 3);
@@ -854,55 +1156,41 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     // ================= OPROJ =================
     if (has_o) {
       const int nt = w - O_BASE;
-      // residual entering the layer: published a stage ago
-      const uint32_t px = row_in ? ll_wait1(lb + OFF_X + (size_t)om * D + nt * 16 + nrow, tag, ok) : 0u;
-      const uint32_t nogain[D / 512] = {};
       __syncthreads();
-      stage_rows_f32<D, D, 0>(sm, As, 0, lb + OFF_O, M, nogain, a.eps, tid, tag, ok);
+      if (few) stage_attn_out<H, 5>(sm, As, lrs, lb + OFF_OP + (size_t)(S_eff - 1) * BLK + (size_t)(M - 1) * D + 513, OFF_OP, BLK,
+                                    OFF_ML, M, S_eff, tid, t8, ok);
+      else stage_attn_out<H, 4>(sm, As, lrs, lb + OFF_OP + (size_t)(S_eff - 1) * BLK + (size_t)(M - 1) * D + 513, OFF_OP, BLK,
+                                OFF_ML, M, S_eff, tid, t8, ok);
       XSM_STAMP(l * 16 + 14);
       const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
-      xm = __uint_as_float(px) + v;
-      if (row_in) ll_st(lb + OFF_XM + (size_t)om * D + nt * 16 + nrow, __float_as_uint(xm), tag);
+      xm = px + v;
+      if (row_in) st32(lb + OFF_XM + (size_t)om * D + nt * 16 + nrow, xm, t8);
     }
     XSM_STAMP(l * 16 + 4);
 
     // ================= UP =================
     if (has_u) {
-      uint32_t gp[D / 512];
-#pragma unroll
-      for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(lt.g2 + 2 * (tid + 256 * j));
+      const f32x4 g4 = gains4(lt.g2, tid);
       __syncthreads();
-      stage_rows_f32<D, D, 2>(sm, As, 0, lb + OFF_XM, M, gp, a.eps, tid, tag, ok, tl ? tl + l * 16 + 13 : nullptr);
+      stage_rows<1, 2, 8>(sm, As, 0, lb + OFF_XM, 0, D, M, g4, a.eps, tid, t8, ok, tl ? tl + l * 16 + 13 : nullptr);
       XSM_STAMP(l * 16 + 7);
       const f32x4 acc = mac_tiles<KD>(wu, As, STD, r, wave * KD, g);
-      const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale<D>(sm, om, a.eps);
-      if (row_in)
-        ll_st(lb + OFF_U + (size_t)om * F + w * 16 + nrow,
-              __float_as_uint(0.5f * v * (1.0f + erff(v * 0.70710678118654752f))), tag);
+      const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale(sm, om, a.eps);
+      if (row_in) st32(lb + OFF_U + (size_t)om * F + w * 16 + nrow, 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)), t8);
     }
     XSM_STAMP(l * 16 + 5);
 
     // ================= DOWN =================
     {
-      const uint32_t nogain[FS / 512] = {};
       __syncthreads();
-      stage_rows_f32<FS, F, 0>(sm, As, 0, lb + OFF_U + d_ks * FS, M, nogain, a.eps, tid, tag, ok);
+      stage_rows<1, 0, 8>(sm, As, 0, lb + OFF_U + d_ks * FS, 0, F, M, f32x4{1.f, 1.f, 1.f, 1.f}, a.eps, tid, t8, ok);
       XSM_STAMP(l * 16 + 12);
-      const f32x4 acc = mac_tiles<KFS>(wd, As, STS, r, wave * KFS, g);
+      const f32x4 acc = mac_tiles<KFS>(wd, As, STD, r, wave * KFS, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
-      const size_t col = (size_t)om * D + d_nt * 16 + nrow;
-      if (d_ks < 3) {
-        if (row_in) ll_st(lb + OFF_PD + (size_t)d_ks * 16 * D + col, __float_as_uint(v), tag);
-      } else {
-        // last slice: the other three partial products, then the residual this workgroup made in OPROJ
-        const int off[3] = {row_in ? (int)col : -1, row_in ? (int)(16 * D + col) : -1, row_in ? (int)(32 * D + col) : -1};
-        uint32_t pw[3];
-        watch_then_sync(lb + OFF_PD + (size_t)32 * D + d_nt * 16, tag, ok, tid);
-        ll_wait_list<3>(lb + OFF_PD, off, tag, pw, ok);
-        const float x = xm + ((__uint_as_float(pw[0]) + __uint_as_float(pw[1])) + (__uint_as_float(pw[2]) + v));
-        if (row_in) ll_st(lb + LS + OFF_X + col, __float_as_uint(x), tag);
-      }
+      // partial block d_ks of the next layer's input; the last slice's workgroup made this tile's
+      // mid-layer residual in OPROJ and adds it to its own partial
+      if (row_in) st32(lb + LS + OFF_XP + (size_t)d_ks * BLK + (size_t)om * D + d_nt * 16 + nrow, d_ks == 3 ? xm + v : v, t8);
     }
     XSM_STAMP(l * 16 + 6);
     if (has_o && l + 1 < a.L) {
@@ -921,9 +1209,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
 
   // =========================== tail ===========================
-  uint64_t* const tb = llb + (size_t)a.L * LS;             // XB[L] lives at the start of this block
-  const size_t OFF_RB = 16 * D;                            // head outputs: [16*K rows][D] fp32 words
-  const size_t OFF_ST = OFF_RB + (size_t)16 * 15 * D;      // per (tile, row) top-2 statistics: 4 words
+  uint32_t* const tb = llb + (size_t)a.L * LS;             // the last layer's output partials live at the start of this block
+  constexpr int OFF_RB = 4 * BLK;                          // head outputs: [16*K rows][D] words
+  constexpr int OFF_ST = OFF_RB + 16 * 15 * D;             // per (tile, row) top-2 statistics: 4 8-byte words
+  uint64_t* const stb = reinterpret_cast<uint64_t*>(tb + OFF_ST);
   const int NTV = V / 16;                                  // vocabulary tiles
   const int rows_all = M + M * K;                          // backbone rows, then head rows (m, k)
   uint16_t* const T0 = As;                                 // rows 0..15 of the unembedding input (hi, lo planes)
@@ -936,11 +1225,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 
   XSM_STAMP(a.L * 16 + 0);
   {
-    uint32_t gp[D / 512];
-#pragma unroll
-    for (int j = 0; j < D / 512; ++j) gp[j] = *reinterpret_cast<const uint32_t*>(a.gf + 2 * (tid + 256 * j));
+    const f32x4 g4 = gains4(a.gf, tid);
     __syncthreads();
-    stage_rows_f32<D, D, 1>(sm, T0, 0, tb + OFF_X, M, gp, a.eps, tid, tag, ok);
+    if (few) stage_rows<4, 1, 5>(sm, T0, 0, tb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok);
+    else stage_rows<4, 1, 4>(sm, T0, 0, tb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok);
   }
   XSM_STAMP(a.L * 16 + 1);
 
@@ -953,7 +1241,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (row_in) {
       const float pre = y + bf2f(a.hb[(size_t)kh * D + c]);
       const float gn = bf2f(T0[(size_t)om * STD + c]) + bf2f(T0[(size_t)(16 + om) * STD + c]);
-      ll_st(tb + OFF_RB + ((size_t)om * K + kh) * D + c, __float_as_uint(gn + pre / (1.0f + __expf(-pre))), tag);
+      st32(tb + OFF_RB + ((size_t)om * K + kh) * D + c, gn + pre / (1.0f + __expf(-pre)), t8);
     }
   }
   XSM_STAMP(a.L * 16 + 2);
@@ -966,11 +1254,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     const int q_lo = mt == 0 ? M : mt * 16, q_hi = min(rows_all, mt * 16 + 16);
     if (w < NTV) {                                     // only workgroups with a vocabulary tile need the rows
       __syncthreads();
-      if (q_hi > q_lo) {
-        const uint32_t nogain[D / 512] = {};
-        stage_rows_f32<D, D, 0>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, q_hi - q_lo, nogain,
-                                    a.eps, tid, tag, ok);
-      }
+      if (q_hi > q_lo)
+        stage_rows<1, 0, 8>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, 0, D, q_hi - q_lo,
+                         f32x4{1.f, 1.f, 1.f, 1.f}, a.eps, tid, t8, ok);
     }
     for (int t = w; t < NTV; t += 256) {
       if (t != w) load_frags<KD>(wv, a.WU, t, KTD, wave * KD, lane);
@@ -994,7 +1280,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           if (z > bv) { sv = bv; bv = z; bi = t * 16 + nr; }
           else sv = fmaxf(sv, z);
         }
-        uint64_t* st = tb + OFF_ST + ((size_t)t * kSmallMaxRows + q) * 4;
+        uint64_t* st = stb + ((size_t)t * kSmallMaxRows + q) * 4;
         ll_st(st, __float_as_uint(bv), tag);
         ll_st(st + 1, (uint32_t)bi, tag);
         ll_st(st + 2, __float_as_uint(sv), tag);
@@ -1024,7 +1310,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           for (int j = 0; j < 3; ++j) off[3 * i + j] = t < NTV ? (t * kSmallMaxRows + grow) * 4 + j : -1;
         }
         uint32_t pw[12];
-        ll_wait_list<12>(tb + OFF_ST, off, tag, pw, ok);
+        ll_wait_list<12>(stb, off, tag, pw, ok);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           if (off[3 * i] < 0) continue;
@@ -1108,21 +1394,22 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #undef XSM_STAMP
 }
 
+// 4-byte words of one layer's exchange buffers, and of the whole region (layers + tail)
+size_t small_ll_layer_stride(int D, int F) {
+  return (size_t)12 * 16 * D + (size_t)16 * (D / 64) * 8 + (size_t)16 * F + (size_t)256 * 1056;
+}
 size_t small_ll_words(int n_layers, int D, int F, int K) {
   const size_t layer = small_ll_layer_stride(D, F);
-  const size_t tail = (size_t)16 * D + (size_t)16 * 15 * D + (size_t)4096 * kSmallMaxRows * 4;
+  const size_t tail = (size_t)4 * 16 * D + (size_t)16 * 15 * D + (size_t)4096 * kSmallMaxRows * 4 * 2;
   (void)K;
   return layer * n_layers + (tail > layer ? tail : layer);
-}
-size_t small_ll_layer_stride(int D, int F) {
-  return (size_t)6 * 16 * D + (size_t)16 * F + (size_t)3 * 16 * D + (size_t)256 * 1056;
 }
 
 bool small_supported(int D, int F) { return D == 1024 && F == 4096; }
 
 void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
   TraceScope trace_("step_small", s);
-  if (D == 1024 && F == 4096) {
+  if (D == 1024 && F == 4096 && a.ll_words * 4 < ((size_t)1 << 31)) {
     auto kfn = k_step_small<1024, 4096>;
     // activation tiles as bf16 hi + lo planes: two 16-row model-width tiles in the tail
     const size_t lds = (size_t)4 * 16 * (1024 + 8) * 2;
