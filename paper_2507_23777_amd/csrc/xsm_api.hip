@@ -412,15 +412,13 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
   const size_t e = ctx->esz;
 
   if (ctx->small_ok && ctx->small_dev && ctx->use_small && !ctx->small_failed && M <= 16 && M + M * K <= kSmallMaxRows && n_seq * g.n_heads <= 256) {
-    // the whole step as one persistent kernel; greedy verification with argmax draws finishes inside
-    // it, the other criteria and sampling rules run on its logits in the verify / emit kernels
-    const bool defer = !(vp->mode == XSM_VERIFY_GREEDY && vp->sample == 0);
-    if (defer)
-      launch_prepare(bt->kv_len, bt->slot, bt->block, n_seq, R, V, g.max_batch, g.max_ctx,
-                     bt->kv_len_bound, eff, slot, wfl, s);
+    // the whole step as one persistent kernel.  Greedy verification with argmax draws works from
+    // per-tile top-2 statistics; the other criteria and sampling rules make the kernel write the
+    // logits rows (into the workspace) and its last stage read them back
+    const bool full = !(vp->mode == XSM_VERIFY_GREEDY && vp->sample == 0);
     SmallArgs a{};
-    a.defer_verify = defer ? 1 : 0;
-    a.eff_out = defer ? eff : nullptr; a.wflags_out = defer ? wfl : nullptr;
+    a.full_verify = full ? 1 : 0;
+    a.vp = *vp;
     a.layers = (const LayerTab*)(wb + ctx->layer_tab_off); a.L = g.n_layers;
     a.E = (const uint16_t*)(wb + ctx->woff.E * e); a.gf = (const uint16_t*)(wb + ctx->woff.gf * e);
     a.hb = (const uint16_t*)(wb + ctx->toff.hb);
@@ -431,8 +429,8 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     a.ctrl = (uint32_t*)(ws + ctx->ws.ctrl);
     a.slot = bt->slot; a.kv_len = bt->kv_len; a.block = bt->block; a.out_tokens = bt->out_tokens;
     a.n_accepted = bt->n_accepted; a.flags = bt->flags;
-    a.logits_dbg = defer ? Z0 : bt->logits_dbg;
-    a.head_logits_dbg = defer ? Zh : bt->head_logits_dbg;      // non-null: keep the head logits of every row
+    a.logits_dbg = full ? Z0 : bt->logits_dbg;
+    a.head_logits_dbg = full ? Zh : bt->head_logits_dbg;       // non-null: keep the head logits of every row
     a.head_all_dbg = (float*)(ws + ctx->ws.head_all); a.acc_out = acc;
     a.tlog = ctx->timeline ? (uint64_t*)(ws + ctx->ws.tlog) : nullptr;
     a.n_seq = n_seq; a.R = R; a.V = V; a.max_batch = g.max_batch; a.max_ctx = g.max_ctx;
@@ -446,18 +444,8 @@ int step_common(xsm_ctx* ctx, const xsm_batch* bt, const xsm_verify_params* vp, 
     a.s_auto = ctx->force_splits > 0 ? 0 : 1;
     a.S = S;
     launch_step_small(a, d, g.d_ffn, s);
-    if (defer) {
-      if (bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
-      launch_verify(Z0, nullptr, bt->block, eff, slot, *vp, acc, y0, wfl, nullptr, n_seq, R, V, d, s);
-      if (K > 0) {                                  // head rows at the accepted position
-        launch_gather_head_dbg(a.head_all_dbg, acc, Zh, n_seq, R, K, V, s);
-        if (bt->head_logits_dbg) launch_copy_f32(Zh, bt->head_logits_dbg, (size_t)n_seq * K * V, s);
-      }
-      launch_emit(Zh, *vp, eff, slot, acc, y0, wfl, (int32_t*)(ws + ctx->ws.toks), bt->block, bt->kv_len,
-                  bt->out_tokens, bt->n_accepted, bt->flags, n_seq, R, K, V, s);
-    } else if (bt->head_logits_dbg && K > 0) {
-      launch_gather_head_dbg(a.head_all_dbg, acc, bt->head_logits_dbg, n_seq, R, K, V, s);
-    }
+    if (full && bt->logits_dbg) launch_copy_f32(Z0, bt->logits_dbg, (size_t)M * V, s);
+    if (bt->head_logits_dbg && K > 0) launch_gather_head_dbg(a.head_all_dbg, acc, bt->head_logits_dbg, n_seq, R, K, V, s);
     hipError_t e3 = hipGetLastError();
     if (e3 != hipSuccess) return fail(ctx, XSM_EHIP, std::string("launch: ") + hipGetErrorString(e3));
     return XSM_OK;

@@ -245,10 +245,10 @@ struct SmallArgs {
   uint64_t* tlog;                        // optional stage timeline [256][L*16 + 8] clock stamps
   int n_seq, R, S, V, max_batch, max_ctx, bound, cap;   // S: key slices per (sequence, head), or their upper limit
   int s_auto;                            // 1: the kernel picks the slice count <= S from the cache lengths it reads
-  int defer_verify;                      // 1: stop after the unembedding (logits of all rows written); the
-                                         // caller runs verification and the draws as separate kernels
-  int32_t* eff_out; uint32_t* wflags_out; // deferred steps: the effective lengths / flag words those kernels
-                                         // read; a sequence lost to a timed-out wait is marked skipped there
+  int full_verify;                       // 0: greedy verification with argmax draws from the per-tile top-2 statistics;
+                                         // 1: the last stage reads the full logits rows (logits_dbg / head_all_dbg must
+                                         // be set) and applies the criterion and sampling rule of vp
+  xsm_verify_params vp;
   float eps, scale_log2;
 };
 constexpr int kSmallMaxRows = 144;     // backbone rows + head rows (M + M K) of one single-launch step

@@ -6,174 +6,9 @@
 // reductions run in a fixed order so results do not depend on timing.
 #include "xsm_device.h"
 #include "xsm_internal.h"
+#include "xsm_verify_device.h"
 
 namespace xsm {
-
-constexpr float kTieMargin = 1e-2f;      // logit gap of an argmax or rank decision
-constexpr float kCdfMargin = 2e-5f;      // distance of a draw's uniform from a CDF edge, relative to the total weight
-constexpr float kCutMargin = 1e-4f;      // relative distance of a tree path's weight from the cut-off
-
-struct RowScratch {
-  float redf[8];
-  int redi[8];
-  float part[256];
-  float bestv[4], secv[4];
-  int besti[4];
-};
-
-// argmax with lowest index among equal maxima; *margin = top1 - top2
-__device__ int row_argmax(const float* z, int V, RowScratch& sm, float* margin) {
-  float bv = -INFINITY, sv = -INFINITY;
-  int bi = 0x7FFFFFFF;
-  auto feed = [&](float x, int v) {
-    if (x > bv || (x == bv && v < bi)) { sv = bv; bv = x; bi = v; }
-    else sv = fmaxf(sv, x);
-  };
-  if ((V & 3) == 0) {                 // 16-byte loads, several in flight per thread
-    const float4* z4 = reinterpret_cast<const float4*>(z);
-    const int n4 = V >> 2;
-    for (int q0 = threadIdx.x; q0 < n4; q0 += 1024) {
-      float4 x[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        x[u] = q0 + u * 256 < n4 ? z4[q0 + u * 256] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int v = (q0 + u * 256) * 4;
-        if (q0 + u * 256 < n4) { feed(x[u].x, v); feed(x[u].y, v + 1); feed(x[u].z, v + 2); feed(x[u].w, v + 3); }
-      }
-    }
-  } else {
-    for (int v = threadIdx.x; v < V; v += 256) feed(z[v], v);
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float bv2 = __shfl_xor(bv, o, WAVE), sv2 = __shfl_xor(sv, o, WAVE);
-    const int bi2 = __shfl_xor(bi, o, WAVE);
-    const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);
-    sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));
-    if (take) { bv = bv2; bi = bi2; }
-  }
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) {
-    sm.bestv[threadIdx.x >> 6] = bv; sm.secv[threadIdx.x >> 6] = sv; sm.besti[threadIdx.x >> 6] = bi;
-  }
-  __syncthreads();
-  bv = sm.bestv[0]; sv = sm.secv[0]; bi = sm.besti[0];
-  for (int w = 1; w < 4; ++w) {
-    const float bv2 = sm.bestv[w], sv2 = sm.secv[w];
-    const int bi2 = sm.besti[w];
-    const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);
-    sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));
-    if (take) { bv = bv2; bi = bi2; }
-  }
-  *margin = bv - sv;
-  return bi;
-}
-
-// number of tokens ranked ahead of x (larger logit, or equal logit and lower index);
-// *gap = distance of z[x] to the nearest other logit on either side of the K_a boundary
-__device__ int row_rank(const float* z, int V, int x, RowScratch& sm) {
-  const float zx = z[x];
-  int c = 0;
-  if ((V & 3) == 0) {
-    const float4* z4 = reinterpret_cast<const float4*>(z);
-    const int n4 = V >> 2;
-#pragma unroll 4
-    for (int q = threadIdx.x; q < n4; q += 256) {
-      const float4 y = z4[q];
-      const int v = q * 4;
-      c += (y.x > zx || (y.x == zx && v < x)) + (y.y > zx || (y.y == zx && v + 1 < x)) +
-           (y.z > zx || (y.z == zx && v + 2 < x)) + (y.w > zx || (y.w == zx && v + 3 < x));
-    }
-  } else {
-    for (int v = threadIdx.x; v < V; v += 256) {
-      const float y = z[v];
-      c += (y > zx || (y == zx && v < x)) ? 1 : 0;
-    }
-  }
-  return block_sum_i(c, sm.redi);
-}
-
-// near-tie test for the rank criterion: is some other logit within the margin of z[x]
-// while x sits at rank ka-1 or ka (a small change could flip the decision)
-__device__ bool rank_near_boundary(const float* z, int V, int x, int rank, int ka, RowScratch& sm) {
-  const float zx = z[x];
-  int above = 0, below = 0;                      // neighbours within the margin
-#pragma unroll 4
-  for (int v = threadIdx.x; v < V; v += 256) {
-    const float dlt = z[v] - zx;
-    if (v != x && dlt >= 0.f && dlt <= kTieMargin) ++above;
-    if (v != x && dlt < 0.f && -dlt <= kTieMargin) ++below;
-  }
-  above = block_sum_i(above, sm.redi);
-  below = block_sum_i(below, sm.redi);
-  // accepted (rank < ka) could become rejected if enough close-below tokens overtake it,
-  // rejected could become accepted if enough close-above tokens drop behind it
-  if (rank < ka) return rank + below >= ka;
-  return rank - above < ka;
-}
-
-// softmax(z/T)[x]
-__device__ float row_prob(const float* z, int V, int x, float invT, RowScratch& sm) {
-  float mx = -INFINITY;
-  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
-  mx = block_max(mx, sm.redf);
-  float s = 0.f;
-  for (int v = threadIdx.x; v < V; v += 256) s += expf((z[v] - mx) * invT);
-  s = block_sum(s, sm.redf);
-  return expf((z[x] - mx) * invT) / s;
-}
-
-// categorical draw by inverse CDF over ascending token index; *near_edge: the uniform lies within
-// kCdfMargin (relative to the total weight) of a CDF edge
-__device__ int row_categorical(const float* z, int V, float invT, float u, RowScratch& sm, bool* near_edge) {
-  float mx = -INFINITY;
-  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
-  mx = block_max(mx, sm.redf);
-  const int chunk = (V + 255) / 256;
-  const int v0 = threadIdx.x * chunk, v1 = min(V, v0 + chunk);
-  float loc = 0.f;
-  for (int v = v0; v < v1; ++v) loc += expf((z[v] - mx) * invT);
-  __syncthreads();
-  sm.part[threadIdx.x] = loc;
-  __syncthreads();
-  if (threadIdx.x == 0) {                       // exclusive scan, fixed order
-    float run = 0.f;
-    for (int t = 0; t < 256; ++t) { const float p = sm.part[t]; sm.part[t] = run; run += p; }
-    sm.redf[4] = run;
-  }
-  __syncthreads();
-  const float target = u * sm.redf[4], band = kCdfMargin * sm.redf[4];
-  float run = sm.part[threadIdx.x];
-  int hit = 0x7FFFFFFF, lastpos = -1, close = fabsf(run - target) <= band ? 1 : 0;
-  for (int v = v0; v < v1; ++v) {
-    const float w = expf((z[v] - mx) * invT);
-    run += w;
-    if (w > 0.f) lastpos = v;
-    if (hit == 0x7FFFFFFF && run > target) hit = v;
-    close |= fabsf(run - target) <= band ? 1 : 0;
-  }
-  *near_edge = block_max_i(close, sm.redi) != 0;
-  hit = block_min_i(hit, sm.redi);
-  if (hit != 0x7FFFFFFF) return hit;
-  return block_max_i(lastpos, sm.redi);
-}
-
-__device__ int row_sample(const float* z, int V, const xsm_verify_params& vp, uint32_t pos,
-                          uint32_t head, uint32_t seq, RowScratch& sm, uint32_t* flag) {
-  if (vp.sample == 0) {
-    float margin;
-    const int t = row_argmax(z, V, sm, &margin);
-    if (margin <= kTieMargin) *flag |= XSM_FLAG_NEAR_TIE;
-    return t;
-  }
-  const float u = philox_uniform(vp.seed, pos, head, seq);
-  bool near_edge;
-  const int t = row_categorical(z, V, 1.0f / vp.temperature, u, sm, &near_edge);
-  if (near_edge) *flag |= XSM_FLAG_NEAR_TIE;
-  return t;
-}
 
 // accept scan + backbone draw + hidden-state gather
 __global__ __launch_bounds__(256) void k_verify(const float* Z0, const float* Hf,
@@ -248,115 +83,6 @@ void launch_head_act(int dtype, const float* G, const float* Hh, const void* con
     hipLaunchKernelGGL(k_head_act<bf16_t>, grid, blk, 0, s, G, Hh, bp, Rk, K, d, total);
   else
     hipLaunchKernelGGL(k_head_act<float>, grid, blk, 0, s, G, Hh, bp, Rk, K, d, total);
-}
-
-// Top-K_s probability-tree sampling of the K head tokens (appendix "Sampling strategies"): level d
-// holds the ks most probable tokens of softmax(z_d / T) with their probabilities as edge weights;
-// a complete path survives if its weight (a product of numbers <= 1, so the smallest of its
-// prefixes' weights) is at least `prune`; one survivor is drawn in proportion to its weight by
-// inverse CDF in depth-first (= lexicographic) order.  cand[1..K] receives the tokens.  Returns
-// true (to every thread) when the draw is a near-tie: the uniform within kCdfMargin of a path
-// boundary, or a path's weight within kCutMargin (relative) of the cut-off.
-__device__ bool pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
-                         RowScratch& sm, int* cand) {
-  __shared__ int top_i[16][4];
-  __shared__ float top_p[16][4];
-  for (int k = 0; k < K; ++k) {
-    const float* z = Zh + (size_t)k * V;
-    float mx = -INFINITY;
-    for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
-    mx = block_max(mx, sm.redf);
-    float sum = 0.f;
-    for (int v = threadIdx.x; v < V; v += 256) sum += expf((z[v] - mx) * invT);
-    sum = block_sum(sum, sm.redf);
-    for (int j = 0; j < ks; ++j) {                 // j-th largest logit, lower index among equals
-      float bv = -INFINITY;
-      int bi = 0x7FFFFFFF;
-      for (int v = threadIdx.x; v < V; v += 256) {
-        bool taken = false;
-        for (int q = 0; q < j; ++q) taken |= top_i[k][q] == v;
-        const float x = z[v];
-        if (!taken && (x > bv || (x == bv && v < bi))) { bv = x; bi = v; }
-      }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const float bv2 = __shfl_xor(bv, o, WAVE);
-        const int bi2 = __shfl_xor(bi, o, WAVE);
-        if (bv2 > bv || (bv2 == bv && bi2 < bi)) { bv = bv2; bi = bi2; }
-      }
-      __syncthreads();
-      if ((threadIdx.x & 63) == 0) { sm.bestv[threadIdx.x >> 6] = bv; sm.besti[threadIdx.x >> 6] = bi; }
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; ++w)
-          if (sm.bestv[w] > bv || (sm.bestv[w] == bv && sm.besti[w] < bi)) { bv = sm.bestv[w]; bi = sm.besti[w]; }
-        top_i[k][j] = bi;
-        top_p[k][j] = bi == 0x7FFFFFFF ? 0.f : expf((bv - mx) * invT) / sum;     // V < ks: no such token
-      }
-      __syncthreads();
-    }
-  }
-  // leaves in lexicographic order, a contiguous run per thread; running sums in double, thread
-  // partials combined in thread order
-  __shared__ double pt_part[256];
-  __shared__ double pt_total;
-  __shared__ int pt_last;
-  int n_paths = 1;
-  for (int k = 0; k < K; ++k) n_paths *= ks;
-  auto weight = [&](int leaf) {                    // digits of `leaf` base ks, first head most significant
-    double w = 1.0;
-    int rem = leaf, div = n_paths;
-    for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
-    return (w >= (double)prune && w > 0.0) ? w : 0.0;   // cut paths carry no weight
-  };
-  auto raw_weight = [&](int leaf) {
-    double w = 1.0;
-    int rem = leaf, div = n_paths;
-    for (int k = 0; k < K; ++k) { div /= ks; w *= (double)top_p[k][rem / div]; rem %= div; }
-    return w;
-  };
-  const int chunk = (n_paths + 255) / 256;
-  const int l0 = min(n_paths, (int)threadIdx.x * chunk), l1 = min(n_paths, l0 + chunk);
-  double loc = 0.0;
-  int lastpos = -1, close = 0;
-  for (int leaf = l0; leaf < l1; ++leaf) {
-    const double w = weight(leaf);
-    loc += w;
-    if (w > 0.0) lastpos = leaf;
-    if (fabs(raw_weight(leaf) - (double)prune) <= (double)kCutMargin * (double)prune) close = 1;
-  }
-  pt_part[threadIdx.x] = loc;
-  lastpos = block_max_i(lastpos, sm.redi);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double run = 0.0;
-    for (int t = 0; t < 256; ++t) { const double p = pt_part[t]; pt_part[t] = run; run += p; }
-    pt_total = run;
-    pt_last = lastpos;
-  }
-  __syncthreads();
-  int hit = 0x7FFFFFFF;
-  if (pt_last >= 0) {
-    const double target = (double)u * pt_total, band = (double)kCdfMargin * pt_total;
-    double run = pt_part[threadIdx.x];
-    if (fabs(run - target) <= band) close = 1;
-    for (int leaf = l0; leaf < l1; ++leaf) {
-      const double w = weight(leaf);
-      run += w;
-      if (fabs(run - target) <= band) close = 1;
-      if (hit == 0x7FFFFFFF && w > 0.0 && run > target) hit = leaf;
-    }
-  }
-  close = block_max_i(close, sm.redi);
-  hit = block_min_i(hit, sm.redi);
-  if (threadIdx.x == 0) {
-    // no survivor: the most probable token of every head; rounding left nothing above the target: the last survivor
-    const int pick = pt_last < 0 ? 0 : (hit == 0x7FFFFFFF ? pt_last : hit);
-    int rem = pick, div = n_paths;
-    for (int k = 0; k < K; ++k) { div /= ks; cand[k + 1] = top_i[k][rem / div]; rem %= div; }
-  }
-  __syncthreads();
-  return close != 0;
 }
 
 // independent draws from the K head rows, one workgroup per (head, sequence): cand[b][k], and

@@ -58,6 +58,7 @@
 // position and rolls the cache length back (Alg. 1 inner loop, resample line, s <- s*).
 #include "xsm_device.h"
 #include "xsm_internal.h"
+#include "xsm_verify_device.h"
 
 namespace xsm {
 
@@ -612,13 +613,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
   __syncthreads();
   // A bounded wait gave up, in this step or an earlier one: sequence b produced nothing.  The
-  // caller sees it in the step's own outputs (n_accepted 0, the timeout flag), and the verify /
-  // emit kernels that follow a deferred step skip the sequence.
+  // caller sees it in the step's own outputs (n_accepted 0, the timeout flag).
   auto report_timeout = [&](int b) {
-    const uint32_t f = sm.flag[b] | XSM_FLAG_DEVICE_TIMEOUT;
     a.n_accepted[b] = 0;
-    a.flags[b] = f;
-    if (a.eff_out) { a.eff_out[b] = -1; a.wflags_out[b] = f; }
+    a.flags[b] = sm.flag[b] | XSM_FLAG_DEVICE_TIMEOUT;
   };
   if (sm.fail != 0) {                       // an earlier step timed out: stay down until reset
     if (w < a.n_seq && tid == 0) report_timeout(w);
@@ -1280,6 +1278,9 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           if (z > bv) { sv = bv; bv = z; bi = t * 16 + nr; }
           else sv = fmaxf(sv, z);
         }
+        // The statistics words double as the completion flag of this tile's piece of the logits
+        // row: what was stored above must be visible device-wide before they are
+        if (dbg) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         uint64_t* st = stb + ((size_t)t * kSmallMaxRows + q) * 4;
         ll_st(st, __float_as_uint(bv), tag);
         ll_st(st + 1, (uint32_t)bi, tag);
@@ -1291,9 +1292,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
   XSM_STAMP(a.L * 16 + 3);
 
-  // ---- FINAL: workgroup b finishes sequence b (greedy verification with argmax draws; the other
-  // criteria and sampling rules read the full logits rows in kernels of their own) ----
-  if (w < a.n_seq && !a.defer_verify) {
+  // ---- FINAL: workgroup b finishes sequence b.  Greedy verification with argmax draws works from
+  // the per-tile statistics alone; the other criteria and sampling rules read the logits rows the
+  // unembedding stored (Sec. 5.4 "Verification criterion"; appendix "Sampling strategies") ----
+  if (w < a.n_seq) {
     const int b = w;
     const int n = sm.len[b];
     // global top-2 of a logits row from the per-tile statistics (one wavefront per row, four tiles
@@ -1332,6 +1334,76 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #undef XSM_FOLD
       if (lane == 0) { sm.st_max[q] = bv; sm.st_sec[q] = sv; sm.st_idx[q] = bi; }
     };
+    if (a.full_verify) {
+      // The rows' statistics are waited for as in the greedy case: when a row's words of all
+      // tiles are in, so is the row (release before them, acquire here).
+      __shared__ int cand[16];
+      RowScratch& rs = *reinterpret_cast<RowScratch*>(&sm.att_o[0][0][0][0]);
+      const xsm_verify_params& vp = a.vp;
+      for (int q = wave; q < R; q += 4) row_top2(q, b * R + q);
+      bool late = __syncthreads_or(!ok);
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      uint32_t fl = sm.flag[b];
+      int acc_n = 0, y0 = 0;
+      if (!late && n >= 0) {
+        for (int j = 1; j < R; ++j) {                       // accept until the first candidate that fails
+          const float* z = a.logits_dbg + (size_t)(b * R + j - 1) * V;
+          const int x = a.block[b * R + j];
+          bool good;
+          if (vp.mode == XSM_VERIFY_THRESHOLD) {
+            const float p = row_prob(z, V, x, 1.0f / vp.temperature, rs);
+            good = p > vp.delta;
+            if (p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin) fl |= XSM_FLAG_NEAR_TIE;
+          } else {
+            const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
+            const int rank = row_rank(z, V, x, rs);
+            good = rank < ka;
+            if (rank_near_boundary(z, V, x, rank, ka, rs)) fl |= XSM_FLAG_NEAR_TIE;
+          }
+          if (!good) break;
+          ++acc_n;
+        }
+        y0 = row_sample(a.logits_dbg + (size_t)(b * R + acc_n) * V, V, vp, (uint32_t)(n + acc_n + 1), 0u, (uint32_t)sm.slot[b], rs, &fl);
+      }
+      // the K head rows of the accepted position
+      for (int k = wave; k < K; k += 4) row_top2(R + k, M + (b * R + acc_n) * K + k);
+      late = __syncthreads_or(!ok) || late;
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      if (!late && n >= 0 && K > 0) {
+        const float* Zh = a.head_all_dbg + (size_t)((b * R + acc_n) * K) * V;
+        if (vp.sample == 2) {
+          const float u = philox_uniform(vp.seed, (uint32_t)(n + acc_n + 1), 254u, (uint32_t)sm.slot[b]);
+          if (pts_draw(Zh, K, V, vp.top_ks, 1.0f / vp.temperature, vp.pts_prune, u, rs, cand)) fl |= XSM_FLAG_NEAR_TIE;
+        } else {
+          for (int k = 1; k <= K; ++k) {
+            const int t = row_sample(Zh + (size_t)(k - 1) * V, V, vp, (uint32_t)(n + acc_n + 1 + k), (uint32_t)k,
+                                     (uint32_t)sm.slot[b], rs, &fl);
+            if (tid == 0) cand[k] = t;
+          }
+        }
+      }
+      __syncthreads();
+      if (tid == 0) {
+        if (late) {
+          report_timeout(b);
+        } else if (n < 0) {
+          a.n_accepted[b] = 0;
+          a.flags[b] = fl;
+        } else {
+          int oldb[16];
+          for (int j = 0; j < R; ++j) oldb[j] = a.block[b * R + j];
+          for (int j = 0; j < acc_n; ++j) a.out_tokens[b * R + j] = oldb[j + 1];
+          a.out_tokens[b * R + acc_n] = y0;
+          for (int j = acc_n + 1; j < R; ++j) a.out_tokens[b * R + j] = -1;
+          a.block[b * R] = y0;
+          for (int k = 1; k <= K; ++k) a.block[b * R + k] = cand[k];
+          a.n_accepted[b] = acc_n + 1;
+          a.kv_len[b] = n + acc_n + 1;
+          a.flags[b] = fl;
+          if (a.acc_out) a.acc_out[b] = acc_n;
+        }
+      }
+    } else {
     // the R backbone rows first; they fix the accepted length, and only the K head rows of that
     // position are needed after it (slots R .. R + K - 1)
     for (int q = wave; q < R; q += 4) row_top2(q, b * R + q);
@@ -1377,6 +1449,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         a.flags[b] = fl;
         if (a.acc_out) a.acc_out[b] = acc_n;
       }
+    }
     }
   }
   XSM_STAMP(a.L * 16 + 4);
