@@ -1336,50 +1336,73 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     };
     if (a.full_verify) {
       // The rows' statistics are waited for as in the greedy case: when a row's words of all
-      // tiles are in, so is the row (release before them, acquire here).
-      __shared__ int cand[16];
+      // tiles are in, so is the row (release before them, acquire here).  The accept checks of
+      // all candidates, and then the draws of the backbone token and of all heads, run side by
+      // side, one wavefront per logits row.
+      __shared__ int cand[17];                            // [0] the backbone's token, [k] head k's
+      __shared__ int good_s[16];
+      __shared__ uint32_t near_s[17];
       RowScratch& rs = *reinterpret_cast<RowScratch*>(&sm.att_o[0][0][0][0]);
       const xsm_verify_params& vp = a.vp;
+      const float invT = 1.0f / vp.temperature;
       for (int q = wave; q < R; q += 4) row_top2(q, b * R + q);
       bool late = __syncthreads_or(!ok);
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      uint32_t fl = sm.flag[b];
-      int acc_n = 0, y0 = 0;
-      if (!late && n >= 0) {
-        for (int j = 1; j < R; ++j) {                       // accept until the first candidate that fails
+      const bool run = !late && n >= 0;
+      if (run) {
+        for (int j = 1 + wave; j <= K; j += 4) {
           const float* z = a.logits_dbg + (size_t)(b * R + j - 1) * V;
           const int x = a.block[b * R + j];
-          bool good;
+          bool good, nb = false;
           if (vp.mode == XSM_VERIFY_THRESHOLD) {
-            const float p = row_prob(z, V, x, 1.0f / vp.temperature, rs);
+            const float p = wave_prob(z, V, x, invT);
             good = p > vp.delta;
-            if (p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin) fl |= XSM_FLAG_NEAR_TIE;
+            nb = p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin;
           } else {
             const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
-            const int rank = row_rank(z, V, x, rs);
-            good = rank < ka;
-            if (rank_near_boundary(z, V, x, rank, ka, rs)) fl |= XSM_FLAG_NEAR_TIE;
+            good = wave_rank(z, V, x, ka, &nb) < ka;
           }
-          if (!good) break;
+          if (lane == 0) { good_s[j] = good ? 1 : 0; near_s[j] = nb ? 1u : 0u; }
+        }
+      }
+      __syncthreads();
+      uint32_t fl = sm.flag[b];
+      int acc_n = 0;
+      if (run) {
+        for (int j = 1; j <= K; ++j) {                      // accept until the first candidate that fails
+          if (near_s[j]) fl |= XSM_FLAG_NEAR_TIE;
+          if (!good_s[j]) break;
           ++acc_n;
         }
-        y0 = row_sample(a.logits_dbg + (size_t)(b * R + acc_n) * V, V, vp, (uint32_t)(n + acc_n + 1), 0u, (uint32_t)sm.slot[b], rs, &fl);
       }
       // the K head rows of the accepted position
       for (int k = wave; k < K; k += 4) row_top2(R + k, M + (b * R + acc_n) * K + k);
       late = __syncthreads_or(!ok) || late;
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      if (!late && n >= 0 && K > 0) {
-        const float* Zh = a.head_all_dbg + (size_t)((b * R + acc_n) * K) * V;
-        if (vp.sample == 2) {
-          const float u = philox_uniform(vp.seed, (uint32_t)(n + acc_n + 1), 254u, (uint32_t)sm.slot[b]);
-          if (pts_draw(Zh, K, V, vp.top_ks, 1.0f / vp.temperature, vp.pts_prune, u, rs, cand)) fl |= XSM_FLAG_NEAR_TIE;
-        } else {
-          for (int k = 1; k <= K; ++k) {
-            const int t = row_sample(Zh + (size_t)(k - 1) * V, V, vp, (uint32_t)(n + acc_n + 1 + k), (uint32_t)k,
-                                     (uint32_t)sm.slot[b], rs, &fl);
-            if (tid == 0) cand[k] = t;
+      if (!late && n >= 0) {
+        const uint32_t pos0 = (uint32_t)(n + acc_n + 1), sq = (uint32_t)sm.slot[b];
+        // draw d: 0 = the backbone's token from row acc_n, k = head k's token
+        for (int d = wave; d <= K; d += 4) {
+          if (d > 0 && vp.sample == 2) continue;           // the heads' tokens are one tree draw, below
+          const int slot_q = d == 0 ? acc_n : R + d - 1;    // where row_top2 left the row's statistics
+          int t;
+          bool nb;
+          if (vp.sample == 0) {
+            t = sm.st_idx[slot_q];
+            nb = sm.st_max[slot_q] - sm.st_sec[slot_q] <= kTieMargin;
+          } else {
+            const float* z = d == 0 ? a.logits_dbg + (size_t)(b * R + acc_n) * V
+                                    : a.head_all_dbg + (size_t)((b * R + acc_n) * K + d - 1) * V;
+            t = wave_categorical(z, V, invT, philox_uniform(vp.seed, pos0 + (uint32_t)d, (uint32_t)d, sq), &nb);
           }
+          if (lane == 0) { cand[d] = t; near_s[d == 0 ? 0 : d] = nb ? 1u : 0u; }
+        }
+        if (vp.sample == 2 && K > 0) {
+          __syncthreads();
+          const float u = philox_uniform(vp.seed, pos0, 254u, sq);
+          const bool nb = pts_draw(a.head_all_dbg + (size_t)((b * R + acc_n) * K) * V, K, V, vp.top_ks, invT, vp.pts_prune, u, rs, cand);
+          if (tid == 0)
+            for (int k = 1; k <= K; ++k) near_s[k] = nb ? 1u : 0u;
         }
       }
       __syncthreads();
@@ -1390,8 +1413,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           a.n_accepted[b] = 0;
           a.flags[b] = fl;
         } else {
+          for (int d = 0; d <= K; ++d)
+            if (near_s[d]) fl |= XSM_FLAG_NEAR_TIE;
           int oldb[16];
           for (int j = 0; j < R; ++j) oldb[j] = a.block[b * R + j];
+          const int y0 = cand[0];
           for (int j = 0; j < acc_n; ++j) a.out_tokens[b * R + j] = oldb[j + 1];
           a.out_tokens[b * R + acc_n] = y0;
           for (int j = acc_n + 1; j < R; ++j) a.out_tokens[b * R + j] = -1;

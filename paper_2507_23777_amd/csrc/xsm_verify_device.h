@@ -176,6 +176,121 @@ __device__ inline int row_sample(const float* z, int V, const xsm_verify_params&
   return t;
 }
 
+// ---- the same decisions with one wavefront per row (no barriers): the single-launch step's last
+// stage runs the accept checks of all candidates, and the draws of all heads, side by side on its
+// four wavefronts.  Rows of V % 4 == 0 floats; every lane receives the result. ----
+
+// inclusive prefix sum over the 64 lanes, lane order (fixed combination order)
+__device__ inline float wave_scan_incl(float v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float t = __shfl_up(v, o, WAVE);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// rank of candidate x (tokens with a larger logit, or an equal one and a lower index) and whether
+// a logit change within the margin could move it across the K_a boundary
+__device__ inline int wave_rank(const float* z, int V, int x, int ka, bool* near_boundary) {
+  const int lane = threadIdx.x & 63;
+  const float zx = z[x];
+  const float4* z4 = reinterpret_cast<const float4*>(z);
+  int c = 0, above = 0, below = 0;
+  for (int q = lane; q < (V >> 2); q += 64) {
+    const float4 y = z4[q];
+    const float e[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int v = q * 4 + i;
+      const float dlt = e[i] - zx;
+      c += (dlt > 0.f || (dlt == 0.f && v < x)) ? 1 : 0;
+      if (v != x && dlt >= 0.f && dlt <= kTieMargin) ++above;
+      if (v != x && dlt < 0.f && -dlt <= kTieMargin) ++below;
+    }
+  }
+  c = wave_sum_i(c); above = wave_sum_i(above); below = wave_sum_i(below);
+  *near_boundary = c < ka ? c + below >= ka : c - above < ka;
+  return c;
+}
+
+// softmax(z/T)[x]
+__device__ inline float wave_prob(const float* z, int V, int x, float invT) {
+  const int lane = threadIdx.x & 63;
+  const float4* z4 = reinterpret_cast<const float4*>(z);
+  float mx = -INFINITY;
+  for (int q = lane; q < (V >> 2); q += 64) {
+    const float4 y = z4[q];
+    mx = fmaxf(fmaxf(mx, fmaxf(y.x, y.y)), fmaxf(y.z, y.w));
+  }
+  mx = wave_max(mx);
+  float s = 0.f;
+  for (int q = lane; q < (V >> 2); q += 64) {
+    const float4 y = z4[q];
+    s += (expf((y.x - mx) * invT) + expf((y.y - mx) * invT)) + (expf((y.z - mx) * invT) + expf((y.w - mx) * invT));
+  }
+  s = wave_sum(s);
+  return expf((z[x] - mx) * invT) / s;
+}
+
+// categorical draw by inverse CDF over ascending token index with the uniform u; *near_edge: u
+// lies within kCdfMargin (relative to the total weight) of a CDF edge.  The running sum walks the
+// row in 256-token steps (a lane's four tokens, a lane scan, the step's total), once for the total
+// and once more, in the same order, for the hit.
+__device__ inline int wave_categorical(const float* z, int V, float invT, float u, bool* near_edge) {
+  const int lane = threadIdx.x & 63;
+  const float4* z4 = reinterpret_cast<const float4*>(z);
+  const int n4 = V >> 2;
+  float mx = -INFINITY;
+  for (int q = lane; q < n4; q += 64) {
+    const float4 y = z4[q];
+    mx = fmaxf(fmaxf(mx, fmaxf(y.x, y.y)), fmaxf(y.z, y.w));
+  }
+  mx = wave_max(mx);
+  float total = 0.f;
+  for (int q0 = 0; q0 < n4; q0 += 64) {
+    const int q = q0 + lane;
+    float s = 0.f;
+    if (q < n4) {
+      const float4 y = z4[q];
+      s = ((expf((y.x - mx) * invT) + expf((y.y - mx) * invT)) + expf((y.z - mx) * invT)) + expf((y.w - mx) * invT);
+    }
+    total += __shfl(wave_scan_incl(s), 63, WAVE);
+  }
+  const float target = u * total, band = kCdfMargin * total;
+  float run = 0.f;
+  int hit = 0x7FFFFFFF, lastpos = -1, close = 0;
+  for (int q0 = 0; q0 < n4 && hit == 0x7FFFFFFF; q0 += 64) {
+    const int q = q0 + lane;
+    float w4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (q < n4) {
+      const float4 y = z4[q];
+      w4[0] = expf((y.x - mx) * invT); w4[1] = expf((y.y - mx) * invT);
+      w4[2] = expf((y.z - mx) * invT); w4[3] = expf((y.w - mx) * invT);
+    }
+    const float s = ((w4[0] + w4[1]) + w4[2]) + w4[3];
+    const float incl = wave_scan_incl(s);
+    float c = run + (incl - s);                     // running sum in front of this lane's tokens
+    if (lane == 0 && q0 == 0 && fabsf(c - target) <= band) close = 1;
+    int mine = 0x7FFFFFFF;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      c += w4[i];
+      if (q < n4) {
+        if (w4[i] > 0.f) lastpos = q * 4 + i;
+        if (mine == 0x7FFFFFFF && c > target) mine = q * 4 + i;
+        if (fabsf(c - target) <= band) close = 1;
+      }
+    }
+    hit = wave_min_i(mine);
+    run += __shfl(incl, 63, WAVE);
+  }
+  *near_edge = wave_max_i(close) != 0;
+  if (hit != 0x7FFFFFFF) return hit;
+  return wave_max_i(lastpos);                       // rounding left nothing above the target: the last token with weight
+}
+
 // Top-K_s probability-tree sampling of the K head tokens (appendix "Sampling strategies"): level d
 // holds the ks most probable tokens of softmax(z_d / T) with their probabilities as edge weights;
 // a complete path survives if its weight (a product of numbers <= 1, so the smallest of its
