@@ -1262,25 +1262,36 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
       *reinterpret_cast<f32x4*>(&sm.red[wave][lane][0]) = acc;
       __syncthreads();
+      // The logits themselves, where somebody reads them (every criterion but greedy-with-argmax, and
+      // the debug copies): thread (row tid / 16, column tid % 16) stores its entry with a
+      // device-coherent store and waits for it, so that after the barrier the whole tile has
+      // arrived; the statistics words stored after it double as the completion flag of this
+      // tile's piece of each row
+      if (a.logits_dbg) {
+        const int q = mt * 16 + (tid >> 4), nr = tid & 15;
+        float* dbg = nullptr;
+        if (q < M) dbg = a.logits_dbg + (size_t)q * V;
+        else if (q < rows_all && a.head_logits_dbg) dbg = a.head_all_dbg + (size_t)(q - M) * V;
+        if (dbg) {
+          const int ln = (nr >> 2) * 16 + (tid >> 4), ii = nr & 3;
+          const float z = (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
+          __hip_atomic_store(dbg + t * 16 + nr, z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
       // threads 0..15: row q = mt*16 + tid; scan the tile's 16 vocabulary entries in order
       if (tid < 16 && mt * 16 + tid < rows_all) {
         const int q = mt * 16 + tid;
         float bv = -INFINITY, sv = -INFINITY;
         int bi = 0;
-        float* dbg = nullptr;
-        if (q < M) { if (a.logits_dbg) dbg = a.logits_dbg + (size_t)q * V; }
-        else if (a.head_logits_dbg) dbg = a.head_all_dbg + (size_t)(q - M) * V;
 #pragma unroll
         for (int nr = 0; nr < 16; ++nr) {
           const int ln = (nr >> 2) * 16 + tid, ii = nr & 3;
           const float z = (sm.red[0][ln][ii] + sm.red[1][ln][ii]) + (sm.red[2][ln][ii] + sm.red[3][ln][ii]);
-          if (dbg) dbg[t * 16 + nr] = z;
           if (z > bv) { sv = bv; bv = z; bi = t * 16 + nr; }
           else sv = fmaxf(sv, z);
         }
-        // The statistics words double as the completion flag of this tile's piece of the logits
-        // row: what was stored above must be visible device-wide before they are
-        if (dbg) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         uint64_t* st = stb + ((size_t)t * kSmallMaxRows + q) * 4;
         ll_st(st, __float_as_uint(bv), tag);
         ll_st(st + 1, (uint32_t)bi, tag);
@@ -1293,8 +1304,113 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   XSM_STAMP(a.L * 16 + 3);
 
   // ---- FINAL: workgroup b finishes sequence b.  Greedy verification with argmax draws works from
-  // the per-tile statistics alone; the other criteria and sampling rules read the logits rows the
-  // unembedding stored (Sec. 5.4 "Verification criterion"; appendix "Sampling strategies") ----
+  // the per-tile statistics alone.  The other criteria and sampling rules need whole logits rows
+  // (Sec. 5.4 "Verification criterion"; appendix "Sampling strategies"): every accept check, and
+  // every draw for every possible accepted length, is a task of its own on its own workgroup, all
+  // of them side by side; a task posts its result as a tagged word and workgroup b picks the
+  // ones its accepted length selects ----
+  uint64_t* const res = stb + 3;                           // result word i: the spare fourth word of statistics group i
+  const int slots_seq = K + R * R;                         // per sequence: K checks, then (accepted length, draw)
+  if (a.full_verify) {
+    const xsm_verify_params& vp = a.vp;
+    const float invT = 1.0f / vp.temperature;
+    RowScratch& rs = *reinterpret_cast<RowScratch*>(&sm.att_o[0][0][0][0]);
+    __shared__ int tree_tok[17];
+    __shared__ TreeLevels lv;
+    // Tasks per sequence: K accept checks, then per accepted length the draws.  Categorical: the
+    // backbone's token and each head's.  Tree: the backbone's token, each head's level of the
+    // tree, and (in a second group behind all of these, which it waits for) the joint draw of the
+    // heads.  Argmax draws come from the statistics and need no task.
+    const int ks = vp.top_ks;
+    const int per_m = vp.sample == 0 ? 0 : R;
+    const int per_seq = K + R * per_m;
+    const int n_first = a.n_seq * per_seq;
+    const int n_tasks = n_first + (vp.sample == 2 && K > 0 ? a.n_seq * R : 0);
+    uint64_t* const lev = res + (size_t)512 * 4;          // tree levels: 8 words per head row, behind the result words
+    // true (in every thread) once logits rows [g0, g0 + nr) are complete: their statistics words
+    // of all tiles carry the tag, and each was stored after its tile's piece of the row had arrived
+    auto rows_complete = [&](int g0, int nr) {
+      bool live = !__syncthreads_or(!ok);
+      for (int spin = 0; live; ++spin) {
+        bool good = true;
+        for (int i = tid; i < nr * NTV; i += 256)
+          good &= (uint32_t)(ll_ld(stb + ((size_t)(i % NTV) * kSmallMaxRows + g0 + i / NTV) * 4) >> 32) == tag;
+        if (__syncthreads_and(good)) break;
+        if (spin >= kSpinBudget) { ok = false; live = false; }
+        __builtin_amdgcn_s_sleep(4);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      return live;
+    };
+    // (tasks go to the workgroups from the far end: the low ones finish sequences)
+    for (int task = 255 - w; task < n_tasks; task += 256) {
+      if (task >= n_first) {                               // joint draw of the heads for accepted length m
+        const int b = (task - n_first) / R, m = (task - n_first) % R;
+        const int n = sm.len[b];
+        if (n < 0) continue;
+        if (tid < K * ks * 2) {
+          const int k = tid / (2 * ks), j = tid % (2 * ks);
+          const int off[1] = {(((b * R + m) * K + k) * 8 + j) * 4};
+          uint32_t pw[1];
+          ll_wait_list<1>(lev, off, tag, pw, ok);
+          if (j < ks) lv.idx[k][j] = (int)pw[0];
+          else lv.p[k][j - ks] = __uint_as_float(pw[0]);
+        }
+        if (__syncthreads_or(!ok)) break;
+        const bool nb = pts_pick(lv, K, ks, vp.pts_prune, philox_uniform(vp.seed, (uint32_t)(n + m + 1), 254u, (uint32_t)sm.slot[b]),
+                                 rs, tree_tok);
+        if (tid < K)
+          ll_st(res + (size_t)(b * slots_seq + K + m * R + tid + 1) * 4, (uint32_t)tree_tok[tid + 1] | (nb ? 0x80000000u : 0u), tag);
+        __syncthreads();
+        continue;
+      }
+      const int b = task / per_seq, i = task % per_seq;
+      const int n = sm.len[b];
+      if (n < 0) continue;
+      uint64_t* const out = res + (size_t)b * slots_seq * 4;
+      if (i < K) {                                         // accept check of candidate j = i + 1 against row j - 1
+        const int grow = b * R + i;
+        if (!rows_complete(grow, 1)) break;
+        const float* z = a.logits_dbg + (size_t)grow * V;
+        const int x = a.block[b * R + i + 1];
+        bool good, nb;
+        if (vp.mode == XSM_VERIFY_THRESHOLD) {
+          const float p = row_prob(z, V, x, invT, rs);
+          good = p > vp.delta;
+          // p crosses delta when the candidate's logit moves by about T |ln(p / delta)|
+          nb = p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin;
+        } else {
+          const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
+          const int rank = row_rank(z, V, x, rs);
+          good = rank < ka;
+          nb = rank_near_boundary(z, V, x, rank, ka, rs);
+        }
+        if (tid == 0) ll_st(out + (size_t)i * 4, (good ? 1u : 0u) | (nb ? 2u : 0u), tag);
+      } else {
+        const int m = (i - K) / per_m, d = (i - K) % per_m;  // accepted length; 0 = the backbone's draw
+        const uint32_t pos0 = (uint32_t)(n + m + 1), sq = (uint32_t)sm.slot[b];
+        uint64_t* const om_ = out + (size_t)(K + m * R) * 4;
+        if (d == 0 || vp.sample == 1) {
+          const int grow = d == 0 ? b * R + m : M + (b * R + m) * K + d - 1;
+          if (!rows_complete(grow, 1)) break;
+          const float* z = d == 0 ? a.logits_dbg + (size_t)grow * V : a.head_all_dbg + (size_t)(grow - M) * V;
+          bool nb;
+          const int t = row_categorical(z, V, invT, philox_uniform(vp.seed, pos0 + (uint32_t)d, (uint32_t)d, sq), rs, &nb);
+          if (tid == 0) ll_st(om_ + (size_t)d * 4, (uint32_t)t | (nb ? 0x80000000u : 0u), tag);
+        } else {                                           // level d - 1 of the tree: head d's ks most probable tokens
+          const int grow = M + (b * R + m) * K + d - 1;
+          if (!rows_complete(grow, 1)) break;
+          row_topk_probs(a.head_all_dbg + (size_t)(grow - M) * V, V, ks, invT, rs, lv.idx[0], lv.p[0]);
+          uint64_t* const lo = lev + (size_t)(grow - M) * 8 * 4;
+          if (tid < ks) {
+            ll_st(lo + (size_t)tid * 4, (uint32_t)lv.idx[0][tid], tag);
+            ll_st(lo + (size_t)(ks + tid) * 4, __float_as_uint(lv.p[0][tid]), tag);
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
   if (w < a.n_seq) {
     const int b = w;
     const int n = sm.len[b];
@@ -1335,77 +1451,41 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       if (lane == 0) { sm.st_max[q] = bv; sm.st_sec[q] = sv; sm.st_idx[q] = bi; }
     };
     if (a.full_verify) {
-      // The rows' statistics are waited for as in the greedy case: when a row's words of all
-      // tiles are in, so is the row (release before them, acquire here).  The accept checks of
-      // all candidates, and then the draws of the backbone token and of all heads, run side by
-      // side, one wavefront per logits row.
       __shared__ int cand[17];                            // [0] the backbone's token, [k] head k's
-      __shared__ int good_s[16];
-      __shared__ uint32_t near_s[17];
-      RowScratch& rs = *reinterpret_cast<RowScratch*>(&sm.att_o[0][0][0][0]);
+      __shared__ uint32_t chk_s[16], near_s[17];
       const xsm_verify_params& vp = a.vp;
-      const float invT = 1.0f / vp.temperature;
-      for (int q = wave; q < R; q += 4) row_top2(q, b * R + q);
-      bool late = __syncthreads_or(!ok);
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      const bool run = !late && n >= 0;
-      if (run) {
-        for (int j = 1 + wave; j <= K; j += 4) {
-          const float* z = a.logits_dbg + (size_t)(b * R + j - 1) * V;
-          const int x = a.block[b * R + j];
-          bool good, nb = false;
-          if (vp.mode == XSM_VERIFY_THRESHOLD) {
-            const float p = wave_prob(z, V, x, invT);
-            good = p > vp.delta;
-            nb = p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin;
-          } else {
-            const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
-            good = wave_rank(z, V, x, ka, &nb) < ka;
-          }
-          if (lane == 0) { good_s[j] = good ? 1 : 0; near_s[j] = nb ? 1u : 0u; }
-        }
-      }
-      __syncthreads();
+      const int base = b * slots_seq * 4;
       uint32_t fl = sm.flag[b];
       int acc_n = 0;
-      if (run) {
-        for (int j = 1; j <= K; ++j) {                      // accept until the first candidate that fails
-          if (near_s[j]) fl |= XSM_FLAG_NEAR_TIE;
-          if (!good_s[j]) break;
-          ++acc_n;
+      bool late = false;
+      if (n >= 0) {
+        if (tid < K) {
+          const int off[1] = {base + tid * 4};
+          uint32_t pw[1];
+          ll_wait_list<1>(res, off, tag, pw, ok);
+          chk_s[tid + 1] = pw[0];
         }
-      }
-      // the K head rows of the accepted position
-      for (int k = wave; k < K; k += 4) row_top2(R + k, M + (b * R + acc_n) * K + k);
-      late = __syncthreads_or(!ok) || late;
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      if (!late && n >= 0) {
-        const uint32_t pos0 = (uint32_t)(n + acc_n + 1), sq = (uint32_t)sm.slot[b];
-        // draw d: 0 = the backbone's token from row acc_n, k = head k's token
-        for (int d = wave; d <= K; d += 4) {
-          if (d > 0 && vp.sample == 2) continue;           // the heads' tokens are one tree draw, below
-          const int slot_q = d == 0 ? acc_n : R + d - 1;    // where row_top2 left the row's statistics
-          int t;
-          bool nb;
-          if (vp.sample == 0) {
-            t = sm.st_idx[slot_q];
-            nb = sm.st_max[slot_q] - sm.st_sec[slot_q] <= kTieMargin;
-          } else {
-            const float* z = d == 0 ? a.logits_dbg + (size_t)(b * R + acc_n) * V
-                                    : a.head_all_dbg + (size_t)((b * R + acc_n) * K + d - 1) * V;
-            t = wave_categorical(z, V, invT, philox_uniform(vp.seed, pos0 + (uint32_t)d, (uint32_t)d, sq), &nb);
+        late = __syncthreads_or(!ok);
+        if (!late)
+          for (int j = 1; j <= K; ++j) {                    // accept until the first candidate that fails
+            if (chk_s[j] & 2u) fl |= XSM_FLAG_NEAR_TIE;
+            if (!(chk_s[j] & 1u)) break;
+            ++acc_n;
           }
-          if (lane == 0) { cand[d] = t; near_s[d == 0 ? 0 : d] = nb ? 1u : 0u; }
-        }
-        if (vp.sample == 2 && K > 0) {
+        // draw d of the accepted length: 0 = the backbone's token from row acc_n, k = head k's
+        if (vp.sample == 0) {
+          for (int d = wave; d <= K; d += 4) row_top2(d, d == 0 ? b * R + acc_n : M + (b * R + acc_n) * K + d - 1);
           __syncthreads();
-          const float u = philox_uniform(vp.seed, pos0, 254u, sq);
-          const bool nb = pts_draw(a.head_all_dbg + (size_t)((b * R + acc_n) * K) * V, K, V, vp.top_ks, invT, vp.pts_prune, u, rs, cand);
-          if (tid == 0)
-            for (int k = 1; k <= K; ++k) near_s[k] = nb ? 1u : 0u;
+          if (tid <= K) { cand[tid] = sm.st_idx[tid]; near_s[tid] = sm.st_max[tid] - sm.st_sec[tid] <= kTieMargin ? 1u : 0u; }
+        } else if (tid <= K) {
+          const int off[1] = {base + (K + acc_n * R + tid) * 4};
+          uint32_t pw[1];
+          ll_wait_list<1>(res, off, tag, pw, ok);
+          cand[tid] = (int)(pw[0] & 0x7FFFFFFFu);
+          near_s[tid] = pw[0] >> 31;
         }
+        late = __syncthreads_or(!ok) || late;
       }
-      __syncthreads();
       if (tid == 0) {
         if (late) {
           report_timeout(b);

@@ -176,167 +176,61 @@ __device__ inline int row_sample(const float* z, int V, const xsm_verify_params&
   return t;
 }
 
-// ---- the same decisions with one wavefront per row (no barriers): the single-launch step's last
-// stage runs the accept checks of all candidates, and the draws of all heads, side by side on its
-// four wavefronts.  Rows of V % 4 == 0 floats; every lane receives the result. ----
-
-// inclusive prefix sum over the 64 lanes, lane order (fixed combination order)
-__device__ inline float wave_scan_incl(float v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const float t = __shfl_up(v, o, WAVE);
-    if (lane >= o) v += t;
-  }
-  return v;
-}
-
-// rank of candidate x (tokens with a larger logit, or an equal one and a lower index) and whether
-// a logit change within the margin could move it across the K_a boundary
-__device__ inline int wave_rank(const float* z, int V, int x, int ka, bool* near_boundary) {
-  const int lane = threadIdx.x & 63;
-  const float zx = z[x];
-  const float4* z4 = reinterpret_cast<const float4*>(z);
-  int c = 0, above = 0, below = 0;
-  for (int q = lane; q < (V >> 2); q += 64) {
-    const float4 y = z4[q];
-    const float e[4] = {y.x, y.y, y.z, y.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int v = q * 4 + i;
-      const float dlt = e[i] - zx;
-      c += (dlt > 0.f || (dlt == 0.f && v < x)) ? 1 : 0;
-      if (v != x && dlt >= 0.f && dlt <= kTieMargin) ++above;
-      if (v != x && dlt < 0.f && -dlt <= kTieMargin) ++below;
-    }
-  }
-  c = wave_sum_i(c); above = wave_sum_i(above); below = wave_sum_i(below);
-  *near_boundary = c < ka ? c + below >= ka : c - above < ka;
-  return c;
-}
-
-// softmax(z/T)[x]
-__device__ inline float wave_prob(const float* z, int V, int x, float invT) {
-  const int lane = threadIdx.x & 63;
-  const float4* z4 = reinterpret_cast<const float4*>(z);
-  float mx = -INFINITY;
-  for (int q = lane; q < (V >> 2); q += 64) {
-    const float4 y = z4[q];
-    mx = fmaxf(fmaxf(mx, fmaxf(y.x, y.y)), fmaxf(y.z, y.w));
-  }
-  mx = wave_max(mx);
-  float s = 0.f;
-  for (int q = lane; q < (V >> 2); q += 64) {
-    const float4 y = z4[q];
-    s += (expf((y.x - mx) * invT) + expf((y.y - mx) * invT)) + (expf((y.z - mx) * invT) + expf((y.w - mx) * invT));
-  }
-  s = wave_sum(s);
-  return expf((z[x] - mx) * invT) / s;
-}
-
-// categorical draw by inverse CDF over ascending token index with the uniform u; *near_edge: u
-// lies within kCdfMargin (relative to the total weight) of a CDF edge.  The running sum walks the
-// row in 256-token steps (a lane's four tokens, a lane scan, the step's total), once for the total
-// and once more, in the same order, for the hit.
-__device__ inline int wave_categorical(const float* z, int V, float invT, float u, bool* near_edge) {
-  const int lane = threadIdx.x & 63;
-  const float4* z4 = reinterpret_cast<const float4*>(z);
-  const int n4 = V >> 2;
-  float mx = -INFINITY;
-  for (int q = lane; q < n4; q += 64) {
-    const float4 y = z4[q];
-    mx = fmaxf(fmaxf(mx, fmaxf(y.x, y.y)), fmaxf(y.z, y.w));
-  }
-  mx = wave_max(mx);
-  float total = 0.f;
-  for (int q0 = 0; q0 < n4; q0 += 64) {
-    const int q = q0 + lane;
-    float s = 0.f;
-    if (q < n4) {
-      const float4 y = z4[q];
-      s = ((expf((y.x - mx) * invT) + expf((y.y - mx) * invT)) + expf((y.z - mx) * invT)) + expf((y.w - mx) * invT);
-    }
-    total += __shfl(wave_scan_incl(s), 63, WAVE);
-  }
-  const float target = u * total, band = kCdfMargin * total;
-  float run = 0.f;
-  int hit = 0x7FFFFFFF, lastpos = -1, close = 0;
-  for (int q0 = 0; q0 < n4 && hit == 0x7FFFFFFF; q0 += 64) {
-    const int q = q0 + lane;
-    float w4[4] = {0.f, 0.f, 0.f, 0.f};
-    if (q < n4) {
-      const float4 y = z4[q];
-      w4[0] = expf((y.x - mx) * invT); w4[1] = expf((y.y - mx) * invT);
-      w4[2] = expf((y.z - mx) * invT); w4[3] = expf((y.w - mx) * invT);
-    }
-    const float s = ((w4[0] + w4[1]) + w4[2]) + w4[3];
-    const float incl = wave_scan_incl(s);
-    float c = run + (incl - s);                     // running sum in front of this lane's tokens
-    if (lane == 0 && q0 == 0 && fabsf(c - target) <= band) close = 1;
-    int mine = 0x7FFFFFFF;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      c += w4[i];
-      if (q < n4) {
-        if (w4[i] > 0.f) lastpos = q * 4 + i;
-        if (mine == 0x7FFFFFFF && c > target) mine = q * 4 + i;
-        if (fabsf(c - target) <= band) close = 1;
-      }
-    }
-    hit = wave_min_i(mine);
-    run += __shfl(incl, 63, WAVE);
-  }
-  *near_edge = wave_max_i(close) != 0;
-  if (hit != 0x7FFFFFFF) return hit;
-  return wave_max_i(lastpos);                       // rounding left nothing above the target: the last token with weight
-}
-
 // Top-K_s probability-tree sampling of the K head tokens (appendix "Sampling strategies"): level d
 // holds the ks most probable tokens of softmax(z_d / T) with their probabilities as edge weights;
 // a complete path survives if its weight (a product of numbers <= 1, so the smallest of its
 // prefixes' weights) is at least `prune`; one survivor is drawn in proportion to its weight by
-// inverse CDF in depth-first (= lexicographic) order.  cand[1..K] receives the tokens.  Returns
-// true (to every thread) when the draw is a near-tie: the uniform within kCdfMargin of a path
-// boundary, or a path's weight within kCutMargin (relative) of the cut-off.
-__device__ inline bool pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
-                         RowScratch& sm, int* cand) {
-  __shared__ int top_i[16][4];
-  __shared__ float top_p[16][4];
-  for (int k = 0; k < K; ++k) {
-    const float* z = Zh + (size_t)k * V;
-    float mx = -INFINITY;
-    for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
-    mx = block_max(mx, sm.redf);
-    float sum = 0.f;
-    for (int v = threadIdx.x; v < V; v += 256) sum += expf((z[v] - mx) * invT);
-    sum = block_sum(sum, sm.redf);
-    for (int j = 0; j < ks; ++j) {                 // j-th largest logit, lower index among equals
-      float bv = -INFINITY;
-      int bi = 0x7FFFFFFF;
-      for (int v = threadIdx.x; v < V; v += 256) {
-        bool taken = false;
-        for (int q = 0; q < j; ++q) taken |= top_i[k][q] == v;
-        const float x = z[v];
-        if (!taken && (x > bv || (x == bv && v < bi))) { bv = x; bi = v; }
-      }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const float bv2 = __shfl_xor(bv, o, WAVE);
-        const int bi2 = __shfl_xor(bi, o, WAVE);
-        if (bv2 > bv || (bv2 == bv && bi2 < bi)) { bv = bv2; bi = bi2; }
-      }
-      __syncthreads();
-      if ((threadIdx.x & 63) == 0) { sm.bestv[threadIdx.x >> 6] = bv; sm.besti[threadIdx.x >> 6] = bi; }
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; ++w)
-          if (sm.bestv[w] > bv || (sm.bestv[w] == bv && sm.besti[w] < bi)) { bv = sm.bestv[w]; bi = sm.besti[w]; }
-        top_i[k][j] = bi;
-        top_p[k][j] = bi == 0x7FFFFFFF ? 0.f : expf((bv - mx) * invT) / sum;     // V < ks: no such token
-      }
-      __syncthreads();
+// inverse CDF in depth-first (= lexicographic) order.  Two steps, so that the levels can be built
+// side by side: row_topk_probs makes one level, pts_pick draws the path.
+struct TreeLevels {
+  int idx[16][4];
+  float p[16][4];
+};
+
+// One level: the ks (<= 4) largest logits of the row, lower index among equals, with their
+// softmax(z / T) probabilities -> idx[0..ks), p[0..ks) (workgroup-shared memory; idx = 0x7FFFFFFF,
+// p = 0 where the row has fewer than ks tokens).  Ends with a barrier.
+__device__ inline void row_topk_probs(const float* z, int V, int ks, float invT, RowScratch& sm, int* idx, float* p) {
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+  mx = block_max(mx, sm.redf);
+  float sum = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) sum += expf((z[v] - mx) * invT);
+  sum = block_sum(sum, sm.redf);
+  for (int j = 0; j < ks; ++j) {                 // j-th largest logit, lower index among equals
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int v = threadIdx.x; v < V; v += 256) {
+      bool taken = false;
+      for (int q = 0; q < j; ++q) taken |= idx[q] == v;
+      const float x = z[v];
+      if (!taken && (x > bv || (x == bv && v < bi))) { bv = x; bi = v; }
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float bv2 = __shfl_xor(bv, o, WAVE);
+      const int bi2 = __shfl_xor(bi, o, WAVE);
+      if (bv2 > bv || (bv2 == bv && bi2 < bi)) { bv = bv2; bi = bi2; }
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sm.bestv[threadIdx.x >> 6] = bv; sm.besti[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < 4; ++w)
+        if (sm.bestv[w] > bv || (sm.bestv[w] == bv && sm.besti[w] < bi)) { bv = sm.bestv[w]; bi = sm.besti[w]; }
+      idx[j] = bi;
+      p[j] = bi == 0x7FFFFFFF ? 0.f : expf((bv - mx) * invT) / sum;     // V < ks: no such token
+    }
+    __syncthreads();
   }
+}
+
+// The draw over the tree that levels lv[0..K) span, with the uniform u: cand[1..K] receives the
+// tokens.  Returns true (to every thread) when the draw is a near-tie: the uniform within
+// kCdfMargin of a path boundary, or a path's weight within kCutMargin (relative) of the cut-off.
+__device__ inline bool pts_pick(const TreeLevels& lv, int K, int ks, float prune, float u, RowScratch& sm, int* cand) {
+  const int (*top_i)[4] = lv.idx;
+  const float (*top_p)[4] = lv.p;
   // leaves in lexicographic order, a contiguous run per thread; running sums in double, thread
   // partials combined in thread order
   __shared__ double pt_part[256];
@@ -398,6 +292,14 @@ __device__ inline bool pts_draw(const float* Zh, int K, int V, int ks, float inv
   }
   __syncthreads();
   return close != 0;
+}
+
+// both steps in one workgroup: Zh = the K head rows, consecutive
+__device__ inline bool pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
+                         RowScratch& sm, int* cand) {
+  __shared__ TreeLevels lv;
+  for (int k = 0; k < K; ++k) row_topk_probs(Zh + (size_t)k * V, V, ks, invT, sm, lv.idx[k], lv.p[k]);
+  return pts_pick(lv, K, ks, prune, u, sm, cand);
 }
 
 }  // namespace xsm
