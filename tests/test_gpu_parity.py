@@ -494,8 +494,8 @@ def test_single_launch_eight_draft_heads(X):
 @pytest.mark.parametrize("single_launch", [1, 0])
 def test_single_launch_with_sampling_rules(X, single_launch):
     """Top-K_a acceptance with categorical draws, the probability threshold, and probability-tree
-    draws at a batch small enough for the persistent kernel: it then stops after the unembedding
-    and the verify / emit kernels take over."""
+    draws at a batch small enough for the persistent kernel, which runs the accept checks and the
+    draws as per-row tasks on its own workgroups (single_launch=0: the verify / emit kernels)."""
     cfg = _c1_small(n_layers=2)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[70, 21], perturb=True)
     eng.xsm_set_option(X.xsm.XSM_OPT_SINGLE_LAUNCH, single_launch)
@@ -530,7 +530,7 @@ def test_single_launch_timeout_is_reported_in_band_and_falls_back(X, rule):
     is set as a timed-out wait would set it; no wait is made to spin and every kernel exits
     normally): the step's own outputs must say that nothing was produced, xsm_check_device must
     report it once, and the following steps must run on the per-stage kernels and match the
-    oracle.  Both with verification inside the kernel and with the verify / emit kernels behind it."""
+    oracle.  Both with the greedy last stage and with the per-row check and draw tasks."""
     cfg = _c1_small(n_layers=2)
     torch = X.torch
     vp = GREEDY if rule == "greedy" else VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=17)
@@ -594,6 +594,44 @@ def test_single_launch_free_running_equals_per_stage(X):
     print(f"[single vs per-stage] {same} of 40 steps identical before the first flagged divergence", flush=True)
     X.H.SUMMARY.append(f"[single vs per-stage free-running] {same} of 40 steps identical")
     assert same >= 10
+
+
+@pytest.mark.parametrize("rule", ["greedy", "tree"])
+def test_single_launch_same_step_for_300_epochs(X, rule):
+    """The exchange words' 8-bit tag wraps every 255 steps, and the step that starts a new cycle
+    scrubs the exchange region first: the same step (same lengths, same block, same seed) repeated
+    300 times must give the same tokens and bit-identical logits every time, before, at and after
+    the wrap, and the per-stage kernels' tokens."""
+    cfg = _c1_small(n_layers=2)
+    torch = X.torch
+    vp = GREEDY if rule == "greedy" else VerifyParams(mode=1, top_ka=8, temperature=0.5, sample=2, seed=31, top_ks=2)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[70, 21], perturb=True)
+    vpg = X.H.to_vp_gpu(X.xsm, vp)
+    first = torch.tensor(si.first_block(cfg, 2))
+    lens = torch.tensor([70, 21], dtype=torch.int32)
+    buf = eng.buffers(2, spec=True, debug=True)
+
+    def step():
+        buf.kv_len.copy_(lens); buf.block.copy_(first)
+        eng.xsm_spec_step(buf, vpg, 70)
+        torch.cuda.synchronize()
+        return (buf.n_accepted.tolist(), buf.out_tokens.tolist(), buf.block.tolist(), buf.flags.tolist())
+
+    X.xsm.xsm_debug_trace_enable(True); X.xsm.xsm_debug_trace_report()
+    ref = step()
+    z_ref = buf.logits.clone()
+    for i in range(1, 300):
+        got = step()
+        assert got == ref, f"step {i}: {got} vs {ref}"
+        if i in (254, 255, 256, 299):
+            assert torch.equal(buf.logits, z_ref), f"step {i}: logits differ from the first step's"
+    ran = X.xsm.xsm_debug_trace_report(); X.xsm.xsm_debug_trace_enable(False)
+    assert ran["step_small"][0] == 300, sorted(ran)
+    eng.xsm_check_device()
+    eng.xsm_set_option(X.xsm.XSM_OPT_SINGLE_LAUNCH, 0)
+    per_stage = step()
+    assert per_stage[:3] == ref[:3] or (per_stage[3][0] | per_stage[3][1] | ref[3][0] | ref[3][1]) & 1
+    eng.xsm_check_device()
 
 
 @pytest.mark.parametrize("path", ["single_launch", "per_stage_sampling"])
