@@ -199,7 +199,7 @@ def stage_timeline(args, torch, pkg, xsm, si) -> int:
     t = eng.xsm_debug_timeline().astype(np.int64)          # [256 workgroups][L*16 + 8] ticks of 10 ns
     eng.xsm_check_device()
     us = (t - t[:, 0].min()) / 100.0
-    names = ["qkv", "att", "merge", "oproj", "up", "down+sum"]
+    names = ["qkv", "att", "merge (16 key slices only)", "oproj", "up", "down"]
     mid = L // 2
     row = us[:, mid * 16:mid * 16 + 7]
     starts = us[:, [l * 16 for l in range(L)]].mean(0)

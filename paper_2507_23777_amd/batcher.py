@@ -8,6 +8,13 @@ produced its token budget or an EOS token; the rows of the batch are then compac
 so that every step runs over live sequences only.  The library's batch rows name
 their cache slot, so compaction moves a few integers, never cache contents.
 
+The host does not wait for the device after every step: `sync_every` = n steps are
+enqueued back to back, each followed by a device-side copy of its outputs (accepted
+count, flags, tokens) into row j of a ring, and the ring comes back in one copy.  EOS
+and token budgets are therefore seen up to n - 1 steps late; what a finished
+sequence produced after its end is dropped (at most (n - 1)(K + 1) tokens, and that
+much cache room is asked for at submission).
+
 Everything here is argument marshalling: the arithmetic of a step runs in the
 library's kernels, row arrays are gathered with device-side indexing.
 """
@@ -36,9 +43,13 @@ class _Live:
 
 
 class Batcher:
-    def __init__(self, engine, vp, spec: bool = True):
-        self.eng, self.vp, self.spec = engine, vp, spec
+    def __init__(self, engine, vp, spec: bool = True, sync_every: int = 4):
+        if sync_every < 1:
+            raise ValueError("sync_every < 1")
+        self.eng, self.vp, self.spec, self.n = engine, vp, spec, sync_every
         self.R = engine.c_cfg.n_draft + 1 if spec else 1
+        self.ring = self.ring_host = None     # [n][rows][2 + R] int32: accepted, flags, tokens
+        self.syncs = 0
         self.pending: list = []
         self.requests: dict = {}
         self.free = list(range(engine.max_batch))
@@ -51,8 +62,9 @@ class Batcher:
         P = 0 if req.prefix is None else int(req.prefix.shape[0])
         if req.max_new_tokens < 1:
             raise ValueError("max_new_tokens < 1")
-        if P + req.max_new_tokens - 1 + self.R > self.eng.max_ctx:
-            raise ValueError("prefix + token budget + block does not fit max_ctx")
+        # a sequence may run on until its group of n steps ends: room for the blocks of all of them
+        if P + req.max_new_tokens - 1 + self.n * self.R > self.eng.max_ctx:
+            raise ValueError("prefix + token budget + the blocks of sync_every steps do not fit max_ctx")
         if len(req.first_block) < self.R:
             raise ValueError(f"first_block needs {self.R} tokens")
         rid = len(self.requests)
@@ -96,41 +108,53 @@ class Batcher:
                 nb.block[k:] = torch.tensor([list(self.requests[lv.rid].first_block[:self.R]) for lv in new],
                                             dtype=torch.int32)
             nb.slot.copy_(torch.tensor([lv.slot for lv in live], dtype=torch.int32))
+            self.ring = torch.zeros((self.n, len(live), 2 + self.R), dtype=torch.int32, device=self.eng.device)
+            self.ring_host = torch.zeros((self.n, len(live), 2 + self.R), dtype=torch.int32,
+                                         pin_memory=self.eng.device.type == "cuda")
         self.live, self.buf = live, nb
 
     def run(self) -> dict:
         """Runs until every submitted request has finished; returns {request id: tokens}."""
         torch = self.eng.torch
         done: dict = {}
+        step = self.eng.xsm_spec_step if self.spec else self.eng.xsm_plain_step
         while self.pending or self.live:
             new = self._admit()
             if new:
                 self._rebuild(list(range(len(self.live))), new)
+            # n steps without a host round trip; the lengths grow on the device, the host only
+            # knows a bound for them (every step adds at most R positions)
             bound = max(lv.length for lv in self.live)
-            if self.spec:
-                self.eng.xsm_spec_step(self.buf, self.vp, bound)
-            else:
-                self.eng.xsm_plain_step(self.buf, self.vp, bound)
-            self.steps += 1
-            n_acc = self.buf.n_accepted.cpu().numpy()          # (synchronises the stream)
-            out = self.buf.out_tokens.cpu().numpy()
-            flags = self.buf.flags.cpu().numpy()
+            for j in range(self.n):
+                step(self.buf, self.vp, min(bound + j * self.R, self.eng.max_ctx - self.R))
+                self.ring[j, :, 0] = self.buf.n_accepted
+                self.ring[j, :, 1] = self.buf.flags
+                self.ring[j, :, 2:] = self.buf.out_tokens
+            self.steps += self.n
+            self.ring_host.copy_(self.ring)                    # one copy back; synchronises the stream
+            if self.eng.device.type == "cuda":
+                torch.cuda.current_stream().synchronize()
+            self.syncs += 1
+            rec = self.ring_host.numpy()
             keep = []
             for i, lv in enumerate(self.live):
-                if flags[i] & 16:           # XSM_FLAG_DEVICE_TIMEOUT: nothing was produced; say why
-                    self.eng.xsm_check_device()
-                    raise RuntimeError(f"request {lv.rid}: the step timed out on the device")
-                if flags[i] & ~1 or n_acc[i] < 1:
-                    raise RuntimeError(f"request {lv.rid}: device flagged input error {int(flags[i])}")
                 req = self.requests[lv.rid]
-                a = int(n_acc[i])
-                self.accepted_per_step.append(a)
-                lv.length += a
                 finished = False
-                for t in out[i, :a]:
-                    lv.tokens.append(int(t))
-                    if int(t) == req.eos or len(lv.tokens) >= req.max_new_tokens:
-                        finished = True
+                for j in range(self.n):
+                    a, fl = int(rec[j, i, 0]), int(rec[j, i, 1])
+                    if fl & 16:             # XSM_FLAG_DEVICE_TIMEOUT: nothing was produced; say why
+                        self.eng.xsm_check_device()
+                        raise RuntimeError(f"request {lv.rid}: the step timed out on the device")
+                    if fl & ~1 or a < 1:
+                        raise RuntimeError(f"request {lv.rid}: device flagged input error {fl}")
+                    self.accepted_per_step.append(a)
+                    lv.length += a
+                    for t in rec[j, i, 2:2 + a]:
+                        lv.tokens.append(int(t))
+                        if int(t) == req.eos or len(lv.tokens) >= req.max_new_tokens:
+                            finished = True
+                            break
+                    if finished:            # the group's later steps of this sequence are dropped
                         break
                 if finished:
                     done[lv.rid] = lv.tokens

@@ -105,8 +105,12 @@ class _StubEngine:
     xsm_plain_step = xsm_spec_step
 
 
+@pytest.mark.parametrize("sync_every", [1, 4])
 @pytest.mark.parametrize("spec", [True, False])
-def test_batcher_admission_compaction_budget_and_eos(spec):
+def test_batcher_admission_compaction_budget_and_eos(spec, sync_every):
+    """Also with the host looking at the outputs only every fourth step: EOS and budgets are then
+    seen late, the tokens a finished sequence went on to produce are dropped, and every request's
+    stream is the same as with a look after every step."""
     import numpy as np
     import torch
     from paper_2507_23777_amd.batcher import Batcher, Request
@@ -128,7 +132,7 @@ def test_batcher_admission_compaction_budget_and_eos(spec):
             eos[i] = toks[11]
             toks = toks[:toks.index(eos[i]) + 1]
         expect[i] = toks
-    bt = Batcher(eng, None, spec=spec)
+    bt = Batcher(eng, None, spec=spec, sync_every=sync_every)
     for i in range(len(P)):
         rid = bt.submit(Request(first_block=[3 + i] + [0] * K, max_new_tokens=budget[i], eos=eos[i],
                                 prefix=None if P[i] == 0 else np.zeros((P[i], 8), np.float32)))
@@ -136,6 +140,7 @@ def test_batcher_admission_compaction_budget_and_eos(spec):
     got = bt.run()
     assert got == expect
     assert sorted(bt.free) == [0, 1, 2] and not bt.live and not bt.pending
+    assert bt.syncs * sync_every == bt.steps == len(eng.batch_sizes)
     assert max(eng.batch_sizes) == 3 and min(eng.batch_sizes) >= 1
     # every request was prefilled exactly once (empty prefixes need none), into a slot that was free
     assert sorted(s for slots, _ in eng.prefills for s in slots).count(0) >= 1

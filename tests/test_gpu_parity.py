@@ -331,7 +331,8 @@ def test_batcher_admission_and_compaction(X, dtype):
     budget = [30, 12, 45, 7, 25, 18, 33]
     prefixes = si.make_prefix(cfg, len(P), P=max(P))
     firsts = si.first_block(cfg, len(P))
-    bt = Batcher(eng, X.H.to_vp_gpu(X.xsm, GREEDY), spec=True)
+    # fp32: a look at the outputs after every step; bf16: every fourth step (late EOS / budget)
+    bt = Batcher(eng, X.H.to_vp_gpu(X.xsm, GREEDY), spec=True, sync_every=1 if dtype == "fp32" else 4)
     for i in range(len(P)):
         bt.submit(Request(first_block=list(map(int, firsts[i])), max_new_tokens=budget[i],
                           prefix=None if P[i] == 0 else prefixes[i, :P[i]]))
