@@ -196,6 +196,19 @@ __device__ __forceinline__ void watch_then_sync(const uint32_t* word, uint32_t t
   __syncthreads();
 }
 
+// The same for a consumer whose wavefronts each depend on a few producers of their own: lane i
+// polls the word at base + off (off < 0: none) and the wavefront goes on, without a barrier, once
+// every polled word carries the tag.  A stage with few consumer workgroups can afford the polls,
+// and a block read that finds a producer's words missing costs it a whole second round trip.
+__device__ __forceinline__ void wave_watch(const uint32_t* base, int off, uint32_t t8, bool& ok) {
+  bool pending = off >= 0 && ok;
+  for (int spin = 0; __builtin_amdgcn_ballot_w64(pending) != 0; ++spin) {
+    if (spin >= kSpinBudget) { ok = false; break; }
+    if (pending) pending = (ld32(base + off) & 0xFFu) != t8;
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
 // Cooperative, coalesced wait for rows [m0, m0 + RB) (clipped to nrows) of NB blocks of tagged
 // words (1024 words per row, row stride RS, block stride BS; buf = block 0, row 0): thread t
 // takes words 4t .. 4t+3 of every row, so a wavefront instruction covers 1 KB of consecutive
@@ -486,22 +499,27 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_
 // Attention's output rows as the O-projection's operand: the partial rows of the S_eff key slices
 // (blocks of 16 x 1024 words at word off_op + slice * blk of the layer buffer rs describes) are
 // merged while they are staged into LDS, O = sum_s f_s O_s / sum_s f_s l_s with f_s = 2^(m_s - max m).
-// The slices' (maximum, sum) pairs of all rows and heads ([16 rows][H][4 slices][2] words at off_ml,
-// 8 KB) go through LDS.  RB rows a round, all loads of a round in flight together.
+// The slices' (maximum, sum) pairs of all rows and heads are [16 rows][H][4 slices][2] words at
+// off_ml.  RB rows a round, all loads of a round in flight together.
 template <int H, int RB>
-__device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgpu_buffer_rsrc_t rs, const uint32_t* watch_word,
+__device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgpu_buffer_rsrc_t rs, const uint32_t* lb, int watch_off,
                                                int off_op, int blk, int off_ml, int M, int S_eff, int tid, uint32_t t8, bool& ok) {
   float* const mls = &sm.att_o[0][0][0][0];
-  watch_then_sync(watch_word, t8, ok, tid);
+  const int wave = tid >> 6, lane = tid & 63;
+  // wavefront w stages the columns of heads 4 w .. 4 w + 3 and waits for those heads' producers
+  wave_watch(lb, watch_off, t8, ok);
   for (int m0 = 0; m0 < M; m0 += RB) {
     const int rows = min(RB, M - m0);
     u32x4 q[4][RB], mlq[2];
-    // (maximum, sum) pieces tid and tid + 256: row = piece / (2 H), slices 2 (piece & 1) and the one after it
+    // (maximum, sum) pieces of the wavefront's own heads: lane = (row % 8, head, slice pair), rows
+    // 0..7 and 8..15; piece (row, head, pair) holds slices 2 pair and 2 pair + 1
     bool need_ml[2];
+    int mlp[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int p = tid + 256 * j;
-      need_ml[j] = m0 == 0 && (p / (2 * H)) < M && (p & 1) * 2 < S_eff;
+      const int row = (lane >> 3) + 8 * j;
+      mlp[j] = (row * H + 4 * wave + ((lane >> 1) & 3)) * 2 + (lane & 1);
+      need_ml[j] = m0 == 0 && row < M && (lane & 1) * 2 < S_eff;
     }
     bool got = false;
     if (ok) {
@@ -514,7 +532,7 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
               q[sl][m] = __builtin_amdgcn_raw_buffer_load_b128(rs, (off_op + sl * blk + (m0 + m) * 1024 + 4 * tid) * 4, 0, kCoherent);
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          if (need_ml[j]) mlq[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (off_ml + 4 * (tid + 256 * j)) * 4, 0, kCoherent);
+          if (need_ml[j]) mlq[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (off_ml + 4 * mlp[j]) * 4, 0, kCoherent);
         uint32_t bad = 0;
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl)
@@ -525,7 +543,7 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
         for (int j = 0; j < 2; ++j)
           if (need_ml[j]) {
             bad |= (mlq[j].x ^ t8) | (mlq[j].y ^ t8);
-            if ((tid & 1) * 2 + 1 < S_eff) bad |= (mlq[j].z ^ t8) | (mlq[j].w ^ t8);
+            if ((lane & 1) * 2 + 1 < S_eff) bad |= (mlq[j].z ^ t8) | (mlq[j].w ^ t8);
           }
         if ((bad & 0xFFu) == 0) { got = true; break; }
         __builtin_amdgcn_s_sleep(4);
@@ -533,9 +551,22 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
       if (!got) ok = false;
     }
     if (m0 == 0) {
+      // The merge weights w_s = f_s / sum_s f_s l_s are made once per (row, head), by the lanes
+      // that hold its (maximum, sum) pairs (the slice pairs of one (row, head) sit in neighbouring
+      // lanes), and go to the columns' threads through LDS: [row][head][4 slices]
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        if (need_ml[j] && got) *reinterpret_cast<f32x4*>(mls + 4 * (tid + 256 * j)) = dec24(mlq[j]);
+      for (int j = 0; j < 2; ++j) {
+        const f32x4 v = dec24(mlq[j]);
+        const bool va = need_ml[j] && got, vb = va && (lane & 1) * 2 + 1 < S_eff;
+        const float ma = va ? v[0] : -INFINITY, mb = vb ? v[2] : -INFINITY;
+        float Mg = fmaxf(ma, mb);
+        Mg = fmaxf(Mg, lane_xor<1>(Mg));
+        const float fa = va ? exp2f(ma - Mg) : 0.f, fb = vb ? exp2f(mb - Mg) : 0.f;
+        float Lg = (va ? v[1] * fa : 0.f) + (vb ? v[3] * fb : 0.f);
+        Lg += lane_xor<1>(Lg);
+        const float inv = Lg > 0.f ? 1.0f / Lg : 0.f;
+        if ((lane >> 3) + 8 * j < M) *reinterpret_cast<float2*>(mls + 2 * mlp[j]) = float2{fa * inv, fb * inv};
+      }
       __syncthreads();
     }
     const int hd = tid >> 4;                              // head of this thread's four columns
@@ -544,20 +575,10 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
       if (m < rows) {
         f32x4 x = f32x4{0.f, 0.f, 0.f, 0.f};
         if (got) {
-          const float* ml = mls + ((m0 + m) * H + hd) * 8;
-          float Mg = ml[0];
-#pragma unroll
-          for (int sl = 1; sl < 4; ++sl)
-            if (sl < S_eff) Mg = fmaxf(Mg, ml[2 * sl]);
-          float Lg = 0.f;
+          const f32x4 wgt = *reinterpret_cast<const f32x4*>(mls + ((m0 + m) * H + hd) * 4);
 #pragma unroll
           for (int sl = 0; sl < 4; ++sl)
-            if (sl < S_eff) {
-              const float f = exp2f(ml[2 * sl] - Mg);
-              Lg += ml[2 * sl + 1] * f;
-              x += dec24(q[sl][m]) * f;
-            }
-          x = Lg > 0.f ? x * (1.0f / Lg) : f32x4{0.f, 0.f, 0.f, 0.f};
+            if (sl < S_eff) x += dec24(q[sl][m]) * wgt[sl];
         }
         put4(As, kST, m0 + m, 4 * tid, x);
       }
@@ -1155,10 +1176,20 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (has_o) {
       const int nt = w - O_BASE;
       __syncthreads();
-      if (few) stage_attn_out<H, 5>(sm, As, lrs, lb + OFF_OP + (size_t)(S_eff - 1) * BLK + (size_t)(M - 1) * D + 513, OFF_OP, BLK,
-                                    OFF_ML, M, S_eff, tid, t8, ok);
-      else stage_attn_out<H, 4>(sm, As, lrs, lb + OFF_OP + (size_t)(S_eff - 1) * BLK + (size_t)(M - 1) * D + 513, OFF_OP, BLK,
-                                OFF_ML, M, S_eff, tid, t8, ok);
+      // lane (head of the wavefront's four, producer j): the word that producer's last wavefront
+      // stores last.  Up to 4 slices: unit (sequence, slice) of the head, its partial row R - 1,
+      // dim 63; merged slices: unit (sequence, slice) finished dims s dps .. of block 0
+      int watch_off = -1;
+      {
+        const int hh = 4 * wave + (lane & 3), j = lane >> 2, P = S > 4 ? S : S_eff;
+        if (j < a.n_seq * P) {
+          const int row = (j / P) * R + R - 1, sl = j % P;
+          watch_off = S > 4 ? OFF_OP + row * D + hh * 64 + sl * (64 / S) + 64 / S - 1
+                            : OFF_OP + sl * BLK + row * D + hh * 64 + 63;
+        }
+      }
+      if (few) stage_attn_out<H, 5>(sm, As, lrs, lb, watch_off, OFF_OP, BLK, OFF_ML, M, S_eff, tid, t8, ok);
+      else stage_attn_out<H, 4>(sm, As, lrs, lb, watch_off, OFF_OP, BLK, OFF_ML, M, S_eff, tid, t8, ok);
       XSM_STAMP(l * 16 + 14);
       const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
