@@ -87,6 +87,12 @@ __device__ __forceinline__ uint4 ldg16(gptr16 p, int piece) { return __builtin_b
 // access that is coherent across the device (sc1)
 constexpr int kRawBufferFlags = 0x00020000, kCoherent = 16;
 
+// 2^x on the hardware's exponential instruction alone (1 ulp; results below the normal range come
+// out as zero, which is what a softmax weight that small is worth).  The library routine wraps the
+// same instruction in a range fix-up of five more, and at one wavefront per SIMD an instruction
+// costs about eight cycles: attention takes seventeen exponentials per 64-key chunk and lane.
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+
 constexpr int kQS = 72;                     // LDS row stride (bf16) of the attention q / new-k / new-v tiles
 
 // ---- 8-byte tagged words {32-bit payload, full epoch}: the tail's per-tile logits statistics ----
@@ -561,7 +567,7 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
         const float ma = va ? v[0] : -INFINITY, mb = vb ? v[2] : -INFINITY;
         float Mg = fmaxf(ma, mb);
         Mg = fmaxf(Mg, lane_xor<1>(Mg));
-        const float fa = va ? exp2f(ma - Mg) : 0.f, fb = vb ? exp2f(mb - Mg) : 0.f;
+        const float fa = va ? exp2_hw(ma - Mg) : 0.f, fb = vb ? exp2_hw(mb - Mg) : 0.f;
         float Lg = (va ? v[1] * fa : 0.f) + (vb ? v[3] * fb : 0.f);
         Lg += lane_xor<1>(Lg);
         const float inv = Lg > 0.f ? 1.0f / Lg : 0.f;
@@ -951,13 +957,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         cmax = fmaxf(cmax, lane_xor<32>(cmax));
         const float m_new = fmaxf(m_run, cmax);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_use);
+        const float alpha = exp2_hw(m_run - m_use);
         float psum = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float p = exp2f(sc[t][i] - m_use);
+            const float p = exp2_hw(sc[t][i] - m_use);
             sc[t][i] = p;
             psum += p;
           }
@@ -1021,11 +1027,11 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         cmax = fmaxf(cmax, lane_xor<32>(cmax));
         const float m_new = fmaxf(m_run, cmax);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_use);
+        const float alpha = exp2_hw(m_run - m_use);
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float p = exp2f(sc[i] - m_use);
+          const float p = exp2_hw(sc[i] - m_use);
           sc[i] = p;
           psum += p;
         }
@@ -1070,7 +1076,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float mw = sm.att_ml[q][0][r];
-        const float f = mw == -INFINITY ? 0.f : exp2f(mw - Mx);
+        const float f = mw == -INFINITY ? 0.f : exp2_hw(mw - Mx);
         Lx += sm.att_ml[q][1][r] * f;
         acc += *reinterpret_cast<const f32x4*>(&sm.att_o[q][wave][lane][0]) * f;
       }
@@ -1079,7 +1085,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       // rows of a skipped sequence are zeros with sum 1).
       const bool none = Mx == -INFINITY;
       const float Mref = n < 0 ? 0.f : none ? kEmptySliceMax : ceilf(Mx);
-      const float resc = none ? 0.f : exp2f(Mx - Mref);
+      const float resc = none ? 0.f : exp2_hw(Mx - Mref);
       const float Lout = n < 0 ? 1.f : Lx * resc;
       acc = n < 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc * resc;
       if (S <= 4) {
@@ -1150,7 +1156,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           for (int k = 0; k < S; ++k) Mg = fmaxf(Mg, cb[k * P + rq]);
           float Lg = 0.f, og = 0.f;
           for (int k = 0; k < S; ++k) {
-            const float f = exp2f(cb[k * P + rq] - Mg);
+            const float f = exp2_hw(cb[k * P + rq] - Mg);
             Lg += cb[k * P + 16 + rq] * f;
             og += cb[k * P + 32 + qd * 16 + rq] * f;
           }
@@ -1202,7 +1208,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (has_u) {
       const f32x4 g4 = gains4(lt.g2, tid);
       __syncthreads();
-      stage_rows<1, 2, 8>(sm, As, 0, lb + OFF_XM, 0, D, M, g4, a.eps, tid, t8, ok, tl ? tl + l * 16 + 13 : nullptr);
+      // (rows a round as a template argument: with 5 rows, a round sized for 8 spends a third of
+      // its staging arithmetic on rows that do not exist)
+      if (few) stage_rows<1, 2, 5>(sm, As, 0, lb + OFF_XM, 0, D, M, g4, a.eps, tid, t8, ok, tl ? tl + l * 16 + 13 : nullptr);
+      else stage_rows<1, 2, 8>(sm, As, 0, lb + OFF_XM, 0, D, M, g4, a.eps, tid, t8, ok, tl ? tl + l * 16 + 13 : nullptr);
       XSM_STAMP(l * 16 + 7);
       const f32x4 acc = mac_tiles<KD>(wu, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale(sm, om, a.eps);
@@ -1213,7 +1222,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     // ================= DOWN =================
     {
       __syncthreads();
-      stage_rows<1, 0, 8>(sm, As, 0, lb + OFF_U + d_ks * FS, 0, F, M, f32x4{1.f, 1.f, 1.f, 1.f}, a.eps, tid, t8, ok);
+      if (few) stage_rows<1, 0, 5>(sm, As, 0, lb + OFF_U + d_ks * FS, 0, F, M, f32x4{1.f, 1.f, 1.f, 1.f}, a.eps, tid, t8, ok);
+      else stage_rows<1, 0, 8>(sm, As, 0, lb + OFF_U + d_ks * FS, 0, F, M, f32x4{1.f, 1.f, 1.f, 1.f}, a.eps, tid, t8, ok);
       XSM_STAMP(l * 16 + 12);
       const f32x4 acc = mac_tiles<KFS>(wd, As, STD, r, wave * KFS, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
