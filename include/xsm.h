@@ -212,10 +212,9 @@ XSM_API int xsm_spec_step_static(xsm_ctx* ctx, const xsm_batch* batch, const xsm
                                  xsm_stream stream);
 
 /* Options.  XSM_OPT_SINGLE_LAUNCH (default 1): when a step has at most 16 block rows in total,
- * the model shape is supported and the device has 256 compute units, run backbone, heads and unembedding as one persistent kernel
- * instead of one kernel per stage (greedy verification with argmax draws also finishes inside it;
- * the other criteria and sampling rules follow in the verify / emit kernels); 0 forces the
- * per-stage kernels.  XSM_OPT_ATTN_SPLITS (tuning aid, default 0 = automatic): key-range slices per
+ * the model shape is supported and the device has 256 compute units, run the whole step (backbone,
+ * heads, unembedding, verification under any criterion, draws under any sampling rule, emit) as
+ * one persistent kernel instead of one kernel per stage; 0 forces the per-stage kernels.  XSM_OPT_ATTN_SPLITS (tuning aid, default 0 = automatic): key-range slices per
  * (sequence, head) of the attention kernel / stage (the single-launch step takes the largest power
  * of two not above it).  XSM_OPT_PREFILL_ROWS (tuning aid, default 0 = as many as the workspace
  * holds, 8192): upper limit of the rows (sequences x positions) one prefill pass takes. */

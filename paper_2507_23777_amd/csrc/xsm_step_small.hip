@@ -1,6 +1,6 @@
 // One speculative (or plain) decoding step as ONE persistent kernel, for the
 // latency regime: at most 16 block rows in total (batch x (K+1) <= 16), bf16,
-// d_model 1024 / FFN 4096 / head_dim 64 models, greedy verification.
+// d_model 1024 / FFN 4096 / head_dim 64 models, every acceptance criterion and sampling rule.
 //
 // At batch 1 a step streams every weight once (hundreds of MB) through ~120 dependent
 // stages of a few MB each, so what bounds it is not bandwidth inside a stage but the
@@ -56,6 +56,10 @@
 // shared unembedding over backbone and head rows with a per-tile top-2 reduction, and one
 // workgroup per sequence that does the accept scan, picks the tokens at the first rejected
 // position and rolls the cache length back (Alg. 1 inner loop, resample line, s <- s*).
+// Greedy verification with argmax draws needs nothing but the per-tile statistics; the other
+// criteria and sampling rules (Sec. 5.4 "Verification criterion"; appendix "Sampling strategies")
+// read whole logits rows: each accept check, and each draw for every accepted length the scan
+// could end at, runs as a task on a workgroup of its own and posts its result as a tagged word.
 #include "xsm_device.h"
 #include "xsm_internal.h"
 #include "xsm_verify_device.h"
