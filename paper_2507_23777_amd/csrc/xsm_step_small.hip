@@ -377,6 +377,7 @@ struct Shared {
   float att_ml[4][2][16];
   float att_o[4][4][64][4];     // attention: the wavefronts' partial outputs; O-projection: the slices' (m, l)
   int len[16], slot[16];
+  int blk[16];                  // the step's input block rows (tokens), read once at set-up
   uint32_t flag[16];
   uint32_t tag;
   int fail;
@@ -641,6 +642,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       len = f ? -1 : n;
     }
     sm.len[tid] = len; sm.slot[tid] = sl; sm.flag[tid] = f;
+    sm.blk[tid] = tid < M ? a.block[tid] : 0;
   }
   __syncthreads();
   // A bounded wait gave up, in this step or an earlier one: sequence b produced nothing.  The
@@ -745,7 +747,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   // ---- EMBED: layer-0 residual rows as tagged words (partial block 3; the others are zero) ----
   for (int idx = w * 256 + tid; idx < M * D; idx += 256 * 256) {
     const int m = idx / D, c = idx % D, b = m / R;
-    const float x = sm.len[b] >= 0 ? bf2f(a.E[(size_t)a.block[m] * D + c]) : 0.f;
+    const float x = sm.len[b] >= 0 ? bf2f(a.E[(size_t)sm.blk[m] * D + c]) : 0.f;
 #pragma unroll
     for (int p = 0; p < 4; ++p) st32(llb + OFF_XP + p * BLK + (size_t)m * D + c, p == 3 ? x : 0.f, t8);
   }
@@ -1254,7 +1256,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   // =========================== tail ===========================
   uint32_t* const tb = llb + (size_t)a.L * LS;             // the last layer's output partials live at the start of this block
   constexpr int OFF_RB = 4 * BLK;                          // head outputs: [16*K rows][D] words
-  constexpr int OFF_ST = OFF_RB + 16 * 15 * D;             // per (tile, row) top-2 statistics: 4 8-byte words
+  constexpr int OFF_ST = OFF_RB + 16 * 15 * D;             // per (row, tile) top-2 statistics: 4 8-byte words, a row's tiles side by side
+  constexpr int kStatTiles = 4096;                         // tiles per row the region is laid out for
   uint64_t* const stb = reinterpret_cast<uint64_t*>(tb + OFF_ST);
   const int NTV = V / 16;                                  // vocabulary tiles
   const int rows_all = M + M * K;                          // backbone rows, then head rows (m, k)
@@ -1337,7 +1340,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           if (z > bv) { sv = bv; bv = z; bi = t * 16 + nr; }
           else sv = fmaxf(sv, z);
         }
-        uint64_t* st = stb + ((size_t)t * kSmallMaxRows + q) * 4;
+        uint64_t* st = stb + ((size_t)q * kStatTiles + t) * 4;
         ll_st(st, __float_as_uint(bv), tag);
         ll_st(st + 1, (uint32_t)bi, tag);
         ll_st(st + 2, __float_as_uint(sv), tag);
@@ -1356,6 +1359,80 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   // ones its accepted length selects ----
   uint64_t* const res = stb + 3;                           // result word i: the spare fourth word of statistics group i
   const int slots_seq = K + R * R;                         // per sequence: K checks, then (accepted length, draw)
+  uint64_t* const top2_res = res + (size_t)3072 * 4;       // greedy: three words per logits row, behind the tree levels
+  // Global top-2 of nr logits rows (row i = grow_of(i)) from their per-tile statistics -> slots
+  // slot0 + i of sm.st_*.  All rows at once: thread t takes tiles t, t + 256, ... of every row
+  // (two 16-byte loads per row and tile, up to eight rows' loads in flight together), the lanes
+  // of a wavefront are folded, and thread i combines the four wavefronts' results of row i in
+  // wavefront order.  Called by the whole workgroup.
+  __shared__ float t2v[4][16], t2s[4][16];
+  __shared__ int t2i[4][16];
+  const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(stb, 0, kSmallMaxRows * kStatTiles * 32, kRawBufferFlags);
+  auto top2_rows = [&](int nr, auto&& grow_of, int slot0) {
+    for (int i0 = 0; i0 < nr; i0 += 8) {
+      float bv[8], sv[8];
+      int bi[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { bv[i] = -INFINITY; sv[i] = -INFINITY; bi[i] = 0x7FFFFFFF; }
+      for (int t = tid; t < NTV; t += 256) {
+        u32x4 qa[8], qb[8];
+        bool got = false;
+        for (int spin = 0; ok && spin < kSpinBudget; ++spin) {
+          uint32_t bad = 0;
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (i0 + i < nr) {
+              const int off = (grow_of(i0 + i) * kStatTiles + t) * 32;
+              qa[i] = __builtin_amdgcn_raw_buffer_load_b128(srs, off, 0, kCoherent);
+              qb[i] = __builtin_amdgcn_raw_buffer_load_b128(srs, off + 16, 0, kCoherent);
+            }
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (i0 + i < nr) bad |= (qa[i].y ^ tag) | (qa[i].w ^ tag) | (qb[i].y ^ tag);
+          if (bad == 0) { got = true; break; }
+          __builtin_amdgcn_s_sleep(4);
+        }
+        if (!got) { ok = false; break; }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (i0 + i < nr) {
+            const float tv = __uint_as_float(qa[i].x), ts = __uint_as_float(qb[i].x);
+            const int ti = (int)qa[i].z;
+            if (tv > bv[i] || (tv == bv[i] && ti < bi[i])) { sv[i] = fmaxf(bv[i], fmaxf(sv[i], ts)); bv[i] = tv; bi[i] = ti; }
+            else sv[i] = fmaxf(sv[i], fmaxf(tv, ts));
+          }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (i0 + i >= nr) break;                            // (uniform)
+#define XSM_FOLD(O)                                                                \
+        {                                                                        \
+          const float bv2 = lane_xor<O>(bv[i]), sv2 = lane_xor<O>(sv[i]);        \
+          const int bi2 = lane_xor<O>(bi[i]);                                    \
+          const bool take = (bv2 > bv[i]) || (bv2 == bv[i] && bi2 < bi[i]);      \
+          sv[i] = fmaxf(fmaxf(sv[i], sv2), fminf(bv[i], bv2));                   \
+          if (take) { bv[i] = bv2; bi[i] = bi2; }                                \
+        }
+        XSM_FOLD(32) XSM_FOLD(16) XSM_FOLD(8) XSM_FOLD(4) XSM_FOLD(2) XSM_FOLD(1)
+#undef XSM_FOLD
+        if (lane == 0) { t2v[wave][i] = bv[i]; t2s[wave][i] = sv[i]; t2i[wave][i] = bi[i]; }
+      }
+      __syncthreads();
+      if (tid < 8 && i0 + tid < nr) {
+        float cv = t2v[0][tid], cs = t2s[0][tid];
+        int ci = t2i[0][tid];
+        for (int q = 1; q < 4; ++q) {
+          const float v2 = t2v[q][tid], s2 = t2s[q][tid];
+          const int i2 = t2i[q][tid];
+          const bool take = (v2 > cv) || (v2 == cv && i2 < ci);
+          cs = fmaxf(fmaxf(cs, s2), fminf(cv, v2));
+          if (take) { cv = v2; ci = i2; }
+        }
+        sm.st_max[slot0 + i0 + tid] = cv; sm.st_sec[slot0 + i0 + tid] = cs; sm.st_idx[slot0 + i0 + tid] = ci;
+      }
+      __syncthreads();
+    }
+  };
   if (a.full_verify) {
     const xsm_verify_params& vp = a.vp;
     const float invT = 1.0f / vp.temperature;
@@ -1379,7 +1456,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       for (int spin = 0; live; ++spin) {
         bool good = true;
         for (int i = tid; i < nr * NTV; i += 256)
-          good &= (uint32_t)(ll_ld(stb + ((size_t)(i % NTV) * kSmallMaxRows + g0 + i / NTV) * 4) >> 32) == tag;
+          good &= (uint32_t)(ll_ld(stb + ((size_t)(g0 + i / NTV) * kStatTiles + i % NTV) * 4) >> 32) == tag;
         if (__syncthreads_and(good)) break;
         if (spin >= kSpinBudget) { ok = false; live = false; }
         __builtin_amdgcn_s_sleep(4);
@@ -1417,7 +1494,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         const int grow = b * R + i;
         if (!rows_complete(grow, 1)) break;
         const float* z = a.logits_dbg + (size_t)grow * V;
-        const int x = a.block[b * R + i + 1];
+        const int x = sm.blk[b * R + i + 1];
         bool good, nb;
         if (vp.mode == XSM_VERIFY_THRESHOLD) {
           const float p = row_prob(z, V, x, invT, rs);
@@ -1455,46 +1532,22 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       }
       __syncthreads();
     }
+  } else {
+    // greedy with argmax draws: one task per logits row folds the row's per-tile statistics and
+    // posts (maximum, its token, runner-up); all rows side by side instead of three rounds of
+    // rows in the finishing workgroup
+    for (int task = 255 - w; task < rows_all; task += 256) {
+      top2_rows(1, [&](int) { return task; }, 0);
+      if (tid < 3 && ok) {
+        const uint32_t pay = tid == 0 ? __float_as_uint(sm.st_max[0]) : tid == 1 ? (uint32_t)sm.st_idx[0] : __float_as_uint(sm.st_sec[0]);
+        ll_st(top2_res + (size_t)(task * 3 + tid) * 4, pay, tag);
+      }
+      __syncthreads();
+    }
   }
   if (w < a.n_seq) {
     const int b = w;
     const int n = sm.len[b];
-    // global top-2 of a logits row from the per-tile statistics (one wavefront per row, four tiles
-    // per lane and request, all twelve words of a request in flight together) -> slot q of sm.st_*
-    auto row_top2 = [&](int q, int grow) {
-      float bv = -INFINITY, sv = -INFINITY;
-      int bi = 0x7FFFFFFF;
-      for (int t0 = 0; t0 < NTV; t0 += 256) {
-        int off[12];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int t = t0 + lane + 64 * i;
-#pragma unroll
-          for (int j = 0; j < 3; ++j) off[3 * i + j] = t < NTV ? (t * kSmallMaxRows + grow) * 4 + j : -1;
-        }
-        uint32_t pw[12];
-        ll_wait_list<12>(stb, off, tag, pw, ok);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if (off[3 * i] < 0) continue;
-          const float tv = __uint_as_float(pw[3 * i]), ts = __uint_as_float(pw[3 * i + 2]);
-          const int ti = (int)pw[3 * i + 1];
-          if (tv > bv || (tv == bv && ti < bi)) { sv = fmaxf(bv, fmaxf(sv, ts)); bv = tv; bi = ti; }
-          else sv = fmaxf(sv, fmaxf(tv, ts));
-        }
-      }
-#define XSM_FOLD(O)                                                          \
-      {                                                                        \
-        const float bv2 = lane_xor<O>(bv), sv2 = lane_xor<O>(sv);              \
-        const int bi2 = lane_xor<O>(bi);                                       \
-        const bool take = (bv2 > bv) || (bv2 == bv && bi2 < bi);               \
-        sv = fmaxf(fmaxf(sv, sv2), fminf(bv, bv2));                            \
-        if (take) { bv = bv2; bi = bi2; }                                      \
-      }
-      XSM_FOLD(32) XSM_FOLD(16) XSM_FOLD(8) XSM_FOLD(4) XSM_FOLD(2) XSM_FOLD(1)
-#undef XSM_FOLD
-      if (lane == 0) { sm.st_max[q] = bv; sm.st_sec[q] = sv; sm.st_idx[q] = bi; }
-    };
     if (a.full_verify) {
       __shared__ int cand[17];                            // [0] the backbone's token, [k] head k's
       __shared__ uint32_t chk_s[16], near_s[17];
@@ -1519,8 +1572,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           }
         // draw d of the accepted length: 0 = the backbone's token from row acc_n, k = head k's
         if (vp.sample == 0) {
-          for (int d = wave; d <= K; d += 4) row_top2(d, d == 0 ? b * R + acc_n : M + (b * R + acc_n) * K + d - 1);
-          __syncthreads();
+          top2_rows(K + 1, [&](int d) { return d == 0 ? b * R + acc_n : M + (b * R + acc_n) * K + d - 1; }, 0);
           if (tid <= K) { cand[tid] = sm.st_idx[tid]; near_s[tid] = sm.st_max[tid] - sm.st_sec[tid] <= kTieMargin ? 1u : 0u; }
         } else if (tid <= K) {
           const int off[1] = {base + (K + acc_n * R + tid) * 4};
@@ -1541,7 +1593,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           for (int d = 0; d <= K; ++d)
             if (near_s[d]) fl |= XSM_FLAG_NEAR_TIE;
           int oldb[16];
-          for (int j = 0; j < R; ++j) oldb[j] = a.block[b * R + j];
+          for (int j = 0; j < R; ++j) oldb[j] = sm.blk[b * R + j];
           const int y0 = cand[0];
           for (int j = 0; j < acc_n; ++j) a.out_tokens[b * R + j] = oldb[j + 1];
           a.out_tokens[b * R + acc_n] = y0;
@@ -1555,17 +1607,17 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         }
       }
     } else {
-    // the R backbone rows first; they fix the accepted length, and only the K head rows of that
-    // position are needed after it (slots R .. R + K - 1)
-    for (int q = wave; q < R; q += 4) row_top2(q, b * R + q);
-    __syncthreads();
-    int acc_all = 0;                                      // (every thread: same values, same result)
-    if (n >= 0)
-      for (int j = 1; j <= K; ++j) {
-        if (a.block[b * R + j] != sm.st_idx[j - 1]) break;
-        ++acc_all;
-      }
-    for (int k = wave; k < K; k += 4) row_top2(R + k, M + (b * R + acc_all) * K + k);
+    // the folded rows of this sequence: slots 0 .. R - 1 the backbone rows, slot R + j K + k head
+    // k's row at accepted length j
+    for (int i = tid; i < (R + R * K) * 3; i += 256) {
+      const int q = i / 3, grow = q < R ? b * R + q : M + b * R * K + (q - R);
+      const int off[1] = {(grow * 3 + i % 3) * 4};
+      uint32_t pw[1];
+      ll_wait_list<1>(top2_res, off, tag, pw, ok);
+      if (i % 3 == 0) sm.st_max[q] = __uint_as_float(pw[0]);
+      else if (i % 3 == 1) sm.st_idx[q] = (int)pw[0];
+      else sm.st_sec[q] = __uint_as_float(pw[0]);
+    }
     const bool late = __syncthreads_or(!ok);              // some statistics never arrived: nothing to emit
     if (tid == 0) {
       uint32_t fl = sm.flag[b];
@@ -1577,21 +1629,21 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       } else {
         int acc_n = 0;
         for (int j = 1; j <= K; ++j) {                    // accept while the candidate is the argmax
-          const bool hit = a.block[b * R + j] == sm.st_idx[j - 1];
+          const bool hit = sm.blk[b * R + j] == sm.st_idx[j - 1];
           if (sm.st_max[j - 1] - sm.st_sec[j - 1] <= kTieMarginS) fl |= XSM_FLAG_NEAR_TIE;
           if (!hit) break;
           ++acc_n;
         }
         if (sm.st_max[acc_n] - sm.st_sec[acc_n] <= kTieMarginS) fl |= XSM_FLAG_NEAR_TIE;
         int oldb[16];
-        for (int j = 0; j < R; ++j) oldb[j] = a.block[b * R + j];
+        for (int j = 0; j < R; ++j) oldb[j] = sm.blk[b * R + j];
         const int y0 = sm.st_idx[acc_n];
         for (int j = 0; j < acc_n; ++j) a.out_tokens[b * R + j] = oldb[j + 1];
         a.out_tokens[b * R + acc_n] = y0;
         for (int j = acc_n + 1; j < R; ++j) a.out_tokens[b * R + j] = -1;
         a.block[b * R] = y0;
         for (int k = 0; k < K; ++k) {
-          const int q = R + k;
+          const int q = R + acc_n * K + k;
           a.block[b * R + 1 + k] = sm.st_idx[q];
           if (sm.st_max[q] - sm.st_sec[q] <= kTieMarginS) fl |= XSM_FLAG_NEAR_TIE;
         }
