@@ -29,19 +29,9 @@ __global__ __launch_bounds__(256) void k_verify(const float* Z0, const float* Hf
   for (int j = 1; j < R; ++j) {
     const float* z = Z0 + (size_t)(b * R + j - 1) * V;
     const int x = block[b * R + j];
-    bool ok;
-    if (vp.mode == XSM_VERIFY_THRESHOLD) {
-      const float p = row_prob(z, V, x, 1.0f / vp.temperature, sm);
-      ok = p > vp.delta;
-      // p crosses delta when the candidate's logit moves by about T |ln(p / delta)|
-      if (p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin)
-        flag |= XSM_FLAG_NEAR_TIE;
-    } else {
-      const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
-      const int rank = row_rank(z, V, x, sm);
-      ok = rank < ka;
-      if (rank_near_boundary(z, V, x, rank, ka, sm)) flag |= XSM_FLAG_NEAR_TIE;
-    }
+    bool near;
+    const bool ok = row_accepts(z, V, x, vp, sm, &near);
+    if (near) flag |= XSM_FLAG_NEAR_TIE;
     if (!ok) break;
     ++a;
   }

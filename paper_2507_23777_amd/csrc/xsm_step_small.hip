@@ -1495,18 +1495,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         if (!rows_complete(grow, 1)) break;
         const float* z = a.logits_dbg + (size_t)grow * V;
         const int x = sm.blk[b * R + i + 1];
-        bool good, nb;
-        if (vp.mode == XSM_VERIFY_THRESHOLD) {
-          const float p = row_prob(z, V, x, invT, rs);
-          good = p > vp.delta;
-          // p crosses delta when the candidate's logit moves by about T |ln(p / delta)|
-          nb = p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin;
-        } else {
-          const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
-          const int rank = row_rank(z, V, x, rs);
-          good = rank < ka;
-          nb = rank_near_boundary(z, V, x, rank, ka, rs);
-        }
+        bool nb;
+        const bool good = row_accepts(z, V, x, vp, rs, &nb);
         if (tid == 0) ll_st(out + (size_t)i * 4, (good ? 1u : 0u) | (nb ? 2u : 0u), tag);
       } else {
         const int m = (i - K) / per_m, d = (i - K) % per_m;  // accepted length; 0 = the backbone's draw
@@ -1517,7 +1507,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
           if (!rows_complete(grow, 1)) break;
           const float* z = d == 0 ? a.logits_dbg + (size_t)grow * V : a.head_all_dbg + (size_t)(grow - M) * V;
           bool nb;
-          const int t = row_categorical(z, V, invT, philox_uniform(vp.seed, pos0 + (uint32_t)d, (uint32_t)d, sq), rs, &nb);
+          const int t = row_draw(z, V, invT, philox_uniform(vp.seed, pos0 + (uint32_t)d, (uint32_t)d, sq), rs, &nb);
           if (tid == 0) ll_st(om_ + (size_t)d * 4, (uint32_t)t | (nb ? 0x80000000u : 0u), tag);
         } else {                                           // level d - 1 of the tree: head d's ks most probable tokens
           const int grow = M + (b * R + m) * K + d - 1;

@@ -161,6 +161,161 @@ __device__ inline int row_categorical(const float* z, int V, float invT, float u
   return block_max_i(lastpos, sm.redi);
 }
 
+// ---- the same decisions for rows of 1024 C4 logits (C4 = 1, 2, 4, 8) with the row held in
+// registers: thread t owns the 4 C4 consecutive tokens from t * 4 C4 on, memory is read once, the
+// running sum over threads is a wavefront scan plus the wavefronts' totals in order, and the three
+// reductions of a draw share one exchange.  exp(y) is the hardware's 2^(y log2 e) (1 ulp). ----
+constexpr float kLog2e = 1.44269504088896340736f;
+
+template <int C4>
+__device__ __forceinline__ void row_to_regs(const float* z, float (&x)[4 * C4]) {
+  const float4* p = reinterpret_cast<const float4*>(z) + (size_t)threadIdx.x * C4;
+#pragma unroll
+  for (int i = 0; i < C4; ++i) {
+    const float4 v = p[i];
+    x[4 * i] = v.x; x[4 * i + 1] = v.y; x[4 * i + 2] = v.z; x[4 * i + 3] = v.w;
+  }
+}
+
+template <int C4>
+__device__ inline int row_categorical_regs(const float* z, float invT, float u, RowScratch& sm, bool* near_edge) {
+  constexpr int C = 4 * C4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, v0 = threadIdx.x * C;
+  float x[C];
+  row_to_regs<C4>(z, x);
+  float mx = x[0];
+#pragma unroll
+  for (int i = 1; i < C; ++i) mx = fmaxf(mx, x[i]);
+  mx = block_max(mx, sm.redf);
+  const float c = invT * kLog2e;
+  float loc = 0.f;
+#pragma unroll
+  for (int i = 0; i < C; ++i) { x[i] = __builtin_amdgcn_exp2f((x[i] - mx) * c); loc += x[i]; }   // x: now the weights
+  float incl = loc;                                   // inclusive sum over the lanes, lane order
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float t = __shfl_up(incl, o, WAVE);
+    if (lane >= o) incl += t;
+  }
+  float run = __shfl_up(incl, 1, WAVE);
+  if (lane == 0) run = 0.f;
+  __syncthreads();
+  if (lane == 63) sm.redf[4 + wave] = incl;
+  __syncthreads();
+  float off = 0.f, total = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (q == wave) off = total;
+    total += sm.redf[4 + q];
+  }
+  run += off;
+  const float target = u * total, band = kCdfMargin * total;
+  int hit = 0x7FFFFFFF, lastpos = -1, close = fabsf(run - target) <= band ? 1 : 0;
+#pragma unroll
+  for (int i = 0; i < C; ++i) {
+    run += x[i];
+    if (x[i] > 0.f) lastpos = v0 + i;
+    if (hit == 0x7FFFFFFF && run > target) hit = v0 + i;
+    close |= fabsf(run - target) <= band ? 1 : 0;
+  }
+  hit = wave_min_i(hit); lastpos = wave_max_i(lastpos); close = wave_max_i(close);
+  __syncthreads();
+  if (lane == 0) { sm.redi[wave] = hit; sm.redi[4 + wave] = lastpos; sm.besti[wave] = close; }
+  __syncthreads();
+  hit = min(min(sm.redi[0], sm.redi[1]), min(sm.redi[2], sm.redi[3]));
+  lastpos = max(max(sm.redi[4], sm.redi[5]), max(sm.redi[6], sm.redi[7]));
+  *near_edge = (sm.besti[0] | sm.besti[1] | sm.besti[2] | sm.besti[3]) != 0;
+  return hit != 0x7FFFFFFF ? hit : lastpos;            // rounding left nothing above the target: the last token with weight
+}
+
+template <int C4>
+__device__ inline float row_prob_regs(const float* z, int xtok, float invT, RowScratch& sm) {
+  constexpr int C = 4 * C4;
+  float x[C];
+  row_to_regs<C4>(z, x);
+  const float zx = z[xtok];
+  float mx = x[0];
+#pragma unroll
+  for (int i = 1; i < C; ++i) mx = fmaxf(mx, x[i]);
+  mx = block_max(mx, sm.redf);
+  const float c = invT * kLog2e;
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < C; ++i) s += __builtin_amdgcn_exp2f((x[i] - mx) * c);
+  s = block_sum(s, sm.redf);
+  return __builtin_amdgcn_exp2f((zx - mx) * c) / s;
+}
+
+// rank of candidate xtok and whether a logit change within the margin could move it across ka
+template <int C4>
+__device__ inline int row_rank_regs(const float* z, int xtok, int ka, RowScratch& sm, bool* near_boundary) {
+  constexpr int C = 4 * C4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, v0 = threadIdx.x * C;
+  float x[C];
+  row_to_regs<C4>(z, x);
+  const float zx = z[xtok];
+  int cnt = 0, above = 0, below = 0;
+#pragma unroll
+  for (int i = 0; i < C; ++i) {
+    const int v = v0 + i;
+    const float dlt = x[i] - zx;
+    cnt += (dlt > 0.f || (dlt == 0.f && v < xtok)) ? 1 : 0;
+    if (v != xtok && dlt >= 0.f && dlt <= kTieMargin) ++above;
+    if (v != xtok && dlt < 0.f && -dlt <= kTieMargin) ++below;
+  }
+  cnt = wave_sum_i(cnt); above = wave_sum_i(above); below = wave_sum_i(below);
+  __syncthreads();
+  if (lane == 0) { sm.redi[wave] = cnt; sm.redi[4 + wave] = above; sm.besti[wave] = below; }
+  __syncthreads();
+  cnt = sm.redi[0] + sm.redi[1] + sm.redi[2] + sm.redi[3];
+  above = sm.redi[4] + sm.redi[5] + sm.redi[6] + sm.redi[7];
+  below = sm.besti[0] + sm.besti[1] + sm.besti[2] + sm.besti[3];
+  *near_boundary = cnt < ka ? cnt + below >= ka : cnt - above < ka;
+  return cnt;
+}
+
+// dispatch on the row length: the register versions for V = 1024, 2048, 4096, 8192
+__device__ inline int row_draw(const float* z, int V, float invT, float u, RowScratch& sm, bool* near_edge) {
+  switch (V) {
+    case 1024: return row_categorical_regs<1>(z, invT, u, sm, near_edge);
+    case 2048: return row_categorical_regs<2>(z, invT, u, sm, near_edge);
+    case 4096: return row_categorical_regs<4>(z, invT, u, sm, near_edge);
+    case 8192: return row_categorical_regs<8>(z, invT, u, sm, near_edge);
+    default: return row_categorical(z, V, invT, u, sm, near_edge);
+  }
+}
+
+// One accept decision (Sec. 5.4 "Verification criterion"): is candidate xtok accepted against the
+// logits row z under the criterion of vp, and is the decision a near-tie
+__device__ inline bool row_accepts(const float* z, int V, int xtok, const xsm_verify_params& vp, RowScratch& sm, bool* near) {
+  if (vp.mode == XSM_VERIFY_THRESHOLD) {
+    const float invT = 1.0f / vp.temperature;
+    float p;
+    switch (V) {
+      case 1024: p = row_prob_regs<1>(z, xtok, invT, sm); break;
+      case 2048: p = row_prob_regs<2>(z, xtok, invT, sm); break;
+      case 4096: p = row_prob_regs<4>(z, xtok, invT, sm); break;
+      case 8192: p = row_prob_regs<8>(z, xtok, invT, sm); break;
+      default: p = row_prob(z, V, xtok, invT, sm);
+    }
+    // p crosses delta when the candidate's logit moves by about T |ln(p / delta)|
+    *near = p > 0.f && vp.delta > 0.f && vp.temperature * fabsf(logf(p) - logf(vp.delta)) <= kTieMargin;
+    return p > vp.delta;
+  }
+  const int ka = vp.mode == XSM_VERIFY_GREEDY ? 1 : vp.top_ka;
+  int rank;
+  switch (V) {
+    case 1024: rank = row_rank_regs<1>(z, xtok, ka, sm, near); break;
+    case 2048: rank = row_rank_regs<2>(z, xtok, ka, sm, near); break;
+    case 4096: rank = row_rank_regs<4>(z, xtok, ka, sm, near); break;
+    case 8192: rank = row_rank_regs<8>(z, xtok, ka, sm, near); break;
+    default:
+      rank = row_rank(z, V, xtok, sm);
+      *near = rank_near_boundary(z, V, xtok, rank, ka, sm);
+  }
+  return rank < ka;
+}
+
 __device__ inline int row_sample(const float* z, int V, const xsm_verify_params& vp, uint32_t pos,
                           uint32_t head, uint32_t seq, RowScratch& sm, uint32_t* flag) {
   if (vp.sample == 0) {
@@ -171,7 +326,7 @@ __device__ inline int row_sample(const float* z, int V, const xsm_verify_params&
   }
   const float u = philox_uniform(vp.seed, pos, head, seq);
   bool near_edge;
-  const int t = row_categorical(z, V, 1.0f / vp.temperature, u, sm, &near_edge);
+  const int t = row_draw(z, V, 1.0f / vp.temperature, u, sm, &near_edge);
   if (near_edge) *flag |= XSM_FLAG_NEAR_TIE;
   return t;
 }
