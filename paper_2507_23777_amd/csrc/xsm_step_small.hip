@@ -1512,7 +1512,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
         } else {                                           // level d - 1 of the tree: head d's ks most probable tokens
           const int grow = M + (b * R + m) * K + d - 1;
           if (!rows_complete(grow, 1)) break;
-          row_topk_probs(a.head_all_dbg + (size_t)(grow - M) * V, V, ks, invT, rs, lv.idx[0], lv.p[0]);
+          row_level(a.head_all_dbg + (size_t)(grow - M) * V, V, ks, invT, rs, lv.idx[0], lv.p[0]);
           uint64_t* const lo = lev + (size_t)(grow - M) * 8 * 4;
           if (tid < ks) {
             ll_st(lo + (size_t)tid * 4, (uint32_t)lv.idx[0][tid], tag);

@@ -380,6 +380,63 @@ __device__ inline void row_topk_probs(const float* z, int V, int ks, float invT,
   }
 }
 
+// One level from registers, for rows of 1024 C4 logits: one memory pass; every round of the
+// selection is a local scan of the thread's own tokens plus one workgroup argmax.
+template <int C4>
+__device__ inline void row_topk_probs_regs(const float* z, int ks, float invT, RowScratch& sm, int* idx, float* p) {
+  constexpr int C = 4 * C4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, v0 = threadIdx.x * C;
+  float x[C];
+  row_to_regs<C4>(z, x);
+  float mx = x[0];
+#pragma unroll
+  for (int i = 1; i < C; ++i) mx = fmaxf(mx, x[i]);
+  mx = block_max(mx, sm.redf);
+  const float c = invT * kLog2e;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < C; ++i) sum += __builtin_amdgcn_exp2f((x[i] - mx) * c);
+  sum = block_sum(sum, sm.redf);
+  for (int j = 0; j < ks; ++j) {                 // j-th largest logit, lower index among equals
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+      if (x[i] > bv) { bv = x[i]; bi = v0 + i; }      // (ascending index: the first of equals stays)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float bv2 = __shfl_xor(bv, o, WAVE);
+      const int bi2 = __shfl_xor(bi, o, WAVE);
+      if (bv2 > bv || (bv2 == bv && bi2 < bi)) { bv = bv2; bi = bi2; }
+    }
+    __syncthreads();
+    if (lane == 0) { sm.bestv[wave] = bv; sm.besti[wave] = bi; }
+    __syncthreads();
+    bv = sm.bestv[0]; bi = sm.besti[0];
+    for (int w = 1; w < 4; ++w)
+      if (sm.bestv[w] > bv || (sm.bestv[w] == bv && sm.besti[w] < bi)) { bv = sm.bestv[w]; bi = sm.besti[w]; }
+    if (threadIdx.x == 0) {
+      idx[j] = bi;
+      p[j] = bi == 0x7FFFFFFF ? 0.f : __builtin_amdgcn_exp2f((bv - mx) * c) / sum;
+    }
+    // the winner leaves the contest (its owner marks it taken)
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+      if (v0 + i == bi) x[i] = -INFINITY;
+  }
+  __syncthreads();
+}
+
+__device__ inline void row_level(const float* z, int V, int ks, float invT, RowScratch& sm, int* idx, float* p) {
+  switch (V) {
+    case 1024: row_topk_probs_regs<1>(z, ks, invT, sm, idx, p); break;
+    case 2048: row_topk_probs_regs<2>(z, ks, invT, sm, idx, p); break;
+    case 4096: row_topk_probs_regs<4>(z, ks, invT, sm, idx, p); break;
+    case 8192: row_topk_probs_regs<8>(z, ks, invT, sm, idx, p); break;
+    default: row_topk_probs(z, V, ks, invT, sm, idx, p);
+  }
+}
+
 // The draw over the tree that levels lv[0..K) span, with the uniform u: cand[1..K] receives the
 // tokens.  Returns true (to every thread) when the draw is a near-tie: the uniform within
 // kCdfMargin of a path boundary, or a path's weight within kCutMargin (relative) of the cut-off.
@@ -453,7 +510,7 @@ __device__ inline bool pts_pick(const TreeLevels& lv, int K, int ks, float prune
 __device__ inline bool pts_draw(const float* Zh, int K, int V, int ks, float invT, float prune, float u,
                          RowScratch& sm, int* cand) {
   __shared__ TreeLevels lv;
-  for (int k = 0; k < K; ++k) row_topk_probs(Zh + (size_t)k * V, V, ks, invT, sm, lv.idx[k], lv.p[k]);
+  for (int k = 0; k < K; ++k) row_level(Zh + (size_t)k * V, V, ks, invT, sm, lv.idx[k], lv.p[k]);
   return pts_pick(lv, K, ks, prune, u, sm, cand);
 }
 
