@@ -408,7 +408,7 @@ __device__ __forceinline__ void put4(uint16_t* As, int ST, int row, int col, f32
 
 constexpr int kST = 1024 + 8;               // LDS row stride (bf16) of a staged 1024-column tile
 
-// Stage nrows rows, 1024 columns each, of NB tagged-word blocks (added up, see read_rows8) into LDS
+// Stage nrows rows, 1024 columns each, of NB tagged-word blocks (added up, see read_rows) into LDS
 // rows dst_row.. as two bf16 planes of row stride kST: hi at As, lo at As + 16 * kST.
 // NORM 1: RMSNorm over the columns with the gains g4 (this thread's columns 4 tid .. 4 tid + 3).
 // NORM 2: only the gains are applied and the rows' sums of squares are left in sm.rowsum[.][row];

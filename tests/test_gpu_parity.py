@@ -169,6 +169,23 @@ def test_probability_tree_sampling(X):
         eng.xsm_spec_step(buf, bad, 40)
 
 
+@pytest.mark.parametrize("V", [1024, 2048, 8192])
+def test_sampling_rules_on_register_resident_rows(X, V):
+    """Vocabularies of 1024, 2048 and 8192 (4096 is the latency model's): the accept checks, the
+    categorical draw and the tree levels then hold a logits row in registers (thread t owns
+    V / 256 consecutive tokens) instead of walking it in memory; every rule once at each size."""
+    cfg = _mid_cfg(vocab=V, n_layers=2, seed=60 + V // 1024)
+    w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2, prefix_lens=[37, 12])
+    # (a draw is a near-tie when its uniform lies within 2e-5 of a CDF edge: with V nearly equal
+    # weights that is 4e-5 V of all draws, so the larger vocabularies draw at a lower temperature)
+    T = 0.8 if V <= 2048 else 0.1
+    for name, vp in (("top-8 categorical", VerifyParams(mode=1, top_ka=8, temperature=T, sample=1, seed=V + 1)),
+                     ("threshold", VerifyParams(mode=2, delta=1.5 / V, temperature=1.0 if V <= 2048 else 0.25, sample=1, seed=V + 2)),
+                     ("tree K_s=3", VerifyParams(mode=1, top_ka=8, temperature=0.04, sample=2, seed=V + 3, top_ks=3))):
+        tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 4, si.first_block(cfg, 2))
+        _report(tal, f"V={V} {name}")
+
+
 def test_plain_step_matches_oracle(X):
     cfg = _mid_cfg(seed=23, vocab=1000)        # vocabulary not a multiple of 16: general-shape kernels
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 2)
