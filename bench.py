@@ -392,6 +392,29 @@ def main() -> int:
                  "spec_step_cost_ratio": round(ms_per_step / pms, 3),
                  "note": "one token per step; a speculative step yields between 1 and K+1 tokens for spec_step_cost_ratio "
                          "times the latency (the paper's Table 3 reports 1.23x for its step and 2.02 tokens per step)"}
+    # the other acceptance criteria and sampling rules on the same model at the same context
+    # (Sec. 5.4 "Verification criterion"; appendix "Sampling strategies"): the same kernel finishes
+    # them, so the interesting number is their cost over greedy
+    rules = None
+    if not args.no_extras:
+        ctx_r = int(len0[0])
+        rules = {"context": ctx_r, "ms_per_step": {}}
+        for rname, rvp in (("greedy", vp),
+                           ("top-8 acceptance, categorical draws T=0.8", pkg.xsm_verify_params(1, 8, 0.5, 0.8, 1, 1234)),
+                           ("threshold 0.5, categorical draws T=0.8", pkg.xsm_verify_params(2, 8, 0.5, 0.8, 1, 1234)),
+                           ("top-8 acceptance, probability tree K_s=2", pkg.xsm_verify_params(1, 8, 0.5, 0.8, 2, 1234, 2, 1e-5)),
+                           ("top-8 acceptance, probability tree K_s=4", pkg.xsm_verify_params(1, 8, 0.5, 0.8, 2, 1234, 4, 1e-5))):
+            buf.block.copy_(torch.tensor(first))
+            for _ in range(5):
+                buf.kv_len.fill_(ctx_r); eng.xsm_spec_step(buf, rvp, ctx_r)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for _ in range(100):
+                buf.kv_len.fill_(ctx_r); eng.xsm_spec_step(buf, rvp, ctx_r)
+            torch.cuda.synchronize()
+            rules["ms_per_step"][rname] = round(1e3 * (time.perf_counter() - t2) / 100, 4)
+        g0 = rules["ms_per_step"]["greedy"]
+        rules["cost_over_greedy"] = {k: round(v / g0, 4) for k, v in rules["ms_per_step"].items() if k != "greedy"}
     eng.xsm_check_device()
     forced = {f"{a:g}": round(B * a / ms_per_step * 1e3, 1) for a in (1.0, 2.02, float(R))}
     sweep = None
@@ -415,7 +438,7 @@ def main() -> int:
            "accepted_tok_per_s": round(accepted / sec, 1), "scr": round(accepted / (B * args.steps), 4),
            "accept_length_histogram": accept_hist, "roofline": roofline, "kernels": kernels,
            "kernel_ms_per_step": round(tot_ms / args.steps, 4),
-           "step_ms_spread": spread, "fixed_context": fixed, "plain_step": plain, "sweep": sweep,
+           "step_ms_spread": spread, "fixed_context": fixed, "plain_step": plain, "sampling_rules": rules, "sweep": sweep,
            "accepted_tok_per_s_at_accept_length": dict(
                forced, note="synthetic acceptance profiles: measured step latency x a given mean number of accepted "
                             "tokens per step (1 = no draft accepted, 2.02 = the paper's Table 3 row E, K+1 = all)")}

@@ -53,6 +53,8 @@ def test_json_line_has_the_agreed_fields():
     assert [f["context"] for f in d["fixed_context"]] == [257, 2048, 4353]
     assert d["plain_step"]["ms_per_step"] > 0 and d["plain_step"]["spec_step_cost_ratio"] > 0.5
     assert rf["traffic_source"]
+    sr = d["sampling_rules"]
+    assert len(sr["cost_over_greedy"]) == 4 and all(0.9 < v < 1.5 for v in sr["cost_over_greedy"].values())
     sw = d["sweep"]
     assert [p["workload"].split(" context")[0] for p in sw] == ["c2 batch 16 K=6", "c4 batch 32 K=4", "c4 batch 128 K=8"]
     for p in sw:
