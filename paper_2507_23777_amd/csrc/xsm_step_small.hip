@@ -417,11 +417,11 @@ constexpr int kST = 1024 + 8;               // LDS row stride (bf16) of a staged
 template <int NB, int NORM, int RB, class Hook = NoHook>
 __device__ __forceinline__ void stage_rows(Shared& sm, uint16_t* As, int dst_row, const uint32_t* buf, int BS, int RS,
                                            int nrows, f32x4 g4, float eps, int tid, uint32_t t8, bool& ok,
-                                           uint64_t* stamp = nullptr, Hook&& after_issue = NoHook{}) {
+                                           uint64_t* stamp = nullptr, Hook&& after_issue = NoHook{}, bool watch0 = true) {
   const int wave = tid >> 6, lane = tid & 63;
   for (int m0 = 0; m0 < nrows; m0 += RB) {
     f32x4 v[8];
-    if (m0 == 0) read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, true, v, ok, stamp, after_issue);
+    if (m0 == 0) read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, watch0, v, ok, stamp, after_issue);
     else read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, false, v, ok, stamp, NoHook{});
     if (NORM) {
       if (NORM == 1 && m0 > 0) __syncthreads();          // this call's earlier readers of rowsum are done
@@ -818,8 +818,14 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       const int q_sec = w / (D / 16), q_ts = w % (D / 16), q_h = q_ts >> 2, q_tt = q_ts & 3;
       float2 cs = float2{1.f, 0.f};
       if (live && q_sec < 2) cs = a.rope[(size_t)(len_m + mj) * 32 + q_tt * 8 + (nrow & 7)];
-      if (few) stage_rows<4, 2, 5>(sm, As, 0, lb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, first_chunk);
-      else stage_rows<4, 2, 4>(sm, As, 0, lb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, first_chunk);
+      // From the second layer on a QKV workgroup comes here straight from its own FFN-down tile, when
+      // the other tiles are landing too: it reads the four partial blocks at once instead of watching
+      // a word first (the read takes longer than the stragglers do, and a row that did come too
+      // early is re-read on its own) - one poll round trip less per layer.  The barriers of
+      // FFN-down's tile sum already separate its LDS reads from the rows staged here.
+      const bool watch0 = l == 0;
+      if (few) stage_rows<4, 2, 5>(sm, As, 0, lb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, first_chunk, watch0);
+      else stage_rows<4, 2, 4>(sm, As, 0, lb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, first_chunk, watch0);
       XSM_STAMP(l * 16 + 8);
       const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid) * row_scale(sm, om, a.eps);
