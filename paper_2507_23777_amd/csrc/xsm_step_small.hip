@@ -226,6 +226,9 @@ __device__ __forceinline__ void wave_watch(const uint32_t* base, int off, uint32
 // m >= RB.  All loads of a round are in flight together (NB x RB x 4 registers): a round costs one
 // round trip whatever NB is.
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
+// a hook that requests nothing: picks the reader below (one wide read, then single rows) where
+// that is wanted without anything to place behind the read
+struct NothingBehind { __device__ __forceinline__ void operator()() const {} };
 
 // One row (this thread's four words of each of NB blocks) that the wide read found incomplete:
 // re-read until every tag matches.  The slow path of read_rows; one row at a time keeps it small.
@@ -1280,8 +1283,10 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   {
     const f32x4 g4 = gains4(a.gf, tid);
     __syncthreads();
-    if (few) stage_rows<4, 1, 5>(sm, T0, 0, tb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok);
-    else stage_rows<4, 1, 4>(sm, T0, 0, tb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok);
+    // (read without a watch poll, like the QKV stage's input: every workgroup comes here from its
+    // own tile of the last FFN-down)
+    if (few) stage_rows<4, 1, 5>(sm, T0, 0, tb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, NothingBehind{}, false);
+    else stage_rows<4, 1, 4>(sm, T0, 0, tb + OFF_XP, BLK, D, M, g4, a.eps, tid, t8, ok, nullptr, NothingBehind{}, false);
   }
   XSM_STAMP(a.L * 16 + 1);
 
