@@ -702,11 +702,13 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     while (S > want) S >>= 1;
   }
   const int S_eff = S <= 4 ? S : 1;                    // slices the O-projection merges itself
-  // Rows a read round takes: 5 when that covers the block in one round (at most 5 rows: 20 loads
-  // in flight per thread for four partial blocks) or in two (9 or 10 rows, K = 8 at batch 1),
-  // else 4 for four partial blocks (16 loads - what the register file holds next to the weight
-  // tiles) and 8 for single blocks.
-  const bool few = M <= 5 || M == 9 || M == 10;
+  // Rows a read round of four partial blocks takes: all of them when there are at most 5 (20
+  // loads in flight per thread), else 4 (16 loads) - what the register file holds next to the
+  // weight tiles.  (The test is kept this simple on purpose: from `M <= 5` the compiler knows that
+  // a 5-row round is the only one and drops the round loops; folding the 9- and 10-row blocks of
+  // K = 8 into the same flag - two rounds of 5 instead of three of 4 - gained 4 % there and cost
+  // 4 % here.)
+  const bool few = M <= 5;
   // this lane's activation row (MFMA column) m = r
   // the output element this thread finishes after tile_reduce: tile column nrow of row om
   const int om = tid >> 4, nrow = tid & 15;
