@@ -603,8 +603,10 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
 
 }  // namespace
 
-template <int D, int F>
+// RC, BC: rows per sequence and sequences as compile-time constants (0: read from the arguments)
+template <int D, int F, int RC, int BC>
 __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
+  const int n_seq = BC ? BC : a.n_seq;
   constexpr int H = D / 64;
   constexpr int KTD = D / 32, KTF = F / 32;          // k-tiles of the two contraction lengths
   constexpr int KD = KTD / 4;                        // per wavefront
@@ -621,7 +623,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
 
   const int w = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int R = a.R, K = R - 1, M = a.n_seq * R, V = a.V;
+  const int R = RC ? RC : a.R, K = R - 1, M = n_seq * R, V = a.V;
 
   // ---- set-up: epoch, layer table, per-sequence validation (every workgroup, redundantly) ----
   if (tid == 0) {
@@ -633,7 +635,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   if (tid < 16) {
     int len = -1, sl = 0;
     uint32_t f = 0;
-    if (tid < a.n_seq) {
+    if (tid < n_seq) {
       const int n = a.kv_len[tid];
       sl = a.slot[tid];
       if (n < 0 || n + R > a.max_ctx || n > a.bound) f |= XSM_FLAG_BAD_LEN;
@@ -655,7 +657,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     a.flags[b] = sm.flag[b] | XSM_FLAG_DEVICE_TIMEOUT;
   };
   if (sm.fail != 0) {                       // an earlier step timed out: stay down until reset
-    if (w < a.n_seq && tid == 0) report_timeout(w);
+    if (w < n_seq && tid == 0) report_timeout(w);
     return;
   }
   const uint32_t tag = sm.tag;                          // full epoch: 8-byte words, barrier words
@@ -681,7 +683,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (__syncthreads_or(!ok)) {
       if (tid == 0) {
         __hip_atomic_store(a.ctrl + 1, 2000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (w < a.n_seq) report_timeout(w);
+        if (w < n_seq) report_timeout(w);
       }
       return;
     }
@@ -696,7 +698,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   int S = a.S;
   if (a.s_auto) {
     int longest = 0;
-    for (int b = 0; b < a.n_seq; ++b) longest = max(longest, sm.len[b]);
+    for (int b = 0; b < n_seq; ++b) longest = max(longest, sm.len[b]);
     const int chunks = (longest + 63) >> 6;
     const int want = chunks <= 2 ? 1 : chunks <= 6 ? 2 : chunks <= 28 ? 4 : 16;
     while (S > want) S >>= 1;
@@ -768,7 +770,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     XSM_STAMP(l * 16 + 0);
 
     // the attention unit of this workgroup: slice s of the keys of (sequence b, head h)
-    const int n_units = a.n_seq * H * S;
+    const int n_units = n_seq * H * S;
     const bool att = w < n_units;
     const int b = att ? w / (H * S) : 0, h = (w / S) % H, s = w % S;
     const int n = att ? sm.len[b] : -1;
@@ -1206,7 +1208,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       int watch_off = -1;
       {
         const int hh = 4 * wave + (lane & 3), j = lane >> 2, P = S > 4 ? S : S_eff;
-        if (j < a.n_seq * P) {
+        if (j < n_seq * P) {
           const int row = (j / P) * R + R - 1, sl = j % P;
           watch_off = S > 4 ? OFF_OP + row * D + hh * 64 + sl * (64 / S) + 64 / S - 1
                             : OFF_OP + sl * BLK + row * D + hh * 64 + 63;
@@ -1259,7 +1261,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (__syncthreads_or(!ok)) {
       if (tid == 0) {
         __hip_atomic_store(a.ctrl + 1, 1u + (uint32_t)l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (w < a.n_seq) report_timeout(w);
+        if (w < n_seq) report_timeout(w);
       }
       return;
     }
@@ -1460,8 +1462,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     const int ks = vp.top_ks;
     const int per_m = vp.sample == 0 ? 0 : R;
     const int per_seq = K + R * per_m;
-    const int n_first = a.n_seq * per_seq;
-    const int n_tasks = n_first + (vp.sample == 2 && K > 0 ? a.n_seq * R : 0);
+    const int n_first = n_seq * per_seq;
+    const int n_tasks = n_first + (vp.sample == 2 && K > 0 ? n_seq * R : 0);
     uint64_t* const lev = res + (size_t)512 * 4;          // tree levels: 8 words per head row, behind the result words
     // true (in every thread) once logits rows [g0, g0 + nr) are complete: their statistics words
     // of all tiles carry the tag, and each was stored after its tile's piece of the row had arrived
@@ -1549,7 +1551,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
       __syncthreads();
     }
   }
-  if (w < a.n_seq) {
+  if (w < n_seq) {
     const int b = w;
     const int n = sm.len[b];
     if (a.full_verify) {
@@ -1663,7 +1665,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   if (__syncthreads_or(!ok)) {
     if (tid == 0) {
       __hip_atomic_store(a.ctrl + 1, 1000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (w < a.n_seq) report_timeout(w);
+      if (w < n_seq) report_timeout(w);
     }
     return;
   }
@@ -1687,14 +1689,26 @@ size_t small_ll_words(int n_layers, int D, int F, int K) {
 
 bool small_supported(int D, int F) { return D == 1024 && F == 4096; }
 
+template <int RC, int BC>
+static void launch_small_t(const SmallArgs& a, size_t lds, hipStream_t s) {
+  auto kfn = k_step_small<1024, 4096, RC, BC>;
+  allow_dynamic_lds((const void*)kfn, lds);
+  hipLaunchKernelGGL(kfn, dim3(256), dim3(256), lds, s, a);
+}
+
 void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
   TraceScope trace_("step_small", s);
   if (D == 1024 && F == 4096 && a.ll_words * 4 < ((size_t)1 << 31)) {
-    auto kfn = k_step_small<1024, 4096>;
     // activation tiles as bf16 hi + lo planes: two 16-row model-width tiles in the tail
     const size_t lds = (size_t)4 * 16 * (1024 + 8) * 2;
-    allow_dynamic_lds((const void*)kfn, lds);
-    hipLaunchKernelGGL(kfn, dim3(256), dim3(256), lds, s, a);
+    // One sequence with K = 0, 2, 4 or 8 heads: the rows per sequence and the batch are compile-time
+    // constants of the instantiation (row loops and their predicates fold away: 8 % of a K = 4
+    // step); everything else takes the instantiation that reads them from the arguments.
+    if (a.n_seq == 1 && a.R == 5) launch_small_t<5, 1>(a, lds, s);
+    else if (a.n_seq == 1 && a.R == 1) launch_small_t<1, 1>(a, lds, s);
+    else if (a.n_seq == 1 && a.R == 3) launch_small_t<3, 1>(a, lds, s);
+    else if (a.n_seq == 1 && a.R == 9) launch_small_t<9, 1>(a, lds, s);
+    else launch_small_t<0, 0>(a, lds, s);
   }
 }
 
