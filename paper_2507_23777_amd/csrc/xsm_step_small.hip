@@ -514,10 +514,10 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_
 // (blocks of 16 x 1024 words at word off_op + slice * blk of the layer buffer rs describes) are
 // merged while they are staged into LDS, O = sum_s f_s O_s / sum_s f_s l_s with f_s = 2^(m_s - max m).
 // The slices' (maximum, sum) pairs of all rows and heads are [16 rows][H][4 slices][2] words at
-// off_ml.  RB rows a round, all loads of a round in flight together.
-template <int H, int RB>
+// off_ml.  RB rows a round, all loads of a round in flight together; S_eff = 1, 2 or 4.
+template <int H, int RB, int S_eff>
 __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgpu_buffer_rsrc_t rs, const uint32_t* lb, int watch_off,
-                                               int off_op, int blk, int off_ml, int M, int S_eff, int tid, uint32_t t8, bool& ok) {
+                                               int off_op, int blk, int off_ml, int M, int tid, uint32_t t8, bool& ok) {
   float* const mls = &sm.att_o[0][0][0][0];
   const int wave = tid >> 6, lane = tid & 63;
   // wavefront w stages the columns of heads 4 w .. 4 w + 3 and waits for those heads' producers
@@ -706,11 +706,12 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   const int S_eff = S <= 4 ? S : 1;                    // slices the O-projection merges itself
   // Rows a read round of four partial blocks takes: all of them when there are at most 5 (20
   // loads in flight per thread), else 4 (16 loads) - what the register file holds next to the
-  // weight tiles.  (The test is kept this simple on purpose: from `M <= 5` the compiler knows that
-  // a 5-row round is the only one and drops the round loops; folding the 9- and 10-row blocks of
-  // K = 8 into the same flag - two rounds of 5 instead of three of 4 - gained 4 % there and cost
-  // 4 % here.)
-  const bool few = M <= 5;
+  // weight tiles.  The 9 rows of K = 8 at batch 1 go in two rounds of 5 instead of three of 4, but
+  // only where the row count is a compile-time constant: in the instantiation that reads it from
+  // the arguments the flag has to stay `M <= 5`, from which the compiler knows that a 5-row round
+  // is the only one and drops the round loops (folding 9 and 10 rows into it there gained 4 % at
+  // K = 8 and cost 4 % at K = 4).
+  const bool few = M <= 5 || (RC != 0 && BC != 0 && (M == 9 || M == 10));
   // this lane's activation row (MFMA column) m = r
   // the output element this thread finishes after tile_reduce: tile column nrow of row om
   const int om = tid >> 4, nrow = tid & 15;
@@ -1214,8 +1215,15 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
                             : OFF_OP + sl * BLK + row * D + hh * 64 + 63;
         }
       }
-      if (few) stage_attn_out<H, 5>(sm, As, lrs, lb, watch_off, OFF_OP, BLK, OFF_ML, M, S_eff, tid, t8, ok);
-      else stage_attn_out<H, 4>(sm, As, lrs, lb, watch_off, OFF_OP, BLK, OFF_ML, M, S_eff, tid, t8, ok);
+      // (the number of partial blocks as a template argument: loads, tag checks and the merge of the
+      // slices that are not there drop out of the code instead of being predicated)
+#define XSM_ATTN_OUT(RB_, SE_) stage_attn_out<H, RB_, SE_>(sm, As, lrs, lb, watch_off, OFF_OP, BLK, OFF_ML, M, tid, t8, ok)
+      if (few) {
+        if (S_eff == 1) XSM_ATTN_OUT(5, 1); else if (S_eff == 2) XSM_ATTN_OUT(5, 2); else XSM_ATTN_OUT(5, 4);
+      } else {
+        if (S_eff == 1) XSM_ATTN_OUT(4, 1); else if (S_eff == 2) XSM_ATTN_OUT(4, 2); else XSM_ATTN_OUT(4, 4);
+      }
+#undef XSM_ATTN_OUT
       XSM_STAMP(l * 16 + 14);
       const f32x4 acc = mac_tiles<KD>(wq, As, STD, r, wave * KD, g);
       const float v = tile_reduce(sm, acc, wave, lane, tid);
