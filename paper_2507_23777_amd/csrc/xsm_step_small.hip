@@ -60,6 +60,7 @@
 // criteria and sampling rules (Sec. 5.4 "Verification criterion"; appendix "Sampling strategies")
 // read whole logits rows: each accept check, and each draw for every accepted length the scan
 // could end at, runs as a task on a workgroup of its own and posts its result as a tagged word.
+#include <type_traits>
 #include "xsm_device.h"
 #include "xsm_internal.h"
 #include "xsm_verify_device.h"
@@ -225,6 +226,8 @@ __device__ __forceinline__ void wave_watch(const uint32_t* base, int off, uint32
 // words; v[m] = the blocks' values added in the fixed order ((b0 + b1) + (b2 + b3)), zero for
 // m >= RB.  All loads of a round are in flight together (NB x RB x 4 registers): a round costs one
 // round trip whatever NB is.
+// rows a reader's result array holds: 8, or 12 for the single-block rounds of up to 12 rows
+constexpr int rows_held(int RB) { return RB <= 8 ? 8 : 12; }
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
 // a hook that requests nothing: picks the reader below (one wide read, then single rows) where
 // that is wanted without anything to place behind the read
@@ -264,7 +267,7 @@ __device__ __forceinline__ f32x4 retry_row(__amdgpu_buffer_rsrc_t rs, int word0,
 // the next stage's poll - a wavefront's loads return in order.
 template <int NB, int RB, class Hook>
 __device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, int m0, int nrows, int tid, uint32_t t8,
-                                          bool watch, f32x4 (&v)[8], bool& ok, uint64_t* stamp, Hook&& after_issue) {
+                                          bool watch, f32x4 (&v)[rows_held(RB)], bool& ok, uint64_t* stamp, Hook&& after_issue) {
   static_assert((NB == 1 || NB == 4) && RB <= 8, "one block, or four partial blocks; at most 8 rows a round");
   const int rows = min(RB, nrows - m0);
   // (later rounds of a block come from the same producers as its first rows: no watch, its poll
@@ -308,11 +311,12 @@ __device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, i
   if (stamp && tid == 0) stamp[1] = wall_clock64();
 }
 
-// The same without a hook: everything is re-read until every tag matches (when the watched word is
+// The reader without a hook: everything is re-read until every tag matches (when the watched word is
 // in but another producer's words are not yet, one more round trip brings all of them).
 template <int NB, int RB>
-__device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, int m0, int nrows, int tid, uint32_t t8,
-                                          bool watch, f32x4 (&v)[8], bool& ok, uint64_t* stamp, NoHook) {
+__device__ __forceinline__ void read_rows_plain(const uint32_t* buf, int BS, int RS, int m0, int nrows, int tid, uint32_t t8,
+                                                bool watch, f32x4 (&v)[rows_held(RB)], bool& ok, uint64_t* stamp) {
+  static_assert(RB <= 12 && (NB == 1 || RB <= 8), "up to 12 rows of one block a round, up to 8 of four");
   const int rows = min(RB, nrows - m0);
   if (watch)
     watch_then_sync(buf + (size_t)(NB - 1) * BS + (size_t)(m0 + (rows > 0 ? rows - 1 : 0)) * RS + 513, t8, ok && rows > 0, tid);
@@ -335,7 +339,7 @@ __device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, i
           if (m < rows) bad |= tagdiff(q[b][m], t8);
       if ((bad & 0xFFu) == 0) {
 #pragma unroll
-        for (int m = RB; m < 8; ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int m = RB; m < rows_held(RB); ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int m = 0; m < RB; ++m) {
           if (m < rows) {
@@ -353,7 +357,7 @@ __device__ __forceinline__ void read_rows(const uint32_t* buf, int BS, int RS, i
     ok = false;
   }
 #pragma unroll
-  for (int m = 0; m < 8; ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int m = 0; m < rows_held(RB); ++m) v[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 }
 
 template <int N>
@@ -423,9 +427,14 @@ __device__ __forceinline__ void stage_rows(Shared& sm, uint16_t* As, int dst_row
                                            uint64_t* stamp = nullptr, Hook&& after_issue = NoHook{}, bool watch0 = true) {
   const int wave = tid >> 6, lane = tid & 63;
   for (int m0 = 0; m0 < nrows; m0 += RB) {
-    f32x4 v[8];
-    if (m0 == 0) read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, watch0, v, ok, stamp, after_issue);
-    else read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, false, v, ok, stamp, NoHook{});
+    static_assert(NORM == 0 || RB <= 8, "the row sums are exchanged eight rows at a time");
+    f32x4 v[rows_held(RB)];
+    if constexpr (std::is_same<typename std::decay<Hook>::type, NoHook>::value) {
+      read_rows_plain<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, m0 == 0 && watch0, v, ok, stamp);
+    } else {
+      if (m0 == 0) read_rows<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, watch0, v, ok, stamp, after_issue);
+      else read_rows_plain<NB, RB>(buf, BS, RS, m0, nrows, tid, t8, false, v, ok, stamp);
+    }
     if (NORM) {
       if (NORM == 1 && m0 > 0) __syncthreads();          // this call's earlier readers of rowsum are done
       // eight row sums per wavefront in ten lane exchanges instead of forty-eight: each exchange
@@ -1325,7 +1334,7 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
     if (w < NTV) {                                     // only workgroups with a vocabulary tile need the rows
       __syncthreads();
       if (q_hi > q_lo)
-        stage_rows<1, 0, 8>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, 0, D, q_hi - q_lo,
+        stage_rows<1, 0, 12>(sm, T, q_lo - mt * 16, tb + OFF_RB + (size_t)(q_lo - M) * D, 0, D, q_hi - q_lo,
                          f32x4{1.f, 1.f, 1.f, 1.f}, a.eps, tid, t8, ok);
     }
     for (int t = w; t < NTV; t += 256) {
