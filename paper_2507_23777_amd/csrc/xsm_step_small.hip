@@ -613,8 +613,9 @@ __device__ __forceinline__ void stage_attn_out(Shared& sm, uint16_t* As, __amdgp
 }  // namespace
 
 // RC, BC, VC: rows per sequence, sequences and vocabulary as compile-time constants (0: read from the
-// arguments)
-template <int D, int F, int RC, int BC, int VC = 0>
+// arguments).  TL: with the stage clock (the stamps cost 1 % of a step, so the instantiations that
+// production steps run are built without them)
+template <int D, int F, int RC, int BC, int VC = 0, bool TL = false>
 __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   const int n_seq = BC ? BC : a.n_seq;
   constexpr int H = D / 64;
@@ -772,8 +773,8 @@ __global__ __launch_bounds__(256) void k_step_small(const SmallArgs a) {
   }
 
   // optional timeline: thread 0 of every workgroup stamps the 100 MHz clock at stage boundaries
-  uint64_t* const tl = a.tlog ? a.tlog + (size_t)w * (a.L * 16 + 8) : nullptr;
-#define XSM_STAMP(idx) do { if (tl && tid == 0) tl[idx] = wall_clock64(); } while (0)
+  uint64_t* const tl = TL && a.tlog ? a.tlog + (size_t)w * (a.L * 16 + 8) : nullptr;
+#define XSM_STAMP(idx) do { if (TL && tl && tid == 0) tl[idx] = wall_clock64(); } while (0)
   for (int l = 0; l < a.L; ++l) {
     uint32_t* const lb = llb + (size_t)l * LS;
     const LayerTab& lt = sm.tab[l];
@@ -1707,9 +1708,9 @@ size_t small_ll_words(int n_layers, int D, int F, int K) {
 
 bool small_supported(int D, int F) { return D == 1024 && F == 4096; }
 
-template <int RC, int BC, int VC = 0>
+template <int RC, int BC, int VC = 0, bool TL = false>
 static void launch_small_t(const SmallArgs& a, size_t lds, hipStream_t s) {
-  auto kfn = k_step_small<1024, 4096, RC, BC, VC>;
+  auto kfn = k_step_small<1024, 4096, RC, BC, VC, TL>;
   allow_dynamic_lds((const void*)kfn, lds);
   hipLaunchKernelGGL(kfn, dim3(256), dim3(256), lds, s, a);
 }
@@ -1723,7 +1724,10 @@ void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
     // constants of the instantiation (row loops and their predicates fold away: 8 % of a K = 4
     // step), for K = 4 with the latency model's vocabulary also that (1.3 %); everything else takes
     // the instantiation that reads them from the arguments.
-    if (a.n_seq == 1 && a.R == 5 && a.V == 4096) launch_small_t<5, 1, 4096>(a, lds, s);
+    if (a.tlog) {                                          // the stage clock was asked for
+      if (a.n_seq == 1 && a.R == 5 && a.V == 4096) launch_small_t<5, 1, 4096, true>(a, lds, s);
+      else launch_small_t<0, 0, 0, true>(a, lds, s);
+    } else if (a.n_seq == 1 && a.R == 5 && a.V == 4096) launch_small_t<5, 1, 4096>(a, lds, s);
     else if (a.n_seq == 1 && a.R == 5) launch_small_t<5, 1>(a, lds, s);
     else if (a.n_seq == 1 && a.R == 1) launch_small_t<1, 1>(a, lds, s);
     else if (a.n_seq == 1 && a.R == 3) launch_small_t<3, 1>(a, lds, s);
