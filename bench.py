@@ -29,10 +29,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # scaled by a plain copy of known size (profiles/c1_step_small_hbm_traffic.md has the command and
 # the counter values).  A counter run cannot happen inside this process, so the figure is the
 # profiling run's, and `traffic_source` in the output says which run that was.
-TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 716.8e6}
+TRAFFIC_BYTES_PER_LAUNCH = {"step_small": 716.9e6}
 TRAFFIC_SOURCE = {"step_small": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `python3 bench.py --steps 60 --warmup 5 "
                                 "--no-extras --no-sweep --no-cpu-baseline` (context 274..359, algorithmic 652.5 MB per "
-                                "launch): 706.3 MB read + 10.5 MB written; profiles/c1_step_small_hbm_traffic.md"}
+                                "launch): 706.4 MB read + 10.5 MB written; profiles/c1_step_small_hbm_traffic.md"}
 
 
 def algorithmic_bytes(cfg: dict, n_seq: int, sum_ctx: float) -> float:
