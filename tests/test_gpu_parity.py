@@ -489,19 +489,20 @@ def test_single_launch_step_matches_oracle_and_per_stage_kernels(X, single_launc
     eng.xsm_check_device()
 
 
-@pytest.mark.parametrize("K", [2, 4])
-def test_single_launch_one_sequence_compile_time_shapes(X, K):
+@pytest.mark.parametrize("K,V", [(2, 4096), (4, 4096), (4, 2048)])
+def test_single_launch_one_sequence_compile_time_shapes(X, K, V):
     """One sequence with K = 2 and K = 4 heads, and plain next-token steps of one sequence: the
     single-launch kernel has an instantiation of its own for each of these shapes (rows per
-    sequence and batch as compile-time constants; K = 8 is covered by the eight-heads case)."""
-    cfg = _c1_small(n_layers=2, n_draft=K)
+    sequence and batch as compile-time constants; K = 8 is covered by the eight-heads case), and
+    for K = 4 one with the latency model's vocabulary as a constant and one without."""
+    cfg = _c1_small(n_layers=2, n_draft=K, vocab=V)
     w, orc, states, eng = X.H.setup_pair(cfg, X.pkg.Engine, 1, perturb=True)
     X.xsm.xsm_debug_trace_enable(True); X.xsm.xsm_debug_trace_report()
     vp = VerifyParams(mode=1, top_ka=8, temperature=0.8, sample=1, seed=77 + K)
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 1))
-    _report(tal, f"c1-shape B1 K{K} greedy")
+    _report(tal, f"c1-shape B1 K{K} V{V} greedy")
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, vp, 4, si.first_block(cfg, 1))
-    _report(tal, f"c1-shape B1 K{K} top-8 categorical")
+    _report(tal, f"c1-shape B1 K{K} V{V} top-8 categorical")
     tal = X.H.lockstep(cfg, orc, states, eng, X.xsm, GREEDY, 4, si.first_block(cfg, 1), plain=True)
     _report(tal, f"c1-shape B1 plain (model with K={K})")
     ran = X.xsm.xsm_debug_trace_report(); X.xsm.xsm_debug_trace_enable(False)
