@@ -1720,7 +1720,7 @@ void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
   if (D == 1024 && F == 4096 && a.ll_words * 4 < ((size_t)1 << 31)) {
     // activation tiles as bf16 hi + lo planes: two 16-row model-width tiles in the tail
     const size_t lds = (size_t)4 * 16 * (1024 + 8) * 2;
-    // One sequence with K = 0, 2, 4 or 8 heads, two or three with K = 4: the rows per sequence and the batch are compile-time
+    // One sequence with K = 0, 2, 4 or 8 heads, two or three with K = 4, plain steps of eight: the rows per sequence and the batch are compile-time
     // constants of the instantiation (row loops and their predicates fold away: 8 % of a K = 4
     // step), for K = 4 with the latency model's vocabulary also that (1.3 %); everything else takes
     // the instantiation that reads them from the arguments.
@@ -1732,6 +1732,7 @@ void launch_step_small(const SmallArgs& a, int D, int F, hipStream_t s) {
     else if (a.n_seq == 2 && a.R == 5) launch_small_t<5, 2>(a, lds, s);
     else if (a.n_seq == 3 && a.R == 5) launch_small_t<5, 3>(a, lds, s);
     else if (a.n_seq == 1 && a.R == 1) launch_small_t<1, 1>(a, lds, s);
+    else if (a.n_seq == 8 && a.R == 1) launch_small_t<1, 8>(a, lds, s);
     else if (a.n_seq == 1 && a.R == 3) launch_small_t<3, 1>(a, lds, s);
     else if (a.n_seq == 1 && a.R == 9) launch_small_t<9, 1>(a, lds, s);
     else launch_small_t<0, 0>(a, lds, s);
